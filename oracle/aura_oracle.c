@@ -1,0 +1,422 @@
+/*
+ * CPU oracle for multi-view feature fusion, material scoring and property
+ * integration (AURA, arXiv 2511.03126).
+ *
+ * THIS IS TEST INFRASTRUCTURE.  It is a plain, slow, per-point implementation of
+ * the definitions in the paper, used to check the GPU library.  It shares no
+ * code, header, table or helper with the GPU library and must never be called
+ * from a product path.
+ *
+ * What each function follows:
+ *   projection pi(x_i, v), proj_depth      Sec. 3.1 "Visibility Checking" (pinhole model;
+ *                                          depth = z in the camera frame, Sec. 3.2.2)
+ *   visibility mask M_vis                  Sec. 3.1 Eq. 1
+ *   feature aggregation                    Sec. 3.1 Eq. 2 (bilinear sampling of F_v)
+ *   similarity omega_k                     Sec. 3.4.1 (cosine similarity to text embedding k)
+ *   kernel regression rho(s)               Sec. 3.4.1 Eq. 4, T from Sec. 4 "Parameters"
+ *   integration to mass                    Sec. 3.4.2 (each query point is the centre of a
+ *                                          voxel; property times voxel volume, summed)
+ *
+ * Precision.  All sums, weights and outputs are double.  The few quantities that
+ * DECIDE an integer (which depth texel is read, whether a point passes the depth
+ * test, which four feature cells are blended, which grid voxel a point falls in)
+ * are evaluated in fp32 with one fixed operation order, written out below with
+ * fmaf(), so that an fp32 implementation can take the same decisions.  The same
+ * quantities are also evaluated in double and the disagreements are reported as
+ * diagnostics.
+ *
+ * Build: gcc -O2 -std=c11 -ffp-contract=off -fopenmp -shared -fPIC (no fast-math).
+ * The OpenMP pragma only distributes independent points over threads; every
+ * point is still computed start to finish by the plain loop nest.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+enum { ORC_F32 = 0, ORC_BF16 = 1, ORC_F16 = 2 };
+enum { ORC_FLAG_FRUSTUM_ONLY = 1, ORC_FLAG_MEAN_ONLY = 2 };
+enum { ORC_DIAG_NEAR_THRESHOLD = 1, ORC_DIAG_NEAR_PIXEL_EDGE = 2, ORC_DIAG_F64_DIFFERS = 4 };
+
+/* ---------------------------------------------------------------- element widening */
+
+static float bits_to_float(uint32_t b) { float f; memcpy(&f, &b, 4); return f; }
+
+/* IEEE binary16 -> binary32, exact. */
+static float half_to_float(uint16_t h) {
+  uint32_t sign = (uint32_t)(h & 0x8000u) << 16;
+  uint32_t exp = (h >> 10) & 0x1fu;
+  uint32_t man = h & 0x3ffu;
+  if (exp == 0) {
+    if (man == 0) return bits_to_float(sign);
+    /* subnormal: value = man * 2^-24 */
+    float v = (float)man * 5.9604644775390625e-8f;
+    return sign ? -v : v;
+  }
+  if (exp == 31) return bits_to_float(sign | 0x7f800000u | (man << 13));
+  return bits_to_float(sign | ((exp + 112u) << 23) | (man << 13));
+}
+
+/* One stored feature element as a double (bf16 = upper half of a binary32). */
+static double feat_at(const void* feat, int dtype, int64_t idx) {
+  if (dtype == ORC_F32) return (double)((const float*)feat)[idx];
+  if (dtype == ORC_BF16) return (double)bits_to_float((uint32_t)((const uint16_t*)feat)[idx] << 16);
+  return (double)half_to_float(((const uint16_t*)feat)[idx]);
+}
+
+/* ---------------------------------------------------------------- a1: projection
+ * cam = { R (row-major 3x3), t (3), fx, fy, cx, cy }; camera frame Xc = R x + t,
+ * +z forward; u = fx*Xc.x/Xc.z + cx, v = fy*Xc.y/Xc.z + cy; proj_depth = Xc.z.   */
+
+static void project_f32(const float* cam, const float* p, float* u, float* v, float* z) {
+  float xc = fmaf(cam[2], p[2], fmaf(cam[1], p[1], fmaf(cam[0], p[0], cam[9])));
+  float yc = fmaf(cam[5], p[2], fmaf(cam[4], p[1], fmaf(cam[3], p[0], cam[10])));
+  float zc = fmaf(cam[8], p[2], fmaf(cam[7], p[1], fmaf(cam[6], p[0], cam[11])));
+  float qx = xc / zc;
+  float qy = yc / zc;
+  *u = fmaf(cam[12], qx, cam[14]);
+  *v = fmaf(cam[13], qy, cam[15]);
+  *z = zc;
+}
+
+static void project_f64(const float* cam, const float* p, double* u, double* v, double* z) {
+  double x = p[0], y = p[1], w = p[2];
+  double xc = (double)cam[0] * x + (double)cam[1] * y + (double)cam[2] * w + (double)cam[9];
+  double yc = (double)cam[3] * x + (double)cam[4] * y + (double)cam[5] * w + (double)cam[10];
+  double zc = (double)cam[6] * x + (double)cam[7] * y + (double)cam[8] * w + (double)cam[11];
+  *u = (double)cam[12] * (xc / zc) + (double)cam[14];
+  *v = (double)cam[13] * (yc / zc) + (double)cam[15];
+  *z = zc;
+}
+
+/* ---------------------------------------------------------------- a2: Eq. 1
+ * Pixel (row r, col c) covers [c,c+1) x [r,r+1).  A point is visible when it is in
+ * front of the camera, lands inside the image, the depth texel is valid (> 0; NaN
+ * fails) and proj_depth <= Depth + tau.  tau = 0 is Eq. 1 as printed.             */
+
+static int visible_f32(const float* depth_v, int H, int W, float tau, float z_near, int frustum_only,
+                       float u, float v, float z) {
+  int inside = (z > z_near) && (u >= 0.0f) && (u < (float)W) && (v >= 0.0f) && (v < (float)H);
+  if (!inside) return 0;
+  if (frustum_only) return 1;
+  int px = (int)floorf(u), py = (int)floorf(v);
+  float d = depth_v[(int64_t)py * W + px];
+  if (!(d > 0.0f)) return 0;
+  float lim = d + tau;
+  return z <= lim;
+}
+
+static int visible_f64(const float* depth_v, int H, int W, float tau, float z_near, int frustum_only,
+                       double u, double v, double z) {
+  int inside = (z > (double)z_near) && (u >= 0.0) && (u < (double)W) && (v >= 0.0) && (v < (double)H);
+  if (!inside) return 0;
+  if (frustum_only) return 1;
+  int px = (int)floor(u), py = (int)floor(v);
+  double d = (double)depth_v[(int64_t)py * W + px];
+  if (!(d > 0.0)) return 0;
+  return z <= d + (double)tau;
+}
+
+static unsigned diag_flags(const float* cam, const float* depth_v, int H, int W, float tau, float z_near,
+                           int frustum_only, const float* p, float u, float v, float z, int vis32) {
+  unsigned f = 0;
+  double ud, vd, zd;
+  project_f64(cam, p, &ud, &vd, &zd);
+  if (visible_f64(depth_v, H, W, tau, z_near, frustum_only, ud, vd, zd) != vis32) f |= ORC_DIAG_F64_DIFFERS;
+  int inside = (z > z_near) && (u >= 0.0f) && (u < (float)W) && (v >= 0.0f) && (v < (float)H);
+  if (fabs(ud - nearbyint(ud)) <= 1e-4 || fabs(vd - nearbyint(vd)) <= 1e-4) f |= ORC_DIAG_NEAR_PIXEL_EDGE;
+  if (inside && !frustum_only) {
+    double d = (double)depth_v[(int64_t)((int)floorf(v)) * W + (int)floorf(u)];
+    if (d > 0.0 && isfinite(d)) {
+      double scale = fabs(d) > 1.0 ? fabs(d) : 1.0;
+      if (fabs(zd - (d + (double)tau)) <= 1e-5 * scale) f |= ORC_DIAG_NEAR_THRESHOLD;
+    }
+  }
+  return f;
+}
+
+/* ---------------------------------------------------------------- a3: bilinear sample
+ * The Hf x Wf grid covers the H x W image; cell k is centred at image coordinate
+ * (k + 0.5) * pitch, pitch = W / Wf.  Grid coordinate g = u / pitch - 0.5, clamped to
+ * [0, Wf-1] (replicated border).  g is taken in fp32 (pitch one fp32 division, then
+ * one division and one subtraction), so an integer pitch puts cell centres exactly on
+ * integers; the cell indices are floor(g) and the blend weights its exact fractional
+ * part, carried in double.                                                        */
+
+static void tap_axis(float coord, int size_img, int size_grid, int* i0, int* i1, double* a) {
+  float pitch = (float)size_img / (float)size_grid;
+  float q = coord / pitch;
+  float g = q - 0.5f;
+  g = fminf(fmaxf(g, 0.0f), (float)(size_grid - 1));
+  float fl = floorf(g);
+  *i0 = (int)fl;
+  *i1 = (*i0 + 1 < size_grid) ? *i0 + 1 : size_grid - 1;
+  *a = (double)g - (double)fl;
+}
+
+static void sample_bilinear(const void* feat_v, int dtype, int Hf, int Wf, int D, int H, int W,
+                            float u, float v, double* out /* [D], accumulated into */) {
+  int x0, x1, y0, y1;
+  double ax, ay;
+  tap_axis(u, W, Wf, &x0, &x1, &ax);
+  tap_axis(v, H, Hf, &y0, &y1, &ay);
+  int64_t o00 = ((int64_t)y0 * Wf + x0) * D, o01 = ((int64_t)y0 * Wf + x1) * D;
+  int64_t o10 = ((int64_t)y1 * Wf + x0) * D, o11 = ((int64_t)y1 * Wf + x1) * D;
+  for (int c = 0; c < D; ++c) {
+    double top = (1.0 - ax) * feat_at(feat_v, dtype, o00 + c) + ax * feat_at(feat_v, dtype, o01 + c);
+    double bot = (1.0 - ax) * feat_at(feat_v, dtype, o10 + c) + ax * feat_at(feat_v, dtype, o11 + c);
+    out[c] += (1.0 - ay) * top + ay * bot;
+  }
+}
+
+static int64_t elt_bytes(int dtype) { return dtype == ORC_F32 ? 4 : 2; }
+
+/* ---------------------------------------------------------------- exported: single-point helpers */
+
+/* Projects one point with one camera: fp32 chain into uvz32[3], double into uvz64[3]. */
+int orc_project_point(const float* cam, const float* xyz, float* uvz32, double* uvz64) {
+  if (!cam || !xyz) return -1;
+  if (uvz32) project_f32(cam, xyz, &uvz32[0], &uvz32[1], &uvz32[2]);
+  if (uvz64) project_f64(cam, xyz, &uvz64[0], &uvz64[1], &uvz64[2]);
+  return 0;
+}
+
+/* Bilinear sample of one view's map at image location (u, v); out[D] is overwritten. */
+int orc_sample_bilinear(const void* feat_v, int dtype, int Hf, int Wf, int D, int H, int W,
+                        float u, float v, double* out) {
+  if (!feat_v || !out) return -1;
+  if (dtype < 0 || dtype > 2 || Hf < 1 || Wf < 1 || D < 1 || H < 1 || W < 1) return -2;
+  for (int c = 0; c < D; ++c) out[c] = 0.0;
+  sample_bilinear(feat_v, dtype, Hf, Wf, D, H, W, u, v, out);
+  return 0;
+}
+
+int orc_max_threads(void) {
+#ifdef _OPENMP
+  return omp_get_max_threads();
+#else
+  return 1;
+#endif
+}
+
+void orc_set_threads(int n) {
+#ifdef _OPENMP
+  if (n > 0) omp_set_num_threads(n);
+#else
+  (void)n;
+#endif
+}
+
+/* Objects are CSR ranges: points pt_offsets[b]..pt_offsets[b+1] see views
+ * view_offsets[b]..view_offsets[b+1].  NULL offsets with B == 1 = one object.     */
+static int check_csr(int64_t N, int n_views, const int64_t* pt_offsets, const int32_t* view_offsets, int B) {
+  if (B < 1) return -2;
+  if (!pt_offsets || !view_offsets) return (B == 1 && !pt_offsets && !view_offsets) ? 0 : -1;
+  if (pt_offsets[0] != 0 || pt_offsets[B] != N || view_offsets[0] != 0 || view_offsets[B] != n_views) return -2;
+  for (int b = 0; b < B; ++b)
+    if (pt_offsets[b + 1] < pt_offsets[b] || view_offsets[b + 1] < view_offsets[b]) return -2;
+  return 0;
+}
+
+/* ---------------------------------------------------------------- exported: a1 + a2
+ * vis[i * vis_pitch + j] = M_vis(x_i, j-th view of the point's object), 0 beyond the
+ * object's view count; count[i] = sum_j vis; uvz (optional) [N][vis_pitch][3] fp32;
+ * diag (optional) [N][vis_pitch] ORC_DIAG_* bits.                                  */
+int orc_project_visibility(const float* cam, const float* depth, int n_views, int H, int W,
+                           float tau, float z_near, unsigned flags,
+                           const float* xyz, int64_t N, const int64_t* pt_offsets,
+                           const int32_t* view_offsets, int B, int vis_pitch,
+                           uint8_t* vis, int32_t* count, float* uvz, uint8_t* diag) {
+  if (!cam || !xyz || !vis || !count) return -1;
+  if (!(flags & ORC_FLAG_FRUSTUM_ONLY) && !depth) return -1;
+  if (N < 0 || n_views < 1 || H < 1 || W < 1) return -2;
+  int rc = check_csr(N, n_views, pt_offsets, view_offsets, B);
+  if (rc) return rc;
+  int frustum_only = (flags & ORC_FLAG_FRUSTUM_ONLY) != 0;
+  for (int b = 0; b < B; ++b) {
+    int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
+    int v0 = view_offsets ? view_offsets[b] : 0, v1 = view_offsets ? view_offsets[b + 1] : n_views;
+    if (v1 - v0 > vis_pitch) return -2;
+#pragma omp parallel for schedule(dynamic, 256)
+    for (int64_t i = p0; i < p1; ++i) {
+      int32_t c = 0;
+      for (int j = 0; j < vis_pitch; ++j) {
+        int64_t o = i * vis_pitch + j;
+        vis[o] = 0;
+        if (diag) diag[o] = 0;
+        if (uvz) uvz[3 * o] = uvz[3 * o + 1] = uvz[3 * o + 2] = 0.0f;
+        if (j >= v1 - v0) continue;
+        const float* cm = cam + (int64_t)(v0 + j) * 16;
+        const float* dv = depth ? depth + (int64_t)(v0 + j) * H * W : NULL;
+        float u, v, z;
+        project_f32(cm, xyz + 3 * i, &u, &v, &z);
+        int m = visible_f32(dv, H, W, tau, z_near, frustum_only, u, v, z);
+        vis[o] = (uint8_t)m;
+        c += m;
+        if (uvz) { uvz[3 * o] = u; uvz[3 * o + 1] = v; uvz[3 * o + 2] = z; }
+        if (diag) diag[o] = (uint8_t)diag_flags(cm, dv, H, W, tau, z_near, frustum_only, xyz + 3 * i, u, v, z, m);
+      }
+      count[i] = c;
+    }
+  }
+  return 0;
+}
+
+/* ---------------------------------------------------------------- exported: a1..a4, Eq. 2
+ * fused[i] = sum_v M_vis F_v(pi(x_i,v)) / sum_v M_vis, then divided by
+ * max(||.||_2, norm_eps) unless ORC_FLAG_MEAN_ONLY.  No visible view: zeros.      */
+int orc_fuse_features(const float* cam, const float* depth, const void* feat, int feat_dtype,
+                      int n_views, int H, int W, int Hf, int Wf, int D,
+                      float tau, float z_near, float norm_eps, unsigned flags,
+                      const float* xyz, int64_t N, const int64_t* pt_offsets,
+                      const int32_t* view_offsets, int B,
+                      double* fused /* [N][D] */, int32_t* count /* [N] or NULL */) {
+  if (!cam || !feat || !xyz || !fused) return -1;
+  if (!(flags & ORC_FLAG_FRUSTUM_ONLY) && !depth) return -1;
+  if (N < 0 || n_views < 1 || H < 1 || W < 1 || Hf < 1 || Wf < 1 || D < 1) return -2;
+  if (feat_dtype < 0 || feat_dtype > 2) return -3;
+  int rc = check_csr(N, n_views, pt_offsets, view_offsets, B);
+  if (rc) return rc;
+  int frustum_only = (flags & ORC_FLAG_FRUSTUM_ONLY) != 0;
+  int64_t view_bytes = (int64_t)Hf * Wf * D * elt_bytes(feat_dtype);
+  for (int b = 0; b < B; ++b) {
+    int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
+    int v0 = view_offsets ? view_offsets[b] : 0, v1 = view_offsets ? view_offsets[b + 1] : n_views;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = p0; i < p1; ++i) {
+      double* acc = fused + i * D;
+      for (int c = 0; c < D; ++c) acc[c] = 0.0;
+      int32_t n = 0;
+      for (int vw = v0; vw < v1; ++vw) {
+        const float* dv = depth ? depth + (int64_t)vw * H * W : NULL;
+        float u, v, z;
+        project_f32(cam + (int64_t)vw * 16, xyz + 3 * i, &u, &v, &z);
+        if (!visible_f32(dv, H, W, tau, z_near, frustum_only, u, v, z)) continue;
+        sample_bilinear((const char*)feat + (int64_t)vw * view_bytes, feat_dtype, Hf, Wf, D, H, W, u, v, acc);
+        ++n;
+      }
+      if (count) count[i] = n;
+      if (n == 0) continue;
+      for (int c = 0; c < D; ++c) acc[c] /= (double)n;
+      if (flags & ORC_FLAG_MEAN_ONLY) continue;
+      double ss = 0.0;
+      for (int c = 0; c < D; ++c) ss += acc[c] * acc[c];
+      double nrm = sqrt(ss);
+      if (nrm < (double)norm_eps) nrm = (double)norm_eps;
+      for (int c = 0; c < D; ++c) acc[c] /= nrm;
+    }
+  }
+  return 0;
+}
+
+/* ---------------------------------------------------------------- exported: a5 + a6, Eq. 4
+ * scores[i][k] = <fused_i, temb_k>; prop[i][p] = sum_k softmax_k(scores/T) y[k][p];
+ * label[i] = argmax_k scores (lowest index on ties); margin[i] = top1 - top2.     */
+int orc_material_scores(const double* fused, int64_t N, int D, const float* temb, int K,
+                        const float* y, int P, float T,
+                        double* scores, double* prop, int32_t* label, double* margin) {
+  if (!fused || !temb || !scores) return -1;
+  if (N < 0 || D < 1 || K < 1 || P < 0 || (prop && (!y || P < 1)) || !(T > 0.0f)) return -2;
+#pragma omp parallel for schedule(dynamic, 64)
+  for (int64_t i = 0; i < N; ++i) {
+    const double* f = fused + i * D;
+    double* w = scores + i * K;
+    for (int k = 0; k < K; ++k) {
+      double s = 0.0;
+      for (int c = 0; c < D; ++c) s += f[c] * (double)temb[(int64_t)k * D + c];
+      w[k] = s;
+    }
+    int best = 0;
+    for (int k = 1; k < K; ++k) if (w[k] > w[best]) best = k;
+    if (label) label[i] = best;
+    if (margin) {
+      double second = -INFINITY;
+      for (int k = 0; k < K; ++k) if (k != best && w[k] > second) second = w[k];
+      margin[i] = (K > 1) ? w[best] - second : INFINITY;
+    }
+    if (prop) {
+      double den = 0.0;
+      for (int p = 0; p < P; ++p) prop[i * P + p] = 0.0;
+      for (int k = 0; k < K; ++k) {
+        double e = exp((w[k] - w[best]) / (double)T);
+        den += e;
+        for (int p = 0; p < P; ++p) prop[i * P + p] += e * (double)y[(int64_t)k * P + p];
+      }
+      for (int p = 0; p < P; ++p) prop[i * P + p] /= den;
+    }
+  }
+  return 0;
+}
+
+/* ---------------------------------------------------------------- exported: a7
+ * A point is used when count == NULL or count[i] > 0.
+ * G == 0 (point-volume mode): mass[b] = sum_i used_i * prop[i][p_index] * vol_i,
+ *   vol_i = vol[i] if vol != NULL else vol_uniform.
+ * G > 0 (grid mode): object b has a cube grid of G^3 voxels of side grid_h[b] with
+ *   lower corner grid_lo[b]; a point's voxel index per axis is
+ *   clamp(floor((x - lo) * (1/h)), 0, G-1) taken in fp32 (1/h one fp32 division);
+ *   mass[b] = h^3 * sum over occupied voxels of the mean property of its points.  */
+int orc_property_integrate(const double* prop, int64_t N, int P, int p_index,
+                           const int32_t* count, const float* vol, float vol_uniform,
+                           const int64_t* pt_offsets, int B,
+                           const float* xyz, const float* grid_lo, const float* grid_h, int G,
+                           double* mass, int64_t* n_used) {
+  if (!prop || !mass) return -1;
+  if (N < 0 || P < 1 || p_index < 0 || p_index >= P || B < 1 || G < 0) return -2;
+  if (G > 0 && (!xyz || !grid_lo || !grid_h)) return -1;
+  if (!pt_offsets && B != 1) return -1;
+  if (pt_offsets) {
+    if (pt_offsets[0] != 0 || pt_offsets[B] != N) return -2;
+    for (int b = 0; b < B; ++b) if (pt_offsets[b + 1] < pt_offsets[b]) return -2;
+  }
+  double* vsum = NULL;
+  int32_t* vcnt = NULL;
+  int64_t G3 = (int64_t)G * G * G;
+  if (G > 0) {
+    vsum = (double*)malloc(sizeof(double) * (size_t)G3);
+    vcnt = (int32_t*)malloc(sizeof(int32_t) * (size_t)G3);
+    if (!vsum || !vcnt) { free(vsum); free(vcnt); return -5; }
+  }
+  for (int b = 0; b < B; ++b) {
+    int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
+    double m = 0.0;
+    int64_t used = 0;
+    if (G == 0) {
+      for (int64_t i = p0; i < p1; ++i) {
+        if (count && count[i] <= 0) continue;
+        double v = vol ? (double)vol[i] : (double)vol_uniform;
+        m += prop[i * P + p_index] * v;
+        ++used;
+      }
+    } else {
+      for (int64_t j = 0; j < G3; ++j) { vsum[j] = 0.0; vcnt[j] = 0; }
+      float h = grid_h[b];
+      float inv_h = 1.0f / h;
+      for (int64_t i = p0; i < p1; ++i) {
+        if (count && count[i] <= 0) continue;
+        int64_t idx = 0;
+        for (int a = 2; a >= 0; --a) {              /* idx = (iz*G + iy)*G + ix */
+          float t = xyz[3 * i + a] - grid_lo[3 * b + a];
+          float s = t * inv_h;
+          float fl = floorf(s);
+          int q = (fl >= (float)(G - 1)) ? G - 1 : ((fl > 0.0f) ? (int)fl : 0);
+          idx = idx * G + q;
+        }
+        vsum[idx] += prop[i * P + p_index];
+        vcnt[idx] += 1;
+        ++used;
+      }
+      double tot = 0.0;
+      for (int64_t j = 0; j < G3; ++j) if (vcnt[j] > 0) tot += vsum[j] / (double)vcnt[j];
+      m = tot * (double)h * (double)h * (double)h;
+    }
+    mass[b] = m;
+    if (n_used) n_used[b] = used;
+  }
+  free(vsum);
+  free(vcnt);
+  return 0;
+}

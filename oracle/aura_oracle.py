@@ -1,0 +1,191 @@
+"""ctypes front end of the CPU oracle (oracle/aura_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
+benchmark's cpu_baseline leg.  Nothing here touches the GPU library, and the GPU
+library never imports this module.  Arrays in, numpy arrays out; all arithmetic
+is in the C file (see its header for the passages of the paper each part follows).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "aura_oracle.c"
+_LIB = _HERE / "libaura_oracle.so"
+
+F32, BF16, F16 = 0, 1, 2
+FLAG_FRUSTUM_ONLY, FLAG_MEAN_ONLY = 1, 2
+DIAG_NEAR_THRESHOLD, DIAG_NEAR_PIXEL_EDGE, DIAG_F64_DIFFERS = 1, 2, 4
+
+_DTYPES = {"f32": F32, "bf16": BF16, "f16": F16}
+
+
+def build(force: bool = False) -> Path:
+    """Compiles the oracle with gcc (no fast-math, no contraction, portable ISA)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+               "-shared", "-fPIC", "-o", str(_LIB), str(_SRC), "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        _lib = C.CDLL(str(_LIB))
+        _lib.orc_max_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _f32(a):
+    return None if a is None else np.ascontiguousarray(a, dtype=np.float32)
+
+
+def _feat(feat, feat_dtype):
+    """Stored feature maps: float32, or uint16 holding bf16 bits, or float16."""
+    code = _DTYPES[feat_dtype]
+    want = {F32: np.float32, BF16: np.uint16, F16: np.float16}[code]
+    feat = np.ascontiguousarray(feat)
+    if feat.dtype != want:
+        raise TypeError(f"feat for {feat_dtype} must be {want}, got {feat.dtype}")
+    return feat, code
+
+
+def _csr(N, n_views, pt_offsets, view_offsets):
+    if pt_offsets is None and view_offsets is None:
+        return None, None, 1
+    po = np.ascontiguousarray(pt_offsets, dtype=np.int64)
+    vo = np.ascontiguousarray(view_offsets, dtype=np.int32)
+    return po, vo, len(po) - 1
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+def max_threads() -> int:
+    return int(lib().orc_max_threads())
+
+
+def set_threads(n: int) -> None:
+    lib().orc_set_threads(C.c_int(n))
+
+
+def project_point(cam16, xyz3):
+    """One point, one camera -> (uvz fp32 chain, uvz double)."""
+    cam16 = _f32(cam16).reshape(16)
+    xyz3 = _f32(xyz3).reshape(3)
+    o32 = np.zeros(3, np.float32)
+    o64 = np.zeros(3, np.float64)
+    _check(lib().orc_project_point(_p(cam16), _p(xyz3), _p(o32), _p(o64)), "project_point")
+    return o32, o64
+
+
+def sample_bilinear(feat_v, feat_dtype, H, W, u, v):
+    """Bilinear sample of one view's [Hf][Wf][D] map at image location (u, v)."""
+    feat_v, code = _feat(feat_v, feat_dtype)
+    Hf, Wf, D = feat_v.shape
+    out = np.zeros(D, np.float64)
+    _check(lib().orc_sample_bilinear(_p(feat_v), C.c_int(code), C.c_int(Hf), C.c_int(Wf), C.c_int(D),
+                                     C.c_int(H), C.c_int(W), C.c_float(u), C.c_float(v), _p(out)),
+           "sample_bilinear")
+    return out
+
+
+def project_visibility(cam, depth, xyz, tau=0.0, z_near=1e-6, flags=0, pt_offsets=None,
+                       view_offsets=None, vis_pitch=None, want_uvz=False, want_diag=False):
+    cam = _f32(cam).reshape(-1, 16)
+    depth = _f32(depth)
+    xyz = _f32(xyz).reshape(-1, 3)
+    n_views, H, W = depth.shape
+    N = xyz.shape[0]
+    po, vo, B = _csr(N, n_views, pt_offsets, view_offsets)
+    if vis_pitch is None:
+        vis_pitch = n_views if vo is None else int(np.max(np.diff(vo)))
+    vis = np.zeros((N, vis_pitch), np.uint8)
+    count = np.zeros(N, np.int32)
+    uvz = np.zeros((N, vis_pitch, 3), np.float32) if want_uvz else None
+    diag = np.zeros((N, vis_pitch), np.uint8) if want_diag else None
+    rc = lib().orc_project_visibility(_p(cam), _p(depth), C.c_int(n_views), C.c_int(H), C.c_int(W),
+                                      C.c_float(tau), C.c_float(z_near), C.c_uint(flags),
+                                      _p(xyz), C.c_int64(N), _p(po), _p(vo), C.c_int(B), C.c_int(vis_pitch),
+                                      _p(vis), _p(count), _p(uvz), _p(diag))
+    _check(rc, "project_visibility")
+    return {"vis": vis, "count": count, "uvz": uvz, "diag": diag}
+
+
+def fuse_features(cam, depth, feat, feat_dtype, xyz, tau=0.0, z_near=1e-6, norm_eps=1e-12, flags=0,
+                  pt_offsets=None, view_offsets=None):
+    cam = _f32(cam).reshape(-1, 16)
+    depth = _f32(depth)
+    xyz = _f32(xyz).reshape(-1, 3)
+    feat, code = _feat(feat, feat_dtype)
+    n_views, H, W = depth.shape
+    _, Hf, Wf, D = feat.shape
+    if feat.shape[0] != n_views:
+        raise ValueError("feat and depth disagree on the number of views")
+    N = xyz.shape[0]
+    po, vo, B = _csr(N, n_views, pt_offsets, view_offsets)
+    fused = np.zeros((N, D), np.float64)
+    count = np.zeros(N, np.int32)
+    rc = lib().orc_fuse_features(_p(cam), _p(depth), _p(feat), C.c_int(code), C.c_int(n_views),
+                                 C.c_int(H), C.c_int(W), C.c_int(Hf), C.c_int(Wf), C.c_int(D),
+                                 C.c_float(tau), C.c_float(z_near), C.c_float(norm_eps), C.c_uint(flags),
+                                 _p(xyz), C.c_int64(N), _p(po), _p(vo), C.c_int(B), _p(fused), _p(count))
+    _check(rc, "fuse_features")
+    return {"fused": fused, "count": count}
+
+
+def material_scores(fused, temb, y=None, T=0.1):
+    fused = np.ascontiguousarray(fused, dtype=np.float64)
+    temb = _f32(temb)
+    N, D = fused.shape
+    K = temb.shape[0]
+    if temb.shape[1] != D:
+        raise ValueError("temb and fused disagree on D")
+    y = None if y is None else _f32(y).reshape(K, -1)
+    P = 0 if y is None else y.shape[1]
+    scores = np.zeros((N, K), np.float64)
+    prop = np.zeros((N, P), np.float64) if y is not None else None
+    label = np.zeros(N, np.int32)
+    margin = np.zeros(N, np.float64)
+    rc = lib().orc_material_scores(_p(fused), C.c_int64(N), C.c_int(D), _p(temb), C.c_int(K), _p(y), C.c_int(P),
+                                   C.c_float(T), _p(scores), _p(prop), _p(label), _p(margin))
+    _check(rc, "material_scores")
+    return {"scores": scores, "prop": prop, "label": label, "margin": margin}
+
+
+def property_integrate(prop, p_index=0, count=None, vol=None, vol_uniform=1.0, pt_offsets=None,
+                       xyz=None, grid_lo=None, grid_h=None, G=0):
+    prop = np.ascontiguousarray(prop, dtype=np.float64)
+    if prop.ndim == 1:
+        prop = prop[:, None]
+    N, P = prop.shape
+    po = None if pt_offsets is None else np.ascontiguousarray(pt_offsets, dtype=np.int64)
+    B = 1 if po is None else len(po) - 1
+    count = None if count is None else np.ascontiguousarray(count, dtype=np.int32)
+    vol = _f32(vol)
+    xyz = None if xyz is None else _f32(xyz).reshape(-1, 3)
+    grid_lo = None if grid_lo is None else _f32(grid_lo).reshape(B, 3)
+    grid_h = None if grid_h is None else _f32(grid_h).reshape(B)
+    mass = np.zeros(B, np.float64)
+    n_used = np.zeros(B, np.int64)
+    rc = lib().orc_property_integrate(_p(prop), C.c_int64(N), C.c_int(P), C.c_int(p_index), _p(count), _p(vol),
+                                      C.c_float(vol_uniform), _p(po), C.c_int(B), _p(xyz), _p(grid_lo),
+                                      _p(grid_h), C.c_int(G), _p(mass), _p(n_used))
+    _check(rc, "property_integrate")
+    return {"mass": mass, "n_used": n_used}
