@@ -1,0 +1,210 @@
+/*
+ * libaura_fuse - multi-view semantic feature fusion onto a 3-D point / voxel set, per-point
+ * material scoring and property integration, for AMD MI355X (gfx950).
+ *
+ * The calls follow the method of "Accelerating Physical Property Reasoning for Augmented
+ * Visual Cognition" (AURA, arXiv 2511.03126):
+ *   aura_project_visibility   Sec. 3.1 "Visibility Checking", Eq. 1
+ *   aura_fuse_features        Sec. 3.1 "Feature Aggregation", Eq. 2 (+ L2 normalisation, implied
+ *                             by the cosine similarity of Sec. 3.4.1)
+ *   aura_material_scores      Sec. 3.4.1: similarity omega_k and the kernel regression of Eq. 4
+ *   aura_property_integrate   Sec. 3.4.2: voxel integration over volumes (mass)
+ *
+ * General rules
+ *   - Plain C ABI.  Every function returns an aura_status_t (0 = AURA_OK, negative = error);
+ *     nothing throws, aborts or prints.
+ *   - Pointers marked [device] are GPU global memory owned by the caller and must stay valid
+ *     until the work enqueued on `stream` has finished.  Pointers marked [host] are ordinary
+ *     host memory that is read before the call returns.  The library allocates and frees
+ *     nothing and keeps no pointer after a call returns.
+ *   - All work is enqueued on `stream` (a hipStream_t passed as void*; NULL = the null stream).
+ *     No call synchronises the stream or the device and no result is copied to the host.
+ *   - Arrays are dense, row-major, innermost index last.  Results are a deterministic function
+ *     of the inputs: the same call gives bitwise the same output.
+ *   - Objects.  A call may cover B independent objects.  Object b owns points
+ *     pt_offsets[b] .. pt_offsets[b+1]-1 of the concatenated point array and views
+ *     view_offsets[b] .. view_offsets[b+1]-1 of the concatenated view arrays; a point is only
+ *     ever tested against the views of its own object.  pt_offsets / view_offsets may both be
+ *     NULL when B == 1 (one object: all points, all views).  All views of a call share
+ *     H, W, Hf, Wf, D and the feature element type.
+ *   - N == 0 is valid and does nothing.
+ */
+#ifndef AURA_FUSE_H
+#define AURA_FUSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t aura_status_t;
+
+enum {
+  AURA_OK = 0,
+  AURA_ERR_NULL = -1,        /* a required pointer is NULL                                   */
+  AURA_ERR_SHAPE = -2,       /* a size is out of range or the offsets are inconsistent       */
+  AURA_ERR_DTYPE = -3,       /* unknown element type                                         */
+  AURA_ERR_ALIGN = -4,       /* a pointer or row pitch is not aligned as documented          */
+  AURA_ERR_WORKSPACE = -5,   /* workspace missing or smaller than aura_workspace_bytes says  */
+  AURA_ERR_HIP = -6,         /* a HIP call failed; see aura_last_hip_error()                 */
+  AURA_ERR_UNSUPPORTED = -7  /* valid request this build has no kernel for                   */
+};
+
+/* Element type of the feature maps. */
+enum { AURA_F32 = 0, AURA_BF16 = 1, AURA_F16 = 2 };
+
+/* aura_params_t.flags */
+enum {
+  AURA_VIS_FRUSTUM_ONLY = 1u,  /* skip the depth comparison of Eq. 1: visible = in front of the
+                                  camera and inside the image                                  */
+  AURA_FUSE_MEAN_ONLY = 2u     /* aura_fuse_features returns the plain mean of Eq. 2 without the
+                                  L2 normalisation                                             */
+};
+
+/* Which call a workspace size is asked for. */
+enum { AURA_CALL_MATERIAL_SCORES = 1, AURA_CALL_PROPERTY_INTEGRATE = 2 };
+
+/* One set of calibrated views (Sec. 3.1: poses, Depth_v and F_v for v in V). */
+typedef struct aura_views_t {
+  int32_t n_views;      /* total number of views over all objects, >= 1                       */
+  int32_t H, W;         /* depth-map (= image) size in pixels                                  */
+  int32_t Hf, Wf, D;    /* feature grid size and channel count                                 */
+  int32_t feat_dtype;   /* AURA_F32 | AURA_BF16 | AURA_F16                                     */
+  const float* cam;     /* [device] [n_views][16]: R (3x3 row-major), t (3), fx, fy, cx, cy.
+                           Camera frame Xc = R x + t with +z forward, +x right, +y down;
+                           pixel u = fx Xc.x / Xc.z + cx, v = fy Xc.y / Xc.z + cy, with pixel
+                           (row r, column c) covering [c, c+1) x [r, r+1)                      */
+  const float* depth;   /* [device] [n_views][H][W] depth along the camera z axis.  A texel that
+                           is <= 0 or NaN is invalid (nothing is visible there); +inf means
+                           nothing is in front.  May be NULL with AURA_VIS_FRUSTUM_ONLY        */
+  const void* feat;     /* [device] [n_views][Hf][Wf][D] feature maps, channel last, 16-byte
+                           aligned.  The grid covers the whole image: cell (r, c) is centred at
+                           pixel coordinate ((c + 0.5) W / Wf, (r + 0.5) H / Hf).
+                           Unused by aura_project_visibility                                   */
+} aura_views_t;
+
+typedef struct aura_params_t {
+  float tau;            /* depth tolerance in scene units: visible iff proj_depth <= Depth + tau.
+                           0 is Eq. 1 as printed                                               */
+  float z_near;         /* points with camera-frame z <= z_near are invisible (e.g. 1e-6)      */
+  float temperature;    /* T of Eq. 4, > 0; the paper uses 0.1                                  */
+  float norm_eps;       /* L2 normalisation divides by max(norm, norm_eps) (e.g. 1e-12)        */
+  uint32_t flags;       /* AURA_VIS_FRUSTUM_ONLY | AURA_FUSE_MEAN_ONLY                          */
+} aura_params_t;
+
+/* Library version as major * 10000 + minor * 100 + patch. */
+int32_t aura_version(void);
+
+/* Static, human-readable text for a status code. */
+const char* aura_strerror(aura_status_t status);
+
+/* The hipError_t of the last failed HIP call made by this thread (0 if none). */
+int32_t aura_last_hip_error(void);
+
+/*
+ * Bytes of device scratch the given call needs (write to *bytes).  The workspace must be
+ * 256-byte aligned.  Only the arguments listed matter:
+ *   AURA_CALL_MATERIAL_SCORES     D, K
+ *   AURA_CALL_PROPERTY_INTEGRATE  N, B, G
+ * Errors: AURA_ERR_NULL (bytes), AURA_ERR_SHAPE, AURA_ERR_UNSUPPORTED (unknown call).
+ */
+aura_status_t aura_workspace_bytes(int32_t call, int64_t N, int32_t B, int32_t D, int32_t K, int32_t G,
+                                   size_t* bytes);
+
+/*
+ * Sec. 3.1 "Visibility Checking", Eq. 1.  Projects every point into every view of its object
+ * and evaluates the visibility mask
+ *     M_vis(x_i, v) = [ z > z_near ] [ 0 <= u < W ] [ 0 <= v < H ] [ Depth_v valid ]
+ *                     [ z <= Depth_v(floor(v), floor(u)) + tau ].
+ * All of it is fp32 with one fixed operation order (three fused multiply-adds per camera-frame
+ * coordinate starting from t, one division, one fused multiply-add for the pixel coordinate),
+ * so the mask is reproducible bit for bit.
+ *
+ *   xyz    [device] [N][3] fp32 world coordinates
+ *   pt_offsets [host] [B+1] int64, view_offsets [host] [B+1] int32 (or both NULL, B == 1)
+ *   vis    [device] [N][vis_pitch] uint8: vis[i][j] = mask for the j-th view of i's object, 0 for
+ *          j beyond the object's view count.  vis_pitch >= the largest per-object view count
+ *   count  [device] [N] int32 = number of views that see the point (may be NULL)
+ *   uvz    [device] [N][vis_pitch][3] fp32 (u, v, proj_depth), or NULL (debug output)
+ * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_HIP.
+ */
+aura_status_t aura_project_visibility(const aura_views_t* views, const aura_params_t* params,
+                                      const float* xyz, int64_t N,
+                                      const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                                      uint8_t* vis, int32_t vis_pitch, int32_t* count, float* uvz,
+                                      void* stream);
+
+/*
+ * Sec. 3.1 "Feature Aggregation", Eq. 2.  For every point: bilinear samples of the feature maps
+ * of the views that see it (the same mask as aura_project_visibility, recomputed), averaged,
+ * then divided by max(L2 norm, norm_eps) unless AURA_FUSE_MEAN_ONLY.  Sampling: grid coordinate
+ * g = u / (W / Wf) - 0.5 (same in v), clamped to [0, Wf - 1]; the four cells around g are blended
+ * with weights from the fractional part.  Half-precision elements are widened exactly; all
+ * arithmetic and the output are fp32.  A point no view sees gets an all-zero row.
+ *
+ *   fused  [device] [N][D] fp32, 16-byte aligned
+ *   count  [device] [N] int32 or NULL
+ * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_DTYPE, AURA_ERR_ALIGN (feat or fused not
+ * 16-byte aligned), AURA_ERR_HIP.
+ */
+aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t* params,
+                                 const float* xyz, int64_t N,
+                                 const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                                 float* fused, int32_t* count, void* stream);
+
+/*
+ * Sec. 3.4.1.  scores[i][k] = <fused_i, temb_k> (the cosine similarity omega_k when both are
+ * unit vectors; temb is used as given), and, when y is given, Eq. 4:
+ *     prop[i][p] = sum_k exp(scores[i][k] / T) y[k][p] / sum_k exp(scores[i][k] / T),
+ * evaluated with the row maximum subtracted.  label[i] = argmax_k scores[i][k], the lowest k
+ * on exact ties.  An all-zero fused row therefore gives the plain mean of y and label 0.
+ *
+ *   fused  [device] [N][D] fp32          temb  [device] [K][D] fp32 (temb_dtype must be AURA_F32)
+ *   y      [device] [K][P] fp32 or NULL  scores [device] [N][K] fp32
+ *   prop   [device] [N][P] fp32 or NULL (needs y)   label [device] [N] int32 or NULL
+ *   workspace [device] aura_workspace_bytes(AURA_CALL_MATERIAL_SCORES, ...) bytes, 256-byte aligned
+ * The products run on the matrix cores with each fp32 operand split into two bf16 terms (three
+ * partial products), accumulated in fp32: absolute error of a score is below 1e-5 for unit vectors.
+ * Limits: 1 <= K <= 128, 1 <= P <= 8.
+ * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_DTYPE, AURA_ERR_WORKSPACE, AURA_ERR_UNSUPPORTED
+ * (K or P beyond the limits), AURA_ERR_HIP.
+ */
+aura_status_t aura_material_scores(const float* fused, int64_t N, int32_t D,
+                                   const void* temb, int32_t temb_dtype, int32_t K,
+                                   const float* y, int32_t P, const aura_params_t* params,
+                                   float* scores, float* prop, int32_t* label,
+                                   void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sec. 3.4.2 "voxel integration over volumes".  Each point is the centre of a voxel; the
+ * integrated property of object b is the sum of property times voxel volume.  A point is used
+ * when count is NULL or count[i] > 0.
+ *   G == 0, point-volume mode:  mass[b] = sum_i prop[i][p_index] * vol_i,  vol_i = vol[i] if vol is
+ *           given, else vol_uniform.
+ *   G  > 0, grid mode: object b has a cube of G^3 voxels of side grid_h[b] whose lower corner is
+ *           grid_lo[b].  A point falls in voxel clamp(floor((x - lo) * (1 / h)), 0, G - 1) per axis
+ *           (fp32).  mass[b] = h^3 * sum over occupied voxels of the mean property of the used
+ *           points inside.
+ * Products are fp32, sums are exact (fixed point) or fp64 in a fixed order.
+ *
+ *   prop   [device] [N][P] fp32          count [device] [N] int32 or NULL
+ *   vol    [device] [N] fp32 or NULL     pt_offsets [host] [B+1] int64 or NULL (B == 1)
+ *   xyz    [device] [N][3] fp32 (grid mode)   grid_lo [host] [B][3] fp32, grid_h [host] [B] fp32
+ *   mass   [device] [B] fp32             n_used [device] [B] int64 or NULL
+ *   workspace [device] aura_workspace_bytes(AURA_CALL_PROPERTY_INTEGRATE, ...) bytes
+ * Limits: B <= 4096; G <= 512 and B * G^3 < 2^31 in grid mode.  prop must be finite.
+ * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_WORKSPACE, AURA_ERR_UNSUPPORTED, AURA_ERR_HIP.
+ */
+aura_status_t aura_property_integrate(const float* prop, int64_t N, int32_t P, int32_t p_index,
+                                      const int32_t* count, const float* vol, float vol_uniform,
+                                      const int64_t* pt_offsets, int32_t B,
+                                      const float* xyz, const float* grid_lo, const float* grid_h, int32_t G,
+                                      float* mass, int64_t* n_used,
+                                      void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AURA_FUSE_H */

@@ -1,0 +1,8 @@
+"""MI355X-native multi-view feature fusion, material scoring and property integration.
+
+Thin Python front end of libaura_fuse.so (hand-written HIP for gfx950).  Nothing is computed in
+Python: every function in `binding` marshals torch tensors into one C-ABI call.
+"""
+from . import binding  # noqa: F401
+from .binding import (Params, Views, fuse_features, material_scores, project_visibility,  # noqa: F401
+                      property_integrate, workspace_bytes)

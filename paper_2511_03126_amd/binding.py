@@ -1,0 +1,203 @@
+"""ctypes binding of libaura_fuse.so: same names as the C ABI (include/aura_fuse.h), argument
+marshalling only.  Tensors are torch CUDA(HIP) tensors owned by the caller; work is enqueued on
+torch's current stream and nothing synchronises.  There is no fallback: if the shared library is
+missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from dataclasses import dataclass
+from pathlib import Path
+
+import numpy as np
+import torch
+
+_LIB_PATH = Path(__file__).resolve().parent / "libaura_fuse.so"
+
+F32, BF16, F16 = 0, 1, 2
+VIS_FRUSTUM_ONLY, FUSE_MEAN_ONLY = 1, 2
+CALL_MATERIAL_SCORES, CALL_PROPERTY_INTEGRATE = 1, 2
+
+_TORCH_DTYPE = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
+
+
+class AuraError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        msg = lib().aura_strerror(status).decode()
+        if status == -6:
+            msg += f" [hipError {lib().aura_last_hip_error()}]"
+        super().__init__(f"{what}: {msg} ({status})")
+
+
+class _ViewsT(C.Structure):
+    _fields_ = [("n_views", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("Hf", C.c_int32), ("Wf", C.c_int32),
+                ("D", C.c_int32), ("feat_dtype", C.c_int32), ("cam", C.c_void_p), ("depth", C.c_void_p),
+                ("feat", C.c_void_p)]
+
+
+class _ParamsT(C.Structure):
+    _fields_ = [("tau", C.c_float), ("z_near", C.c_float), ("temperature", C.c_float), ("norm_eps", C.c_float),
+                ("flags", C.c_uint32)]
+
+
+_lib = None
+
+
+def lib():
+    """Loads the shared library (built by paper_2511_03126_amd.build / __graft_entry__.build)."""
+    global _lib
+    if _lib is None:
+        if not _LIB_PATH.exists():
+            raise FileNotFoundError(f"{_LIB_PATH} is missing: run `python -m paper_2511_03126_amd.build` first")
+        L = C.CDLL(str(_LIB_PATH))
+        L.aura_version.restype = C.c_int32
+        L.aura_strerror.restype = C.c_char_p
+        L.aura_strerror.argtypes = [C.c_int32]
+        L.aura_last_hip_error.restype = C.c_int32
+        L.aura_workspace_bytes.restype = C.c_int32
+        L.aura_workspace_bytes.argtypes = [C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
+                                           C.POINTER(C.c_size_t)]
+        vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+        L.aura_project_visibility.restype = C.c_int32
+        L.aura_project_visibility.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32,
+                                              vp, i32, vp, vp, vp]
+        L.aura_fuse_features.restype = C.c_int32
+        L.aura_fuse_features.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32, vp, vp, vp]
+        L.aura_material_scores.restype = C.c_int32
+        L.aura_material_scores.argtypes = [vp, i64, i32, vp, i32, i32, vp, i32, C.POINTER(_ParamsT), vp, vp, vp,
+                                           vp, C.c_size_t, vp]
+        L.aura_property_integrate.restype = C.c_int32
+        L.aura_property_integrate.argtypes = [vp, i64, i32, i32, vp, vp, f32, vp, i32, vp, vp, vp, i32, vp, vp,
+                                              vp, C.c_size_t, vp]
+        _lib = L
+    return _lib
+
+
+@dataclass
+class Params:
+    tau: float = 0.0
+    z_near: float = 1e-6
+    temperature: float = 0.1
+    norm_eps: float = 1e-12
+    flags: int = 0
+
+    def c(self):
+        return _ParamsT(self.tau, self.z_near, self.temperature, self.norm_eps, self.flags)
+
+
+@dataclass
+class Views:
+    """Device tensors of one view set: cam [V][16] f32, depth [V][H][W] f32, feat [V][Hf][Wf][D]."""
+    cam: torch.Tensor
+    depth: torch.Tensor | None
+    feat: torch.Tensor | None = None
+    H: int | None = None
+    W: int | None = None
+
+    def c(self):
+        cam = _dev(self.cam, torch.float32, "cam")
+        V = cam.shape[0]
+        if self.depth is not None:
+            depth = _dev(self.depth, torch.float32, "depth")
+            H, W = depth.shape[1], depth.shape[2]
+        else:
+            H, W = self.H, self.W
+        v = _ViewsT(V, H, W, 0, 0, 0, 0, cam.data_ptr(), _ptr(self.depth), None)
+        if self.feat is not None:
+            f = self.feat
+            if not (f.is_cuda and f.is_contiguous() and f.dtype in _TORCH_DTYPE):
+                raise TypeError("feat must be a contiguous device tensor of float32, bfloat16 or float16")
+            v.Hf, v.Wf, v.D, v.feat_dtype, v.feat = f.shape[1], f.shape[2], f.shape[3], _TORCH_DTYPE[f.dtype], f.data_ptr()
+        return v
+
+
+def _dev(t, dtype, name):
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise TypeError(f"{name} must be a contiguous device tensor of {dtype}")
+    return t
+
+
+def _ptr(t):
+    return None if t is None else t.data_ptr()
+
+
+def _host(a, dtype):
+    """Object offsets and grid descriptions live in host memory (numpy)."""
+    return None if a is None else np.ascontiguousarray(a, dtype=dtype)
+
+
+def _hptr(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _check(status, what):
+    if status != 0:
+        raise AuraError(status, what)
+
+
+def workspace_bytes(call: int, N: int = 0, B: int = 1, D: int = 1, K: int = 1, G: int = 0) -> int:
+    out = C.c_size_t(0)
+    _check(lib().aura_workspace_bytes(call, N, B, D, K, G, C.byref(out)), "aura_workspace_bytes")
+    return int(out.value)
+
+
+def _objects(pt_offsets, view_offsets):
+    po, vo = _host(pt_offsets, np.int64), _host(view_offsets, np.int32)
+    B = 1 if po is None else len(po) - 1
+    return po, vo, B
+
+
+def project_visibility(views: Views, params: Params, xyz, vis, count=None, uvz=None, pt_offsets=None,
+                       view_offsets=None):
+    """vis [N][vis_pitch] uint8, count [N] int32, uvz [N][vis_pitch][3] f32 are filled in place."""
+    xyz = _dev(xyz, torch.float32, "xyz")
+    _dev(vis, torch.uint8, "vis")
+    po, vo, B = _objects(pt_offsets, view_offsets)
+    v, p = views.c(), params.c()
+    _check(lib().aura_project_visibility(C.byref(v), C.byref(p), xyz.data_ptr(), xyz.shape[0], _hptr(po), _hptr(vo),
+                                         B, vis.data_ptr(), vis.shape[1], _ptr(count), _ptr(uvz), _stream()),
+           "aura_project_visibility")
+
+
+def fuse_features(views: Views, params: Params, xyz, fused, count=None, pt_offsets=None, view_offsets=None):
+    """fused [N][D] f32 and count [N] int32 are filled in place."""
+    xyz = _dev(xyz, torch.float32, "xyz")
+    _dev(fused, torch.float32, "fused")
+    po, vo, B = _objects(pt_offsets, view_offsets)
+    v, p = views.c(), params.c()
+    _check(lib().aura_fuse_features(C.byref(v), C.byref(p), xyz.data_ptr(), xyz.shape[0], _hptr(po), _hptr(vo), B,
+                                    fused.data_ptr(), _ptr(count), _stream()), "aura_fuse_features")
+
+
+def material_scores(fused, temb, y, params: Params, scores, prop=None, label=None, workspace=None):
+    """scores [N][K], prop [N][P], label [N] are filled in place; workspace is a uint8 device tensor."""
+    fused = _dev(fused, torch.float32, "fused")
+    temb = _dev(temb, torch.float32, "temb")
+    N, D = fused.shape
+    K = temb.shape[0]
+    P = 0 if y is None else y.shape[1]
+    p = params.c()
+    _check(lib().aura_material_scores(fused.data_ptr(), N, D, temb.data_ptr(), F32, K, _ptr(y), P, C.byref(p),
+                                      scores.data_ptr(), _ptr(prop), _ptr(label), _ptr(workspace),
+                                      0 if workspace is None else workspace.numel(), _stream()),
+           "aura_material_scores")
+
+
+def property_integrate(prop, mass, p_index=0, count=None, vol=None, vol_uniform=1.0, pt_offsets=None, xyz=None,
+                       grid_lo=None, grid_h=None, G=0, n_used=None, workspace=None):
+    """mass [B] f32 and n_used [B] int64 are filled in place."""
+    prop = _dev(prop, torch.float32, "prop")
+    N, P = prop.shape
+    po = _host(pt_offsets, np.int64)
+    B = 1 if po is None else len(po) - 1
+    glo, gh = _host(grid_lo, np.float32), _host(grid_h, np.float32)
+    _check(lib().aura_property_integrate(prop.data_ptr(), N, P, p_index, _ptr(count), _ptr(vol), vol_uniform,
+                                         _hptr(po), B, _ptr(xyz), _hptr(glo), _hptr(gh), G, mass.data_ptr(),
+                                         _ptr(n_used), _ptr(workspace),
+                                         0 if workspace is None else workspace.numel(), _stream()),
+           "aura_property_integrate")

@@ -1,0 +1,245 @@
+// C ABI of libaura_fuse: argument validation and launch logic.  See include/aura_fuse.h for the
+// contract of every entry point.  Validation happens before any HIP call, so every error path
+// except AURA_ERR_HIP can be exercised on a machine without a GPU.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <vector>
+
+#include "../../include/aura_fuse.h"
+#include "launch.hpp"
+
+namespace {
+
+thread_local int32_t g_last_hip_error = 0;
+
+aura_status_t hip_status(hipError_t e) {
+  if (e == hipSuccess) return AURA_OK;
+  g_last_hip_error = (int32_t)e;
+  return AURA_ERR_HIP;
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+// Checks the object ranges and expands the "one object" shorthand.
+aura_status_t check_objects(int64_t N, int32_t n_views, const int64_t* pt_offsets, const int32_t* view_offsets,
+                            int32_t B, std::vector<aura::ObjRange>* out, int* max_views) {
+  if (B < 1) return AURA_ERR_SHAPE;
+  if ((pt_offsets == nullptr) != (view_offsets == nullptr)) return AURA_ERR_NULL;
+  if (!pt_offsets && B != 1) return AURA_ERR_NULL;
+  out->clear();
+  *max_views = 0;
+  for (int b = 0; b < B; ++b) {
+    const int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
+    const int64_t v0 = view_offsets ? view_offsets[b] : 0, v1 = view_offsets ? view_offsets[b + 1] : n_views;
+    if (p1 < p0 || v1 < v0 || p0 < 0 || v0 < 0 || p1 > N || v1 > n_views) return AURA_ERR_SHAPE;
+    if (p1 - p0 > 0x7fffffff) return AURA_ERR_SHAPE;
+    if (b == 0 && (p0 != 0 || v0 != 0)) return AURA_ERR_SHAPE;
+    if (b == B - 1 && (p1 != N || v1 != n_views)) return AURA_ERR_SHAPE;
+    aura::ObjRange r{};
+    r.pt_begin = p0;
+    r.n_pts = (int)(p1 - p0);
+    r.view_begin = (int)v0;
+    r.n_views = (int)(v1 - v0);
+    out->push_back(r);
+    *max_views = std::max(*max_views, r.n_views);
+  }
+  return AURA_OK;
+}
+
+aura_status_t check_views(const aura_views_t* v, const aura_params_t* p, bool need_feat) {
+  if (!v || !p) return AURA_ERR_NULL;
+  if (!v->cam) return AURA_ERR_NULL;
+  if (!(p->flags & AURA_VIS_FRUSTUM_ONLY) && !v->depth) return AURA_ERR_NULL;
+  if (v->n_views < 1 || v->H < 1 || v->W < 1) return AURA_ERR_SHAPE;
+  if ((int64_t)v->H * v->W > 0x7fffffff) return AURA_ERR_SHAPE;
+  if (need_feat) {
+    if (!v->feat) return AURA_ERR_NULL;
+    if (v->Hf < 1 || v->Wf < 1 || v->D < 1) return AURA_ERR_SHAPE;
+    if ((int64_t)v->Hf * v->Wf * v->D > 0x7fffffff) return AURA_ERR_SHAPE;
+    if (v->feat_dtype != AURA_F32 && v->feat_dtype != AURA_BF16 && v->feat_dtype != AURA_F16) return AURA_ERR_DTYPE;
+    if (!aligned(v->feat, 16)) return AURA_ERR_ALIGN;
+  }
+  return AURA_OK;
+}
+
+aura::VisArgs vis_args(const aura_views_t* v, const aura_params_t* p) {
+  aura::VisArgs a{};
+  a.cam = v->cam;
+  a.depth = (p->flags & AURA_VIS_FRUSTUM_ONLY) ? nullptr : v->depth;
+  a.H = v->H;
+  a.W = v->W;
+  a.tau = p->tau;
+  a.z_near = p->z_near;
+  a.frustum_only = (p->flags & AURA_VIS_FRUSTUM_ONLY) ? 1 : 0;
+  return a;
+}
+
+// Runs `launch(table, n_obj, max_pts)` over the objects in tables of kMaxObjPerLaunch.
+template <typename F>
+aura_status_t for_each_table(const std::vector<aura::ObjRange>& objs, F launch) {
+  for (size_t base = 0; base < objs.size(); base += aura::kMaxObjPerLaunch) {
+    aura::ObjTable tab{};
+    const int n = (int)std::min<size_t>(aura::kMaxObjPerLaunch, objs.size() - base);
+    int max_pts = 0;
+    for (int t = 0; t < n; ++t) {
+      tab.o[t] = objs[base + t];
+      max_pts = std::max(max_pts, tab.o[t].n_pts);
+    }
+    aura_status_t s = hip_status(launch(tab, n, max_pts));
+    if (s != AURA_OK) return s;
+  }
+  return AURA_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t aura_version(void) { return 100; }
+
+const char* aura_strerror(aura_status_t status) {
+  switch (status) {
+    case AURA_OK: return "ok";
+    case AURA_ERR_NULL: return "a required pointer is NULL";
+    case AURA_ERR_SHAPE: return "a size is out of range or the object offsets are inconsistent";
+    case AURA_ERR_DTYPE: return "unknown element type";
+    case AURA_ERR_ALIGN: return "a pointer or row pitch is not aligned as documented";
+    case AURA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case AURA_ERR_HIP: return "a HIP call failed (see aura_last_hip_error)";
+    case AURA_ERR_UNSUPPORTED: return "request is valid but not supported by this build";
+    default: return "unknown status";
+  }
+}
+
+int32_t aura_last_hip_error(void) { return g_last_hip_error; }
+
+aura_status_t aura_workspace_bytes(int32_t call, int64_t N, int32_t B, int32_t D, int32_t K, int32_t G,
+                                   size_t* bytes) {
+  if (!bytes) return AURA_ERR_NULL;
+  *bytes = 0;
+  if (call == AURA_CALL_MATERIAL_SCORES) {
+    if (D < 1 || K < 1) return AURA_ERR_SHAPE;
+    if (K > 128) return AURA_ERR_UNSUPPORTED;
+    *bytes = aura::scores_workspace_bytes(D, K);
+    return AURA_OK;
+  }
+  if (call == AURA_CALL_PROPERTY_INTEGRATE) {
+    if (N < 0 || B < 1 || G < 0) return AURA_ERR_SHAPE;
+    if (B > 4096 || G > 512 || (G > 0 && (int64_t)B * G * G * G >= (1ll << 31))) return AURA_ERR_UNSUPPORTED;
+    *bytes = aura::integrate_workspace_bytes(N, B, G);
+    return AURA_OK;
+  }
+  return AURA_ERR_UNSUPPORTED;
+}
+
+aura_status_t aura_project_visibility(const aura_views_t* views, const aura_params_t* params,
+                                      const float* xyz, int64_t N,
+                                      const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                                      uint8_t* vis, int32_t vis_pitch, int32_t* count, float* uvz,
+                                      void* stream) {
+  aura_status_t s = check_views(views, params, false);
+  if (s != AURA_OK) return s;
+  if (N < 0) return AURA_ERR_SHAPE;
+  std::vector<aura::ObjRange> objs;
+  int max_views = 0;
+  s = check_objects(N, views->n_views, pt_offsets, view_offsets, B, &objs, &max_views);
+  if (s != AURA_OK) return s;
+  if (vis_pitch < max_views || vis_pitch < 1) return AURA_ERR_SHAPE;
+  if (N == 0) return AURA_OK;
+  if (!xyz || !vis) return AURA_ERR_NULL;
+  const aura::VisArgs va = vis_args(views, params);
+  return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts) {
+    return aura::launch_project_visibility(va, xyz, vis, vis_pitch, count, uvz, tab, n, max_pts,
+                                           static_cast<hipStream_t>(stream));
+  });
+}
+
+aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t* params,
+                                 const float* xyz, int64_t N,
+                                 const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                                 float* fused, int32_t* count, void* stream) {
+  aura_status_t s = check_views(views, params, true);
+  if (s != AURA_OK) return s;
+  if (N < 0) return AURA_ERR_SHAPE;
+  std::vector<aura::ObjRange> objs;
+  int max_views = 0;
+  s = check_objects(N, views->n_views, pt_offsets, view_offsets, B, &objs, &max_views);
+  if (s != AURA_OK) return s;
+  if (N == 0) return AURA_OK;
+  if (!xyz || !fused) return AURA_ERR_NULL;
+  if (!aligned(fused, 16)) return AURA_ERR_ALIGN;
+  const aura::VisArgs va = vis_args(views, params);
+  aura::FeatArgs fa{};
+  fa.feat = views->feat;
+  fa.Hf = views->Hf;
+  fa.Wf = views->Wf;
+  fa.D = views->D;
+  fa.dtype = views->feat_dtype;
+  fa.pitch_x = (float)views->W / (float)views->Wf;
+  fa.pitch_y = (float)views->H / (float)views->Hf;
+  const int mean_only = (params->flags & AURA_FUSE_MEAN_ONLY) ? 1 : 0;
+  return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts) {
+    return aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only, tab, n, max_pts,
+                                      static_cast<hipStream_t>(stream));
+  });
+}
+
+aura_status_t aura_material_scores(const float* fused, int64_t N, int32_t D,
+                                   const void* temb, int32_t temb_dtype, int32_t K,
+                                   const float* y, int32_t P, const aura_params_t* params,
+                                   float* scores, float* prop, int32_t* label,
+                                   void* workspace, size_t workspace_bytes, void* stream) {
+  if (!params || !temb) return AURA_ERR_NULL;
+  if (N < 0 || D < 1 || K < 1 || P < 0) return AURA_ERR_SHAPE;
+  if (temb_dtype != AURA_F32) return temb_dtype == AURA_BF16 || temb_dtype == AURA_F16 ? AURA_ERR_UNSUPPORTED : AURA_ERR_DTYPE;
+  if (prop && (!y || P < 1)) return AURA_ERR_NULL;
+  if (!(params->temperature > 0.0f)) return AURA_ERR_SHAPE;
+  if (K > 128 || P > 8) return AURA_ERR_UNSUPPORTED;
+  if (N == 0) return AURA_OK;
+  if (!fused || !scores) return AURA_ERR_NULL;
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < aura::scores_workspace_bytes(D, K))
+    return AURA_ERR_WORKSPACE;
+  return hip_status(aura::launch_material_scores(fused, N, D, static_cast<const float*>(temb), K, y, P,
+                                                 params->temperature, scores, prop, label, workspace,
+                                                 static_cast<hipStream_t>(stream)));
+}
+
+aura_status_t aura_property_integrate(const float* prop, int64_t N, int32_t P, int32_t p_index,
+                                      const int32_t* count, const float* vol, float vol_uniform,
+                                      const int64_t* pt_offsets, int32_t B,
+                                      const float* xyz, const float* grid_lo, const float* grid_h, int32_t G,
+                                      float* mass, int64_t* n_used,
+                                      void* workspace, size_t workspace_bytes, void* stream) {
+  if (N < 0 || P < 1 || p_index < 0 || p_index >= P || B < 1 || G < 0) return AURA_ERR_SHAPE;
+  if (!pt_offsets && B != 1) return AURA_ERR_NULL;
+  if (!mass) return AURA_ERR_NULL;
+  if (G > 0 && (!grid_lo || !grid_h)) return AURA_ERR_NULL;
+  if (B > 4096 || G > 512 || (G > 0 && (int64_t)B * G * G * G >= (1ll << 31))) return AURA_ERR_UNSUPPORTED;
+  std::vector<aura::MassObj> objs((size_t)B);
+  for (int b = 0; b < B; ++b) {
+    const int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
+    if (p1 < p0 || p0 < 0 || p1 > N || p1 - p0 > 0x7fffffff) return AURA_ERR_SHAPE;
+    if ((b == 0 && p0 != 0) || (b == B - 1 && p1 != N)) return AURA_ERR_SHAPE;
+    aura::MassObj& o = objs[(size_t)b];
+    o.pt_begin = p0;
+    o.n_pts = (int)(p1 - p0);
+    o.lo[0] = o.lo[1] = o.lo[2] = 0.0f;
+    o.h = 1.0f;
+    if (G > 0) {
+      o.lo[0] = grid_lo[3 * b];
+      o.lo[1] = grid_lo[3 * b + 1];
+      o.lo[2] = grid_lo[3 * b + 2];
+      o.h = grid_h[b];
+      if (!(o.h > 0.0f)) return AURA_ERR_SHAPE;
+    }
+  }
+  if (N > 0 && (!prop || (G > 0 && !xyz))) return AURA_ERR_NULL;
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < aura::integrate_workspace_bytes(N, B, G))
+    return AURA_ERR_WORKSPACE;
+  return hip_status(aura::launch_property_integrate(prop, P, p_index, count, vol, vol_uniform, objs.data(), B, xyz, G,
+                                                    mass, reinterpret_cast<long long*>(n_used), workspace,
+                                                    static_cast<hipStream_t>(stream)));
+}
+
+}  // extern "C"

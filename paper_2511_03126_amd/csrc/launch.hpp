@@ -1,0 +1,47 @@
+// Host-side launch functions of the kernels (one per .hip file), called by the C ABI layer.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "aura_device.hpp"
+
+namespace aura {
+
+// Per-call description of the feature maps for the fusion kernel.
+struct FeatArgs {
+  const void* feat;   // [n_views][Hf][Wf][D]
+  int Hf, Wf, D;
+  int dtype;          // 0 fp32, 1 bf16, 2 fp16
+  float pitch_x;      // W / Wf, H / Hf as fp32 quotients
+  float pitch_y;
+};
+
+hipError_t launch_project_visibility(const VisArgs& vis, const float* xyz, uint8_t* out_vis, int vis_pitch,
+                                     int* out_count, float* out_uvz, const ObjTable& tab, int n_obj,
+                                     int max_pts, hipStream_t stream);
+
+hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const float* xyz, float* fused,
+                                int* out_count, float norm_eps, int mean_only, const ObjTable& tab, int n_obj,
+                                int max_pts, hipStream_t stream);
+
+size_t scores_workspace_bytes(int D, int K);
+hipError_t launch_material_scores(const float* fused, long long N, int D, const float* temb, int K,
+                                  const float* y, int P, float temperature, float* scores, float* prop,
+                                  int* label, void* workspace, hipStream_t stream);
+
+// Objects of one integration launch (host side; copied into kernel arguments in chunks).
+struct MassObj {
+  long long pt_begin;
+  int n_pts;
+  float lo[3];
+  float h;
+};
+
+size_t integrate_workspace_bytes(long long N, int B, int G);
+hipError_t launch_property_integrate(const float* prop, int P, int p_index, const int* count, const float* vol,
+                                     float vol_uniform, const MassObj* objs, int B, const float* xyz, int G,
+                                     float* mass, long long* n_used, void* workspace, hipStream_t stream);
+
+}  // namespace aura

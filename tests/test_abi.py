@@ -1,0 +1,130 @@
+"""CPU-only checks of the C ABI: the shared library loads, exports every function the header
+declares, and rejects bad arguments with the documented status before touching the GPU."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "aura_fuse.h")
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2511_03126_amd import binding
+    if not binding._LIB_PATH.exists():
+        from paper_2511_03126_amd.build import build
+        build()
+    binding.lib()
+    return binding
+
+
+def _declared_functions():
+    text = re.sub(r"/\*.*?\*/", "", open(HEADER).read(), flags=re.S)
+    return sorted(set(re.findall(r"\b(aura_[a-z_]+)\s*\(", text)))
+
+
+def test_every_declared_function_is_exported(B):
+    names = _declared_functions()
+    assert {"aura_project_visibility", "aura_fuse_features", "aura_material_scores", "aura_property_integrate",
+            "aura_workspace_bytes", "aura_version", "aura_strerror", "aura_last_hip_error"} <= set(names)
+    for n in names:
+        assert hasattr(B.lib(), n), n
+
+
+def test_version_and_error_strings(B):
+    assert B.lib().aura_version() >= 100
+    for code in range(0, -8, -1):
+        assert len(B.lib().aura_strerror(code)) > 1
+    assert B.lib().aura_last_hip_error() == 0
+
+
+def test_workspace_sizes(B):
+    assert B.workspace_bytes(B.CALL_MATERIAL_SCORES, D=768, K=32) == 24 * 1 * 4096
+    assert B.workspace_bytes(B.CALL_MATERIAL_SCORES, D=1024, K=128) == 32 * 4 * 4096
+    assert B.workspace_bytes(B.CALL_MATERIAL_SCORES, D=33, K=65) == 2 * 4 * 4096      # 3 tiles round up to 4
+    small = B.workspace_bytes(B.CALL_PROPERTY_INTEGRATE, N=1000, B=1, G=0)
+    grid = B.workspace_bytes(B.CALL_PROPERTY_INTEGRATE, N=1000, B=2, G=64)
+    assert 0 < small < 4096 and grid >= 2 * 64 ** 3 * 12
+    with pytest.raises(B.AuraError) as e:
+        B.workspace_bytes(B.CALL_MATERIAL_SCORES, D=64, K=129)
+    assert e.value.status == -7
+    with pytest.raises(B.AuraError) as e:
+        B.workspace_bytes(99)
+    assert e.value.status == -7
+    with pytest.raises(B.AuraError) as e:
+        B.workspace_bytes(B.CALL_PROPERTY_INTEGRATE, N=-1)
+    assert e.value.status == -2
+
+
+def _views(B, **kw):
+    fake = 0x1000      # never dereferenced: validation fails first
+    v = B._ViewsT(4, 32, 32, 4, 4, 64, B.F32, fake, fake, fake)
+    for k, val in kw.items():
+        setattr(v, k, val)
+    return v
+
+
+def test_argument_validation_returns_status_codes(B):
+    L = B.lib()
+    p = B.Params().c()
+    fake = C.c_void_p(0x1000)
+    po = np.array([0, 5, 10], np.int64)
+    vo = np.array([0, 2, 4], np.int32)
+    hp = lambda a: a.ctypes.data_as(C.c_void_p)
+    pv = lambda v, N=10, po_=None, vo_=None, B_=1, pitch=4, xyz=fake, vis=fake: L.aura_project_visibility(
+        C.byref(v), C.byref(p), xyz, N, po_, vo_, B_, vis, pitch, None, None, None)
+    assert pv(_views(B), xyz=None) == -1
+    assert pv(_views(B), vis=None) == -1
+    assert pv(_views(B, cam=None)) == -1
+    assert pv(_views(B, depth=None)) == -1
+    assert pv(_views(B, n_views=0)) == -2
+    assert pv(_views(B), N=-1) == -2
+    assert pv(_views(B), pitch=3) == -2                                    # fewer columns than views
+    assert pv(_views(B), po_=hp(po), vo_=None, B_=2) == -1                 # only one of the offset arrays
+    assert pv(_views(B), po_=None, vo_=None, B_=2) == -1
+    assert pv(_views(B), po_=hp(po), vo_=hp(vo), B_=2, N=11) == -2         # offsets do not end at N
+    bad = np.array([0, 7, 5], np.int64)
+    assert pv(_views(B), po_=hp(bad), vo_=hp(vo), B_=2, N=5) == -2         # not monotone
+    assert pv(_views(B), N=0, xyz=None, vis=None) == 0                     # empty input is fine
+
+    ff = lambda v, fused=fake: L.aura_fuse_features(C.byref(v), C.byref(p), fake, 10, None, None, 1, fused, None, None)
+    assert ff(_views(B, feat=None)) == -1
+    assert ff(_views(B, feat_dtype=7)) == -3
+    assert ff(_views(B, feat=0x1004)) == -4
+    assert ff(_views(B), fused=C.c_void_p(0x1004)) == -4
+    assert ff(_views(B, D=0)) == -2
+    assert ff(_views(B), fused=None) == -1
+
+    ms = lambda N=10, D=64, K=8, P=1, temb=fake, dt=B.F32, y=fake, prop=fake, ws=C.c_void_p(0x1000), wsb=1 << 20, par=p: \
+        L.aura_material_scores(fake, N, D, temb, dt, K, y, P, C.byref(par) if par is not None else None, fake, prop,
+                               None, ws, wsb, None)
+    assert ms(temb=None) == -1
+    assert ms(par=None) == -1
+    assert ms(D=0) == -2
+    assert ms(K=129) == -7
+    assert ms(P=9) == -7
+    assert ms(dt=B.BF16) == -7
+    assert ms(dt=5) == -3
+    assert ms(y=None) == -1                                                # prop wanted but no y
+    assert ms(ws=None) == -5
+    assert ms(wsb=16) == -5
+    assert ms(ws=C.c_void_p(0x1010)) == -5
+    cold = B.Params(temperature=0.0).c()
+    assert ms(par=cold) == -2
+
+    pi = lambda N=10, P=1, pidx=0, B_=1, G=0, mass=fake, ws=C.c_void_p(0x1000), wsb=1 << 30, po_=None, glo=None, gh=None, xyz=None: \
+        L.aura_property_integrate(fake, N, P, pidx, None, None, 1.0, po_, B_, xyz, glo, gh, G, mass, None, ws, wsb, None)
+    assert pi(mass=None) == -1
+    assert pi(pidx=1) == -2
+    assert pi(B_=2) == -1
+    assert pi(G=8) == -1                                                   # grid mode without a grid
+    assert pi(G=600, glo=fake, gh=fake) == -7
+    assert pi(ws=None) == -5
+    assert pi(wsb=8) == -5
+    glo = np.zeros((1, 3), np.float32)
+    gh = np.zeros(1, np.float32)
+    assert pi(G=8, glo=hp(glo), gh=hp(gh), xyz=fake) == -2                 # voxel size must be positive
+    assert pi(po_=hp(np.array([0, 4], np.int64))) == -2                    # offsets do not end at N
