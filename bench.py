@@ -1,0 +1,123 @@
+#!/usr/bin/env python3
+"""Benchmark of the fusion hot path on one MI355X.
+
+One step = one pass of the whole path over one synthetic scene already resident in HBM:
+aura_project_visibility -> aura_fuse_features -> aura_material_scores -> aura_property_integrate.
+Prints ONE JSON line: whole-path throughput in fused point-views per second, the roofline figure
+of the dominant kernel (the fusion gather, HBM bound) measured with events on the launch stream
+inside the timed region, and the CPU oracle timed on a bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+sys.path.insert(0, os.path.join(ROOT, "tests"))
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E
+
+
+def fuse_algorithmic_bytes(s):
+    """Each input read once, the fused rows and counts written once."""
+    elt = 4 if s.feat_dtype == "f32" else 2
+    return (12 * s.N + 64 * s.n_views + 4 * s.n_views * s.H * s.W + elt * s.n_views * s.Hf * s.Wf * s.D
+            + 4 * s.N * s.D + 4 * s.N)
+
+
+def cpu_baseline(scene, seconds_target=15.0):
+    """The oracle, as it stands, on a contiguous sample of the scene's first object."""
+    import numpy as np
+    from oracle import aura_oracle as orc
+    s = scene
+    p1 = int(s.pt_offsets[1])
+    v1 = int(s.view_offsets[1])
+    cam, depth, feat = s.cam[:v1], s.depth[:v1], s.feat[:v1]
+
+    def run(n):
+        xyz = s.xyz[:n]
+        t0 = time.perf_counter()
+        pv = orc.project_visibility(cam, depth, xyz, tau=s.tau, z_near=s.z_near)
+        fu = orc.fuse_features(cam, depth, feat, s.feat_dtype, xyz, tau=s.tau, z_near=s.z_near)
+        sc = orc.material_scores(fu["fused"], s.temb, s.y, T=s.temperature)
+        orc.property_integrate(sc["prop"], 0, fu["count"], vol_uniform=s.vol_uniform, xyz=xyz,
+                               grid_lo=None if s.G == 0 else s.grid_lo[:1], grid_h=None if s.G == 0 else s.grid_h[:1],
+                               G=s.G)
+        del pv
+        return time.perf_counter() - t0
+
+    n = min(p1, 2000)
+    t = run(n)                       # also warms the library up
+    n = int(min(p1, max(n, n * seconds_target / max(t, 1e-3))))
+    n = min(n, 400_000)
+    t = run(n)
+    return {"value": n * v1 / t, "unit": "point-views/s", "cores": orc.max_threads(), "kind": "oracle",
+            "sample": f"first {n} points of object 0 x {v1} views, whole path, {t:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on exactly one GPU (the path shards by points; see DESIGN.md); "
+                 "use --gpus 1")
+
+    import torch
+    import gpu_harness as H
+    from workloads.scenes import make_scene
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+
+    s = make_scene(args.workload)
+    d = H.DeviceScene(s)
+    for _ in range(max(args.warmup, 0)):
+        d.step()
+    torch.cuda.synchronize()
+
+    names = ["project_visibility", "fuse_features", "material_scores", "property_integrate"]
+    calls = [d.project_visibility, d.fuse_features, d.material_scores, d.property_integrate]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(args.steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        ev[k][0].record()
+        for c, call in enumerate(calls):
+            call()
+            ev[k][c + 1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    call_ms = {n: sum(ev[k][c].elapsed_time(ev[k][c + 1]) for k in range(args.steps)) / args.steps
+               for c, n in enumerate(names)}
+    pv = s.point_views
+    fuse_bytes = fuse_algorithmic_bytes(s)
+    achieved = fuse_bytes / (call_ms["fuse_features"] * 1e-3) / 1e9
+    gpu = d.results()
+    out = {
+        "metric": "fused point-views/sec", "value": pv / (ms_per_step * 1e-3), "unit": "point-views/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload}: N={s.N} points, B={s.B} objects, {s.n_views} views {s.H}x{s.W}, "
+                               f"feature grid {s.Hf}x{s.Wf}x{s.D} {s.feat_dtype}, K={s.K} materials, P={s.P}, "
+                               f"mass grid G={s.G}", "point_views": pv,
+                   "visible_fraction": float(gpu["vis"].mean()), "unseen_points": float((gpu["count"] == 0).mean()),
+                   "order": s.meta["order"], "seed": s.meta["seed"]},
+        "calls_ms": call_ms,
+        "roofline": {"bound": "hbm", "kernel": "k_fuse_gather (aura_fuse_features)", "achieved": achieved,
+                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes": fuse_bytes, "avg_launch_ms": call_ms["fuse_features"]},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(s)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -356,7 +356,7 @@ def _materials(rng, K, D, P):
 
 def _grid_for(points, G):
     lo, hi = points.min(0), points.max(0)
-    h = 1.001 * float(np.max(hi - lo)) / G
+    h = 1.001 * max(float(np.max(hi - lo)), 1e-6) / G
     glo = 0.5 * (lo + hi) - 0.5 * G * h
     return glo.astype(np.float32), np.float32(h)
 
