@@ -15,7 +15,7 @@ import torch
 _LIB_PATH = Path(__file__).resolve().parent / "libaura_fuse.so"
 
 F32, BF16, F16 = 0, 1, 2
-VIS_FRUSTUM_ONLY, FUSE_MEAN_ONLY = 1, 2
+VIS_FRUSTUM_ONLY, FUSE_MEAN_ONLY, FUSE_GATHER = 1, 2, 4
 CALL_MATERIAL_SCORES, CALL_PROPERTY_INTEGRATE = 1, 2
 
 _TORCH_DTYPE = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}

@@ -57,6 +57,7 @@ aura_status_t check_views(const aura_views_t* v, const aura_params_t* p, bool ne
     if (!v->feat) return AURA_ERR_NULL;
     if (v->Hf < 1 || v->Wf < 1 || v->D < 1) return AURA_ERR_SHAPE;
     if ((int64_t)v->Hf * v->Wf * v->D > 0x7fffffff) return AURA_ERR_SHAPE;
+    if ((int64_t)v->n_views * v->Hf * v->Wf > 0x7fffffff) return AURA_ERR_SHAPE;
     if (v->feat_dtype != AURA_F32 && v->feat_dtype != AURA_BF16 && v->feat_dtype != AURA_F16) return AURA_ERR_DTYPE;
     if (!aligned(v->feat, 16)) return AURA_ERR_ALIGN;
   }
@@ -179,8 +180,10 @@ aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t*
   fa.pitch_x = (float)views->W / (float)views->Wf;
   fa.pitch_y = (float)views->H / (float)views->Hf;
   const int mean_only = (params->flags & AURA_FUSE_MEAN_ONLY) ? 1 : 0;
+  const int force_gather = (params->flags & AURA_FUSE_GATHER) ? 1 : 0;
   return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts) {
-    return aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only, tab, n, max_pts,
+    return aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only, force_gather, tab, n,
+                                      max_pts,
                                       static_cast<hipStream_t>(stream));
   });
 }

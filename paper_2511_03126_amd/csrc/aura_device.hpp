@@ -65,17 +65,29 @@ __device__ __forceinline__ Proj project(const float* __restrict__ c, float x, fl
   return p;
 }
 
-// M_vis of Eq. 1 (with the tolerance tau) for one projected point; depth_v is the view's map.
-__device__ __forceinline__ bool visible(const VisArgs& a, const float* __restrict__ depth_v, const Proj& p) {
-#pragma clang fp contract(off)
-  bool inside = (p.z > a.z_near) && (p.u >= 0.0f) && (p.u < (float)a.W) && (p.v >= 0.0f) && (p.v < (float)a.H);
-  if (!inside) return false;
-  if (a.frustum_only) return true;
+// M_vis of Eq. 1 (with the tolerance tau), in three steps so that a kernel may issue the depth
+// read early: (1) in front of the camera and inside the image, (2) which texel, (3) the comparison.
+__device__ __forceinline__ bool in_frustum(const VisArgs& a, const Proj& p) {
+  return (p.z > a.z_near) && (p.u >= 0.0f) && (p.u < (float)a.W) && (p.v >= 0.0f) && (p.v < (float)a.H);
+}
+
+// Only meaningful when in_frustum() holds.
+__device__ __forceinline__ int depth_texel(const VisArgs& a, const Proj& p) {
   int px = (int)floorf(p.u), py = (int)floorf(p.v);
-  float d = depth_v[(long long)py * a.W + px];
+  return py * a.W + px;
+}
+
+__device__ __forceinline__ bool passes_depth(const VisArgs& a, const Proj& p, float d) {
+#pragma clang fp contract(off)
   if (!(d > 0.0f)) return false;
   float lim = d + a.tau;
   return p.z <= lim;
+}
+
+__device__ __forceinline__ bool visible(const VisArgs& a, const float* __restrict__ depth_v, const Proj& p) {
+  if (!in_frustum(a, p)) return false;
+  if (a.frustum_only) return true;
+  return passes_depth(a, p, depth_v[depth_texel(a, p)]);
 }
 
 // The two cells around grid coordinate g = coord / pitch - 0.5 (clamped) and the weight of the

@@ -12,6 +12,7 @@
 // the repeated cell reads are served by the caches, which is why points should arrive spatially
 // sorted and why workgroup ids are mapped so that each XCD walks a contiguous range of points.
 #include "aura_device.hpp"
+#include "fuse_args.hpp"
 #include "launch.hpp"
 
 namespace aura {
@@ -25,16 +26,6 @@ typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 constexpr int kFuseWaves = 4;
 constexpr int kFusePtsPerWave = 8;
 constexpr int kFusePtsPerBlock = kFuseWaves * kFusePtsPerWave;
-
-struct FuseArgs {
-  VisArgs vis;
-  FeatArgs feat;
-  const float* xyz;
-  float* fused;
-  int* out_count;
-  float norm_eps;
-  int mean_only;
-};
 
 __device__ __forceinline__ void widen_pair(uint32_t w, int dtype_is_bf16, float& lo, float& hi) {
   if (dtype_is_bf16) {
@@ -251,10 +242,11 @@ static hipError_t dispatch_d(const FuseArgs& a, const ObjTable& tab, int n_obj, 
 }
 
 hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const float* xyz, float* fused,
-                                int* out_count, float norm_eps, int mean_only, const ObjTable& tab, int n_obj,
-                                int max_pts, hipStream_t stream) {
+                                int* out_count, float norm_eps, int mean_only, int force_gather,
+                                const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream) {
   if (n_obj == 0 || max_pts == 0) return hipSuccess;
   FuseArgs a{vis, feat, xyz, fused, out_count, norm_eps, mean_only};
+  if (!force_gather && fuse_tile_supported(feat.dtype, feat.D)) return launch_fuse_tile(a, tab, n_obj, max_pts, stream);
   switch (feat.dtype) {
     case 0: return dispatch_d<0>(a, tab, n_obj, max_pts, stream);
     case 1: return dispatch_d<1>(a, tab, n_obj, max_pts, stream);

@@ -23,8 +23,8 @@ hipError_t launch_project_visibility(const VisArgs& vis, const float* xyz, uint8
                                      int max_pts, hipStream_t stream);
 
 hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const float* xyz, float* fused,
-                                int* out_count, float norm_eps, int mean_only, const ObjTable& tab, int n_obj,
-                                int max_pts, hipStream_t stream);
+                                int* out_count, float norm_eps, int mean_only, int force_gather,
+                                const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream);
 
 size_t scores_workspace_bytes(int D, int K);
 hipError_t launch_material_scores(const float* fused, long long N, int D, const float* temb, int K,
