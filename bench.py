@@ -100,6 +100,8 @@ def main():
     fuse_bytes = fuse_algorithmic_bytes(s)
     achieved = fuse_bytes / (call_ms["fuse_features"] * 1e-3) / 1e9
     gpu = d.results()
+    tile = s.feat_dtype != "f32" and s.D % 256 == 0 and s.D <= 1024
+    kernel = (f"k_fuse_tile<{s.feat_dtype}, {s.D // 256} waves>" if tile else "k_fuse_gather") + " (aura_fuse_features)"
     out = {
         "metric": "fused point-views/sec", "value": pv / (ms_per_step * 1e-3), "unit": "point-views/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -110,7 +112,7 @@ def main():
                    "visible_fraction": float(gpu["vis"].mean()), "unseen_points": float((gpu["count"] == 0).mean()),
                    "order": s.meta["order"], "seed": s.meta["seed"]},
         "calls_ms": call_ms,
-        "roofline": {"bound": "hbm", "kernel": "k_fuse_gather (aura_fuse_features)", "achieved": achieved,
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "algorithmic_bytes": fuse_bytes, "avg_launch_ms": call_ms["fuse_features"]},
     }

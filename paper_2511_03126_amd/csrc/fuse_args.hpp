@@ -16,7 +16,7 @@ struct FuseArgs {
   int mean_only;
 };
 
-bool fuse_tile_supported(int dtype, int D);
+bool fuse_tile_supported(int dtype, int D, int Hf, int Wf);
 hipError_t launch_fuse_tile(const FuseArgs& a, const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream);
 
 }  // namespace aura

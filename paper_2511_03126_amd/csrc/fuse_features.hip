@@ -246,7 +246,7 @@ hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const 
                                 const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream) {
   if (n_obj == 0 || max_pts == 0) return hipSuccess;
   FuseArgs a{vis, feat, xyz, fused, out_count, norm_eps, mean_only};
-  if (!force_gather && fuse_tile_supported(feat.dtype, feat.D)) return launch_fuse_tile(a, tab, n_obj, max_pts, stream);
+  if (!force_gather && fuse_tile_supported(feat.dtype, feat.D, feat.Hf, feat.Wf)) return launch_fuse_tile(a, tab, n_obj, max_pts, stream);
   switch (feat.dtype) {
     case 0: return dispatch_d<0>(a, tab, n_obj, max_pts, stream);
     case 1: return dispatch_d<1>(a, tab, n_obj, max_pts, stream);

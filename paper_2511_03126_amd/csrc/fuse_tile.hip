@@ -42,6 +42,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x2 __attribute__((ext_vector_type(2)));
 
 constexpr int kTilePts = 32;      // points per workgroup (M of the MFMA tile)
 constexpr int kViewBatch = 32;    // views handled per pass over the point tile
@@ -92,8 +93,9 @@ __device__ __forceinline__ void mma_step(const u32x4& ah, const u32x4& al, const
     u32x4 b;
 #pragma unroll
     for (int e2 = 0; e2 < 4; ++e2) {
+      // bytes 0..3 of the selector index the first cell's dword, 4..7 the second cell's
       const uint32_t lo = q[2 * e2][t >> 1], hi = q[2 * e2 + 1][t >> 1];
-      b[e2] = (t & 1) ? ((lo >> 16) | (hi & 0xffff0000u)) : ((lo & 0xffffu) | (hi << 16));
+      b[e2] = __builtin_amdgcn_perm(hi, lo, (t & 1) ? 0x07060302u : 0x05040100u);
     }
     acc[t] = mma<DT>(ah, b, acc[t]);
     acc[t] = mma<DT>(al, b, acc[t]);
@@ -116,6 +118,7 @@ void k_fuse_tile(FuseArgs a, ObjTable tab) {
   __shared__ __attribute__((aligned(16))) uint16_t s_wlo[kTilePts][kListPad];
   __shared__ float s_ss[S][kTilePts];
   __shared__ int s_cnt[kTilePts];
+  __shared__ float s_scale[kTilePts];
 
   const ObjRange ob = tab.o[blockIdx.y];
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
@@ -162,25 +165,26 @@ void k_fuse_tile(FuseArgs a, ObjTable tab) {
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
       const int vl = it * 2 * S + slot;
-      int xy = -1, x0 = 1 << 20, y0 = 1 << 20, x1 = -1, y1 = -1;
+      int xy = -1;
+      s16x2 lo2 = {0x7fff, 0x7fff}, hi2 = {-1, -1};   // (x, y) of the first / second cell, 16 bits each
       float ax = 0.0f, ay = 0.0f;
       const bool seen = vl < nvb && p_valid && fr[it] && (a.vis.frustum_only || passes_depth(a.vis, pr[it], dep[it]));
       if (seen) {
         const Tap tx = tap_axis(pr[it].u, a.feat.pitch_x, Wf), ty = tap_axis(pr[it].v, a.feat.pitch_y, Hf);
-        x0 = tx.i0; x1 = tx.i1; ax = tx.a;
-        y0 = ty.i0; y1 = ty.i1; ay = ty.a;
-        xy = (y0 << 16) | x0;
+        ax = tx.a;
+        ay = ty.a;
+        xy = (ty.i0 << 16) | tx.i0;
+        lo2 = s16x2{(short)tx.i0, (short)ty.i0};
+        hi2 = s16x2{(short)tx.i1, (short)ty.i1};
         ++my_cnt;
       }
       // bounding box over the 32 points of this view (the 32 lanes of a half wave share vl)
-      int bx0 = x0, by0 = y0, bx1 = x1, by1 = y1;
 #pragma unroll
       for (int o = 16; o > 0; o >>= 1) {
-        bx0 = min(bx0, __shfl_xor(bx0, o, kWave));
-        by0 = min(by0, __shfl_xor(by0, o, kWave));
-        bx1 = max(bx1, __shfl_xor(bx1, o, kWave));
-        by1 = max(by1, __shfl_xor(by1, o, kWave));
+        lo2 = __builtin_elementwise_min(lo2, __builtin_bit_cast(s16x2, __shfl_xor(__builtin_bit_cast(int, lo2), o, kWave)));
+        hi2 = __builtin_elementwise_max(hi2, __builtin_bit_cast(s16x2, __shfl_xor(__builtin_bit_cast(int, hi2), o, kWave)));
       }
+      const int bx0 = lo2[0], by0 = lo2[1], bx1 = hi2[0], by1 = hi2[1];
       if (vl < nvb) {
         s_xy[vl][p] = xy;
         s_ax[vl][p] = ax;
@@ -286,36 +290,38 @@ void k_fuse_tile(FuseArgs a, ObjTable tab) {
     }
   }
 
-  // ---- D: mean, L2 norm, store
+  // ---- D: mean, L2 norm, store.  One factor per point, inv_count / max(norm of the mean, eps),
+  // is computed once and applied to the raw sums.
   __syncthreads();
-  float inv[16];
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int row = 8 * (r >> 2) + 4 * g + (r & 3);
-    const int c = s_cnt[row];
-    inv[r] = c > 0 ? 1.0f / (float)c : 0.0f;
     float ss = 0.0f;
 #pragma unroll
-    for (int t = 0; t < 8; ++t) {
-      acc[t][r] *= inv[r];
-      ss = __builtin_fmaf(acc[t][r], acc[t][r], ss);
-    }
+    for (int t = 0; t < 8; ++t) ss = __builtin_fmaf(acc[t][r], acc[t][r], ss);
 #pragma unroll
     for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, kWave);
     if (m == 0) s_ss[span][row] = ss;
+  }
+  __syncthreads();
+  if (tid < kTilePts) {
+    const int c = s_cnt[tid];
+    const float inv = c > 0 ? 1.0f / (float)c : 0.0f;
+    float f = inv;
+    if (!a.mean_only) {
+      float tot = 0.0f;
+#pragma unroll
+      for (int w = 0; w < S; ++w) tot += s_ss[w][tid];
+      f = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
+    }
+    s_scale[tid] = f;
   }
   __syncthreads();
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int row = 8 * (r >> 2) + 4 * g + (r & 3);
     if (li0 + row >= ob.n_pts) continue;
-    float scale = 1.0f;
-    if (!a.mean_only) {
-      float tot = 0.0f;
-#pragma unroll
-      for (int w = 0; w < S; ++w) tot += s_ss[w][row];
-      scale = 1.0f / fmaxf(sqrtf(tot), a.norm_eps);
-    }
+    const float scale = s_scale[row];
     float* o = a.fused + (ob.pt_begin + li0 + row) * D + span * kSpan + 8 * m;
     const f32x4 v0 = {acc[0][r] * scale, acc[1][r] * scale, acc[2][r] * scale, acc[3][r] * scale};
     const f32x4 v1 = {acc[4][r] * scale, acc[5][r] * scale, acc[6][r] * scale, acc[7][r] * scale};
@@ -332,8 +338,9 @@ static hipError_t launch_tile(const FuseArgs& a, const ObjTable& tab, int n_obj,
   return hipGetLastError();
 }
 
-bool fuse_tile_supported(int dtype, int D) {
-  return (dtype == 1 || dtype == 2) && D % kSpan == 0 && D / kSpan >= 1 && D / kSpan <= 6 && D / kSpan != 5;
+bool fuse_tile_supported(int dtype, int D, int Hf, int Wf) {
+  // cell coordinates travel as 16-bit pairs inside the kernel
+  return (dtype == 1 || dtype == 2) && Hf <= 32767 && Wf <= 32767 && D % kSpan == 0 && D / kSpan >= 1 && D / kSpan <= 6 && D / kSpan != 5;
 }
 
 hipError_t launch_fuse_tile(const FuseArgs& a, const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream) {
