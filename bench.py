@@ -100,8 +100,9 @@ def main():
     fuse_bytes = fuse_algorithmic_bytes(s)
     achieved = fuse_bytes / (call_ms["fuse_features"] * 1e-3) / 1e9
     gpu = d.results()
-    tile = s.feat_dtype != "f32" and s.D % 256 == 0 and s.D <= 1024
-    kernel = (f"k_fuse_tile<{s.feat_dtype}, {s.D // 256} waves>" if tile else "k_fuse_gather") + " (aura_fuse_features)"
+    tile = d.ws_fuse is not None
+    kernel = "aura_fuse_features: " + (f"k_tile_prepare + k_tile_product<{s.feat_dtype}, {s.D // 256} waves>" if tile
+                                       else "k_fuse_gather")
     out = {
         "metric": "fused point-views/sec", "value": pv / (ms_per_step * 1e-3), "unit": "point-views/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

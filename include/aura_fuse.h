@@ -62,12 +62,23 @@ enum {
   AURA_FUSE_MEAN_ONLY = 2u,    /* aura_fuse_features returns the plain mean of Eq. 2 without the
                                   L2 normalisation                                             */
   AURA_FUSE_GATHER = 4u        /* aura_fuse_features uses the per-point gather kernel even where the
-                                  matrix-core kernel applies (16-bit maps, D a multiple of 256).
+                                  matrix-core kernels apply (16-bit maps, D a multiple of 256).
                                   Meant for point sets that are not spatially sorted            */
 };
 
 /* Which call a workspace size is asked for. */
-enum { AURA_CALL_MATERIAL_SCORES = 1, AURA_CALL_PROPERTY_INTEGRATE = 2 };
+enum { AURA_CALL_MATERIAL_SCORES = 1, AURA_CALL_PROPERTY_INTEGRATE = 2, AURA_CALL_FUSE_FEATURES = 3 };
+
+/* Problem sizes for aura_workspace_bytes; fields a call does not list are ignored. */
+typedef struct aura_sizes_t {
+  int64_t N;            /* points                                                              */
+  int32_t B;            /* objects                                                             */
+  int32_t n_views;      /* views over all objects                                              */
+  int32_t Hf, Wf, D;    /* feature grid and channel count                                      */
+  int32_t feat_dtype;   /* AURA_F32 | AURA_BF16 | AURA_F16                                     */
+  int32_t K;            /* candidate materials                                                 */
+  int32_t G;            /* voxels per axis of the integration grid, 0 = point-volume mode      */
+} aura_sizes_t;
 
 /* One set of calibrated views (Sec. 3.1: poses, Depth_v and F_v for v in V). */
 typedef struct aura_views_t {
@@ -107,14 +118,15 @@ const char* aura_strerror(aura_status_t status);
 int32_t aura_last_hip_error(void);
 
 /*
- * Bytes of device scratch the given call needs (write to *bytes).  The workspace must be
- * 256-byte aligned.  Only the arguments listed matter:
+ * Bytes of device scratch the given call needs (written to *bytes; may be 0).  The workspace
+ * must be 256-byte aligned.  Only the fields listed matter:
  *   AURA_CALL_MATERIAL_SCORES     D, K
  *   AURA_CALL_PROPERTY_INTEGRATE  N, B, G
- * Errors: AURA_ERR_NULL (bytes), AURA_ERR_SHAPE, AURA_ERR_UNSUPPORTED (unknown call).
+ *   AURA_CALL_FUSE_FEATURES       N, B, n_views, Hf, Wf, D, feat_dtype
+ * Errors: AURA_ERR_NULL (sizes, bytes), AURA_ERR_SHAPE, AURA_ERR_DTYPE, AURA_ERR_UNSUPPORTED
+ * (unknown call, or sizes beyond the limits of the call).
  */
-aura_status_t aura_workspace_bytes(int32_t call, int64_t N, int32_t B, int32_t D, int32_t K, int32_t G,
-                                   size_t* bytes);
+aura_status_t aura_workspace_bytes(int32_t call, const aura_sizes_t* sizes, size_t* bytes);
 
 /*
  * Sec. 3.1 "Visibility Checking", Eq. 1.  Projects every point into every view of its object
@@ -149,13 +161,21 @@ aura_status_t aura_project_visibility(const aura_views_t* views, const aura_para
  *
  *   fused  [device] [N][D] fp32, 16-byte aligned
  *   count  [device] [N] int32 or NULL
+ *   workspace [device] aura_workspace_bytes(AURA_CALL_FUSE_FEATURES, ...) bytes, 256-byte aligned,
+ *          or NULL.  With a workspace, 16-bit maps whose D is a multiple of 256 (up to 1536, except
+ *          1280; maps below 4 GiB; at most 256 views per object) run on the matrix cores: the
+ *          points are taken 32 at a time and should arrive spatially sorted (e.g. Morton order),
+ *          and the maps must be finite everywhere.  Without one, or for other shapes, or with
+ *          AURA_FUSE_GATHER, a per-point gather kernel is used.  Both give the same result up to
+ *          fp32 rounding.
  * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_DTYPE, AURA_ERR_ALIGN (feat or fused not
- * 16-byte aligned), AURA_ERR_HIP.
+ * 16-byte aligned), AURA_ERR_WORKSPACE (given but misaligned or too small), AURA_ERR_HIP.
  */
 aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t* params,
                                  const float* xyz, int64_t N,
                                  const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
-                                 float* fused, int32_t* count, void* stream);
+                                 float* fused, int32_t* count,
+                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Sec. 3.4.1.  scores[i][k] = <fused_i, temb_k> (the cosine similarity omega_k when both are

@@ -16,7 +16,7 @@ _LIB_PATH = Path(__file__).resolve().parent / "libaura_fuse.so"
 
 F32, BF16, F16 = 0, 1, 2
 VIS_FRUSTUM_ONLY, FUSE_MEAN_ONLY, FUSE_GATHER = 1, 2, 4
-CALL_MATERIAL_SCORES, CALL_PROPERTY_INTEGRATE = 1, 2
+CALL_MATERIAL_SCORES, CALL_PROPERTY_INTEGRATE, CALL_FUSE_FEATURES = 1, 2, 3
 
 _TORCH_DTYPE = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 
@@ -34,6 +34,11 @@ class _ViewsT(C.Structure):
     _fields_ = [("n_views", C.c_int32), ("H", C.c_int32), ("W", C.c_int32), ("Hf", C.c_int32), ("Wf", C.c_int32),
                 ("D", C.c_int32), ("feat_dtype", C.c_int32), ("cam", C.c_void_p), ("depth", C.c_void_p),
                 ("feat", C.c_void_p)]
+
+
+class _SizesT(C.Structure):
+    _fields_ = [("N", C.c_int64), ("B", C.c_int32), ("n_views", C.c_int32), ("Hf", C.c_int32), ("Wf", C.c_int32),
+                ("D", C.c_int32), ("feat_dtype", C.c_int32), ("K", C.c_int32), ("G", C.c_int32)]
 
 
 class _ParamsT(C.Structure):
@@ -56,14 +61,14 @@ def lib():
         L.aura_strerror.argtypes = [C.c_int32]
         L.aura_last_hip_error.restype = C.c_int32
         L.aura_workspace_bytes.restype = C.c_int32
-        L.aura_workspace_bytes.argtypes = [C.c_int32, C.c_int64, C.c_int32, C.c_int32, C.c_int32, C.c_int32,
-                                           C.POINTER(C.c_size_t)]
+        L.aura_workspace_bytes.argtypes = [C.c_int32, C.POINTER(_SizesT), C.POINTER(C.c_size_t)]
         vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
         L.aura_project_visibility.restype = C.c_int32
         L.aura_project_visibility.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32,
                                               vp, i32, vp, vp, vp]
         L.aura_fuse_features.restype = C.c_int32
-        L.aura_fuse_features.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32, vp, vp, vp]
+        L.aura_fuse_features.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32, vp, vp,
+                                         vp, C.c_size_t, vp]
         L.aura_material_scores.restype = C.c_int32
         L.aura_material_scores.argtypes = [vp, i64, i32, vp, i32, i32, vp, i32, C.POINTER(_ParamsT), vp, vp, vp,
                                            vp, C.c_size_t, vp]
@@ -140,10 +145,19 @@ def _check(status, what):
         raise AuraError(status, what)
 
 
-def workspace_bytes(call: int, N: int = 0, B: int = 1, D: int = 1, K: int = 1, G: int = 0) -> int:
+def workspace_bytes(call: int, N: int = 0, B: int = 1, D: int = 1, K: int = 1, G: int = 0, n_views: int = 1,
+                    Hf: int = 1, Wf: int = 1, feat_dtype: int = F32) -> int:
     out = C.c_size_t(0)
-    _check(lib().aura_workspace_bytes(call, N, B, D, K, G, C.byref(out)), "aura_workspace_bytes")
+    sz = _SizesT(N, B, n_views, Hf, Wf, D, feat_dtype, K, G)
+    _check(lib().aura_workspace_bytes(call, C.byref(sz), C.byref(out)), "aura_workspace_bytes")
     return int(out.value)
+
+
+def fuse_workspace_bytes(views: "Views", N: int, B: int = 1) -> int:
+    """Workspace size of fuse_features for these views (0 when the per-point gather kernel is used)."""
+    f = views.feat
+    return workspace_bytes(CALL_FUSE_FEATURES, N=N, B=B, D=f.shape[3], n_views=f.shape[0], Hf=f.shape[1],
+                           Wf=f.shape[2], feat_dtype=_TORCH_DTYPE[f.dtype])
 
 
 def _objects(pt_offsets, view_offsets):
@@ -164,14 +178,16 @@ def project_visibility(views: Views, params: Params, xyz, vis, count=None, uvz=N
            "aura_project_visibility")
 
 
-def fuse_features(views: Views, params: Params, xyz, fused, count=None, pt_offsets=None, view_offsets=None):
-    """fused [N][D] f32 and count [N] int32 are filled in place."""
+def fuse_features(views: Views, params: Params, xyz, fused, count=None, pt_offsets=None, view_offsets=None,
+                  workspace=None):
+    """fused [N][D] f32 and count [N] int32 are filled in place; workspace is a uint8 device tensor or None."""
     xyz = _dev(xyz, torch.float32, "xyz")
     _dev(fused, torch.float32, "fused")
     po, vo, B = _objects(pt_offsets, view_offsets)
     v, p = views.c(), params.c()
     _check(lib().aura_fuse_features(C.byref(v), C.byref(p), xyz.data_ptr(), xyz.shape[0], _hptr(po), _hptr(vo), B,
-                                    fused.data_ptr(), _ptr(count), _stream()), "aura_fuse_features")
+                                    fused.data_ptr(), _ptr(count), _ptr(workspace),
+                                    0 if workspace is None else workspace.numel(), _stream()), "aura_fuse_features")
 
 
 def material_scores(fused, temb, y, params: Params, scores, prop=None, label=None, workspace=None):

@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "../../include/aura_fuse.h"
+#include "fuse_args.hpp"
 #include "launch.hpp"
 
 namespace {
@@ -29,6 +30,7 @@ aura_status_t check_objects(int64_t N, int32_t n_views, const int64_t* pt_offset
   if (!pt_offsets && B != 1) return AURA_ERR_NULL;
   out->clear();
   *max_views = 0;
+  int64_t tiles = 0;
   for (int b = 0; b < B; ++b) {
     const int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
     const int64_t v0 = view_offsets ? view_offsets[b] : 0, v1 = view_offsets ? view_offsets[b + 1] : n_views;
@@ -41,6 +43,9 @@ aura_status_t check_objects(int64_t N, int32_t n_views, const int64_t* pt_offset
     r.n_pts = (int)(p1 - p0);
     r.view_begin = (int)v0;
     r.n_views = (int)(v1 - v0);
+    if (tiles > 0x7fffffff) return AURA_ERR_SHAPE;
+    r.tile_begin = (int)tiles;
+    tiles += (r.n_pts + aura::kTilePts - 1) / aura::kTilePts;
     out->push_back(r);
     *max_views = std::max(*max_views, r.n_views);
   }
@@ -115,20 +120,34 @@ const char* aura_strerror(aura_status_t status) {
 
 int32_t aura_last_hip_error(void) { return g_last_hip_error; }
 
-aura_status_t aura_workspace_bytes(int32_t call, int64_t N, int32_t B, int32_t D, int32_t K, int32_t G,
-                                   size_t* bytes) {
-  if (!bytes) return AURA_ERR_NULL;
+// Whether aura_fuse_features takes the matrix-core tile path for these sizes.
+static bool tile_path(int32_t dtype, int32_t D, int32_t Hf, int32_t Wf, int32_t n_views, int32_t max_views) {
+  const long long feat_bytes = (long long)n_views * Hf * Wf * D * 2;
+  return aura::fuse_tile_supported(dtype, D, Hf, Wf, feat_bytes, max_views);
+}
+
+aura_status_t aura_workspace_bytes(int32_t call, const aura_sizes_t* sz, size_t* bytes) {
+  if (!bytes || !sz) return AURA_ERR_NULL;
   *bytes = 0;
   if (call == AURA_CALL_MATERIAL_SCORES) {
-    if (D < 1 || K < 1) return AURA_ERR_SHAPE;
-    if (K > 128) return AURA_ERR_UNSUPPORTED;
-    *bytes = aura::scores_workspace_bytes(D, K);
+    if (sz->D < 1 || sz->K < 1) return AURA_ERR_SHAPE;
+    if (sz->K > 128) return AURA_ERR_UNSUPPORTED;
+    *bytes = aura::scores_workspace_bytes(sz->D, sz->K);
     return AURA_OK;
   }
   if (call == AURA_CALL_PROPERTY_INTEGRATE) {
-    if (N < 0 || B < 1 || G < 0) return AURA_ERR_SHAPE;
-    if (B > 4096 || G > 512 || (G > 0 && (int64_t)B * G * G * G >= (1ll << 31))) return AURA_ERR_UNSUPPORTED;
-    *bytes = aura::integrate_workspace_bytes(N, B, G);
+    if (sz->N < 0 || sz->B < 1 || sz->G < 0) return AURA_ERR_SHAPE;
+    if (sz->B > 4096 || sz->G > 512 || (sz->G > 0 && (int64_t)sz->B * sz->G * sz->G * sz->G >= (1ll << 31)))
+      return AURA_ERR_UNSUPPORTED;
+    *bytes = aura::integrate_workspace_bytes(sz->N, sz->B, sz->G);
+    return AURA_OK;
+  }
+  if (call == AURA_CALL_FUSE_FEATURES) {
+    if (sz->N < 0 || sz->B < 1 || sz->n_views < 1 || sz->Hf < 1 || sz->Wf < 1 || sz->D < 1) return AURA_ERR_SHAPE;
+    if (sz->feat_dtype != AURA_F32 && sz->feat_dtype != AURA_BF16 && sz->feat_dtype != AURA_F16) return AURA_ERR_DTYPE;
+    // the per-object view count is not known here; the call itself checks it again
+    if (tile_path(sz->feat_dtype, sz->D, sz->Hf, sz->Wf, sz->n_views, 1))
+      *bytes = aura::fuse_tile_workspace_bytes(sz->N, sz->B, sz->n_views);
     return AURA_OK;
   }
   return AURA_ERR_UNSUPPORTED;
@@ -159,7 +178,8 @@ aura_status_t aura_project_visibility(const aura_views_t* views, const aura_para
 aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t* params,
                                  const float* xyz, int64_t N,
                                  const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
-                                 float* fused, int32_t* count, void* stream) {
+                                 float* fused, int32_t* count,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
   aura_status_t s = check_views(views, params, true);
   if (s != AURA_OK) return s;
   if (N < 0) return AURA_ERR_SHAPE;
@@ -180,11 +200,19 @@ aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t*
   fa.pitch_x = (float)views->W / (float)views->Wf;
   fa.pitch_y = (float)views->H / (float)views->Hf;
   const int mean_only = (params->flags & AURA_FUSE_MEAN_ONLY) ? 1 : 0;
-  const int force_gather = (params->flags & AURA_FUSE_GATHER) ? 1 : 0;
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  // matrix-core tile path: 16-bit maps, D a multiple of 256, a workspace, and not switched off
+  aura::TileWs tws{};
+  const bool tile = workspace && !(params->flags & AURA_FUSE_GATHER) &&
+                    tile_path(views->feat_dtype, views->D, views->Hf, views->Wf, views->n_views, max_views);
+  if (tile) {
+    if (!aligned(workspace, 256) || workspace_bytes < aura::fuse_tile_workspace_bytes(N, B, views->n_views))
+      return AURA_ERR_WORKSPACE;
+    tws = aura::fuse_tile_workspace(workspace, N, B, views->n_views);
+  }
   return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts) {
-    return aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only, force_gather, tab, n,
-                                      max_pts,
-                                      static_cast<hipStream_t>(stream));
+    return aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only, tile ? &tws : nullptr,
+                                      tab, n, max_pts, st);
   });
 }
 

@@ -19,7 +19,7 @@ struct ObjRange {
   int n_pts;
   int view_begin;
   int n_views;
-  int pad_;
+  int tile_begin;   // index of the object's first 32-point tile within the call
 };
 
 struct ObjTable {

@@ -1,4 +1,5 @@
-// Kernel arguments shared by the two fusion kernels (gather and matrix-core tile).
+// Kernel arguments shared by the fusion kernels (per-point gather, and the matrix-core tile path
+// with its prepare and product kernels).
 #pragma once
 
 #include "aura_device.hpp"
@@ -16,7 +17,42 @@ struct FuseArgs {
   int mean_only;
 };
 
-bool fuse_tile_supported(int dtype, int D, int Hf, int Wf);
-hipError_t launch_fuse_tile(const FuseArgs& a, const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream);
+// ---- workspace of the tile path ------------------------------------------------------------
+// A tile is 32 consecutive points of one object.  The prepare kernel turns a tile into a list of
+// k-steps; a k-step is 16 feature cells and the 32 x 16 matrix of bilinear weights of the tile's
+// points for those cells, already in the register layout of the matrix-core A operand.
+
+constexpr int kTilePts = 32;        // points per tile (M of the matrix-core product)
+constexpr int kStepCells = 16;      // cells per k-step (K of the matrix-core product)
+constexpr int kMaxSeg = 8;          // view batches (of 32 views) a tile can describe
+
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+
+struct TileHdr {
+  int nseg;                 // number of segments; -1: the prepare kernel fused this tile itself
+  int pad_[3];
+  int seg_off[kMaxSeg];     // first k-step of each segment within the tile's run of k-steps
+  int seg_steps[kMaxSeg];   // k-steps of each segment
+  int cnt[kTilePts];        // views that see each point
+};
+
+struct __attribute__((aligned(64))) TileStep {
+  uint32_t cell[kStepCells];   // byte offset of each cell row from the first feature element
+  u32x4_t a_hi[64];            // lane l = 32 g + m: weights of point m for cells 8 g .. 8 g + 7 (16-bit)
+  u32x4_t a_lo[64];            // second term of the two-term split of the same weights
+};
+
+struct TileWs {
+  TileHdr* hdr;      // [n_tiles]
+  TileStep* steps;   // [n_tiles][quota]: every tile owns a fixed run of k-steps
+  int quota;
+};
+
+bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes, int max_views);
+size_t fuse_tile_workspace_bytes(long long N, int B, int n_views);
+// Splits a workspace of fuse_tile_workspace_bytes(N, B, n_views) bytes into its parts.
+TileWs fuse_tile_workspace(void* workspace, long long N, int B, int n_views);
+hipError_t launch_fuse_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
+                            hipStream_t stream);
 
 }  // namespace aura

@@ -242,11 +242,11 @@ static hipError_t dispatch_d(const FuseArgs& a, const ObjTable& tab, int n_obj, 
 }
 
 hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const float* xyz, float* fused,
-                                int* out_count, float norm_eps, int mean_only, int force_gather,
+                                int* out_count, float norm_eps, int mean_only, const TileWs* tile_ws,
                                 const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream) {
   if (n_obj == 0 || max_pts == 0) return hipSuccess;
   FuseArgs a{vis, feat, xyz, fused, out_count, norm_eps, mean_only};
-  if (!force_gather && fuse_tile_supported(feat.dtype, feat.D, feat.Hf, feat.Wf)) return launch_fuse_tile(a, tab, n_obj, max_pts, stream);
+  if (tile_ws) return launch_fuse_tile(a, *tile_ws, tab, n_obj, max_pts, stream);
   switch (feat.dtype) {
     case 0: return dispatch_d<0>(a, tab, n_obj, max_pts, stream);
     case 1: return dispatch_d<1>(a, tab, n_obj, max_pts, stream);

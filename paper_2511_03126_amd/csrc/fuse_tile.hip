@@ -4,32 +4,42 @@
 //     sum_v M_vis(x_i, v) F_v(pi(x_i, v)) = sum_c  w[i][c] * F[c],
 // where c runs over (view, cell) pairs and w[i][c] is the bilinear weight of cell c for point i
 // (zero unless the view sees the point and c is one of the four cells around the projection).
-// For 32 spatially neighbouring points the cells with a non-zero weight fall, per view, inside a
-// small window of the feature grid (a few cells), so the sum is a small dense product
+// For a tile of 32 spatially neighbouring points only about a hundred cells carry a non-zero
+// weight, so the sum is a small dense product
 //     [32 points x L cells] . [L cells x D channels]
-// with L around one hundred.  The gather formulation reads every cell row once per point and view
-// (4 D elements per pair) and spends its time widening and multiplying on the vector ALUs; the
-// dense form reads each cell of the window once per 32 points and runs on the matrix cores, which
-// take the stored 16-bit features as they are.
+// that runs on the matrix cores with the stored 16-bit features as they are.  The gather
+// formulation reads every cell row once per point and view (4 D elements per pair) and spends
+// its time widening and multiplying on the vector ALUs; here each cell of the list is read once
+// per tile.
 //
-// One workgroup fuses 32 consecutive points; wave s of the workgroup owns channels
-// [256 s, 256 s + 256).
+// Two kernels:
+//
+// k_tile_prepare (one workgroup of 256 threads per tile, little register state, many tiles in
+// flight per CU so that the projection -> depth-read -> list chain of one tile hides behind the
+// others):
 //   A  every (point, view) pair is projected and tested (Eq. 1, the shared fp32 decision
-//      functions); each view's window = bounding box of the cells touched by the points it sees.
-//   B  the windows are laid end to end into a cell list; the weights are scattered into a
-//      [32][L] matrix in LDS, split into two 16-bit terms (hi + lo) so that the product carries
-//      about 16 mantissa bits of each weight.
-//   C  per 16 cells: each lane reads 16 bytes (8 channels) of 8 cell rows straight from global
-//      memory, regroups them into the 8 B-operands (one per channel phase t = channel mod 8),
-//      and issues v_mfma_f32_32x32x16 with the hi and the lo weights.  Lists longer than the LDS
-//      matrix are processed in chunks; more than 32 views per object in batches.
-//   D  mean, L2 norm (half-wave reduction, then across the waves through LDS), streaming store.
-//      Accumulator t, register r of lane l is point 8 (r/4) + 4 (l/32) + r%4, channel
-//      256 s + 8 (l%32) + t: every lane stores 8 consecutive channels of a point.
+//      functions).  Per view, the bounding box of the touched cells is found with a half-wave
+//      reduction.
+//   B  views whose box fits 16 x 16 cells mark the touched cells in a 256-bit map (exact list,
+//      no duplicates, no untouched cells); larger boxes (points far apart) give each visible
+//      pair four private entries.  A scan over the views lays the per-view lists end to end.
+//   C  per chunk of the list: the weights are scattered into a [32][cells] matrix in LDS, split
+//      into two 16-bit terms (hi + lo, about 16 mantissa bits), and copied out as k-steps of 16
+//      cells in the operand layout of the matrix-core instruction.  Every tile owns a fixed number
+//      of k-steps of storage; a tile that needs more (points far apart) is fused on the spot by a
+//      plain gather, so which way a tile goes depends on the tile alone and results are
+//      reproducible bit for bit.
 //
-// Weights of cells that only pad a window (no point taps them) are zero, so feature maps must be
-// finite everywhere.  Points that are far apart (unsorted input) give large windows: the kernel
-// stays correct but loses its advantage; the gather kernel can be forced with AURA_FUSE_GATHER.
+// k_tile_product (one workgroup per tile, wave s owns channels [256 s, 256 s + 256)): per k-step
+// each lane reads 16 bytes (8 channels) of 8 cell rows straight from global memory (the rows of a
+// tile's neighbours keep them in L2), regroups them with byte permutes into the 8 B-operands
+// (one per channel phase t = channel mod 8) and issues v_mfma_f32_32x32x16 with the hi and the lo
+// weights.  No LDS and no barrier inside the loop; the next k-step is in flight while the current
+// one is multiplied.  Then mean, L2 norm (half-wave reduction, across the waves through LDS) and
+// streaming stores.  Accumulator t, register r of lane l is point 8 (r/4) + 4 (l/32) + r%4,
+// channel 256 s + 8 (l%32) + t: every lane stores 8 consecutive channels of a point.
+//
+// List entries that only pad the last k-step have zero weights, so feature maps must be finite.
 #include "aura_device.hpp"
 #include "fuse_args.hpp"
 #include "launch.hpp"
@@ -41,14 +51,20 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef short s16x2 __attribute__((ext_vector_type(2)));
 
-constexpr int kTilePts = 32;      // points per workgroup (M of the MFMA tile)
-constexpr int kViewBatch = 32;    // views handled per pass over the point tile
-constexpr int kListMax = 128;     // cells per chunk of the weight matrix in LDS
-constexpr int kListPad = kListMax + 8;   // row pitch: consecutive rows start 4 banks apart
-constexpr int kSpan = 256;        // channels per wave: 32 lanes x 8 channels
+constexpr int kViewBatch = 32;                 // views handled per pass over the point tile
+constexpr int kPrepThreads = 256;
+constexpr int kSlots = kPrepThreads / kTilePts;   // views processed side by side (one per half wave)
+constexpr int kNIT = kViewBatch / kSlots;      // (point, view) pairs per thread and batch
+constexpr int kChunkSteps = 12;                // k-steps of the weight matrix held in LDS
+constexpr int kChunk = kChunkSteps * kStepCells;
+constexpr int kPitch = kChunk + 8;             // row pitch in 16-bit elements (rows start 4 banks apart)
+constexpr int kSpan = 256;                     // channels per wave of the product kernel
+constexpr int kWinSide = 16;                   // side of the per-view cell map
+
+static_assert(kSlots * kTilePts == kPrepThreads && kNIT * kSlots == kViewBatch, "thread mapping");
+static_assert(sizeof(TileStep) == 64 + 2048, "k-step layout");
 
 template <int DT>
 __device__ __forceinline__ void split_weight(float w, uint16_t& hi, uint16_t& lo) {
@@ -65,197 +81,318 @@ __device__ __forceinline__ void split_weight(float w, uint16_t& hi, uint16_t& lo
   }
 }
 
-template <int DT>
-__device__ __forceinline__ f32x16 mma(u32x4 a, u32x4 b, f32x16 c) {
-  if constexpr (DT == 1)
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-  else
-    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+// ---- half-wave reductions on the data-parallel-primitive lanes: after the call, lane 31 holds
+// the result over lanes 0..31 and lane 63 the result over lanes 32..63.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ s16x2 dpp_pull(s16x2 identity, s16x2 v) {
+  return __builtin_bit_cast(s16x2, __builtin_amdgcn_update_dpp(__builtin_bit_cast(int, identity), __builtin_bit_cast(int, v),
+                                                                CTRL, ROW_MASK, 0xf, false));
 }
 
-// Reads the 8 cell rows of k-step s for this lane: 16 bytes (8 channels) of each.
-__device__ __forceinline__ void load_cells(const char* __restrict__ fbase, const int* s_cell, int s, int g, int D,
-                                           u32x4 (&q)[8]) {
-  const i32x4 ca = *reinterpret_cast<const i32x4*>(&s_cell[16 * s + 8 * g]);
-  const i32x4 cb = *reinterpret_cast<const i32x4*>(&s_cell[16 * s + 8 * g + 4]);
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int cell = e < 4 ? ca[e] : cb[e - 4];
-    q[e] = *reinterpret_cast<const u32x4*>(fbase + (long long)cell * D * 2);
-  }
+template <bool IS_MIN>
+__device__ __forceinline__ s16x2 half_wave_reduce(s16x2 v) {
+  const s16x2 id = IS_MIN ? s16x2{0x7fff, 0x7fff} : s16x2{-0x8000, -0x8000};
+#define AURA_RED_STEP(ctrl, mask)                                                                  \
+  v = IS_MIN ? __builtin_elementwise_min(v, dpp_pull<ctrl, mask>(id, v)) : __builtin_elementwise_max(v, dpp_pull<ctrl, mask>(id, v))
+  AURA_RED_STEP(0x111, 0xf);   // row_shr:1
+  AURA_RED_STEP(0x112, 0xf);   // row_shr:2
+  AURA_RED_STEP(0x114, 0xf);   // row_shr:4
+  AURA_RED_STEP(0x118, 0xf);   // row_shr:8  -> lane 15 of every row of 16 holds the row's result
+  AURA_RED_STEP(0x142, 0xa);   // row_bcast:15 into rows 1 and 3
+#undef AURA_RED_STEP
+  return v;
 }
 
-// 16 matrix-core instructions of one k-step: operand t holds channel 8 m + t of the 8 cells.
+// One (point, view) pair after Eq. 1 and the cell selection.
+struct PairRec {
+  int xy;        // y0 << 16 | x0 of the first cell, -1: the view does not see the point
+  float ax, ay;  // weights of the second cell per axis
+};
+
+// The slow way out when a tile needs more k-steps than it owns: the workgroup fuses its 32 points by a
+// per-point gather (wave per point, lanes over channels, 512 channels per sweep).
 template <int DT>
-__device__ __forceinline__ void mma_step(const u32x4& ah, const u32x4& al, const u32x4 (&q)[8], f32x16 (&acc)[8]) {
+__device__ __forceinline__ void gather_tile(const FuseArgs& a, const ObjRange& ob, int li0, int tid) {
+  const int wave = tid / kWave, lane = tid % kWave;
+  const int D = a.feat.D, Hf = a.feat.Hf, Wf = a.feat.Wf;
+  const long long view_bytes = (long long)Hf * Wf * D * 2;
+  for (int k = 0; k < kTilePts / (kPrepThreads / kWave); ++k) {
+    const int li = li0 + wave * (kTilePts / (kPrepThreads / kWave)) + k;
+    if (li >= ob.n_pts) break;
+    const long long i = ob.pt_begin + li;
+    const float x = a.xyz[3 * i], y = a.xyz[3 * i + 1], z = a.xyz[3 * i + 2];
+    float* __restrict__ out_row = a.fused + i * D;
+    float ss = 0.0f;
+    int cnt = 0;
+    for (int cb = 0; cb < D; cb += 8 * kWave) {
+      const int ch = cb + 8 * lane;
+      float acc[8];
 #pragma unroll
-  for (int t = 0; t < 8; ++t) {
-    u32x4 b;
+      for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
+      cnt = 0;
+      for (int vb = 0; vb < ob.n_views; vb += kWave) {
+        bool seen = false;
+        int x0 = 0, y0 = 0;
+        float ax = 0.0f, ay = 0.0f;
+        if (vb + lane < ob.n_views) {
+          const int v = ob.view_begin + vb + lane;
+          const Proj p = project(a.vis.cam + (long long)v * 16, x, y, z);
+          const float* dv = a.vis.depth ? a.vis.depth + (long long)v * a.vis.H * a.vis.W : nullptr;
+          seen = visible(a.vis, dv, p);
+          if (seen) {
+            const Tap tx = tap_axis(p.u, a.feat.pitch_x, Wf), ty = tap_axis(p.v, a.feat.pitch_y, Hf);
+            x0 = tx.i0; ax = tx.a;
+            y0 = ty.i0; ay = ty.a;
+          }
+        }
+        unsigned long long m = __ballot(seen);
+        cnt += __popcll(m);
+        while (m) {
+          const int src = __builtin_ctzll(m);
+          m &= m - 1;
+          const int sx0 = __builtin_amdgcn_readlane(x0, src), sy0 = __builtin_amdgcn_readlane(y0, src);
+          const float sax = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ax), src));
+          const float say = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ay), src));
+          const int sx1 = sx0 + 1 < Wf ? sx0 + 1 : Wf - 1, sy1 = sy0 + 1 < Hf ? sy0 + 1 : Hf - 1;
+          const float wgt[4] = {(1.0f - sax) * (1.0f - say), sax * (1.0f - say), (1.0f - sax) * say, sax * say};
+          const int cell[4] = {sy0 * Wf + sx0, sy0 * Wf + sx1, sy1 * Wf + sx0, sy1 * Wf + sx1};
+          const char* vbase = static_cast<const char*>(a.feat.feat) + (long long)(ob.view_begin + vb + src) * view_bytes;
+          if (ch < D) {
 #pragma unroll
-    for (int e2 = 0; e2 < 4; ++e2) {
-      // bytes 0..3 of the selector index the first cell's dword, 4..7 the second cell's
-      const uint32_t lo = q[2 * e2][t >> 1], hi = q[2 * e2 + 1][t >> 1];
-      b[e2] = __builtin_amdgcn_perm(hi, lo, (t & 1) ? 0x07060302u : 0x05040100u);
+            for (int c = 0; c < 4; ++c) {
+              const u32x4 raw = *reinterpret_cast<const u32x4*>(vbase + ((long long)cell[c] * D + ch) * 2);
+#pragma unroll
+              for (int j = 0; j < 4; ++j) {
+                float lo, hi;
+                if constexpr (DT == 1) {
+                  lo = __uint_as_float(raw[j] << 16);
+                  hi = __uint_as_float(raw[j] & 0xffff0000u);
+                } else {
+                  lo = (float)__builtin_bit_cast(_Float16, (uint16_t)(raw[j] & 0xffffu));
+                  hi = (float)__builtin_bit_cast(_Float16, (uint16_t)(raw[j] >> 16));
+                }
+                acc[2 * j] = __builtin_fmaf(wgt[c], lo, acc[2 * j]);
+                acc[2 * j + 1] = __builtin_fmaf(wgt[c], hi, acc[2 * j + 1]);
+              }
+            }
+          }
+        }
+      }
+      const float inv = cnt > 0 ? 1.0f / (float)cnt : 0.0f;
+      if (ch < D) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          acc[e] *= inv;
+          ss = __builtin_fmaf(acc[e], acc[e], ss);
+          out_row[ch + e] = acc[e];
+        }
+      }
     }
-    acc[t] = mma<DT>(ah, b, acc[t]);
-    acc[t] = mma<DT>(al, b, acc[t]);
+    if (!a.mean_only) {
+      const float scale = 1.0f / fmaxf(sqrtf(wave_sum(ss)), a.norm_eps);
+      // every lane rescales exactly the channels it stored above
+      for (int cb = 0; cb < D; cb += 8 * kWave) {
+        const int ch = cb + 8 * lane;
+        if (ch < D) {
+#pragma unroll
+          for (int e = 0; e < 8; ++e) out_row[ch + e] *= scale;
+        }
+      }
+    }
+    if (a.out_count && lane == 0) a.out_count[i] = cnt;
   }
 }
 
-// DT: 1 bf16, 2 fp16 feature maps.  S waves per workgroup, D == 256 * S.
-template <int DT, int S>
-__global__ __launch_bounds__(kWave* S) __attribute__((amdgpu_waves_per_eu(2, 2)))
-void k_fuse_tile(FuseArgs a, ObjTable tab) {
-  constexpr int T = kWave * S;
-  constexpr int NIT = (kViewBatch + 2 * S - 1) / (2 * S);   // (point, view) pairs per thread and batch
-  __shared__ int s_xy[kViewBatch][kTilePts];        // y0 << 16 | x0, or -1: not visible
-  __shared__ float s_ax[kViewBatch][kTilePts];
-  __shared__ float s_ay[kViewBatch][kTilePts];
-  __shared__ int s_win[kViewBatch][4];              // xmin, ymin, width, height of the view's window
-  __shared__ int s_base[kViewBatch + 1];            // first list index of each view's window
-  __shared__ __attribute__((aligned(16))) int s_cell[kListMax];   // cell index (view, y, x flattened) per list entry
-  __shared__ __attribute__((aligned(16))) uint16_t s_whi[kTilePts][kListPad];
-  __shared__ __attribute__((aligned(16))) uint16_t s_wlo[kTilePts][kListPad];
-  __shared__ float s_ss[S][kTilePts];
+// DT: 1 bf16, 2 fp16 feature maps (decides the 16-bit format of the weights).
+template <int DT>
+__global__ __launch_bounds__(kPrepThreads) __attribute__((amdgpu_waves_per_eu(4)))
+void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
+  __shared__ int s_win[kViewBatch][2];                 // first cell (x, y) of the view's map
+  __shared__ int s_mode[kViewBatch];                   // 0 nothing seen, 1 cell map, 2 private entries
+  __shared__ uint32_t s_vmask[kViewBatch];             // which of the 32 points the view sees
+  __shared__ __attribute__((aligned(16))) uint32_t s_bits[kViewBatch][8];   // 16 x 16 map of touched cells
+  __shared__ __attribute__((aligned(16))) int s_wbase[kViewBatch][8];       // set bits before each word
+  __shared__ int s_base[kViewBatch + 1];               // first list index of each view
+  __shared__ __attribute__((aligned(16))) uint32_t s_cell[kChunk];
+  __shared__ __attribute__((aligned(16))) uint16_t s_whi[kTilePts][kPitch];
+  __shared__ __attribute__((aligned(16))) uint16_t s_wlo[kTilePts][kPitch];
   __shared__ int s_cnt[kTilePts];
-  __shared__ float s_scale[kTilePts];
+  __shared__ int s_seg[2 * kMaxSeg];
 
   const ObjRange ob = tab.o[blockIdx.y];
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
   if ((int)blockIdx.x >= nblk) return;
   const int blk = xcd_contiguous(blockIdx.x, nblk);
-  const int tid = threadIdx.x, lane = tid % kWave, span = tid / kWave;
-  const int D = a.feat.D, Hf = a.feat.Hf, Wf = a.feat.Wf;
-  const int p = tid % kTilePts;          // point of this thread in phases A and B
-  const int slot = tid / kTilePts;       // view slot of this thread in phases A and B
+  TileHdr* __restrict__ hdr = ws.hdr + ob.tile_begin + blk;
+  const long long slot0 = (long long)(ob.tile_begin + blk) * ws.quota;   // first k-step the tile owns
+  const int tid = threadIdx.x, lane = tid % kWave;
+  const int Hf = a.feat.Hf, Wf = a.feat.Wf;
+  const uint32_t row_bytes = (uint32_t)a.feat.D * 2u;
+  const int p = tid % kTilePts;          // point of this thread
+  const int slot = tid / kTilePts;       // view slot of this thread
   const int li0 = blk * kTilePts;
   const bool p_valid = li0 + p < ob.n_pts;
   const long long ip = ob.pt_begin + li0 + (p_valid ? p : 0);
   const float px = a.xyz[3 * ip], py = a.xyz[3 * ip + 1], pz = a.xyz[3 * ip + 2];
-  const int m = lane & 31, g = lane >> 5;
-  const char* fbase = static_cast<const char*>(a.feat.feat) + ((long long)span * kSpan + 8 * m) * 2;
-
-  f32x16 acc[8];
-#pragma unroll
-  for (int t = 0; t < 8; ++t)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
 
   if (tid < kTilePts) s_cnt[tid] = 0;
+  int nseg = 0, used = 0;   // segments and k-steps written so far
+  bool exhausted = false;
 
-  for (int vb0 = 0; vb0 < ob.n_views; vb0 += kViewBatch) {
+  for (int vb0 = 0; vb0 < ob.n_views; vb0 += kViewBatch, ++nseg) {
     const int nvb = min(kViewBatch, ob.n_views - vb0);
-    __syncthreads();   // previous batch fully consumed (and s_cnt initialised)
+    __syncthreads();   // the previous batch is done with the tables (and s_cnt is initialised)
+    s_bits[tid / 8][tid % 8] = 0u;
 
-    // ---- A: project and test.  All projections first and the depth reads unconditional (at a
-    // clamped texel), so that the reads of all pairs of a thread are in flight together.
-    Proj pr[NIT];
-    float dep[NIT];
-    bool fr[NIT];
-#pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-      const int vl = min(it * 2 * S + slot, nvb - 1);
-      const int v = ob.view_begin + vb0 + vl;
-      pr[it] = project(a.vis.cam + (long long)v * 16, px, py, pz);
-      fr[it] = in_frustum(a.vis, pr[it]);
-      dep[it] = 1.0f;
-      if (a.vis.depth) dep[it] = a.vis.depth[(long long)v * a.vis.H * a.vis.W + (fr[it] ? depth_texel(a.vis, pr[it]) : 0)];
-    }
+    // ---- A: project and test; bounding box of the touched cells per view
+    PairRec pr[kNIT];
     int my_cnt = 0;
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-      const int vl = it * 2 * S + slot;
-      int xy = -1;
-      s16x2 lo2 = {0x7fff, 0x7fff}, hi2 = {-1, -1};   // (x, y) of the first / second cell, 16 bits each
-      float ax = 0.0f, ay = 0.0f;
-      const bool seen = vl < nvb && p_valid && fr[it] && (a.vis.frustum_only || passes_depth(a.vis, pr[it], dep[it]));
+    for (int it = 0; it < kNIT; ++it) {
+      pr[it].xy = -1;
+      pr[it].ax = pr[it].ay = 0.0f;
+      if (it * kSlots >= nvb) continue;   // uniform
+      const int vl = it * kSlots + slot;
+      const int v = ob.view_begin + vb0 + min(vl, nvb - 1);
+      const Proj pj = project(a.vis.cam + (long long)v * 16, px, py, pz);
+      const bool fr = in_frustum(a.vis, pj);
+      float dep = 1.0f;
+      if (a.vis.depth) dep = a.vis.depth[(long long)v * a.vis.H * a.vis.W + (fr ? depth_texel(a.vis, pj) : 0)];
+      const bool seen = vl < nvb && p_valid && fr && (a.vis.frustum_only || passes_depth(a.vis, pj, dep));
+      s16x2 lo2 = {0x7fff, 0x7fff}, hi2 = {-1, -1};   // (x, y) of the first / second cell
       if (seen) {
-        const Tap tx = tap_axis(pr[it].u, a.feat.pitch_x, Wf), ty = tap_axis(pr[it].v, a.feat.pitch_y, Hf);
-        ax = tx.a;
-        ay = ty.a;
-        xy = (ty.i0 << 16) | tx.i0;
+        const Tap tx = tap_axis(pj.u, a.feat.pitch_x, Wf), ty = tap_axis(pj.v, a.feat.pitch_y, Hf);
+        pr[it].ax = tx.a;
+        pr[it].ay = ty.a;
+        pr[it].xy = (ty.i0 << 16) | tx.i0;
         lo2 = s16x2{(short)tx.i0, (short)ty.i0};
         hi2 = s16x2{(short)tx.i1, (short)ty.i1};
         ++my_cnt;
       }
-      // bounding box over the 32 points of this view (the 32 lanes of a half wave share vl)
-#pragma unroll
-      for (int o = 16; o > 0; o >>= 1) {
-        lo2 = __builtin_elementwise_min(lo2, __builtin_bit_cast(s16x2, __shfl_xor(__builtin_bit_cast(int, lo2), o, kWave)));
-        hi2 = __builtin_elementwise_max(hi2, __builtin_bit_cast(s16x2, __shfl_xor(__builtin_bit_cast(int, hi2), o, kWave)));
-      }
-      const int bx0 = lo2[0], by0 = lo2[1], bx1 = hi2[0], by1 = hi2[1];
-      if (vl < nvb) {
-        s_xy[vl][p] = xy;
-        s_ax[vl][p] = ax;
-        s_ay[vl][p] = ay;
-        if (p == 0) {
-          const bool any = bx1 >= 0;
-          s_win[vl][0] = any ? bx0 : 0;
-          s_win[vl][1] = any ? by0 : 0;
-          s_win[vl][2] = any ? bx1 - bx0 + 1 : 0;
-          s_win[vl][3] = any ? by1 - by0 + 1 : 0;
-        }
+      const unsigned long long seen_mask = __ballot(seen);
+      lo2 = half_wave_reduce<true>(lo2);
+      hi2 = half_wave_reduce<false>(hi2);
+      if (p == kTilePts - 1 && vl < nvb) {
+        const bool any = hi2[0] >= 0;
+        const int ww = hi2[0] - lo2[0] + 1, wh = hi2[1] - lo2[1] + 1;
+        s_win[vl][0] = lo2[0];
+        s_win[vl][1] = lo2[1];
+        s_mode[vl] = !any ? 0 : (ww <= kWinSide && wh <= kWinSide ? 1 : 2);
+        s_vmask[vl] = (uint32_t)(seen_mask >> (lane & 32));
       }
     }
     if (my_cnt) atomicAdd(&s_cnt[p], my_cnt);
     __syncthreads();
-    if (tid < kWave) {   // exclusive scan of the window sizes by the first wave
-      const int sz = lane < nvb ? s_win[lane][2] * s_win[lane][3] : 0;
-      int inc = sz;
+
+    // ---- B: mark the touched cells of every view that uses a map
+#pragma unroll
+    for (int it = 0; it < kNIT; ++it) {
+      if (pr[it].xy < 0) continue;
+      const int vl = it * kSlots + slot;
+      if (s_mode[vl] != 1) continue;
+      const int x0 = pr[it].xy & 0xffff, y0 = pr[it].xy >> 16;
+      const int bit = (y0 - s_win[vl][1]) * kWinSide + (x0 - s_win[vl][0]);
+      const bool has_x1 = x0 + 1 < Wf, has_y1 = y0 + 1 < Hf;   // at the border the second cell has weight 0
+      atomicOr(&s_bits[vl][bit >> 5], 1u << (bit & 31));
+      if (has_x1) atomicOr(&s_bits[vl][(bit + 1) >> 5], 1u << ((bit + 1) & 31));
+      if (has_y1) atomicOr(&s_bits[vl][(bit + kWinSide) >> 5], 1u << ((bit + kWinSide) & 31));
+      if (has_x1 && has_y1) atomicOr(&s_bits[vl][(bit + kWinSide + 1) >> 5], 1u << ((bit + kWinSide + 1) & 31));
+    }
+    __syncthreads();
+    if (tid < kWave) {   // list length of every view, exclusive scan over the views
+      int n = 0;
+      if (lane < nvb) {
+        if (s_mode[lane] == 1) {
+#pragma unroll
+          for (int w = 0; w < 8; ++w) {
+            s_wbase[lane][w] = n;
+            n += __popc(s_bits[lane][w]);
+          }
+        } else if (s_mode[lane] == 2) {
+          n = 4 * __popc(s_vmask[lane]);
+        }
+      }
+      int inc = n;
 #pragma unroll
       for (int o = 1; o < kViewBatch; o <<= 1) {
         const int up = __shfl_up(inc, o, kWave);
         if (lane >= o) inc += up;
       }
-      if (lane < nvb) s_base[lane] = inc - sz;
-      if (lane == nvb - 1) s_base[nvb] = inc;
+      if (lane < kViewBatch) s_base[lane] = inc - n;
+      if (lane == kViewBatch - 1) s_base[kViewBatch] = inc;
     }
     __syncthreads();
-    const int L = s_base[nvb];
+    const int L = s_base[kViewBatch];
+    const int nsteps = (L + kStepCells - 1) / kStepCells;
+    if (used + nsteps > ws.quota) {   // uniform
+      exhausted = true;
+      break;
+    }
+    const int off = used;
+    used += nsteps;
+    if (tid == 0) {
+      s_seg[nseg] = off;
+      s_seg[kMaxSeg + nseg] = nsteps;
+    }
 
-    // ---- B + C: chunks of the cell list
-    for (int c0 = 0; c0 < L; c0 += kListMax) {
-      const int Lc = min(kListMax, L - c0);
-      const int ksteps = (Lc + 15) / 16;
-      if (c0 > 0) __syncthreads();   // the previous chunk's operands have been read
-      // zero the weight matrix (16 bytes per store)
-      for (int q = tid; q < kTilePts * ksteps * 2; q += T) {
+    // ---- C: chunks of the list -> weight matrix in LDS -> k-steps in global memory
+    for (int c0 = 0; c0 < L; c0 += kChunk) {
+      const int Lc = min(kChunk, L - c0);
+      const int ksteps = (Lc + kStepCells - 1) / kStepCells;
+      if (c0 > 0) __syncthreads();   // the previous chunk has been copied out
+      for (int q = tid; q < kTilePts * ksteps * 2; q += kPrepThreads) {   // zero the matrix, 16 bytes per store
         const int row = q / (ksteps * 2), col = (q % (ksteps * 2)) * 8;
         const u32x4 z = {0u, 0u, 0u, 0u};
         *reinterpret_cast<u32x4*>(&s_whi[row][col]) = z;
         *reinterpret_cast<u32x4*>(&s_wlo[row][col]) = z;
       }
-      // cell index of every list entry of the chunk: each view's window is enumerated row by row;
-      // the entries that pad the last k-step point at a cell that exists (their weights are zero)
-      {
-        const int vl = tid % kViewBatch;
-        if (vl < nvb) {
-          const int wx = s_win[vl][0], wy = s_win[vl][1], ww = s_win[vl][2], n = ww * s_win[vl][3];
-          const int base = s_base[vl] - c0, cell0 = (ob.view_begin + vb0 + vl) * Hf;
-          for (int local = tid / kViewBatch; local < n; local += T / kViewBatch) {
-            const int q = base + local;
-            if (q >= 0 && q < Lc) s_cell[q] = (cell0 + wy + local / ww) * Wf + wx + local % ww;
+      // entries that pad the last k-step point at a cell that exists (their weights are zero)
+      if (tid >= Lc && tid < ksteps * kStepCells) s_cell[tid] = (uint32_t)((ob.view_begin + vb0) * Hf * Wf) * row_bytes;
+      {   // cells of the views with a map: thread = (view, word of the map)
+        const int vl = tid / 8, w = tid % 8;
+        if (vl < nvb && s_mode[vl] == 1) {
+          uint32_t bits = s_bits[vl][w];
+          int q = s_base[vl] + s_wbase[vl][w] - c0;
+          const int cell0 = (ob.view_begin + vb0 + vl) * Hf + s_win[vl][1], wx = s_win[vl][0];
+          while (bits) {
+            const int b = __builtin_ctz(bits) + 32 * w;
+            bits &= bits - 1;
+            if (q >= 0 && q < Lc) s_cell[q] = (uint32_t)((cell0 + b / kWinSide) * Wf + wx + b % kWinSide) * row_bytes;
+            ++q;
           }
         }
-        if (tid >= Lc && tid < ksteps * 16) s_cell[tid] = (ob.view_begin + vb0) * Hf * Wf;
       }
       __syncthreads();
-      // scatter the bilinear weights of every visible (point, view) pair
+      // weights (and the cells of private entries) of every visible pair
 #pragma unroll
-      for (int it = 0; it < NIT; ++it) {
-        const int vl = it * 2 * S + slot;
-        if (vl >= nvb) continue;
-        const int xy = s_xy[vl][p];
-        if (xy < 0) continue;
-        const int x0 = xy & 0xffff, y0 = xy >> 16;
-        const float ax = s_ax[vl][p], ay = s_ay[vl][p];
-        const int wx = s_win[vl][0], wy = s_win[vl][1], ww = s_win[vl][2];
-        const int i00 = s_base[vl] + (y0 - wy) * ww + (x0 - wx) - c0;
-        const bool has_x1 = x0 + 1 < Wf, has_y1 = y0 + 1 < Hf;   // at the border the second cell has weight 0
+      for (int it = 0; it < kNIT; ++it) {
+        if (pr[it].xy < 0) continue;
+        const int vl = it * kSlots + slot;
+        const int x0 = pr[it].xy & 0xffff, y0 = pr[it].xy >> 16;
+        const float ax = pr[it].ax, ay = pr[it].ay;
+        const bool has_x1 = x0 + 1 < Wf, has_y1 = y0 + 1 < Hf;
         const float wgt[4] = {(1.0f - ax) * (1.0f - ay), ax * (1.0f - ay), (1.0f - ax) * ay, ax * ay};
-        const int idx[4] = {i00, i00 + 1, i00 + ww, i00 + ww + 1};
         const bool on[4] = {true, has_x1, has_y1, has_x1 && has_y1};
+        int idx[4];
+        if (s_mode[vl] == 1) {
+          const int bit = (y0 - s_win[vl][1]) * kWinSide + (x0 - s_win[vl][0]);
+          const int bs[4] = {bit, bit + 1, bit + kWinSide, bit + kWinSide + 1};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            const int b = on[k] ? bs[k] : bit;
+            idx[k] = s_base[vl] + s_wbase[vl][b >> 5] + __popc(s_bits[vl][b >> 5] & ((1u << (b & 31)) - 1u)) - c0;
+          }
+        } else {
+          const int first = s_base[vl] + 4 * __popc(s_vmask[vl] & ((1u << p) - 1u)) - c0;
+          const int cell0 = (ob.view_begin + vb0 + vl) * Hf;
+          const int x1 = has_x1 ? x0 + 1 : x0, y1 = has_y1 ? y0 + 1 : y0;
+          const int cx[4] = {x0, x1, x0, x1}, cy[4] = {y0, y0, y1, y1};
+#pragma unroll
+          for (int k = 0; k < 4; ++k) {
+            idx[k] = first + k;
+            if (idx[k] >= 0 && idx[k] < Lc) s_cell[idx[k]] = (uint32_t)((cell0 + cy[k]) * Wf + cx[k]) * row_bytes;
+          }
+        }
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           if (on[k] && idx[k] >= 0 && idx[k] < Lc) {
@@ -267,32 +404,158 @@ void k_fuse_tile(FuseArgs a, ObjTable tab) {
         }
       }
       __syncthreads();
-      // ---- C: matrix-core product for this wave's 256 channels; the cell rows of the next k-step
-      // are requested before the products of the current one are issued
-      {
-        u32x4 q0[8], q1[8];
-        load_cells(fbase, s_cell, 0, g, D, q0);
-        for (int s = 0; s < ksteps; s += 2) {
-          if (s + 1 < ksteps) load_cells(fbase, s_cell, s + 1, g, D, q1);
-          {
-            const u32x4 ah = *reinterpret_cast<const u32x4*>(&s_whi[m][16 * s + 8 * g]);
-            const u32x4 al = *reinterpret_cast<const u32x4*>(&s_wlo[m][16 * s + 8 * g]);
-            mma_step<DT>(ah, al, q0, acc);
-          }
-          if (s + 1 < ksteps) {
-            if (s + 2 < ksteps) load_cells(fbase, s_cell, s + 2, g, D, q0);
-            const u32x4 ah = *reinterpret_cast<const u32x4*>(&s_whi[m][16 * (s + 1) + 8 * g]);
-            const u32x4 al = *reinterpret_cast<const u32x4*>(&s_wlo[m][16 * (s + 1) + 8 * g]);
-            mma_step<DT>(ah, al, q1, acc);
-          }
-        }
+      // copy out: per k-step 16 cell offsets and the two operand matrices (64 lanes x 16 bytes each)
+      TileStep* __restrict__ out = ws.steps + slot0 + off + c0 / kStepCells;
+      for (int q = tid; q < ksteps * 128; q += kPrepThreads) {
+        const int s = q >> 7, part = (q >> 6) & 1, l = q & 63, g = l >> 5, m = l & 31;
+        const uint16_t* src = part ? &s_wlo[m][kStepCells * s + 8 * g] : &s_whi[m][kStepCells * s + 8 * g];
+        const u32x4 val = *reinterpret_cast<const u32x4*>(src);
+        u32x4* dst = part ? &out[s].a_lo[l] : &out[s].a_hi[l];
+        *reinterpret_cast<u32x4*>(dst) = val;
+      }
+      if (tid < ksteps * kStepCells) out[tid / kStepCells].cell[tid % kStepCells] = s_cell[tid];
+    }
+  }
+
+  __syncthreads();
+  if (exhausted) {
+    if (tid == 0) hdr->nseg = -1;
+    gather_tile<DT>(a, ob, li0, tid);
+    return;
+  }
+  if (tid == 0) hdr->nseg = nseg;
+  if (tid < kMaxSeg) {
+    hdr->seg_off[tid] = tid < nseg ? s_seg[tid] : 0;
+    hdr->seg_steps[tid] = tid < nseg ? s_seg[kMaxSeg + tid] : 0;
+  }
+  if (tid < kTilePts) {
+    hdr->cnt[tid] = s_cnt[tid];
+    if (a.out_count && li0 + tid < ob.n_pts) a.out_count[ob.pt_begin + li0 + tid] = s_cnt[tid];
+  }
+}
+
+// ------------------------------------------------------------------------------------ product
+
+template <int DT>
+__device__ __forceinline__ f32x16 mma(u32x4 a, u32x4 b, f32x16 c) {
+  if constexpr (DT == 1)
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+}
+
+// Operands of one k-step in registers: 8 cell rows x 16 bytes and the two weight operands.
+struct StepRegs {
+  u32x4 q[8];
+  u32x4 ah, al;
+};
+
+// The 16 cell offsets of a k-step are the same for every lane: they are read through the scalar
+// unit, one k-step ahead of the rows they address, so that issuing a k-step's row reads never
+// waits on a vector load.
+struct StepCells {
+  uint32_t c[kStepCells];
+};
+
+__device__ __forceinline__ StepCells load_cells(const TileStep* __restrict__ st) {
+  StepCells k;
+#pragma unroll
+  for (int e = 0; e < kStepCells; ++e) k.c[e] = st->cell[e];
+  return k;
+}
+
+__device__ __forceinline__ void load_step(const char* __restrict__ feat, const TileStep* __restrict__ st, const StepCells& k,
+                                          uint32_t lane_off, uint32_t g_mask, int lane, StepRegs& r) {
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    // lanes 0..31 take cells 0..7, lanes 32..63 cells 8..15 (bitwise select: both offsets stay scalar)
+    const uint32_t c = k.c[e] ^ ((k.c[e] ^ k.c[8 + e]) & g_mask);
+    r.q[e] = *reinterpret_cast<const u32x4*>(feat + (c + lane_off));
+  }
+  r.ah = st->a_hi[lane];
+  r.al = st->a_lo[lane];
+}
+
+// 16 matrix-core instructions of one k-step: operand t holds channel 8 m + t of the 8 cells.
+template <int DT>
+__device__ __forceinline__ void mma_step(const StepRegs& r, f32x16 (&acc)[8]) {
+#pragma unroll
+  for (int t = 0; t < 8; ++t) {
+    u32x4 b;
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      // bytes 0..3 of the selector index the first cell's dword, 4..7 the second cell's
+      const uint32_t lo = r.q[2 * e2][t >> 1], hi = r.q[2 * e2 + 1][t >> 1];
+      b[e2] = __builtin_amdgcn_perm(hi, lo, (t & 1) ? 0x07060302u : 0x05040100u);
+    }
+    acc[t] = mma<DT>(r.ah, b, acc[t]);
+    acc[t] = mma<DT>(r.al, b, acc[t]);
+  }
+}
+
+struct ProdArgs {
+  const char* feat;
+  int D;
+  const TileHdr* hdr;
+  const TileStep* steps;
+  int quota;
+  float* fused;
+  float norm_eps;
+  int mean_only;
+};
+
+// DT: 1 bf16, 2 fp16 feature maps.  S waves per workgroup, D == 256 * S.
+template <int DT, int S>
+__global__ __launch_bounds__(kWave* S) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void k_tile_product(ProdArgs a, ObjTable tab) {
+  __shared__ float s_ss[S][kTilePts];
+  __shared__ float s_scale[kTilePts];
+
+  const ObjRange ob = tab.o[blockIdx.y];
+  const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
+  if ((int)blockIdx.x >= nblk) return;
+  const int blk = xcd_contiguous(blockIdx.x, nblk);
+  const TileHdr* __restrict__ hdr = a.hdr + ob.tile_begin + blk;
+  const long long slot0 = (long long)(ob.tile_begin + blk) * a.quota;
+  const int nseg = hdr->nseg;
+  if (nseg < 0) return;   // fused by the prepare kernel
+  const int tid = threadIdx.x, lane = tid % kWave, span = tid / kWave;
+  const int m = lane & 31, g = lane >> 5;
+  const int D = a.D;
+  const int li0 = blk * kTilePts;
+  const uint32_t lane_off = (uint32_t)(span * kSpan + 8 * m) * 2u;
+  const uint32_t g_mask = g ? 0xffffffffu : 0u;
+
+  f32x16 acc[8];
+#pragma unroll
+  for (int t = 0; t < 8; ++t)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+
+  for (int seg = 0; seg < nseg; ++seg) {
+    const TileStep* __restrict__ st = a.steps + slot0 + hdr->seg_off[seg];
+    const int n = hdr->seg_steps[seg];
+    if (n == 0) continue;
+    StepRegs r0, r1;
+    StepCells k0 = load_cells(st), k1 = load_cells(st + min(1, n - 1));
+    load_step(a.feat, st, k0, lane_off, g_mask, lane, r0);
+    k0 = load_cells(st + min(2, n - 1));
+    if (n > 1) load_step(a.feat, st + 1, k1, lane_off, g_mask, lane, r1);
+    k1 = load_cells(st + min(3, n - 1));
+    for (int s = 0; s < n; s += 2) {
+      mma_step<DT>(r0, acc);
+      if (s + 2 < n) load_step(a.feat, st + s + 2, k0, lane_off, g_mask, lane, r0);
+      k0 = load_cells(st + min(s + 4, n - 1));
+      if (s + 1 < n) {
+        mma_step<DT>(r1, acc);
+        if (s + 3 < n) load_step(a.feat, st + s + 3, k1, lane_off, g_mask, lane, r1);
+        k1 = load_cells(st + min(s + 5, n - 1));
       }
     }
   }
 
-  // ---- D: mean, L2 norm, store.  One factor per point, inv_count / max(norm of the mean, eps),
-  // is computed once and applied to the raw sums.
-  __syncthreads();
+  // ---- mean, L2 norm, store.  One factor per point, inv_count / max(norm of the mean, eps), is
+  // computed once and applied to the raw sums.
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int row = 8 * (r >> 2) + 4 * g + (r & 3);
@@ -305,7 +568,7 @@ void k_fuse_tile(FuseArgs a, ObjTable tab) {
   }
   __syncthreads();
   if (tid < kTilePts) {
-    const int c = s_cnt[tid];
+    const int c = hdr->cnt[tid];
     const float inv = c > 0 ? 1.0f / (float)c : 0.0f;
     float f = inv;
     if (!a.mean_only) {
@@ -328,27 +591,60 @@ void k_fuse_tile(FuseArgs a, ObjTable tab) {
     __builtin_nontemporal_store(v0, reinterpret_cast<f32x4*>(o));
     __builtin_nontemporal_store(v1, reinterpret_cast<f32x4*>(o + 4));
   }
-  if (a.out_count && tid < kTilePts && li0 + tid < ob.n_pts) a.out_count[ob.pt_begin + li0 + tid] = s_cnt[tid];
+}
+
+// ------------------------------------------------------------------------------------ host
+
+static long long tile_count_bound(long long N, int B) { return N / kTilePts + B; }
+
+static int steps_quota(int B, int n_views) {
+  // k-steps of storage per tile: two per view of an object, within [4, 32] (measured need on
+  // spatially sorted points: 0.3 to 0.4 per view for coarse grids, up to 1 for pixel-sized cells)
+  const long long per_obj = (n_views + B - 1) / B;
+  return (int)(2 * per_obj < 4 ? 4 : (2 * per_obj > 32 ? 32 : 2 * per_obj));
+}
+
+static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+size_t fuse_tile_workspace_bytes(long long N, int B, int n_views) {
+  const size_t tiles = (size_t)tile_count_bound(N, B);
+  return round256(tiles * sizeof(TileHdr)) + tiles * (size_t)steps_quota(B, n_views) * sizeof(TileStep);
+}
+
+TileWs fuse_tile_workspace(void* workspace, long long N, int B, int n_views) {
+  char* base = static_cast<char*>(workspace);
+  TileWs ws;
+  ws.hdr = reinterpret_cast<TileHdr*>(base);
+  ws.steps = reinterpret_cast<TileStep*>(base + round256((size_t)tile_count_bound(N, B) * sizeof(TileHdr)));
+  ws.quota = steps_quota(B, n_views);
+  return ws;
+}
+
+bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes, int max_views) {
+  // cell coordinates travel as 16-bit pairs and cell rows as 32-bit byte offsets inside the kernels
+  return (dtype == 1 || dtype == 2) && Hf <= 32767 && Wf <= 32767 && D % kSpan == 0 && D / kSpan >= 1 &&
+         D / kSpan <= 6 && D / kSpan != 5 && feat_bytes <= 0xffffffffll && max_views <= kMaxSeg * kViewBatch;
 }
 
 template <int DT, int S>
-static hipError_t launch_tile(const FuseArgs& a, const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream) {
-  dim3 grid((max_pts + kTilePts - 1) / kTilePts, n_obj), block(kWave * S);
-  hipLaunchKernelGGL((k_fuse_tile<DT, S>), grid, block, 0, stream, a, tab);
+static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
+                              hipStream_t stream) {
+  const dim3 grid((max_pts + kTilePts - 1) / kTilePts, n_obj);
+  hipLaunchKernelGGL((k_tile_prepare<DT>), grid, dim3(kPrepThreads), 0, stream, a, ws, tab);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  ProdArgs pa{static_cast<const char*>(a.feat.feat), a.feat.D, ws.hdr, ws.steps, ws.quota, a.fused, a.norm_eps, a.mean_only};
+  hipLaunchKernelGGL((k_tile_product<DT, S>), grid, dim3(kWave * S), 0, stream, pa, tab);
   return hipGetLastError();
 }
 
-bool fuse_tile_supported(int dtype, int D, int Hf, int Wf) {
-  // cell coordinates travel as 16-bit pairs inside the kernel
-  return (dtype == 1 || dtype == 2) && Hf <= 32767 && Wf <= 32767 && D % kSpan == 0 && D / kSpan >= 1 && D / kSpan <= 6 && D / kSpan != 5;
-}
-
-hipError_t launch_fuse_tile(const FuseArgs& a, const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream) {
+hipError_t launch_fuse_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
+                            hipStream_t stream) {
   const int S = a.feat.D / kSpan;
-#define AURA_TILE_CASE(s)                                                              \
-  case s:                                                                              \
-    return a.feat.dtype == 1 ? launch_tile<1, s>(a, tab, n_obj, max_pts, stream)       \
-                             : launch_tile<2, s>(a, tab, n_obj, max_pts, stream)
+#define AURA_TILE_CASE(s)                                                                  \
+  case s:                                                                                  \
+    return a.feat.dtype == 1 ? launch_tile<1, s>(a, ws, tab, n_obj, max_pts, stream)       \
+                             : launch_tile<2, s>(a, ws, tab, n_obj, max_pts, stream)
   switch (S) {
     AURA_TILE_CASE(1);
     AURA_TILE_CASE(2);

@@ -22,8 +22,10 @@ hipError_t launch_project_visibility(const VisArgs& vis, const float* xyz, uint8
                                      int* out_count, float* out_uvz, const ObjTable& tab, int n_obj,
                                      int max_pts, hipStream_t stream);
 
+struct TileWs;
+// tile_ws == nullptr: per-point gather kernel; otherwise the matrix-core tile path with that workspace.
 hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const float* xyz, float* fused,
-                                int* out_count, float norm_eps, int mean_only, int force_gather,
+                                int* out_count, float norm_eps, int mean_only, const TileWs* tile_ws,
                                 const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream);
 
 size_t scores_workspace_bytes(int D, int K);

@@ -17,8 +17,8 @@
 namespace aura {
 
 constexpr int kMassBlock = 256;
-constexpr int kMassPtsPerBlock = 4096;   // slice of points summed by one workgroup
-constexpr int kVoxPerBlock = 4096;       // slice of voxels summed by one workgroup
+constexpr int kMassPtsPerBlock = 512;    // slice of points summed by one workgroup
+constexpr int kVoxPerBlock = 2048;       // slice of voxels summed by one workgroup
 
 struct MassObjDev {
   long long pt_begin;

@@ -41,6 +41,8 @@ class DeviceScene:
         self.label = torch.empty(N, dtype=torch.int32, device=dev)
         self.mass = torch.empty(s.B, dtype=torch.float32, device=dev)
         self.n_used = torch.empty(s.B, dtype=torch.int64, device=dev)
+        nb = aura.fuse_workspace_bytes(self.views, N, s.B)
+        self.ws_fuse = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
         self.ws_scores = torch.empty(aura.workspace_bytes(binding.CALL_MATERIAL_SCORES, D=s.D, K=s.K),
                                      dtype=torch.uint8, device=dev)
         self.ws_mass = torch.empty(aura.workspace_bytes(binding.CALL_PROPERTY_INTEGRATE, N=N, B=s.B, G=s.G),
@@ -52,7 +54,7 @@ class DeviceScene:
 
     def fuse_features(self):
         aura.fuse_features(self.views, self.params, self.xyz, self.fused, self.count_fuse, self.pt_offsets,
-                           self.view_offsets)
+                           self.view_offsets, self.ws_fuse)
 
     def material_scores(self):
         aura.material_scores(self.fused, self.temb, self.y, self.params, self.scores, self.prop, self.label,

@@ -57,6 +57,18 @@ def test_workspace_sizes(B):
     with pytest.raises(B.AuraError) as e:
         B.workspace_bytes(B.CALL_PROPERTY_INTEGRATE, N=-1)
     assert e.value.status == -2
+    # fusion: only 16-bit maps with D a multiple of 256 use the matrix-core path and need scratch
+    fuse = lambda **kw: B.workspace_bytes(B.CALL_FUSE_FEATURES, **{**dict(N=200_000, B=1, n_views=16, Hf=32, Wf=32), **kw})
+    assert fuse(D=512, feat_dtype=B.F32) == 0
+    assert fuse(D=100, feat_dtype=B.BF16) == 0
+    assert fuse(D=1280, feat_dtype=B.F16) == 0
+    tiles = 200_000 // 32 + 1
+    assert fuse(D=768, feat_dtype=B.BF16) == -(-tiles * 208 // 256) * 256 + tiles * 32 * 2112
+    assert fuse(D=768, feat_dtype=B.BF16, n_views=4) == -(-tiles * 208 // 256) * 256 + tiles * 8 * 2112
+    with pytest.raises(B.AuraError) as e:
+        fuse(D=768, feat_dtype=9)
+    assert e.value.status == -3
+    assert B.lib().aura_workspace_bytes(B.CALL_FUSE_FEATURES, None, C.byref(C.c_size_t())) == -1
 
 
 def _views(B, **kw):
@@ -90,13 +102,17 @@ def test_argument_validation_returns_status_codes(B):
     assert pv(_views(B), po_=hp(bad), vo_=hp(vo), B_=2, N=5) == -2         # not monotone
     assert pv(_views(B), N=0, xyz=None, vis=None) == 0                     # empty input is fine
 
-    ff = lambda v, fused=fake: L.aura_fuse_features(C.byref(v), C.byref(p), fake, 10, None, None, 1, fused, None, None)
+    ff = lambda v, fused=fake, ws=None, wsb=0: L.aura_fuse_features(C.byref(v), C.byref(p), fake, 10, None, None, 1,
+                                                                  fused, None, ws, wsb, None)
     assert ff(_views(B, feat=None)) == -1
     assert ff(_views(B, feat_dtype=7)) == -3
     assert ff(_views(B, feat=0x1004)) == -4
     assert ff(_views(B), fused=C.c_void_p(0x1004)) == -4
     assert ff(_views(B, D=0)) == -2
     assert ff(_views(B), fused=None) == -1
+    half = dict(feat_dtype=B.BF16, D=256)                                  # a shape the matrix-core path takes
+    assert ff(_views(B, **half), ws=C.c_void_p(0x1010), wsb=1 << 30) == -5 # workspace not 256-byte aligned
+    assert ff(_views(B, **half), ws=C.c_void_p(0x1000), wsb=64) == -5      # workspace too small
 
     ms = lambda N=10, D=64, K=8, P=1, temb=fake, dt=B.F32, y=fake, prop=fake, ws=C.c_void_p(0x1000), wsb=1 << 20, par=p: \
         L.aura_material_scores(fake, N, D, temb, dt, K, y, P, C.byref(par) if par is not None else None, fake, prop,

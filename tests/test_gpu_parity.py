@@ -163,6 +163,28 @@ def test_scores_kernel_alone_on_random_unit_rows(H, orc):
         assert es <= 1e-5 and ep <= 1e-4 and not bad.any()
 
 
+@pytest.mark.parametrize("name,kw", [("c2", dict(n_points=6000)),
+                                     ("c3", dict(n_points=6000, overrides=dict(V=5, HW=112, grid=112))),
+                                     ("c5", dict(n_points=3000, n_objects=3))])
+def test_unsorted_points_on_the_matrix_core_path(H, orc, name, kw):
+    """Points in random order: the per-view cell boxes of a 32-point tile are large, so views fall back
+    to private list entries, the lists span several chunks, and the k-step storage runs out for part
+    of the tiles (those are fused by the in-kernel gather; with few visible pairs the lists still fit).
+    Results must not change."""
+    s = make_scene(name, order="random", **kw)
+    d = H.DeviceScene(s)
+    assert d.ws_fuse is not None
+    d.step()
+    gpu = d.results()
+    ref = H.oracle_points(orc, s)
+    print(H.compare_points(gpu, ref, s), flush=True)
+    # tile headers (208 bytes each, at the start of the workspace): nseg == -1 marks the gather
+    ntile = int(np.sum((np.diff(s.pt_offsets) + 31) // 32))
+    nseg = d.ws_fuse[:ntile * 208].cpu().numpy().view(np.int32).reshape(ntile, 52)[:, 0]
+    print(f"tiles {ntile}, fused by the in-kernel gather {int((nseg < 0).sum())}", flush=True)
+    assert (nseg < 0).any() and ((nseg > 0).any() or name != "c3")
+
+
 def test_flags_and_degenerate_inputs(H, orc):
     import paper_2511_03126_amd as aura
     from paper_2511_03126_amd import binding
