@@ -163,7 +163,7 @@ aura_status_t aura_project_visibility(const aura_views_t* views, const aura_para
  *   count  [device] [N] int32 or NULL
  *   workspace [device] aura_workspace_bytes(AURA_CALL_FUSE_FEATURES, ...) bytes, 256-byte aligned,
  *          or NULL.  With a workspace, 16-bit maps whose D is a multiple of 256 (up to 1536, except
- *          1280; maps below 4 GiB; at most 256 views per object) run on the matrix cores: the
+ *          1280; maps below 4 GiB) run on the matrix cores: the
  *          points are taken 32 at a time and should arrive spatially sorted (e.g. Morton order),
  *          and the maps must be finite everywhere.  Without one, or for other shapes, or with
  *          AURA_FUSE_GATHER, a per-point gather kernel is used.  Both give the same result up to

@@ -121,9 +121,9 @@ const char* aura_strerror(aura_status_t status) {
 int32_t aura_last_hip_error(void) { return g_last_hip_error; }
 
 // Whether aura_fuse_features takes the matrix-core tile path for these sizes.
-static bool tile_path(int32_t dtype, int32_t D, int32_t Hf, int32_t Wf, int32_t n_views, int32_t max_views) {
+static bool tile_path(int32_t dtype, int32_t D, int32_t Hf, int32_t Wf, int32_t n_views) {
   const long long feat_bytes = (long long)n_views * Hf * Wf * D * 2;
-  return aura::fuse_tile_supported(dtype, D, Hf, Wf, feat_bytes, max_views);
+  return aura::fuse_tile_supported(dtype, D, Hf, Wf, feat_bytes);
 }
 
 aura_status_t aura_workspace_bytes(int32_t call, const aura_sizes_t* sz, size_t* bytes) {
@@ -145,8 +145,7 @@ aura_status_t aura_workspace_bytes(int32_t call, const aura_sizes_t* sz, size_t*
   if (call == AURA_CALL_FUSE_FEATURES) {
     if (sz->N < 0 || sz->B < 1 || sz->n_views < 1 || sz->Hf < 1 || sz->Wf < 1 || sz->D < 1) return AURA_ERR_SHAPE;
     if (sz->feat_dtype != AURA_F32 && sz->feat_dtype != AURA_BF16 && sz->feat_dtype != AURA_F16) return AURA_ERR_DTYPE;
-    // the per-object view count is not known here; the call itself checks it again
-    if (tile_path(sz->feat_dtype, sz->D, sz->Hf, sz->Wf, sz->n_views, 1))
+    if (tile_path(sz->feat_dtype, sz->D, sz->Hf, sz->Wf, sz->n_views))
       *bytes = aura::fuse_tile_workspace_bytes(sz->N, sz->B, sz->n_views);
     return AURA_OK;
   }
@@ -204,7 +203,7 @@ aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t*
   // matrix-core tile path: 16-bit maps, D a multiple of 256, a workspace, and not switched off
   aura::TileWs tws{};
   const bool tile = workspace && !(params->flags & AURA_FUSE_GATHER) &&
-                    tile_path(views->feat_dtype, views->D, views->Hf, views->Wf, views->n_views, max_views);
+                    tile_path(views->feat_dtype, views->D, views->Hf, views->Wf, views->n_views);
   if (tile) {
     if (!aligned(workspace, 256) || workspace_bytes < aura::fuse_tile_workspace_bytes(N, B, views->n_views))
       return AURA_ERR_WORKSPACE;

@@ -24,15 +24,12 @@ struct FuseArgs {
 
 constexpr int kTilePts = 32;        // points per tile (M of the matrix-core product)
 constexpr int kStepCells = 16;      // cells per k-step (K of the matrix-core product)
-constexpr int kMaxSeg = 8;          // view batches (of 32 views) a tile can describe
 
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 
 struct TileHdr {
-  int nseg;                 // number of segments; -1: the prepare kernel fused this tile itself
+  int nsteps;               // k-steps written for the tile; -1: the prepare kernel fused this tile itself
   int pad_[3];
-  int seg_off[kMaxSeg];     // first k-step of each segment within the tile's run of k-steps
-  int seg_steps[kMaxSeg];   // k-steps of each segment
   int cnt[kTilePts];        // views that see each point
 };
 
@@ -48,7 +45,7 @@ struct TileWs {
   int quota;
 };
 
-bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes, int max_views);
+bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes);
 size_t fuse_tile_workspace_bytes(long long N, int B, int n_views);
 // Splits a workspace of fuse_tile_workspace_bytes(N, B, n_views) bytes into its parts.
 TileWs fuse_tile_workspace(void* workspace, long long N, int B, int n_views);

@@ -20,7 +20,7 @@
 //   A  every (point, view) pair is projected and tested (Eq. 1, the shared fp32 decision
 //      functions).  Per view, the bounding box of the touched cells is found with a half-wave
 //      reduction.
-//   B  views whose box fits 16 x 16 cells mark the touched cells in a 256-bit map (exact list,
+//   B  views whose box fits 32 x 32 cells mark the touched cells in a 1024-bit map (exact list,
 //      no duplicates, no untouched cells); larger boxes (points far apart) give each visible
 //      pair four private entries.  A scan over the views lays the per-view lists end to end.
 //   C  per chunk of the list: the weights are scattered into a [32][cells] matrix in LDS, split
@@ -31,13 +31,15 @@
 //      reproducible bit for bit.
 //
 // k_tile_product (one workgroup per tile, wave s owns channels [256 s, 256 s + 256)): per k-step
-// each lane reads 16 bytes (8 channels) of 8 cell rows straight from global memory (the rows of a
-// tile's neighbours keep them in L2), regroups them with byte permutes into the 8 B-operands
-// (one per channel phase t = channel mod 8) and issues v_mfma_f32_32x32x16 with the hi and the lo
-// weights.  No LDS and no barrier inside the loop; the next k-step is in flight while the current
-// one is multiplied.  Then mean, L2 norm (half-wave reduction, across the waves through LDS) and
-// streaming stores.  Accumulator t, register r of lane l is point 8 (r/4) + 4 (l/32) + r%4,
-// channel 256 s + 8 (l%32) + t: every lane stores 8 consecutive channels of a point.
+// each lane reads two 8-byte pieces (4 channels each, 128 channels apart) of 8 cell rows straight
+// from global memory (the rows of a tile's neighbours keep them in L2), regroups them with byte
+// permutes into the 8 B-operands and issues v_mfma_f32_32x32x16 with the hi and the lo weights.
+// No LDS and no barrier inside the loop; reads run several k-steps ahead of the products.  Then
+// mean, L2 norm (half-wave reduction, across the waves through LDS) and streaming stores.
+// Accumulator t = 4 h + j, register r of lane l is point 8 (r/4) + 4 (l/32) + r%4, channel
+// 256 s + 128 h + 4 (l%32) + j: a store instruction writes 16 bytes per lane and the 32 lanes of
+// a half wave cover 512 contiguous bytes of a row (full cache lines; writing 16 of every 32
+// bytes, as a lane owning 8 consecutive channels would, halves the achieved write bandwidth).
 //
 // List entries that only pad the last k-step have zero weights, so feature maps must be finite.
 #include "aura_device.hpp"
@@ -61,7 +63,7 @@ constexpr int kChunkSteps = 12;                // k-steps of the weight matrix h
 constexpr int kChunk = kChunkSteps * kStepCells;
 constexpr int kPitch = kChunk + 8;             // row pitch in 16-bit elements (rows start 4 banks apart)
 constexpr int kSpan = 256;                     // channels per wave of the product kernel
-constexpr int kWinSide = 16;                   // side of the per-view cell map
+constexpr int kWinSide = 32;                   // side of the per-view cell map: one 32-bit word per row
 
 static_assert(kSlots * kTilePts == kPrepThreads && kNIT * kSlots == kViewBatch, "thread mapping");
 static_assert(sizeof(TileStep) == 64 + 2048, "k-step layout");
@@ -210,14 +212,13 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
   __shared__ int s_win[kViewBatch][2];                 // first cell (x, y) of the view's map
   __shared__ int s_mode[kViewBatch];                   // 0 nothing seen, 1 cell map, 2 private entries
   __shared__ uint32_t s_vmask[kViewBatch];             // which of the 32 points the view sees
-  __shared__ __attribute__((aligned(16))) uint32_t s_bits[kViewBatch][8];   // 16 x 16 map of touched cells
-  __shared__ __attribute__((aligned(16))) int s_wbase[kViewBatch][8];       // set bits before each word
+  __shared__ __attribute__((aligned(16))) uint32_t s_bits[kViewBatch][kWinSide];   // map of touched cells, row = word
+  __shared__ __attribute__((aligned(16))) uint16_t s_wbase[kViewBatch][kWinSide];  // set bits before each row
   __shared__ int s_base[kViewBatch + 1];               // first list index of each view
   __shared__ __attribute__((aligned(16))) uint32_t s_cell[kChunk];
   __shared__ __attribute__((aligned(16))) uint16_t s_whi[kTilePts][kPitch];
   __shared__ __attribute__((aligned(16))) uint16_t s_wlo[kTilePts][kPitch];
   __shared__ int s_cnt[kTilePts];
-  __shared__ int s_seg[2 * kMaxSeg];
 
   const ObjRange ob = tab.o[blockIdx.y];
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
@@ -236,13 +237,13 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
   const float px = a.xyz[3 * ip], py = a.xyz[3 * ip + 1], pz = a.xyz[3 * ip + 2];
 
   if (tid < kTilePts) s_cnt[tid] = 0;
-  int nseg = 0, used = 0;   // segments and k-steps written so far
+  int used = 0;   // k-steps written so far (the view batches follow one another in the tile's run)
   bool exhausted = false;
 
-  for (int vb0 = 0; vb0 < ob.n_views; vb0 += kViewBatch, ++nseg) {
+  for (int vb0 = 0; vb0 < ob.n_views; vb0 += kViewBatch) {
     const int nvb = min(kViewBatch, ob.n_views - vb0);
     __syncthreads();   // the previous batch is done with the tables (and s_cnt is initialised)
-    s_bits[tid / 8][tid % 8] = 0u;
+    *reinterpret_cast<u32x4*>(&s_bits[tid / 8][4 * (tid % 8)]) = u32x4{0u, 0u, 0u, 0u};
 
     // ---- A: project and test; bounding box of the touched cells per view
     PairRec pr[kNIT];
@@ -303,9 +304,9 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
       int n = 0;
       if (lane < nvb) {
         if (s_mode[lane] == 1) {
-#pragma unroll
-          for (int w = 0; w < 8; ++w) {
-            s_wbase[lane][w] = n;
+#pragma unroll 8
+          for (int w = 0; w < kWinSide; ++w) {
+            s_wbase[lane][w] = (uint16_t)n;
             n += __popc(s_bits[lane][w]);
           }
         } else if (s_mode[lane] == 2) {
@@ -330,10 +331,6 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
     }
     const int off = used;
     used += nsteps;
-    if (tid == 0) {
-      s_seg[nseg] = off;
-      s_seg[kMaxSeg + nseg] = nsteps;
-    }
 
     // ---- C: chunks of the list -> weight matrix in LDS -> k-steps in global memory
     for (int c0 = 0; c0 < L; c0 += kChunk) {
@@ -348,17 +345,19 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
       }
       // entries that pad the last k-step point at a cell that exists (their weights are zero)
       if (tid >= Lc && tid < ksteps * kStepCells) s_cell[tid] = (uint32_t)((ob.view_begin + vb0) * Hf * Wf) * row_bytes;
-      {   // cells of the views with a map: thread = (view, word of the map)
-        const int vl = tid / 8, w = tid % 8;
+      {   // cells of the views with a map: thread = (view, four rows of the map)
+        const int vl = tid / 8;
         if (vl < nvb && s_mode[vl] == 1) {
-          uint32_t bits = s_bits[vl][w];
-          int q = s_base[vl] + s_wbase[vl][w] - c0;
           const int cell0 = (ob.view_begin + vb0 + vl) * Hf + s_win[vl][1], wx = s_win[vl][0];
-          while (bits) {
-            const int b = __builtin_ctz(bits) + 32 * w;
-            bits &= bits - 1;
-            if (q >= 0 && q < Lc) s_cell[q] = (uint32_t)((cell0 + b / kWinSide) * Wf + wx + b % kWinSide) * row_bytes;
-            ++q;
+          for (int w = 4 * (tid % 8); w < 4 * (tid % 8) + 4; ++w) {
+            uint32_t bits = s_bits[vl][w];
+            int q = s_base[vl] + s_wbase[vl][w] - c0;
+            while (bits) {
+              const int b = __builtin_ctz(bits);
+              bits &= bits - 1;
+              if (q >= 0 && q < Lc) s_cell[q] = (uint32_t)((cell0 + w) * Wf + wx + b) * row_bytes;
+              ++q;
+            }
           }
         }
       }
@@ -419,15 +418,11 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
 
   __syncthreads();
   if (exhausted) {
-    if (tid == 0) hdr->nseg = -1;
+    if (tid == 0) hdr->nsteps = -1;
     gather_tile<DT>(a, ob, li0, tid);
     return;
   }
-  if (tid == 0) hdr->nseg = nseg;
-  if (tid < kMaxSeg) {
-    hdr->seg_off[tid] = tid < nseg ? s_seg[tid] : 0;
-    hdr->seg_steps[tid] = tid < nseg ? s_seg[kMaxSeg + tid] : 0;
-  }
+  if (tid == 0) hdr->nsteps = used;
   if (tid < kTilePts) {
     hdr->cnt[tid] = s_cnt[tid];
     if (a.out_count && li0 + tid < ob.n_pts) a.out_count[ob.pt_begin + li0 + tid] = s_cnt[tid];
@@ -444,15 +439,20 @@ __device__ __forceinline__ f32x16 mma(u32x4 a, u32x4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-// Operands of one k-step in registers: 8 cell rows x 16 bytes and the two weight operands.
-struct StepRegs {
-  u32x4 q[8];
-  u32x4 ah, al;
+// Operands of one k-step in registers: the two weight operands, and 8 cell rows x 16 bytes.
+struct StepA {
+  u32x4 hi, lo;
+};
+
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+struct StepQ {
+  u32x2 q[2][8];   // [half of the wave's channel span][cell]: 4 channels each
 };
 
 // The 16 cell offsets of a k-step are the same for every lane: they are read through the scalar
-// unit, one k-step ahead of the rows they address, so that issuing a k-step's row reads never
-// waits on a vector load.
+// unit, ahead of the rows they address, so that issuing a k-step's row reads never waits on a
+// vector load.
 struct StepCells {
   uint32_t c[kStepCells];
 };
@@ -464,32 +464,37 @@ __device__ __forceinline__ StepCells load_cells(const TileStep* __restrict__ st)
   return k;
 }
 
-__device__ __forceinline__ void load_step(const char* __restrict__ feat, const TileStep* __restrict__ st, const StepCells& k,
-                                          uint32_t lane_off, uint32_t g_mask, int lane, StepRegs& r) {
+__device__ __forceinline__ void load_a(const TileStep* __restrict__ st, int lane, StepA& r) {
+  r.hi = st->a_hi[lane];
+  r.lo = st->a_lo[lane];
+}
+
+__device__ __forceinline__ void load_q(const char* __restrict__ feat, const StepCells& k, uint32_t lane_off, uint32_t g_mask,
+                                       StepQ& r) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     // lanes 0..31 take cells 0..7, lanes 32..63 cells 8..15 (bitwise select: both offsets stay scalar)
     const uint32_t c = k.c[e] ^ ((k.c[e] ^ k.c[8 + e]) & g_mask);
-    r.q[e] = *reinterpret_cast<const u32x4*>(feat + (c + lane_off));
+    r.q[0][e] = *reinterpret_cast<const u32x2*>(feat + (c + lane_off));
+    r.q[1][e] = *reinterpret_cast<const u32x2*>(feat + (c + lane_off + (kSpan / 2) * 2));
   }
-  r.ah = st->a_hi[lane];
-  r.al = st->a_lo[lane];
 }
 
-// 16 matrix-core instructions of one k-step: operand t holds channel 8 m + t of the 8 cells.
+// 16 matrix-core instructions of one k-step: operand t = 4 h + j holds channel 128 h + 4 m + j of
+// the 8 cells.
 template <int DT>
-__device__ __forceinline__ void mma_step(const StepRegs& r, f32x16 (&acc)[8]) {
+__device__ __forceinline__ void mma_step(const StepA& w, const StepQ& r, f32x16 (&acc)[8]) {
 #pragma unroll
   for (int t = 0; t < 8; ++t) {
     u32x4 b;
 #pragma unroll
     for (int e2 = 0; e2 < 4; ++e2) {
       // bytes 0..3 of the selector index the first cell's dword, 4..7 the second cell's
-      const uint32_t lo = r.q[2 * e2][t >> 1], hi = r.q[2 * e2 + 1][t >> 1];
+      const uint32_t lo = r.q[t >> 2][2 * e2][(t >> 1) & 1], hi = r.q[t >> 2][2 * e2 + 1][(t >> 1) & 1];
       b[e2] = __builtin_amdgcn_perm(hi, lo, (t & 1) ? 0x07060302u : 0x05040100u);
     }
-    acc[t] = mma<DT>(r.ah, b, acc[t]);
-    acc[t] = mma<DT>(r.al, b, acc[t]);
+    acc[t] = mma<DT>(w.hi, b, acc[t]);
+    acc[t] = mma<DT>(w.lo, b, acc[t]);
   }
 }
 
@@ -505,6 +510,12 @@ struct ProdArgs {
 };
 
 // DT: 1 bf16, 2 fp16 feature maps.  S waves per workgroup, D == 256 * S.
+//
+// Reads run ahead of the products: the weight operands (written by the prepare kernel, so they
+// come from far memory) four k-steps, the cell rows (shared with the neighbouring tiles, so mostly
+// L2 hits) two k-steps.  A tile's k-steps sit at a fixed place, so the first reads do not wait for
+// the tile header; reads beyond the tile's last k-step stay inside the tile's own run of storage
+// (the quota is at least 4) and their values are never used.
 template <int DT, int S>
 __global__ __launch_bounds__(kWave* S) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k_tile_product(ProdArgs a, ObjTable tab) {
@@ -516,15 +527,25 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
   if ((int)blockIdx.x >= nblk) return;
   const int blk = xcd_contiguous(blockIdx.x, nblk);
   const TileHdr* __restrict__ hdr = a.hdr + ob.tile_begin + blk;
-  const long long slot0 = (long long)(ob.tile_begin + blk) * a.quota;
-  const int nseg = hdr->nseg;
-  if (nseg < 0) return;   // fused by the prepare kernel
+  const TileStep* __restrict__ st = a.steps + (long long)(ob.tile_begin + blk) * a.quota;
+  const int last = a.quota - 1;
   const int tid = threadIdx.x, lane = tid % kWave, span = tid / kWave;
   const int m = lane & 31, g = lane >> 5;
   const int D = a.D;
   const int li0 = blk * kTilePts;
-  const uint32_t lane_off = (uint32_t)(span * kSpan + 8 * m) * 2u;
+  const uint32_t lane_off = (uint32_t)(span * kSpan + 4 * m) * 2u;   // first half; the second is kSpan bytes on
   const uint32_t g_mask = g ? 0xffffffffu : 0u;
+
+  StepA wa[4];
+  StepQ rq[2];
+  StepCells kc[2];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) load_a(st + j, lane, wa[j]);
+  kc[0] = load_cells(st);
+  kc[1] = load_cells(st + 1);
+  const int n = hdr->nsteps;
+  if (n < 0) return;   // fused by the prepare kernel
+  const int my_cnt = hdr->cnt[tid % kTilePts];
 
   f32x16 acc[8];
 #pragma unroll
@@ -532,24 +553,18 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
 
-  for (int seg = 0; seg < nseg; ++seg) {
-    const TileStep* __restrict__ st = a.steps + slot0 + hdr->seg_off[seg];
-    const int n = hdr->seg_steps[seg];
-    if (n == 0) continue;
-    StepRegs r0, r1;
-    StepCells k0 = load_cells(st), k1 = load_cells(st + min(1, n - 1));
-    load_step(a.feat, st, k0, lane_off, g_mask, lane, r0);
-    k0 = load_cells(st + min(2, n - 1));
-    if (n > 1) load_step(a.feat, st + 1, k1, lane_off, g_mask, lane, r1);
-    k1 = load_cells(st + min(3, n - 1));
-    for (int s = 0; s < n; s += 2) {
-      mma_step<DT>(r0, acc);
-      if (s + 2 < n) load_step(a.feat, st + s + 2, k0, lane_off, g_mask, lane, r0);
-      k0 = load_cells(st + min(s + 4, n - 1));
-      if (s + 1 < n) {
-        mma_step<DT>(r1, acc);
-        if (s + 3 < n) load_step(a.feat, st + s + 3, k1, lane_off, g_mask, lane, r1);
-        k1 = load_cells(st + min(s + 5, n - 1));
+  if (n > 0) load_q(a.feat, kc[0], lane_off, g_mask, rq[0]);
+  kc[0] = load_cells(st + 2);
+  if (n > 1) load_q(a.feat, kc[1], lane_off, g_mask, rq[1]);
+  kc[1] = load_cells(st + 3);
+  for (int s = 0; s < n; s += 4) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      if (s + j < n) {
+        mma_step<DT>(wa[j], rq[j & 1], acc);
+        if (s + j + 2 < n) load_q(a.feat, kc[j & 1], lane_off, g_mask, rq[j & 1]);
+        kc[j & 1] = load_cells(st + min(s + j + 4, last));
+        load_a(st + min(s + j + 4, last), lane, wa[j]);
       }
     }
   }
@@ -568,8 +583,7 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
   }
   __syncthreads();
   if (tid < kTilePts) {
-    const int c = hdr->cnt[tid];
-    const float inv = c > 0 ? 1.0f / (float)c : 0.0f;
+    const float inv = my_cnt > 0 ? 1.0f / (float)my_cnt : 0.0f;
     float f = inv;
     if (!a.mean_only) {
       float tot = 0.0f;
@@ -585,11 +599,11 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
     const int row = 8 * (r >> 2) + 4 * g + (r & 3);
     if (li0 + row >= ob.n_pts) continue;
     const float scale = s_scale[row];
-    float* o = a.fused + (ob.pt_begin + li0 + row) * D + span * kSpan + 8 * m;
+    float* o = a.fused + (ob.pt_begin + li0 + row) * D + span * kSpan + 4 * m;
     const f32x4 v0 = {acc[0][r] * scale, acc[1][r] * scale, acc[2][r] * scale, acc[3][r] * scale};
     const f32x4 v1 = {acc[4][r] * scale, acc[5][r] * scale, acc[6][r] * scale, acc[7][r] * scale};
     __builtin_nontemporal_store(v0, reinterpret_cast<f32x4*>(o));
-    __builtin_nontemporal_store(v1, reinterpret_cast<f32x4*>(o + 4));
+    __builtin_nontemporal_store(v1, reinterpret_cast<f32x4*>(o + kSpan / 2));
   }
 }
 
@@ -620,10 +634,10 @@ TileWs fuse_tile_workspace(void* workspace, long long N, int B, int n_views) {
   return ws;
 }
 
-bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes, int max_views) {
+bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes) {
   // cell coordinates travel as 16-bit pairs and cell rows as 32-bit byte offsets inside the kernels
   return (dtype == 1 || dtype == 2) && Hf <= 32767 && Wf <= 32767 && D % kSpan == 0 && D / kSpan >= 1 &&
-         D / kSpan <= 6 && D / kSpan != 5 && feat_bytes <= 0xffffffffll && max_views <= kMaxSeg * kViewBatch;
+         D / kSpan <= 6 && D / kSpan != 5 && feat_bytes <= 0xffffffffll;
 }
 
 template <int DT, int S>

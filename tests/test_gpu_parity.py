@@ -178,9 +178,9 @@ def test_unsorted_points_on_the_matrix_core_path(H, orc, name, kw):
     gpu = d.results()
     ref = H.oracle_points(orc, s)
     print(H.compare_points(gpu, ref, s), flush=True)
-    # tile headers (208 bytes each, at the start of the workspace): nseg == -1 marks the gather
+    # tile headers (144 bytes each, at the start of the workspace): a k-step count of -1 marks the gather
     ntile = int(np.sum((np.diff(s.pt_offsets) + 31) // 32))
-    nseg = d.ws_fuse[:ntile * 208].cpu().numpy().view(np.int32).reshape(ntile, 52)[:, 0]
+    nseg = d.ws_fuse[:ntile * 144].cpu().numpy().view(np.int32).reshape(ntile, 36)[:, 0]
     print(f"tiles {ntile}, fused by the in-kernel gather {int((nseg < 0).sum())}", flush=True)
     assert (nseg < 0).any() and ((nseg > 0).any() or name != "c3")
 
