@@ -227,6 +227,18 @@ aura_status_t aura_property_integrate(const float* prop, int64_t N, int32_t P, i
                                       float* mass, int64_t* n_used,
                                       void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * Bandwidth calibration (not part of the method).  A plain copy of `bytes` bytes from src to dst,
+ * and a plain fill of dst with a 32-bit pattern, each by one grid-stride kernel of 16-byte
+ * accesses with streaming stores.  The benchmark times them to state what the memory system
+ * delivers to the simplest kernel, and profiler byte counters are scaled by their reading for
+ * these known sizes.
+ *   dst, src [device] 16-byte aligned, not overlapping; bytes a multiple of 16 (0 does nothing)
+ * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE (bytes not a multiple of 16), AURA_ERR_ALIGN, AURA_ERR_HIP.
+ */
+aura_status_t aura_calibration_copy(void* dst, const void* src, size_t bytes, void* stream);
+aura_status_t aura_calibration_fill(void* dst, size_t bytes, uint32_t value, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

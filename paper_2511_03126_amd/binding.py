@@ -75,6 +75,10 @@ def lib():
         L.aura_property_integrate.restype = C.c_int32
         L.aura_property_integrate.argtypes = [vp, i64, i32, i32, vp, vp, f32, vp, i32, vp, vp, vp, i32, vp, vp,
                                               vp, C.c_size_t, vp]
+        L.aura_calibration_copy.restype = C.c_int32
+        L.aura_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
+        L.aura_calibration_fill.restype = C.c_int32
+        L.aura_calibration_fill.argtypes = [vp, C.c_size_t, C.c_uint32, vp]
         _lib = L
     return _lib
 
@@ -217,3 +221,15 @@ def property_integrate(prop, mass, p_index=0, count=None, vol=None, vol_uniform=
                                          _ptr(n_used), _ptr(workspace),
                                          0 if workspace is None else workspace.numel(), _stream()),
            "aura_property_integrate")
+
+
+def calibration_copy(dst, src):
+    """Plain device copy of src into dst (uint8 device tensors of equal size, a multiple of 16 bytes)."""
+    _check(lib().aura_calibration_copy(dst.data_ptr(), src.data_ptr(), src.numel() * src.element_size(), _stream()),
+           "aura_calibration_copy")
+
+
+def calibration_fill(dst, value=0):
+    """Plain device fill of dst with a 32-bit pattern."""
+    _check(lib().aura_calibration_fill(dst.data_ptr(), dst.numel() * dst.element_size(), value, _stream()),
+           "aura_calibration_fill")

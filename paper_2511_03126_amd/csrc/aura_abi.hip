@@ -272,4 +272,20 @@ aura_status_t aura_property_integrate(const float* prop, int64_t N, int32_t P, i
                                                     static_cast<hipStream_t>(stream)));
 }
 
+aura_status_t aura_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {
+  if (bytes == 0) return AURA_OK;
+  if (!dst || !src) return AURA_ERR_NULL;
+  if (bytes % 16 != 0) return AURA_ERR_SHAPE;
+  if (!aligned(dst, 16) || !aligned(src, 16)) return AURA_ERR_ALIGN;
+  return hip_status(aura::launch_calibration_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
+}
+
+aura_status_t aura_calibration_fill(void* dst, size_t bytes, uint32_t value, void* stream) {
+  if (bytes == 0) return AURA_OK;
+  if (!dst) return AURA_ERR_NULL;
+  if (bytes % 16 != 0) return AURA_ERR_SHAPE;
+  if (!aligned(dst, 16)) return AURA_ERR_ALIGN;
+  return hip_status(aura::launch_calibration_fill(dst, bytes, value, static_cast<hipStream_t>(stream)));
+}
+
 }  // extern "C"

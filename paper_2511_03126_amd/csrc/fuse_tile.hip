@@ -42,6 +42,8 @@
 // bytes, as a lane owning 8 consecutive channels would, halves the achieved write bandwidth).
 //
 // List entries that only pad the last k-step have zero weights, so feature maps must be finite.
+#include <algorithm>
+
 #include "aura_device.hpp"
 #include "fuse_args.hpp"
 #include "launch.hpp"
@@ -62,7 +64,7 @@ constexpr int kNIT = kViewBatch / kSlots;      // (point, view) pairs per thread
 constexpr int kChunkSteps = 12;                // k-steps of the weight matrix held in LDS
 constexpr int kChunk = kChunkSteps * kStepCells;
 constexpr int kPitch = kChunk + 8;             // row pitch in 16-bit elements (rows start 4 banks apart)
-constexpr int kSpan = 256;                     // channels per wave of the product kernel
+constexpr int kHalf = 128;                     // channels of one half wave's row piece: 32 lanes x 4 channels
 constexpr int kWinSide = 32;                   // side of the per-view cell map: one 32-bit word per row
 
 static_assert(kSlots * kTilePts == kPrepThreads && kNIT * kSlots == kViewBatch, "thread mapping");
@@ -102,6 +104,21 @@ __device__ __forceinline__ s16x2 half_wave_reduce(s16x2 v) {
   AURA_RED_STEP(0x118, 0xf);   // row_shr:8  -> lane 15 of every row of 16 holds the row's result
   AURA_RED_STEP(0x142, 0xa);   // row_bcast:15 into rows 1 and 3
 #undef AURA_RED_STEP
+  return v;
+}
+
+// Sum over each half of the wave with lane-shift adds (no LDS traffic): lanes 31 and 63 hold the sums.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ float dpp_add(float v) {
+  return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
+}
+
+__device__ __forceinline__ float half_wave_sum(float v) {
+  v = dpp_add<0x111, 0xf>(v);   // row_shr:1
+  v = dpp_add<0x112, 0xf>(v);   // row_shr:2
+  v = dpp_add<0x114, 0xf>(v);   // row_shr:4
+  v = dpp_add<0x118, 0xf>(v);   // row_shr:8  -> lane 15 of every row of 16 holds the row's sum
+  v = dpp_add<0x142, 0xa>(v);   // row_bcast:15 into rows 1 and 3
   return v;
 }
 
@@ -446,8 +463,9 @@ struct StepA {
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
+template <int H>
 struct StepQ {
-  u32x2 q[2][8];   // [half of the wave's channel span][cell]: 4 channels each
+  u32x2 q[H][8];   // [128-channel piece of the wave's span][cell]: 4 channels each
 };
 
 // The 16 cell offsets of a k-step are the same for every lane: they are read through the scalar
@@ -457,10 +475,20 @@ struct StepCells {
   uint32_t c[kStepCells];
 };
 
+// What the prepare kernel wrote is constant for the product kernel: reading it through the
+// constant address space keeps wave-uniform reads on the scalar unit even inside the tile loop,
+// where the compiler must otherwise assume that the stores of fused rows might alias them.
+typedef const uint32_t __attribute__((address_space(4))) * const_words;
+
+__device__ __forceinline__ const_words as_constant(const void* p) {
+  return (const_words)(uintptr_t)p;
+}
+
 __device__ __forceinline__ StepCells load_cells(const TileStep* __restrict__ st) {
+  const const_words w = as_constant(st->cell);
   StepCells k;
 #pragma unroll
-  for (int e = 0; e < kStepCells; ++e) k.c[e] = st->cell[e];
+  for (int e = 0; e < kStepCells; ++e) k.c[e] = w[e];
   return k;
 }
 
@@ -469,23 +497,24 @@ __device__ __forceinline__ void load_a(const TileStep* __restrict__ st, int lane
   r.lo = st->a_lo[lane];
 }
 
+template <int H>
 __device__ __forceinline__ void load_q(const char* __restrict__ feat, const StepCells& k, uint32_t lane_off, uint32_t g_mask,
-                                       StepQ& r) {
+                                       StepQ<H>& r) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
     // lanes 0..31 take cells 0..7, lanes 32..63 cells 8..15 (bitwise select: both offsets stay scalar)
     const uint32_t c = k.c[e] ^ ((k.c[e] ^ k.c[8 + e]) & g_mask);
-    r.q[0][e] = *reinterpret_cast<const u32x2*>(feat + (c + lane_off));
-    r.q[1][e] = *reinterpret_cast<const u32x2*>(feat + (c + lane_off + (kSpan / 2) * 2));
+#pragma unroll
+    for (int h = 0; h < H; ++h) r.q[h][e] = *reinterpret_cast<const u32x2*>(feat + (c + lane_off + h * kHalf * 2));
   }
 }
 
-// 16 matrix-core instructions of one k-step: operand t = 4 h + j holds channel 128 h + 4 m + j of
+// The matrix-core instructions of one k-step: operand t = 4 h + j holds channel 128 h + 4 m + j of
 // the 8 cells.
-template <int DT>
-__device__ __forceinline__ void mma_step(const StepA& w, const StepQ& r, f32x16 (&acc)[8]) {
+template <int DT, int H>
+__device__ __forceinline__ void mma_step(const StepA& w, const StepQ<H>& r, f32x16 (&acc)[4 * H]) {
 #pragma unroll
-  for (int t = 0; t < 8; ++t) {
+  for (int t = 0; t < 4 * H; ++t) {
     u32x4 b;
 #pragma unroll
     for (int e2 = 0; e2 < 4; ++e2) {
@@ -509,101 +538,173 @@ struct ProdArgs {
   int mean_only;
 };
 
-// DT: 1 bf16, 2 fp16 feature maps.  S waves per workgroup, D == 256 * S.
+// DT: 1 bf16, 2 fp16 feature maps.  S waves per workgroup, each owning H pieces of 128 channels:
+// D == 128 * H * S.
 //
-// Reads run ahead of the products: the weight operands (written by the prepare kernel, so they
-// come from far memory) four k-steps, the cell rows (shared with the neighbouring tiles, so mostly
-// L2 hits) two k-steps.  A tile's k-steps sit at a fixed place, so the first reads do not wait for
-// the tile header; reads beyond the tile's last k-step stay inside the tile's own run of storage
-// (the quota is at least 4) and their values are never used.
-template <int DT, int S>
+// A workgroup walks over several tiles.  Reads run ahead of the products: the weight operands
+// (written by the prepare kernel, so they come from far memory) four k-steps, the cell rows
+// (shared with the neighbouring tiles, so mostly L2 hits) two k-steps.  A tile's k-steps sit at a
+// fixed place, so nothing waits for the tile header, and the first reads of the NEXT tile (header
+// and cell offsets at the start of the current tile, weight operands and cell rows right after its
+// last product) are in flight while the current tile is normalised and stored.  Reads beyond a
+// tile's last k-step stay inside the tile's own run of storage (the quota is at least 4) and their
+// values are never used.
+//
+// Tile order: the workgroups with the same id modulo 8 run on the same XCD; XCD c owns one
+// contiguous range of the object's tiles and its workgroups take the tiles of that range round
+// robin, so that at any time the tiles in flight on an XCD are neighbours and share cell rows
+// in its L2.
+constexpr int kXcd = 8;
+constexpr int kProdGroupsMax = 512;   // two workgroups per compute unit
+
+template <int DT, int S, int H>
 __global__ __launch_bounds__(kWave* S) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k_tile_product(ProdArgs a, ObjTable tab) {
+  constexpr int kSpan = kHalf * H;   // channels per wave
   __shared__ float s_ss[S][kTilePts];
   __shared__ float s_scale[kTilePts];
 
   const ObjRange ob = tab.o[blockIdx.y];
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
-  if ((int)blockIdx.x >= nblk) return;
-  const int blk = xcd_contiguous(blockIdx.x, nblk);
-  const TileHdr* __restrict__ hdr = a.hdr + ob.tile_begin + blk;
-  const TileStep* __restrict__ st = a.steps + (long long)(ob.tile_begin + blk) * a.quota;
+  const int groups = min(nblk, (int)gridDim.x);   // workgroups that work on this object
+  if ((int)blockIdx.x >= groups) return;
+  // this workgroup's tiles: first, first + stride, ... below end
+  const int xcd = blockIdx.x % kXcd, per = nblk / kXcd, rem = nblk % kXcd;
+  const int first = xcd * per + min(xcd, rem) + (int)blockIdx.x / kXcd;
+  const int end = xcd * per + min(xcd, rem) + per + (xcd < rem ? 1 : 0);
+  const int stride = (groups - xcd + kXcd - 1) / kXcd;
+  if (first >= end) return;
+
   const int last = a.quota - 1;
-  const int tid = threadIdx.x, lane = tid % kWave, span = tid / kWave;
+  const int tid = threadIdx.x, lane = tid % kWave;
+  const int span = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave index: uniform, kept in a scalar register
   const int m = lane & 31, g = lane >> 5;
   const int D = a.D;
-  const int li0 = blk * kTilePts;
-  const uint32_t lane_off = (uint32_t)(span * kSpan + 4 * m) * 2u;   // first half; the second is kSpan bytes on
+  const uint32_t lane_off = (uint32_t)(span * kSpan + 4 * m) * 2u;   // byte offset of the lane's first piece
   const uint32_t g_mask = g ? 0xffffffffu : 0u;
 
   StepA wa[4];
-  StepQ rq[2];
+  StepQ<H> rq[2];
   StepCells kc[2];
-#pragma unroll
-  for (int j = 0; j < 4; ++j) load_a(st + j, lane, wa[j]);
+
+  // the first tile's opening reads
+  int blk = first;
+  const TileStep* __restrict__ st = a.steps + (long long)(ob.tile_begin + blk) * a.quota;
+  int n = (int)as_constant(&a.hdr[ob.tile_begin + blk].nsteps)[0];
+  int my_cnt = a.hdr[ob.tile_begin + blk].cnt[tid % kTilePts];
   kc[0] = load_cells(st);
   kc[1] = load_cells(st + 1);
-  const int n = hdr->nsteps;
-  if (n < 0) return;   // fused by the prepare kernel
-  const int my_cnt = hdr->cnt[tid % kTilePts];
-
-  f32x16 acc[8];
 #pragma unroll
-  for (int t = 0; t < 8; ++t)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
-
+  for (int j = 0; j < 4; ++j) load_a(st + j, lane, wa[j]);
   if (n > 0) load_q(a.feat, kc[0], lane_off, g_mask, rq[0]);
-  kc[0] = load_cells(st + 2);
   if (n > 1) load_q(a.feat, kc[1], lane_off, g_mask, rq[1]);
-  kc[1] = load_cells(st + 3);
-  for (int s = 0; s < n; s += 4) {
+
+  for (;;) {
+    // header of the next tile (clamped to this one at the end of the walk)
+    const int nxt = blk + stride < end ? blk + stride : blk;
+    const TileStep* __restrict__ st_next = a.steps + (long long)(ob.tile_begin + nxt) * a.quota;
+    const int n_next = (int)as_constant(&a.hdr[ob.tile_begin + nxt].nsteps)[0];
+
+    f32x16 acc[4 * H];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      if (s + j < n) {
-        mma_step<DT>(wa[j], rq[j & 1], acc);
-        if (s + j + 2 < n) load_q(a.feat, kc[j & 1], lane_off, g_mask, rq[j & 1]);
-        kc[j & 1] = load_cells(st + min(s + j + 4, last));
+    for (int t = 0; t < 4 * H; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+
+    // Groups of four k-steps without a branch inside: every group issues the same reads (indices
+    // clamped to the tile's last k-step, so a few rows are read twice at the end), which lets the
+    // wait counters before each product allow for exactly the reads issued after its operands.
+    const int nl = max(n - 1, 0);
+    kc[0] = load_cells(st + min(2, nl));
+    kc[1] = load_cells(st + min(3, nl));
+    int s = 0;
+    for (; s + 4 <= n; s += 4) {
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        mma_step<DT, H>(wa[j], rq[j & 1], acc);
+        __builtin_amdgcn_sched_barrier(0);   // keep the reads behind the products that free their registers
+        load_q(a.feat, kc[j & 1], lane_off, g_mask, rq[j & 1]);
+        kc[j & 1] = load_cells(st + min(s + j + 4, nl));
         load_a(st + min(s + j + 4, last), lane, wa[j]);
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
-  }
+    // the last one to three k-steps
+    const int left = n - s;
+    if (left >= 1) mma_step<DT, H>(wa[0], rq[0], acc);
+    if (left >= 3) load_q(a.feat, kc[0], lane_off, g_mask, rq[0]);
+    if (left >= 2) mma_step<DT, H>(wa[1], rq[1], acc);
+    if (left >= 3) mma_step<DT, H>(wa[2], rq[0], acc);
 
-  // ---- mean, L2 norm, store.  One factor per point, inv_count / max(norm of the mean, eps), is
-  // computed once and applied to the raw sums.
+    // the next tile's opening reads fly while this tile is normalised and stored
+    const int cnt_cur = my_cnt;
+    if (nxt != blk) {
+      kc[0] = load_cells(st_next);
+      kc[1] = load_cells(st_next + 1);
+      my_cnt = a.hdr[ob.tile_begin + nxt].cnt[tid % kTilePts];
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int row = 8 * (r >> 2) + 4 * g + (r & 3);
-    float ss = 0.0f;
-#pragma unroll
-    for (int t = 0; t < 8; ++t) ss = __builtin_fmaf(acc[t][r], acc[t][r], ss);
-#pragma unroll
-    for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, kWave);
-    if (m == 0) s_ss[span][row] = ss;
-  }
-  __syncthreads();
-  if (tid < kTilePts) {
-    const float inv = my_cnt > 0 ? 1.0f / (float)my_cnt : 0.0f;
-    float f = inv;
-    if (!a.mean_only) {
-      float tot = 0.0f;
-#pragma unroll
-      for (int w = 0; w < S; ++w) tot += s_ss[w][tid];
-      f = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
+      for (int j = 0; j < 4; ++j) load_a(st_next + j, lane, wa[j]);
     }
-    s_scale[tid] = f;
-  }
-  __syncthreads();
+
+    if (n >= 0) {   // n < 0: fused by the prepare kernel
+      // mean, L2 norm, store.  One factor per point, inv_count / max(norm of the mean, eps), is
+      // computed once and applied to the raw sums.
 #pragma unroll
-  for (int r = 0; r < 16; ++r) {
-    const int row = 8 * (r >> 2) + 4 * g + (r & 3);
-    if (li0 + row >= ob.n_pts) continue;
-    const float scale = s_scale[row];
-    float* o = a.fused + (ob.pt_begin + li0 + row) * D + span * kSpan + 4 * m;
-    const f32x4 v0 = {acc[0][r] * scale, acc[1][r] * scale, acc[2][r] * scale, acc[3][r] * scale};
-    const f32x4 v1 = {acc[4][r] * scale, acc[5][r] * scale, acc[6][r] * scale, acc[7][r] * scale};
-    __builtin_nontemporal_store(v0, reinterpret_cast<f32x4*>(o));
-    __builtin_nontemporal_store(v1, reinterpret_cast<f32x4*>(o + kSpan / 2));
+      for (int r = 0; r < 16; ++r) {
+        const int row = 8 * (r >> 2) + 4 * g + (r & 3);
+        float ss = 0.0f;
+#pragma unroll
+        for (int t = 0; t < 4 * H; ++t) ss = __builtin_fmaf(acc[t][r], acc[t][r], ss);
+        ss = half_wave_sum(ss);
+        if (m == 31) s_ss[span][row] = ss;
+      }
+      __syncthreads();
+      if (tid < kTilePts) {
+        const float inv = cnt_cur > 0 ? 1.0f / (float)cnt_cur : 0.0f;
+        float f = inv;
+        if (!a.mean_only) {
+          float tot = 0.0f;
+#pragma unroll
+          for (int w = 0; w < S; ++w) tot += s_ss[w][tid];
+          f = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
+        }
+        s_scale[tid] = f;
+      }
+      __syncthreads();
+    }
+    if (nxt != blk) {
+      if (n_next > 0) load_q(a.feat, kc[0], lane_off, g_mask, rq[0]);
+      if (n_next > 1) load_q(a.feat, kc[1], lane_off, g_mask, rq[1]);
+    }
+    if (n >= 0) {
+      // Buffer stores: the wave's part of the tile (rows of D floats, starting at a wave-uniform
+      // address) is described by a buffer resource whose size covers the rows that exist, so a lane
+      // only needs one 32-bit offset register and rows beyond the object's last point are dropped
+      // by the bounds check instead of by branches.
+      const int li0 = blk * kTilePts;
+      float* obase = a.fused + (ob.pt_begin + li0) * D + span * kSpan;
+      const uint32_t row_bytes = (uint32_t)D * 4u;
+      const int rows = min(kTilePts, ob.n_pts - li0);
+      const __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(obase, 0, (int)(rows * row_bytes), 0x00020000);
+      const uint32_t lane_out = (uint32_t)(4 * g) * row_bytes + (uint32_t)(4 * m) * 4u;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row0 = 8 * (r >> 2) + (r & 3);
+        const float scale = s_scale[row0 + 4 * g];
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+          const f32x4 v = {acc[4 * h][r] * scale, acc[4 * h + 1][r] * scale, acc[4 * h + 2][r] * scale, acc[4 * h + 3][r] * scale};
+          // the scalar-offset operand stays 0: with a register there, a store directly followed by
+          // an instruction that overwrites its data registers was seen to write stale lanes
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), out,
+                                                 (int)(lane_out + (uint32_t)row0 * row_bytes) + h * kHalf * 4, 0, /*streaming*/ 2);
+        }
+      }
+    }
+    if (nxt == blk) break;
+    blk = nxt;
+    st = st_next;
+    n = n_next;
   }
 }
 
@@ -636,35 +737,37 @@ TileWs fuse_tile_workspace(void* workspace, long long N, int B, int n_views) {
 
 bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes) {
   // cell coordinates travel as 16-bit pairs and cell rows as 32-bit byte offsets inside the kernels
-  return (dtype == 1 || dtype == 2) && Hf <= 32767 && Wf <= 32767 && D % kSpan == 0 && D / kSpan >= 1 &&
-         D / kSpan <= 6 && D / kSpan != 5 && feat_bytes <= 0xffffffffll;
+  return (dtype == 1 || dtype == 2) && Hf <= 32767 && Wf <= 32767 && D % 256 == 0 && D / 256 >= 1 && D / 256 <= 6 &&
+         D / 256 != 5 && feat_bytes <= 0xffffffffll;
 }
 
-template <int DT, int S>
+template <int DT, int S, int H>
 static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
                               hipStream_t stream) {
-  const dim3 grid((max_pts + kTilePts - 1) / kTilePts, n_obj);
-  hipLaunchKernelGGL((k_tile_prepare<DT>), grid, dim3(kPrepThreads), 0, stream, a, ws, tab);
+  const int max_tiles = (max_pts + kTilePts - 1) / kTilePts;
+  hipLaunchKernelGGL((k_tile_prepare<DT>), dim3(max_tiles, n_obj), dim3(kPrepThreads), 0, stream, a, ws, tab);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProdArgs pa{static_cast<const char*>(a.feat.feat), a.feat.D, ws.hdr, ws.steps, ws.quota, a.fused, a.norm_eps, a.mean_only};
-  hipLaunchKernelGGL((k_tile_product<DT, S>), grid, dim3(kWave * S), 0, stream, pa, tab);
+  // several objects in one launch share the machine: fewer workgroups per object
+  const int groups = std::max(kXcd, std::min(max_tiles, (kProdGroupsMax / n_obj + kXcd - 1) / kXcd * kXcd));
+  hipLaunchKernelGGL((k_tile_product<DT, S, H>), dim3(std::min(groups, max_tiles), n_obj), dim3(kWave * S), 0, stream, pa, tab);
   return hipGetLastError();
 }
 
 hipError_t launch_fuse_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
                             hipStream_t stream) {
-  const int S = a.feat.D / kSpan;
-#define AURA_TILE_CASE(s)                                                                  \
-  case s:                                                                                  \
-    return a.feat.dtype == 1 ? launch_tile<1, s>(a, ws, tab, n_obj, max_pts, stream)       \
-                             : launch_tile<2, s>(a, ws, tab, n_obj, max_pts, stream)
-  switch (S) {
-    AURA_TILE_CASE(1);
-    AURA_TILE_CASE(2);
-    AURA_TILE_CASE(3);
-    AURA_TILE_CASE(4);
-    AURA_TILE_CASE(6);
+  // waves x pieces per wave for each supported D (a multiple of 256)
+#define AURA_TILE_CASE(d, s, h)                                                               \
+  case d:                                                                                     \
+    return a.feat.dtype == 1 ? launch_tile<1, s, h>(a, ws, tab, n_obj, max_pts, stream)       \
+                             : launch_tile<2, s, h>(a, ws, tab, n_obj, max_pts, stream)
+  switch (a.feat.D) {
+    AURA_TILE_CASE(256, 1, 2);
+    AURA_TILE_CASE(512, 2, 2);
+    AURA_TILE_CASE(768, 3, 2);
+    AURA_TILE_CASE(1024, 4, 2);
+    AURA_TILE_CASE(1536, 6, 2);
     default: return hipErrorInvalidValue;
   }
 #undef AURA_TILE_CASE

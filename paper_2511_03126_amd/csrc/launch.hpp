@@ -46,4 +46,7 @@ hipError_t launch_property_integrate(const float* prop, int P, int p_index, cons
                                      float vol_uniform, const MassObj* objs, int B, const float* xyz, int G,
                                      float* mass, long long* n_used, void* workspace, hipStream_t stream);
 
+hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
+hipError_t launch_calibration_fill(void* dst, size_t bytes, uint32_t value, hipStream_t stream);
+
 }  // namespace aura

@@ -29,7 +29,8 @@ def _declared_functions():
 def test_every_declared_function_is_exported(B):
     names = _declared_functions()
     assert {"aura_project_visibility", "aura_fuse_features", "aura_material_scores", "aura_property_integrate",
-            "aura_workspace_bytes", "aura_version", "aura_strerror", "aura_last_hip_error"} <= set(names)
+            "aura_workspace_bytes", "aura_version", "aura_strerror", "aura_last_hip_error",
+            "aura_calibration_copy", "aura_calibration_fill"} <= set(names)
     for n in names:
         assert hasattr(B.lib(), n), n
 
@@ -130,6 +131,14 @@ def test_argument_validation_returns_status_codes(B):
     assert ms(ws=C.c_void_p(0x1010)) == -5
     cold = B.Params(temperature=0.0).c()
     assert ms(par=cold) == -2
+
+    cc = lambda dst=fake, src=fake, n=1024: L.aura_calibration_copy(dst, src, n, None)
+    assert cc(dst=None) == -1 and cc(src=None) == -1
+    assert cc(n=1000) == -2                                                # not a multiple of 16 bytes
+    assert cc(dst=C.c_void_p(0x1004)) == -4
+    assert cc(n=0, dst=None, src=None) == 0
+    cf = lambda dst=fake, n=1024: L.aura_calibration_fill(dst, n, 7, None)
+    assert cf(dst=None) == -1 and cf(n=24) == -2 and cf(dst=C.c_void_p(0x1008)) == -4 and cf(n=0, dst=None) == 0
 
     pi = lambda N=10, P=1, pidx=0, B_=1, G=0, mass=fake, ws=C.c_void_p(0x1000), wsb=1 << 30, po_=None, glo=None, gh=None, xyz=None: \
         L.aura_property_integrate(fake, N, P, pidx, None, None, 1.0, po_, B_, xyz, glo, gh, G, mass, None, ws, wsb, None)

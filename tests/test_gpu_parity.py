@@ -238,3 +238,18 @@ def test_point_volume_mode_with_per_point_volumes_and_objects(H, orc):
     ref = orc.property_integrate(prop.astype(np.float64), 1, count, vol=vol, pt_offsets=off)
     assert np.array_equal(used.cpu().numpy(), ref["n_used"])
     assert np.allclose(mass.cpu().numpy(), ref["mass"], rtol=1e-5, atol=0)
+
+
+def test_calibration_copy_and_fill_move_exactly_the_bytes_asked_for(H):
+    from paper_2511_03126_amd import binding
+    for n in (16, 4096 + 16, 3 * 1024 * 1024 + 48, 64 * 1024 * 1024):
+        src = torch.randint(0, 256, (n + 32,), dtype=torch.uint8, device="cuda:0")
+        dst = torch.full((n + 32,), 0xAB, dtype=torch.uint8, device="cuda:0")
+        binding.calibration_copy(dst[16:16 + n], src[16:16 + n])
+        torch.cuda.synchronize()
+        assert torch.equal(dst[16:16 + n], src[16:16 + n])
+        assert (dst[:16] == 0xAB).all() and (dst[16 + n:] == 0xAB).all()      # nothing outside the range
+        binding.calibration_fill(dst[16:16 + n], 0x01020304)
+        torch.cuda.synchronize()
+        assert (dst[16:16 + n].view(torch.int32) == 0x01020304).all()
+        assert (dst[:16] == 0xAB).all() and (dst[16 + n:] == 0xAB).all()
