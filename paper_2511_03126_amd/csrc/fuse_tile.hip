@@ -456,9 +456,14 @@ __device__ __forceinline__ f32x16 mma(u32x4 a, u32x4 b, f32x16 c) {
     return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-// Operands of one k-step in registers: the two weight operands, and 8 cell rows x 16 bytes.
+// Operands of one k-step in registers: the two weight operands, the lane's 8 cell offsets, and
+// 8 cell rows.
 struct StepA {
   u32x4 hi, lo;
+};
+
+struct StepC {
+  u32x4 lo, hi;   // byte offsets of the lane's cells: 8 g .. 8 g + 3 and 8 g + 4 .. 8 g + 7
 };
 
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
@@ -468,44 +473,69 @@ struct StepQ {
   u32x2 q[H][8];   // [128-channel piece of the wave's span][cell]: 4 channels each
 };
 
-// The 16 cell offsets of a k-step are the same for every lane: they are read through the scalar
-// unit, ahead of the rows they address, so that issuing a k-step's row reads never waits on a
-// vector load.
-struct StepCells {
-  uint32_t c[kStepCells];
-};
-
-// What the prepare kernel wrote is constant for the product kernel: reading it through the
-// constant address space keeps wave-uniform reads on the scalar unit even inside the tile loop,
-// where the compiler must otherwise assume that the stores of fused rows might alias them.
+// What the prepare kernel wrote is constant for the product kernel: reading the tile header
+// through the constant address space keeps the wave-uniform read on the scalar unit even inside
+// the tile loop, where the compiler must otherwise assume that the stores of fused rows alias it.
 typedef const uint32_t __attribute__((address_space(4))) * const_words;
 
-__device__ __forceinline__ const_words as_constant(const void* p) {
-  return (const_words)(uintptr_t)p;
+__device__ __forceinline__ int load_nsteps(const TileHdr* h) {
+  return (int)((const_words)(uintptr_t)&h->nsteps)[0];
 }
 
-__device__ __forceinline__ StepCells load_cells(const TileStep* __restrict__ st) {
-  const const_words w = as_constant(st->cell);
-  StepCells k;
-#pragma unroll
-  for (int e = 0; e < kStepCells; ++e) k.c[e] = w[e];
-  return k;
+// A tile's k-steps are staged in LDS before they are used (two buffers of kStage k-steps): the
+// weight operands were written by the prepare kernel and come from far memory, the copy for the
+// next tile is issued when the current tile starts and is hidden behind it.  The copy is a
+// direct global -> LDS load (no registers): one instruction moves 64 x 16 contiguous bytes.
+//
+// The copy instruction is written as inline assembly on purpose.  Issued through the compiler's
+// builtin, a copy that is still in flight makes every later wait for a vector read a wait for ALL
+// outstanding reads (the compiler cannot tell which LDS reads the copy may feed), which serialises
+// the row reads of the product loop.  Hidden from that bookkeeping, the copies only make the
+// hardware counter larger than the compiler assumes; reads complete in order, so its waits remain
+// sufficient.  The workgroup waits for the copies explicitly (wait_copies) before the barrier that
+// publishes a buffer.
+template <int S>
+constexpr int stage_steps_for() { return S == 1 ? 4 : (S == 2 ? 8 : 16); }   // keeps 8 waves per compute unit in LDS
+
+__device__ __forceinline__ void copy_64x16(const char* g, char* lds) {
+  // m0 = LDS byte address of the 1 KiB piece; lane l's 16 bytes land at m0 + 16 l
+  const uint32_t lds_addr = __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(__attribute__((address_space(3))) char*)lds);
+  uint32_t saved_m0;
+  asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_mov_b32 m0, %0"
+               : "=&s"(saved_m0) : "s"(lds_addr), "v"(g) : "memory");
 }
 
-__device__ __forceinline__ void load_a(const TileStep* __restrict__ st, int lane, StepA& r) {
+__device__ __forceinline__ void wait_copies() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+template <int S>
+__device__ __forceinline__ void stage_steps(char* lds, const TileStep* __restrict__ src, int nsteps, int span, int lane) {
+  const int bytes = nsteps * (int)sizeof(TileStep);
+  const char* g = reinterpret_cast<const char*>(src);
+  for (int piece = span; piece * 1024 < bytes; piece += S) {
+    const int off = piece * 1024 + lane * 16;
+    if (off < bytes) copy_64x16(g + off, lds + piece * 1024);
+  }
+}
+
+__device__ __forceinline__ void lds_a(const char* lds, int k, int lane, StepA& r) {
+  const TileStep* st = reinterpret_cast<const TileStep*>(lds) + k;
   r.hi = st->a_hi[lane];
   r.lo = st->a_lo[lane];
 }
 
+__device__ __forceinline__ void lds_c(const char* lds, int k, int g, StepC& r) {
+  const TileStep* st = reinterpret_cast<const TileStep*>(lds) + k;
+  r.lo = *reinterpret_cast<const u32x4*>(&st->cell[8 * g]);
+  r.hi = *reinterpret_cast<const u32x4*>(&st->cell[8 * g + 4]);
+}
+
 template <int H>
-__device__ __forceinline__ void load_q(const char* __restrict__ feat, const StepCells& k, uint32_t lane_off, uint32_t g_mask,
-                                       StepQ<H>& r) {
+__device__ __forceinline__ void load_q(const char* __restrict__ feat, const StepC& c, uint32_t lane_off, StepQ<H>& r) {
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    // lanes 0..31 take cells 0..7, lanes 32..63 cells 8..15 (bitwise select: both offsets stay scalar)
-    const uint32_t c = k.c[e] ^ ((k.c[e] ^ k.c[8 + e]) & g_mask);
+    const uint32_t cell = e < 4 ? c.lo[e] : c.hi[e - 4];
 #pragma unroll
-    for (int h = 0; h < H; ++h) r.q[h][e] = *reinterpret_cast<const u32x2*>(feat + (c + lane_off + h * kHalf * 2));
+    for (int h = 0; h < H; ++h) r.q[h][e] = *reinterpret_cast<const u32x2*>(feat + (cell + lane_off + h * kHalf * 2));
   }
 }
 
@@ -541,14 +571,13 @@ struct ProdArgs {
 // DT: 1 bf16, 2 fp16 feature maps.  S waves per workgroup, each owning H pieces of 128 channels:
 // D == 128 * H * S.
 //
-// A workgroup walks over several tiles.  Reads run ahead of the products: the weight operands
-// (written by the prepare kernel, so they come from far memory) four k-steps, the cell rows
-// (shared with the neighbouring tiles, so mostly L2 hits) two k-steps.  A tile's k-steps sit at a
-// fixed place, so nothing waits for the tile header, and the first reads of the NEXT tile (header
-// and cell offsets at the start of the current tile, weight operands and cell rows right after its
-// last product) are in flight while the current tile is normalised and stored.  Reads beyond a
-// tile's last k-step stay inside the tile's own run of storage (the quota is at least 4) and their
-// values are never used.
+// A workgroup walks over several tiles.  While a tile is multiplied, the k-steps of the next one
+// are copied into the other LDS buffer; per k-step the weight operands and cell offsets come from
+// LDS and the cell rows (shared with the neighbouring tiles, so mostly L2 hits) are read two
+// k-steps ahead of their product.  The k-steps are taken in pairs without a branch inside, so that
+// the wait counters before each product allow for exactly the reads issued after its operands.
+// The next tile's first rows are requested between the norm reduction and the stores of the
+// current tile.
 //
 // Tile order: the workgroups with the same id modulo 8 run on the same XCD; XCD c owns one
 // contiguous range of the object's tiles and its workgroups take the tiles of that range round
@@ -561,6 +590,8 @@ template <int DT, int S, int H>
 __global__ __launch_bounds__(kWave* S) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k_tile_product(ProdArgs a, ObjTable tab) {
   constexpr int kSpan = kHalf * H;   // channels per wave
+  constexpr int kStage = stage_steps_for<S>();
+  __shared__ __attribute__((aligned(16))) char s_steps[2][kStage * sizeof(TileStep)];
   __shared__ float s_ss[S][kTilePts];
   __shared__ float s_scale[kTilePts];
 
@@ -575,35 +606,46 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
   const int stride = (groups - xcd + kXcd - 1) / kXcd;
   if (first >= end) return;
 
-  const int last = a.quota - 1;
   const int tid = threadIdx.x, lane = tid % kWave;
   const int span = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave index: uniform, kept in a scalar register
   const int m = lane & 31, g = lane >> 5;
   const int D = a.D;
   const uint32_t lane_off = (uint32_t)(span * kSpan + 4 * m) * 2u;   // byte offset of the lane's first piece
-  const uint32_t g_mask = g ? 0xffffffffu : 0u;
 
-  StepA wa[4];
+  StepA wa[2];
+  StepC wc[2];
   StepQ<H> rq[2];
-  StepCells kc[2];
 
-  // the first tile's opening reads
+  // the first tile: header, k-steps into buffer 0, rows of its first two k-steps
   int blk = first;
-  const TileStep* __restrict__ st = a.steps + (long long)(ob.tile_begin + blk) * a.quota;
-  int n = (int)as_constant(&a.hdr[ob.tile_begin + blk].nsteps)[0];
+  int buf = 0;
+  int n = load_nsteps(a.hdr + ob.tile_begin + blk);
   int my_cnt = a.hdr[ob.tile_begin + blk].cnt[tid % kTilePts];
-  kc[0] = load_cells(st);
-  kc[1] = load_cells(st + 1);
-#pragma unroll
-  for (int j = 0; j < 4; ++j) load_a(st + j, lane, wa[j]);
-  if (n > 0) load_q(a.feat, kc[0], lane_off, g_mask, rq[0]);
-  if (n > 1) load_q(a.feat, kc[1], lane_off, g_mask, rq[1]);
+  int nxt = blk + stride < end ? blk + stride : blk;   // clamped to this tile at the end of the walk
+  int n_next = load_nsteps(a.hdr + ob.tile_begin + nxt);
+  stage_steps<S>(s_steps[0], a.steps + (long long)(ob.tile_begin + blk) * a.quota, min(max(n, 0), kStage), span, lane);
+  wait_copies();
+  __syncthreads();
+  if (n > 0) {
+    const int l0 = min(n, kStage) - 1;
+    lds_c(s_steps[0], 0, g, wc[0]);
+    lds_c(s_steps[0], min(1, l0), g, wc[1]);
+    load_q(a.feat, wc[0], lane_off, rq[0]);
+    load_q(a.feat, wc[1], lane_off, rq[1]);
+    lds_a(s_steps[0], 0, lane, wa[0]);
+    lds_a(s_steps[0], min(1, l0), lane, wa[1]);
+    lds_c(s_steps[0], min(2, l0), g, wc[0]);
+    lds_c(s_steps[0], min(3, l0), g, wc[1]);
+  }
 
   for (;;) {
-    // header of the next tile (clamped to this one at the end of the walk)
-    const int nxt = blk + stride < end ? blk + stride : blk;
+    const TileStep* __restrict__ st = a.steps + (long long)(ob.tile_begin + blk) * a.quota;
     const TileStep* __restrict__ st_next = a.steps + (long long)(ob.tile_begin + nxt) * a.quota;
-    const int n_next = (int)as_constant(&a.hdr[ob.tile_begin + nxt].nsteps)[0];
+    // the tile after the next: its header is read now, a full tile before it is needed
+    const int nxt2 = nxt + stride < end ? nxt + stride : nxt;
+    const int n_next2 = load_nsteps(a.hdr + ob.tile_begin + nxt2);
+    // the next tile's k-steps go to the other buffer while this tile is multiplied
+    if (nxt != blk) stage_steps<S>(s_steps[buf ^ 1], st_next, min(max(n_next, 0), kStage), span, lane);
 
     f32x16 acc[4 * H];
 #pragma unroll
@@ -611,44 +653,44 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
 
-    // Groups of four k-steps without a branch inside: every group issues the same reads (indices
-    // clamped to the tile's last k-step, so a few rows are read twice at the end), which lets the
-    // wait counters before each product allow for exactly the reads issued after its operands.
-    const int nl = max(n - 1, 0);
-    kc[0] = load_cells(st + min(2, nl));
-    kc[1] = load_cells(st + min(3, nl));
-    int s = 0;
-    for (; s + 4 <= n; s += 4) {
-#pragma unroll
-      for (int j = 0; j < 4; ++j) {
-        mma_step<DT, H>(wa[j], rq[j & 1], acc);
-        __builtin_amdgcn_sched_barrier(0);   // keep the reads behind the products that free their registers
-        load_q(a.feat, kc[j & 1], lane_off, g_mask, rq[j & 1]);
-        kc[j & 1] = load_cells(st + min(s + j + 4, nl));
-        load_a(st + min(s + j + 4, last), lane, wa[j]);
-        __builtin_amdgcn_sched_barrier(0);
+    const char* sb = s_steps[buf];
+    for (int base = 0; base < n; base += kStage) {
+      const int cnt = min(kStage, n - base), l0 = cnt - 1;
+      if (base > 0) {
+        // a tile with more k-steps than a buffer holds (rare): refill the buffer in place
+        __syncthreads();
+        stage_steps<S>(s_steps[buf], st + base, cnt, span, lane);
+        wait_copies();
+        __syncthreads();
+        lds_c(sb, 0, g, wc[0]);
+        lds_c(sb, min(1, l0), g, wc[1]);
+        load_q(a.feat, wc[0], lane_off, rq[0]);
+        load_q(a.feat, wc[1], lane_off, rq[1]);
+        lds_a(sb, 0, lane, wa[0]);
+        lds_a(sb, min(1, l0), lane, wa[1]);
+        lds_c(sb, min(2, l0), g, wc[0]);
+        lds_c(sb, min(3, l0), g, wc[1]);
       }
-    }
-    // the last one to three k-steps
-    const int left = n - s;
-    if (left >= 1) mma_step<DT, H>(wa[0], rq[0], acc);
-    if (left >= 3) load_q(a.feat, kc[0], lane_off, g_mask, rq[0]);
-    if (left >= 2) mma_step<DT, H>(wa[1], rq[1], acc);
-    if (left >= 3) mma_step<DT, H>(wa[2], rq[0], acc);
-
-    // the next tile's opening reads fly while this tile is normalised and stored
-    const int cnt_cur = my_cnt;
-    if (nxt != blk) {
-      kc[0] = load_cells(st_next);
-      kc[1] = load_cells(st_next + 1);
-      my_cnt = a.hdr[ob.tile_begin + nxt].cnt[tid % kTilePts];
+      int s = 0;
+      for (; s + 2 <= cnt; s += 2) {
 #pragma unroll
-      for (int j = 0; j < 4; ++j) load_a(st_next + j, lane, wa[j]);
+        for (int j = 0; j < 2; ++j) {
+          mma_step<DT, H>(wa[j], rq[j], acc);
+          __builtin_amdgcn_sched_barrier(0);   // keep the reads behind the products that free their registers
+          load_q(a.feat, wc[j], lane_off, rq[j]);             // rows of k-step s + j + 2
+          lds_a(sb, min(s + j + 2, l0), lane, wa[j]);
+          lds_c(sb, min(s + j + 4, l0), g, wc[j]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+      if (s < cnt) mma_step<DT, H>(wa[0], rq[0], acc);   // odd count: the last k-step
     }
 
+    // ---- mean, L2 norm, store.  One factor per point, inv_count / max(norm of the mean, eps), is
+    // computed once and applied to the raw sums.
+    const int cnt_cur = my_cnt;
+    if (nxt != blk) my_cnt = a.hdr[ob.tile_begin + nxt].cnt[tid % kTilePts];
     if (n >= 0) {   // n < 0: fused by the prepare kernel
-      // mean, L2 norm, store.  One factor per point, inv_count / max(norm of the mean, eps), is
-      // computed once and applied to the raw sums.
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = 8 * (r >> 2) + 4 * g + (r & 3);
@@ -658,23 +700,32 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
         ss = half_wave_sum(ss);
         if (m == 31) s_ss[span][row] = ss;
       }
-      __syncthreads();
-      if (tid < kTilePts) {
-        const float inv = cnt_cur > 0 ? 1.0f / (float)cnt_cur : 0.0f;
-        float f = inv;
-        if (!a.mean_only) {
-          float tot = 0.0f;
-#pragma unroll
-          for (int w = 0; w < S; ++w) tot += s_ss[w][tid];
-          f = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
-        }
-        s_scale[tid] = f;
-      }
-      __syncthreads();
     }
-    if (nxt != blk) {
-      if (n_next > 0) load_q(a.feat, kc[0], lane_off, g_mask, rq[0]);
-      if (n_next > 1) load_q(a.feat, kc[1], lane_off, g_mask, rq[1]);
+    wait_copies();
+    __syncthreads();   // also: every wave is done with this tile's buffer, the next tile's copy has landed
+    if (n >= 0 && tid < kTilePts) {
+      const float inv = cnt_cur > 0 ? 1.0f / (float)cnt_cur : 0.0f;
+      float f = inv;
+      if (!a.mean_only) {
+        float tot = 0.0f;
+#pragma unroll
+        for (int w = 0; w < S; ++w) tot += s_ss[w][tid];
+        f = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
+      }
+      s_scale[tid] = f;
+    }
+    __syncthreads();
+    if (nxt != blk && n_next > 0) {   // the next tile's opening reads fly while this tile is stored
+      const char* sn = s_steps[buf ^ 1];
+      const int l0 = min(n_next, kStage) - 1;
+      lds_c(sn, 0, g, wc[0]);
+      lds_c(sn, min(1, l0), g, wc[1]);
+      load_q(a.feat, wc[0], lane_off, rq[0]);
+      load_q(a.feat, wc[1], lane_off, rq[1]);
+      lds_a(sn, 0, lane, wa[0]);
+      lds_a(sn, min(1, l0), lane, wa[1]);
+      lds_c(sn, min(2, l0), g, wc[0]);
+      lds_c(sn, min(3, l0), g, wc[1]);
     }
     if (n >= 0) {
       // Buffer stores: the wave's part of the tile (rows of D floats, starting at a wave-uniform
@@ -683,7 +734,10 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
       // by the bounds check instead of by branches.
       const int li0 = blk * kTilePts;
       float* obase = a.fused + (ob.pt_begin + li0) * D + span * kSpan;
-      const uint32_t row_bytes = (uint32_t)D * 4u;
+      uint32_t row_bytes = (uint32_t)D * 4u;
+      // opaque to the optimiser: otherwise the 32 per-row offsets below, which do not change from tile
+      // to tile, are kept in registers across the whole tile loop and push other values into scratch
+      asm volatile("" : "+s"(row_bytes));
       const int rows = min(kTilePts, ob.n_pts - li0);
       const __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(obase, 0, (int)(rows * row_bytes), 0x00020000);
       const uint32_t lane_out = (uint32_t)(4 * g) * row_bytes + (uint32_t)(4 * m) * 4u;
@@ -703,8 +757,10 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
     }
     if (nxt == blk) break;
     blk = nxt;
-    st = st_next;
+    nxt = nxt2;
     n = n_next;
+    n_next = n_next2;
+    buf ^= 1;
   }
 }
 
