@@ -92,7 +92,7 @@ aura_status_t for_each_table(const std::vector<aura::ObjRange>& objs, F launch) 
       tab.o[t] = objs[base + t];
       max_pts = std::max(max_pts, tab.o[t].n_pts);
     }
-    aura_status_t s = hip_status(launch(tab, n, max_pts));
+    aura_status_t s = hip_status(launch(tab, n, max_pts, (int)base));
     if (s != AURA_OK) return s;
   }
   return AURA_OK;
@@ -168,7 +168,7 @@ aura_status_t aura_project_visibility(const aura_views_t* views, const aura_para
   if (N == 0) return AURA_OK;
   if (!xyz || !vis) return AURA_ERR_NULL;
   const aura::VisArgs va = vis_args(views, params);
-  return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts) {
+  return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts, int obj_base) {
     return aura::launch_project_visibility(va, xyz, vis, vis_pitch, count, uvz, tab, n, max_pts,
                                            static_cast<hipStream_t>(stream));
   });
@@ -209,7 +209,8 @@ aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t*
       return AURA_ERR_WORKSPACE;
     tws = aura::fuse_tile_workspace(workspace, N, B, views->n_views);
   }
-  return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts) {
+  return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts, int obj_base) {
+    tws.obj_base = obj_base;
     return aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only, tile ? &tws : nullptr,
                                       tab, n, max_pts, st);
   });

@@ -40,16 +40,19 @@ struct __attribute__((aligned(64))) TileStep {
 };
 
 struct TileWs {
-  TileHdr* hdr;      // [n_tiles]
-  TileStep* steps;   // [n_tiles][quota]: every tile owns a fixed run of k-steps
+  TileHdr* hdr;         // [n_tiles]
+  unsigned* counters;   // [B][8]: tiles handed out so far, per object and XCD (zeroed by the prepare kernel)
+  TileStep* steps;      // [n_tiles][quota]: every tile owns a fixed run of k-steps
   int quota;
+  int obj_base;         // index of the launch's first object within the call
 };
 
 bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes);
 size_t fuse_tile_workspace_bytes(long long N, int B, int n_views);
 // Splits a workspace of fuse_tile_workspace_bytes(N, B, n_views) bytes into its parts.
 TileWs fuse_tile_workspace(void* workspace, long long N, int B, int n_views);
-hipError_t launch_fuse_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
+hipError_t launch_fuse_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,  // ws.obj_base set
+                           
                             hipStream_t stream);
 
 }  // namespace aura

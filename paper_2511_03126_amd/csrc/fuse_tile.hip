@@ -254,6 +254,7 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
   const float px = a.xyz[3 * ip], py = a.xyz[3 * ip + 1], pz = a.xyz[3 * ip + 2];
 
   if (tid < kTilePts) s_cnt[tid] = 0;
+  if (blockIdx.x == 0 && tid < 8) ws.counters[(ws.obj_base + blockIdx.y) * 8 + tid] = 0u;   // for the product kernel
   int used = 0;   // k-steps written so far (the view batches follow one another in the tile's run)
   bool exhausted = false;
 
@@ -562,6 +563,7 @@ struct ProdArgs {
   int D;
   const TileHdr* hdr;
   const TileStep* steps;
+  unsigned* counters;   // [objects of the launch][8]
   int quota;
   float* fused;
   float norm_eps;
@@ -580,9 +582,10 @@ struct ProdArgs {
 // current tile.
 //
 // Tile order: the workgroups with the same id modulo 8 run on the same XCD; XCD c owns one
-// contiguous range of the object's tiles and its workgroups take the tiles of that range round
-// robin, so that at any time the tiles in flight on an XCD are neighbours and share cell rows
-// in its L2.
+// contiguous range of the object's tiles and its workgroups take the next tile of that range from
+// a counter (tiles differ in length, a fixed split leaves a tail), so that at any time the tiles in
+// flight on an XCD are neighbours and share cell rows in its L2.  A workgroup asks for a tile two
+// tiles ahead of using it, so the counter's round trip is never waited for.
 constexpr int kXcd = 8;
 constexpr int kProdGroupsMax = 512;   // two workgroups per compute unit
 
@@ -599,12 +602,11 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
   const int groups = min(nblk, (int)gridDim.x);   // workgroups that work on this object
   if ((int)blockIdx.x >= groups) return;
-  // this workgroup's tiles: first, first + stride, ... below end
+  // the XCD's range of tiles [r0, r0 + len) and its counter
   const int xcd = blockIdx.x % kXcd, per = nblk / kXcd, rem = nblk % kXcd;
-  const int first = xcd * per + min(xcd, rem) + (int)blockIdx.x / kXcd;
-  const int end = xcd * per + min(xcd, rem) + per + (xcd < rem ? 1 : 0);
-  const int stride = (groups - xcd + kXcd - 1) / kXcd;
-  if (first >= end) return;
+  const int r0 = xcd * per + min(xcd, rem), len = per + (xcd < rem ? 1 : 0);
+  unsigned* __restrict__ ctr = a.counters + blockIdx.y * kXcd + xcd;
+  __shared__ int s_take[2];
 
   const int tid = threadIdx.x, lane = tid % kWave;
   const int span = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave index: uniform, kept in a scalar register
@@ -616,13 +618,17 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
   StepC wc[2];
   StepQ<H> rq[2];
 
-  // the first tile: header, k-steps into buffer 0, rows of its first two k-steps
-  int blk = first;
+  // the first two tiles; then header, k-steps into buffer 0, rows of the first tile's first two k-steps
+  if (tid == 0) s_take[0] = (int)atomicAdd(ctr, 2u);
+  __syncthreads();
+  const int t0 = s_take[0];
+  if (t0 >= len) return;
+  int blk = r0 + t0;
+  int nxt = t0 + 1 < len ? blk + 1 : -1;   // -1: no further tile
   int buf = 0;
   int n = load_nsteps(a.hdr + ob.tile_begin + blk);
   int my_cnt = a.hdr[ob.tile_begin + blk].cnt[tid % kTilePts];
-  int nxt = blk + stride < end ? blk + stride : blk;   // clamped to this tile at the end of the walk
-  int n_next = load_nsteps(a.hdr + ob.tile_begin + nxt);
+  int n_next = nxt >= 0 ? load_nsteps(a.hdr + ob.tile_begin + nxt) : 0;
   stage_steps<S>(s_steps[0], a.steps + (long long)(ob.tile_begin + blk) * a.quota, min(max(n, 0), kStage), span, lane);
   wait_copies();
   __syncthreads();
@@ -640,12 +646,12 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
 
   for (;;) {
     const TileStep* __restrict__ st = a.steps + (long long)(ob.tile_begin + blk) * a.quota;
-    const TileStep* __restrict__ st_next = a.steps + (long long)(ob.tile_begin + nxt) * a.quota;
-    // the tile after the next: its header is read now, a full tile before it is needed
-    const int nxt2 = nxt + stride < end ? nxt + stride : nxt;
-    const int n_next2 = load_nsteps(a.hdr + ob.tile_begin + nxt2);
+    // ask for the tile after the next (the answer is picked up in the epilogue)
+    int asked = 0;
+    if (tid == 0 && nxt >= 0) asked = (int)atomicAdd(ctr, 1u);
     // the next tile's k-steps go to the other buffer while this tile is multiplied
-    if (nxt != blk) stage_steps<S>(s_steps[buf ^ 1], st_next, min(max(n_next, 0), kStage), span, lane);
+    if (nxt >= 0)
+      stage_steps<S>(s_steps[buf ^ 1], a.steps + (long long)(ob.tile_begin + nxt) * a.quota, min(max(n_next, 0), kStage), span, lane);
 
     f32x16 acc[4 * H];
 #pragma unroll
@@ -689,7 +695,8 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
     // ---- mean, L2 norm, store.  One factor per point, inv_count / max(norm of the mean, eps), is
     // computed once and applied to the raw sums.
     const int cnt_cur = my_cnt;
-    if (nxt != blk) my_cnt = a.hdr[ob.tile_begin + nxt].cnt[tid % kTilePts];
+    if (nxt >= 0) my_cnt = a.hdr[ob.tile_begin + nxt].cnt[tid % kTilePts];
+    if (tid == 0) s_take[buf ^ 1] = asked;
     if (n >= 0) {   // n < 0: fused by the prepare kernel
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
@@ -715,7 +722,11 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
       s_scale[tid] = f;
     }
     __syncthreads();
-    if (nxt != blk && n_next > 0) {   // the next tile's opening reads fly while this tile is stored
+    // the tile after the next: its header is read now, a full tile before it is needed
+    const int t2 = s_take[buf ^ 1];
+    const int nxt2 = (nxt >= 0 && t2 < len) ? r0 + t2 : -1;
+    const int n_next2 = nxt2 >= 0 ? load_nsteps(a.hdr + ob.tile_begin + nxt2) : 0;
+    if (nxt >= 0 && n_next > 0) {   // the next tile's opening reads fly while this tile is stored
       const char* sn = s_steps[buf ^ 1];
       const int l0 = min(n_next, kStage) - 1;
       lds_c(sn, 0, g, wc[0]);
@@ -755,7 +766,7 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
         }
       }
     }
-    if (nxt == blk) break;
+    if (nxt < 0) break;
     blk = nxt;
     nxt = nxt2;
     n = n_next;
@@ -779,15 +790,20 @@ static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 size_t fuse_tile_workspace_bytes(long long N, int B, int n_views) {
   const size_t tiles = (size_t)tile_count_bound(N, B);
-  return round256(tiles * sizeof(TileHdr)) + tiles * (size_t)steps_quota(B, n_views) * sizeof(TileStep);
+  return round256(tiles * sizeof(TileHdr)) + round256((size_t)B * 8 * sizeof(unsigned)) +
+         tiles * (size_t)steps_quota(B, n_views) * sizeof(TileStep);
 }
 
 TileWs fuse_tile_workspace(void* workspace, long long N, int B, int n_views) {
   char* base = static_cast<char*>(workspace);
   TileWs ws;
   ws.hdr = reinterpret_cast<TileHdr*>(base);
-  ws.steps = reinterpret_cast<TileStep*>(base + round256((size_t)tile_count_bound(N, B) * sizeof(TileHdr)));
+  base += round256((size_t)tile_count_bound(N, B) * sizeof(TileHdr));
+  ws.counters = reinterpret_cast<unsigned*>(base);
+  base += round256((size_t)B * 8 * sizeof(unsigned));
+  ws.steps = reinterpret_cast<TileStep*>(base);
   ws.quota = steps_quota(B, n_views);
+  ws.obj_base = 0;
   return ws;
 }
 
@@ -804,7 +820,8 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
   hipLaunchKernelGGL((k_tile_prepare<DT>), dim3(max_tiles, n_obj), dim3(kPrepThreads), 0, stream, a, ws, tab);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  ProdArgs pa{static_cast<const char*>(a.feat.feat), a.feat.D, ws.hdr, ws.steps, ws.quota, a.fused, a.norm_eps, a.mean_only};
+  ProdArgs pa{static_cast<const char*>(a.feat.feat), a.feat.D, ws.hdr, ws.steps, ws.counters + (size_t)ws.obj_base * kXcd,
+              ws.quota, a.fused, a.norm_eps, a.mean_only};
   // several objects in one launch share the machine: fewer workgroups per object
   const int groups = std::max(kXcd, std::min(max_tiles, (kProdGroupsMax / n_obj + kXcd - 1) / kXcd * kXcd));
   hipLaunchKernelGGL((k_tile_product<DT, S, H>), dim3(std::min(groups, max_tiles), n_obj), dim3(kWave * S), 0, stream, pa, tab);

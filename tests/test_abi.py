@@ -64,8 +64,8 @@ def test_workspace_sizes(B):
     assert fuse(D=100, feat_dtype=B.BF16) == 0
     assert fuse(D=1280, feat_dtype=B.F16) == 0
     tiles = 200_000 // 32 + 1
-    assert fuse(D=768, feat_dtype=B.BF16) == -(-tiles * 144 // 256) * 256 + tiles * 32 * 2112
-    assert fuse(D=768, feat_dtype=B.BF16, n_views=4) == -(-tiles * 144 // 256) * 256 + tiles * 8 * 2112
+    assert fuse(D=768, feat_dtype=B.BF16) == -(-tiles * 144 // 256) * 256 + 256 + tiles * 32 * 2112
+    assert fuse(D=768, feat_dtype=B.BF16, n_views=4) == -(-tiles * 144 // 256) * 256 + 256 + tiles * 8 * 2112
     with pytest.raises(B.AuraError) as e:
         fuse(D=768, feat_dtype=9)
     assert e.value.status == -3
