@@ -57,6 +57,30 @@ def cpu_baseline(scene, seconds_target=15.0):
             "sample": f"first {n} points of object 0 x {v1} views, whole path, {t:.1f} s"}
 
 
+CAL_BYTES = 256 << 20   # size of the calibration copy (read) and of its destination (write)
+
+
+def calibrate(torch, reps=10):
+    """What the memory system gives the plainest kernels: the library's copy and fill over 256 MiB, timed
+    outside the benchmark's timed region.  A profiler run of this file therefore always holds launches of a
+    copy kernel of known size (CAL_BYTES read, CAL_BYTES written) to scale its byte counters by."""
+    from paper_2511_03126_amd import binding
+    src = torch.zeros(CAL_BYTES, dtype=torch.uint8, device="cuda")
+    dst = torch.empty(CAL_BYTES, dtype=torch.uint8, device="cuda")
+    out = {"bytes": CAL_BYTES}
+    for name, fn, moved in (("copy", lambda: binding.calibration_copy(dst, src), 2 * CAL_BYTES),
+                            ("fill", lambda: binding.calibration_fill(dst, 0), CAL_BYTES)):
+        fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name + "_GBps"] = moved / (e0.elapsed_time(e1) * 1e-3 / reps) / 1e9
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -76,6 +100,7 @@ def main():
 
     s = make_scene(args.workload)
     d = H.DeviceScene(s)
+    calibration = calibrate(torch)
     for _ in range(max(args.warmup, 0)):
         d.step()
     torch.cuda.synchronize()
@@ -116,6 +141,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
                      "algorithmic_bytes": fuse_bytes, "avg_launch_ms": call_ms["fuse_features"]},
+        "calibration": calibration,
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(s)
