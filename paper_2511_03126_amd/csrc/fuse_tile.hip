@@ -34,8 +34,8 @@
 // each lane reads two 8-byte pieces (4 channels each, 128 channels apart) of 8 cell rows straight
 // from global memory (the rows of a tile's neighbours keep them in L2), regroups them with byte
 // permutes into the 8 B-operands and issues v_mfma_f32_32x32x16 with the hi and the lo weights.
-// No LDS and no barrier inside the loop; reads run several k-steps ahead of the products.  Then
-// mean, L2 norm (half-wave reduction, across the waves through LDS) and streaming stores.
+// No barrier inside the loop; reads run two k-steps ahead of the products.  Then mean, L2 norm
+// (half-wave reduction, across the waves through LDS) and streaming stores.
 // Accumulator t = 4 h + j, register r of lane l is point 8 (r/4) + 4 (l/32) + r%4, channel
 // 256 s + 128 h + 4 (l%32) + j: a store instruction writes 16 bytes per lane and the 32 lanes of
 // a half wave cover 512 contiguous bytes of a row (full cache lines; writing 16 of every 32
@@ -496,7 +496,7 @@ __device__ __forceinline__ int load_nsteps(const TileHdr* h) {
 // sufficient.  The workgroup waits for the copies explicitly (wait_copies) before the barrier that
 // publishes a buffer.
 template <int S>
-constexpr int stage_steps_for() { return S == 1 ? 4 : (S == 2 ? 8 : 16); }   // keeps 8 waves per compute unit in LDS
+constexpr int stage_steps_for() { return S == 1 ? 4 : (S == 2 ? 8 : 16); }   // S: units of 256 channels   // keeps 8 waves per compute unit in LDS
 
 __device__ __forceinline__ void copy_64x16(const char* g, char* lds) {
   // m0 = LDS byte address of the 1 KiB piece; lane l's 16 bytes land at m0 + 16 l
@@ -571,32 +571,58 @@ struct ProdArgs {
 };
 
 // DT: 1 bf16, 2 fp16 feature maps.  S waves per workgroup, each owning H pieces of 128 channels:
-// D == 128 * H * S.
+// D == 128 * H * S.  PF: k-steps whose cell rows are requested ahead of their products.
 //
 // A workgroup walks over several tiles.  While a tile is multiplied, the k-steps of the next one
 // are copied into the other LDS buffer; per k-step the weight operands and cell offsets come from
-// LDS and the cell rows (shared with the neighbouring tiles, so mostly L2 hits) are read two
-// k-steps ahead of their product.  The k-steps are taken in pairs without a branch inside, so that
-// the wait counters before each product allow for exactly the reads issued after its operands.
-// The next tile's first rows are requested between the norm reduction and the stores of the
-// current tile.
+// LDS and the cell rows (shared with the neighbouring tiles, so mostly L2 hits) are read PF
+// k-steps ahead of their product.  The k-steps are taken in groups of PF without a branch inside, so
+// that the wait counters before each product allow for exactly the reads issued after its operands.
+// A tile has one barrier (after its products); nothing in the tile loop waits for a round trip to memory
+// that was started in the same tile:
+//   * the ticket of a tile (see below) is asked for three tiles ahead,
+//   * the length of its list is read two tiles ahead (a vector read: a scalar read would share its
+//     counter with the LDS reads and stall them),
+//   * its k-steps are copied one tile ahead,
+//   * its first rows are requested right after the previous tile's stores.
+// Memory operations inside the loop are unconditional (reads for a tile that does not exist go to cell 0,
+// stores of rows that do not exist are dropped by the buffer bounds check): behind a branch the compiler
+// has to assume the worst about outstanding operations and waits for all of them.
 //
 // Tile order: the workgroups with the same id modulo 8 run on the same XCD; XCD c owns one
 // contiguous range of the object's tiles and its workgroups take the next tile of that range from
 // a counter (tiles differ in length, a fixed split leaves a tail), so that at any time the tiles in
-// flight on an XCD are neighbours and share cell rows in its L2.  A workgroup asks for a tile two
-// tiles ahead of using it, so the counter's round trip is never waited for.
+// flight on an XCD are neighbours and share cell rows in its L2.
 constexpr int kXcd = 8;
-constexpr int kProdGroupsMax = 512;   // two workgroups per compute unit
+constexpr int kProdGroupsMax = 768;   // two workgroups fit a compute unit at a time; the rest take over as the first run out of tiles
 
-template <int DT, int S, int H>
-__global__ __launch_bounds__(kWave* S) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// The opening reads of a tile whose k-steps are staged at `sb` (n of them, possibly none): the rows of its
+// first PF k-steps and the weights of its first k-step.  With nothing staged the reads go to cell 0 and are
+// not used.
+template <int H, int PF>
+__device__ __forceinline__ void open_tile(const char* sb, int n_staged, const char* __restrict__ feat, uint32_t lane_off,
+                                          int lane, int g, StepA (&wa)[2], StepQ<H> (&rq)[PF]) {
+  const uint32_t on = n_staged > 0 ? 0xffffffffu : 0u;
+  const int l0 = max(n_staged - 1, 0);
+#pragma unroll
+  for (int j = 0; j < PF; ++j) {
+    StepC c;
+    lds_c(sb, min(j, l0), g, c);
+    c.lo &= on;
+    c.hi &= on;
+    load_q(feat, c, lane_off, rq[j]);
+  }
+  lds_a(sb, 0, lane, wa[0]);
+}
+
+template <int DT, int S, int H, int PF>
+__global__ __launch_bounds__(kWave* S) __attribute__((amdgpu_waves_per_eu(H == 1 ? 3 : 2, H == 1 ? 3 : 2)))
 void k_tile_product(ProdArgs a, ObjTable tab) {
   constexpr int kSpan = kHalf * H;   // channels per wave
-  constexpr int kStage = stage_steps_for<S>();
+  constexpr int kStage = stage_steps_for<S * H / 2>();
   __shared__ __attribute__((aligned(16))) char s_steps[2][kStage * sizeof(TileStep)];
-  __shared__ float s_ss[S][kTilePts];
-  __shared__ float s_scale[kTilePts];
+  __shared__ float s_ss[2][S][kTilePts];   // [tile parity]: a wave may write the next tile's sums while another still reads
+  __shared__ int s_take[2];
 
   const ObjRange ob = tab.o[blockIdx.y];
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
@@ -606,7 +632,7 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
   const int xcd = blockIdx.x % kXcd, per = nblk / kXcd, rem = nblk % kXcd;
   const int r0 = xcd * per + min(xcd, rem), len = per + (xcd < rem ? 1 : 0);
   unsigned* __restrict__ ctr = a.counters + blockIdx.y * kXcd + xcd;
-  __shared__ int s_take[2];
+  const TileHdr* __restrict__ hdrs = a.hdr + ob.tile_begin;
 
   const int tid = threadIdx.x, lane = tid % kWave;
   const int span = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave index: uniform, kept in a scalar register
@@ -614,44 +640,38 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
   const int D = a.D;
   const uint32_t lane_off = (uint32_t)(span * kSpan + 4 * m) * 2u;   // byte offset of the lane's first piece
 
-  StepA wa[2];
-  StepC wc[2];
-  StepQ<H> rq[2];
+  StepA wa[2];      // weight operands of the current and the next k-step
+  StepC wc;         // cell offsets of the k-step whose rows are requested next
+  StepQ<H> rq[PF];  // cell rows of the next PF k-steps
 
-  // the first two tiles; then header, k-steps into buffer 0, rows of the first tile's first two k-steps
-  if (tid == 0) s_take[0] = (int)atomicAdd(ctr, 2u);
+  // The first three tiles.  In the loop, a tile's ticket is asked for three tiles ahead, the length of its
+  // list is read two tiles ahead and its k-steps are copied one tile ahead, so that none of the three
+  // round trips is waited for.
+  if (tid == 0) s_take[0] = (int)atomicAdd(ctr, 3u);
   __syncthreads();
   const int t0 = s_take[0];
   if (t0 >= len) return;
   int blk = r0 + t0;
-  int nxt = t0 + 1 < len ? blk + 1 : -1;   // -1: no further tile
+  int nxt = t0 + 1 < len ? blk + 1 : -1;    // -1: no further tile
+  int nxt2 = t0 + 2 < len ? blk + 2 : -1;
   int buf = 0;
-  int n = load_nsteps(a.hdr + ob.tile_begin + blk);
-  int my_cnt = a.hdr[ob.tile_begin + blk].cnt[tid % kTilePts];
-  int n_next = nxt >= 0 ? load_nsteps(a.hdr + ob.tile_begin + nxt) : 0;
+  int n = load_nsteps(hdrs + blk);
+  int n_next = nxt >= 0 ? load_nsteps(hdrs + nxt) : 0;
+  int pend_n = hdrs[max(nxt2, 0)].nsteps;   // list length of the tile after the next, picked up one tile later
   stage_steps<S>(s_steps[0], a.steps + (long long)(ob.tile_begin + blk) * a.quota, min(max(n, 0), kStage), span, lane);
   wait_copies();
   __syncthreads();
-  if (n > 0) {
-    const int l0 = min(n, kStage) - 1;
-    lds_c(s_steps[0], 0, g, wc[0]);
-    lds_c(s_steps[0], min(1, l0), g, wc[1]);
-    load_q(a.feat, wc[0], lane_off, rq[0]);
-    load_q(a.feat, wc[1], lane_off, rq[1]);
-    lds_a(s_steps[0], 0, lane, wa[0]);
-    lds_a(s_steps[0], min(1, l0), lane, wa[1]);
-    lds_c(s_steps[0], min(2, l0), g, wc[0]);
-    lds_c(s_steps[0], min(3, l0), g, wc[1]);
-  }
+  open_tile<H, PF>(s_steps[0], min(max(n, 0), kStage), a.feat, lane_off, lane, g, wa, rq);
 
-  for (;;) {
+  while (blk >= 0) {
     const TileStep* __restrict__ st = a.steps + (long long)(ob.tile_begin + blk) * a.quota;
-    // ask for the tile after the next (the answer is picked up in the epilogue)
+    // ask for the tile three tiles ahead (the answer is picked up after this tile's products)
     int asked = 0;
-    if (tid == 0 && nxt >= 0) asked = (int)atomicAdd(ctr, 1u);
+    if (tid == 0 && nxt2 >= 0) asked = (int)atomicAdd(ctr, 1u);
     // the next tile's k-steps go to the other buffer while this tile is multiplied
-    if (nxt >= 0)
-      stage_steps<S>(s_steps[buf ^ 1], a.steps + (long long)(ob.tile_begin + nxt) * a.quota, min(max(n_next, 0), kStage), span, lane);
+    stage_steps<S>(s_steps[buf ^ 1], a.steps + (long long)(ob.tile_begin + max(nxt, 0)) * a.quota,
+                   nxt >= 0 ? min(max(n_next, 0), kStage) : 0, span, lane);
+    const int my_cnt = hdrs[blk].cnt[tid % kTilePts];   // views that see point (lane % 32) of this tile
 
     f32x16 acc[4 * H];
 #pragma unroll
@@ -668,94 +688,84 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
         stage_steps<S>(s_steps[buf], st + base, cnt, span, lane);
         wait_copies();
         __syncthreads();
-        lds_c(sb, 0, g, wc[0]);
-        lds_c(sb, min(1, l0), g, wc[1]);
-        load_q(a.feat, wc[0], lane_off, rq[0]);
-        load_q(a.feat, wc[1], lane_off, rq[1]);
-        lds_a(sb, 0, lane, wa[0]);
-        lds_a(sb, min(1, l0), lane, wa[1]);
-        lds_c(sb, min(2, l0), g, wc[0]);
-        lds_c(sb, min(3, l0), g, wc[1]);
+        open_tile<H, PF>(sb, cnt, a.feat, lane_off, lane, g, wa, rq);
       }
+      // k-steps in groups of PF without a branch inside: rows of k-step s + j + PF are requested right after
+      // the products of k-step s + j have freed their registers (requests past the end repeat the last k-step)
       int s = 0;
-      for (; s + 2 <= cnt; s += 2) {
+      for (; s + PF <= cnt; s += PF) {
 #pragma unroll
-        for (int j = 0; j < 2; ++j) {
-          mma_step<DT, H>(wa[j], rq[j], acc);
+        for (int j = 0; j < PF; ++j) {
+          lds_c(sb, min(s + j + PF, l0), g, wc);
+          lds_a(sb, min(s + j + 1, l0), lane, wa[(j + 1) & 1]);
+          mma_step<DT, H>(wa[j & 1], rq[j], acc);
           __builtin_amdgcn_sched_barrier(0);   // keep the reads behind the products that free their registers
-          load_q(a.feat, wc[j], lane_off, rq[j]);             // rows of k-step s + j + 2
-          lds_a(sb, min(s + j + 2, l0), lane, wa[j]);
-          lds_c(sb, min(s + j + 4, l0), g, wc[j]);
+          load_q(a.feat, wc, lane_off, rq[j]);
           __builtin_amdgcn_sched_barrier(0);
         }
       }
-      if (s < cnt) mma_step<DT, H>(wa[0], rq[0], acc);   // odd count: the last k-step
+      // the last cnt - s < PF k-steps: their rows are there (or on the way), nothing more to request
+#pragma unroll
+      for (int j = 0; j < PF - 1; ++j) {
+        if (s + j < cnt) {
+          lds_a(sb, min(s + j + 1, l0), lane, wa[(j + 1) & 1]);
+          mma_step<DT, H>(wa[j & 1], rq[j], acc);
+        }
+      }
     }
 
-    // ---- mean, L2 norm, store.  One factor per point, inv_count / max(norm of the mean, eps), is
-    // computed once and applied to the raw sums.
-    const int cnt_cur = my_cnt;
-    if (nxt >= 0) my_cnt = a.hdr[ob.tile_begin + nxt].cnt[tid % kTilePts];
-    if (tid == 0) s_take[buf ^ 1] = asked;
-    if (n >= 0) {   // n < 0: fused by the prepare kernel
+    // ---- sums of squares of the wave's channels, per point
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = 8 * (r >> 2) + 4 * g + (r & 3);
-        float ss = 0.0f;
+    for (int r = 0; r < 16; ++r) {
+      const int row = 8 * (r >> 2) + 4 * g + (r & 3);
+      float ss = 0.0f;
 #pragma unroll
-        for (int t = 0; t < 4 * H; ++t) ss = __builtin_fmaf(acc[t][r], acc[t][r], ss);
-        ss = half_wave_sum(ss);
-        if (m == 31) s_ss[span][row] = ss;
-      }
+      for (int t = 0; t < 4 * H; ++t) ss = __builtin_fmaf(acc[t][r], acc[t][r], ss);
+      ss = half_wave_sum(ss);
+      if (m == 31) s_ss[buf][span][row] = ss;
     }
+    if (tid == 0) s_take[buf] = asked;
+    const int n_next2 = __builtin_amdgcn_readfirstlane(pend_n);
     wait_copies();
-    __syncthreads();   // also: every wave is done with this tile's buffer, the next tile's copy has landed
-    if (n >= 0 && tid < kTilePts) {
-      const float inv = cnt_cur > 0 ? 1.0f / (float)cnt_cur : 0.0f;
-      float f = inv;
-      if (!a.mean_only) {
-        float tot = 0.0f;
+    __syncthreads();   // the one barrier of a tile: sums, ticket and the next tile's k-steps are in LDS; every
+                       // wave is done with this tile's buffer
+
+    // the tile three ahead: its list length is requested now and read after the next tile's products
+    const int t3 = s_take[buf];
+    const int nxt3 = (nxt2 >= 0 && t3 < len) ? r0 + t3 : -1;
+    pend_n = hdrs[max(nxt3, 0)].nsteps;
+
+    // ---- mean and L2 norm: one factor per point, inv_count / max(norm of the mean, eps), applied to the raw
+    // sums.  Lane l of every wave computes the factor of point l % 32; a lane fetches the factors of its 16
+    // rows from those lanes.
+    float factor;
+    {
+      const float inv = my_cnt > 0 ? 1.0f / (float)my_cnt : 0.0f;
+      float tot = 0.0f;
 #pragma unroll
-        for (int w = 0; w < S; ++w) tot += s_ss[w][tid];
-        f = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
-      }
-      s_scale[tid] = f;
+      for (int w = 0; w < S; ++w) tot += s_ss[buf][w][m];
+      const float normed = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
+      factor = a.mean_only ? inv : normed;
     }
-    __syncthreads();
-    // the tile after the next: its header is read now, a full tile before it is needed
-    const int t2 = s_take[buf ^ 1];
-    const int nxt2 = (nxt >= 0 && t2 < len) ? r0 + t2 : -1;
-    const int n_next2 = nxt2 >= 0 ? load_nsteps(a.hdr + ob.tile_begin + nxt2) : 0;
-    if (nxt >= 0 && n_next > 0) {   // the next tile's opening reads fly while this tile is stored
-      const char* sn = s_steps[buf ^ 1];
-      const int l0 = min(n_next, kStage) - 1;
-      lds_c(sn, 0, g, wc[0]);
-      lds_c(sn, min(1, l0), g, wc[1]);
-      load_q(a.feat, wc[0], lane_off, rq[0]);
-      load_q(a.feat, wc[1], lane_off, rq[1]);
-      lds_a(sn, 0, lane, wa[0]);
-      lds_a(sn, min(1, l0), lane, wa[1]);
-      lds_c(sn, min(2, l0), g, wc[0]);
-      lds_c(sn, min(3, l0), g, wc[1]);
-    }
-    if (n >= 0) {
+    {
       // Buffer stores: the wave's part of the tile (rows of D floats, starting at a wave-uniform
       // address) is described by a buffer resource whose size covers the rows that exist, so a lane
-      // only needs one 32-bit offset register and rows beyond the object's last point are dropped
-      // by the bounds check instead of by branches.
+      // only needs one 32-bit offset register and rows beyond the object's last point (or all rows, for
+      // a tile that the prepare kernel fused itself: n < 0) are dropped by the bounds check instead of by
+      // branches.
       const int li0 = blk * kTilePts;
       float* obase = a.fused + (ob.pt_begin + li0) * D + span * kSpan;
       uint32_t row_bytes = (uint32_t)D * 4u;
       // opaque to the optimiser: otherwise the 32 per-row offsets below, which do not change from tile
       // to tile, are kept in registers across the whole tile loop and push other values into scratch
       asm volatile("" : "+s"(row_bytes));
-      const int rows = min(kTilePts, ob.n_pts - li0);
+      const int rows = n >= 0 ? min(kTilePts, ob.n_pts - li0) : 0;
       const __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(obase, 0, (int)(rows * row_bytes), 0x00020000);
       const uint32_t lane_out = (uint32_t)(4 * g) * row_bytes + (uint32_t)(4 * m) * 4u;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row0 = 8 * (r >> 2) + (r & 3);
-        const float scale = s_scale[row0 + 4 * g];
+        const float scale = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (row0 + 4 * g), __float_as_int(factor)));
 #pragma unroll
         for (int h = 0; h < H; ++h) {
           const f32x4 v = {acc[4 * h][r] * scale, acc[4 * h + 1][r] * scale, acc[4 * h + 2][r] * scale, acc[4 * h + 3][r] * scale};
@@ -766,9 +776,15 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
         }
       }
     }
-    if (nxt < 0) break;
+    // The next tile's opening reads.  They are issued after the stores: the counter of outstanding memory
+    // operations is in order, and with the stores behind them the compiler's wait before the first product
+    // would cover every read at once instead of one k-step at a time.
+    __builtin_amdgcn_sched_barrier(0);
+    open_tile<H, PF>(s_steps[buf ^ 1], nxt >= 0 ? min(max(n_next, 0), kStage) : 0, a.feat, lane_off, lane, g, wa, rq);
+
     blk = nxt;
     nxt = nxt2;
+    nxt2 = nxt3;
     n = n_next;
     n_next = n_next2;
     buf ^= 1;
@@ -813,7 +829,7 @@ bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes)
          D / 256 != 5 && feat_bytes <= 0xffffffffll;
 }
 
-template <int DT, int S, int H>
+template <int DT, int S, int H, int PF>
 static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
                               hipStream_t stream) {
   const int max_tiles = (max_pts + kTilePts - 1) / kTilePts;
@@ -824,23 +840,23 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
               ws.quota, a.fused, a.norm_eps, a.mean_only};
   // several objects in one launch share the machine: fewer workgroups per object
   const int groups = std::max(kXcd, std::min(max_tiles, (kProdGroupsMax / n_obj + kXcd - 1) / kXcd * kXcd));
-  hipLaunchKernelGGL((k_tile_product<DT, S, H>), dim3(std::min(groups, max_tiles), n_obj), dim3(kWave * S), 0, stream, pa, tab);
+  hipLaunchKernelGGL((k_tile_product<DT, S, H, PF>), dim3(std::min(groups, max_tiles), n_obj), dim3(kWave * S), 0, stream, pa, tab);
   return hipGetLastError();
 }
 
 hipError_t launch_fuse_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
                             hipStream_t stream) {
-  // waves x pieces per wave for each supported D (a multiple of 256)
-#define AURA_TILE_CASE(d, s, h)                                                               \
+  // waves x pieces of 128 channels per wave x k-steps of rows requested ahead, for each supported D
+#define AURA_TILE_CASE(d, s, h, pf)                                                           \
   case d:                                                                                     \
-    return a.feat.dtype == 1 ? launch_tile<1, s, h>(a, ws, tab, n_obj, max_pts, stream)       \
-                             : launch_tile<2, s, h>(a, ws, tab, n_obj, max_pts, stream)
+    return a.feat.dtype == 1 ? launch_tile<1, s, h, pf>(a, ws, tab, n_obj, max_pts, stream)   \
+                             : launch_tile<2, s, h, pf>(a, ws, tab, n_obj, max_pts, stream)
   switch (a.feat.D) {
-    AURA_TILE_CASE(256, 1, 2);
-    AURA_TILE_CASE(512, 2, 2);
-    AURA_TILE_CASE(768, 3, 2);
-    AURA_TILE_CASE(1024, 4, 2);
-    AURA_TILE_CASE(1536, 6, 2);
+    AURA_TILE_CASE(256, 1, 2, 2);
+    AURA_TILE_CASE(512, 2, 2, 2);
+    AURA_TILE_CASE(768, 3, 2, 2);
+    AURA_TILE_CASE(1024, 4, 2, 2);
+    AURA_TILE_CASE(1536, 6, 2, 2);
     default: return hipErrorInvalidValue;
   }
 #undef AURA_TILE_CASE
