@@ -2,10 +2,11 @@
 """Benchmark of the fusion hot path on one MI355X.
 
 One step = one pass of the whole path over one synthetic scene already resident in HBM:
-aura_project_visibility -> aura_fuse_features -> aura_material_scores -> aura_property_integrate.
+aura_project_visibility -> aura_fuse_scores (fusion, then scoring) -> aura_property_integrate
+(--staged: aura_fuse_features and aura_material_scores as two calls instead).
 Prints ONE JSON line: whole-path throughput in fused point-views per second, the roofline figure
-of the dominant kernel (the fusion gather, HBM bound) measured with events on the launch stream
-inside the timed region, and the CPU oracle timed on a bounded sample of the same workload.
+of the dominant call (the fusion, HBM bound on writing the fused rows) measured with events on the
+launch stream inside the timed region, and the CPU oracle timed on a bounded sample of the same workload.
 """
 import argparse
 import json
@@ -25,6 +26,11 @@ def fuse_algorithmic_bytes(s):
     elt = 4 if s.feat_dtype == "f32" else 2
     return (12 * s.N + 64 * s.n_views + 4 * s.n_views * s.H * s.W + elt * s.n_views * s.Hf * s.Wf * s.D
             + 4 * s.N * s.D + 4 * s.N)
+
+
+def scores_algorithmic_bytes(s):
+    """Embeddings read once; scores, properties and labels written once (the fused rows are not read back)."""
+    return 4 * s.K * s.D + 4 * s.N * s.K + 4 * s.N * s.P + 4 * s.N
 
 
 def cpu_baseline(scene, seconds_target=15.0):
@@ -88,6 +94,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--staged", action="store_true", help="fusion and scoring as two library calls")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (the path shards by points; see DESIGN.md); "
@@ -101,12 +108,17 @@ def main():
     s = make_scene(args.workload)
     d = H.DeviceScene(s)
     calibration = calibrate(torch)
+    if args.staged:
+        names = ["project_visibility", "fuse_features", "material_scores", "property_integrate"]
+        calls = [d.project_visibility, d.fuse_features, d.material_scores, d.property_integrate]
+    else:
+        names = ["project_visibility", "fuse_scores", "property_integrate"]
+        calls = [d.project_visibility, d.fuse_scores, d.property_integrate]
     for _ in range(max(args.warmup, 0)):
-        d.step()
+        for call in calls:
+            call()
     torch.cuda.synchronize()
 
-    names = ["project_visibility", "fuse_features", "material_scores", "property_integrate"]
-    calls = [d.project_visibility, d.fuse_features, d.material_scores, d.property_integrate]
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -122,12 +134,16 @@ def main():
     call_ms = {n: sum(ev[k][c].elapsed_time(ev[k][c + 1]) for k in range(args.steps)) / args.steps
                for c, n in enumerate(names)}
     pv = s.point_views
-    fuse_bytes = fuse_algorithmic_bytes(s)
-    achieved = fuse_bytes / (call_ms["fuse_features"] * 1e-3) / 1e9
-    gpu = d.results()
     tile = d.ws_fuse is not None
-    kernel = "aura_fuse_features: " + (f"k_tile_prepare + k_tile_product<{s.feat_dtype}, {s.D // 256} waves>" if tile
-                                       else "k_fuse_gather")
+    fuse_call = "fuse_features" if args.staged else "fuse_scores"
+    fuse_bytes = fuse_algorithmic_bytes(s) + (0 if args.staged else scores_algorithmic_bytes(s))
+    achieved = fuse_bytes / (call_ms[fuse_call] * 1e-3) / 1e9
+    gpu = d.results()
+    kernel = f"aura_{fuse_call}: " + (f"k_tile_prepare + k_tile_product<{s.feat_dtype}, {s.D // 256} waves>" if tile
+                                      else "k_fuse_gather")
+    if not args.staged:
+        by_cells = tile and s.n_views * s.Hf * s.Wf <= s.N
+        kernel += " + k_cell_scores + k_tile_scores" if by_cells else " + k_split_embeddings + k_material_scores"
     out = {
         "metric": "fused point-views/sec", "value": pv / (ms_per_step * 1e-3), "unit": "point-views/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -140,7 +156,7 @@ def main():
         "calls_ms": call_ms,
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
-                     "algorithmic_bytes": fuse_bytes, "avg_launch_ms": call_ms["fuse_features"]},
+                     "algorithmic_bytes": fuse_bytes, "avg_launch_ms": call_ms[fuse_call]},
         "calibration": calibration,
     }
     if not args.no_cpu_baseline:

@@ -8,6 +8,7 @@
  *   aura_fuse_features        Sec. 3.1 "Feature Aggregation", Eq. 2 (+ L2 normalisation, implied
  *                             by the cosine similarity of Sec. 3.4.1)
  *   aura_material_scores      Sec. 3.4.1: similarity omega_k and the kernel regression of Eq. 4
+ *   aura_fuse_scores          the two calls above in one (Eq. 2, then Sec. 3.4.1 / Eq. 4)
  *   aura_property_integrate   Sec. 3.4.2: voxel integration over volumes (mass)
  *
  * General rules
@@ -67,7 +68,8 @@ enum {
 };
 
 /* Which call a workspace size is asked for. */
-enum { AURA_CALL_MATERIAL_SCORES = 1, AURA_CALL_PROPERTY_INTEGRATE = 2, AURA_CALL_FUSE_FEATURES = 3 };
+enum { AURA_CALL_MATERIAL_SCORES = 1, AURA_CALL_PROPERTY_INTEGRATE = 2, AURA_CALL_FUSE_FEATURES = 3,
+       AURA_CALL_FUSE_SCORES = 4 };
 
 /* Problem sizes for aura_workspace_bytes; fields a call does not list are ignored. */
 typedef struct aura_sizes_t {
@@ -123,6 +125,7 @@ int32_t aura_last_hip_error(void);
  *   AURA_CALL_MATERIAL_SCORES     D, K
  *   AURA_CALL_PROPERTY_INTEGRATE  N, B, G
  *   AURA_CALL_FUSE_FEATURES       N, B, n_views, Hf, Wf, D, feat_dtype
+ *   AURA_CALL_FUSE_SCORES         N, B, n_views, Hf, Wf, D, feat_dtype, K
  * Errors: AURA_ERR_NULL (sizes, bytes), AURA_ERR_SHAPE, AURA_ERR_DTYPE, AURA_ERR_UNSUPPORTED
  * (unknown call, or sizes beyond the limits of the call).
  */
@@ -199,6 +202,35 @@ aura_status_t aura_material_scores(const float* fused, int64_t N, int32_t D,
                                    const float* y, int32_t P, const aura_params_t* params,
                                    float* scores, float* prop, int32_t* label,
                                    void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sec. 3.1 Eq. 2 followed by Sec. 3.4.1 / Eq. 4 in one call: everything aura_fuse_features writes
+ * (fused, count) and everything aura_material_scores writes (scores, prop, label) for the same
+ * points, with the arguments and rules of those two calls.
+ *
+ * The similarity omega_k = <f, t_k> is linear in f, and the fused feature is a weighted sum of
+ * feature cells.  Where the fusion runs on the matrix cores (see aura_fuse_features) and the call has
+ * no more feature cells (n_views * Hf * Wf) than points, the library therefore first computes the
+ * similarity of every feature cell to every material and then applies the fusion weights of each
+ * point to those K numbers instead of to the D channels; the fused rows are written but never read
+ * back.  This is the same sum in another order: scores agree with
+ * aura_material_scores(aura_fuse_features(...)) up to fp32 rounding (the per-cell similarities and the
+ * weights are carried as two 16-bit terms each, about 16 mantissa bits).  In every other case the
+ * call is exactly the two calls in sequence.
+ *
+ *   fused  [device] [N][D] fp32, 16-byte aligned (required)    count [device] [N] int32 or NULL
+ *   temb   [device] [K][D] fp32 (temb_dtype must be AURA_F32)  y     [device] [K][P] fp32 or NULL
+ *   scores [device] [N][K] fp32   prop [device] [N][P] fp32 or NULL (needs y)   label [device] [N] or NULL
+ *   workspace [device] aura_workspace_bytes(AURA_CALL_FUSE_SCORES, ...) bytes, 256-byte aligned (required)
+ * Limits: 1 <= K <= 128, 1 <= P <= 8.
+ * Errors: those of aura_fuse_features and aura_material_scores.
+ */
+aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* params,
+                               const float* xyz, int64_t N,
+                               const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                               const void* temb, int32_t temb_dtype, int32_t K, const float* y, int32_t P,
+                               float* fused, int32_t* count, float* scores, float* prop, int32_t* label,
+                               void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Sec. 3.4.2 "voxel integration over volumes".  Each point is the centre of a voxel; the

@@ -4,5 +4,6 @@ Thin Python front end of libaura_fuse.so (hand-written HIP for gfx950).  Nothing
 Python: every function in `binding` marshals torch tensors into one C-ABI call.
 """
 from . import binding  # noqa: F401
-from .binding import (Params, Views, fuse_features, fuse_workspace_bytes, material_scores,  # noqa: F401
-                      project_visibility, property_integrate, workspace_bytes)
+from .binding import (Params, Views, fuse_features, fuse_scores, fuse_scores_workspace_bytes,  # noqa: F401
+                      fuse_workspace_bytes, material_scores, project_visibility, property_integrate,
+                      workspace_bytes)

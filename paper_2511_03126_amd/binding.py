@@ -16,7 +16,7 @@ _LIB_PATH = Path(__file__).resolve().parent / "libaura_fuse.so"
 
 F32, BF16, F16 = 0, 1, 2
 VIS_FRUSTUM_ONLY, FUSE_MEAN_ONLY, FUSE_GATHER = 1, 2, 4
-CALL_MATERIAL_SCORES, CALL_PROPERTY_INTEGRATE, CALL_FUSE_FEATURES = 1, 2, 3
+CALL_MATERIAL_SCORES, CALL_PROPERTY_INTEGRATE, CALL_FUSE_FEATURES, CALL_FUSE_SCORES = 1, 2, 3, 4
 
 _TORCH_DTYPE = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 
@@ -72,6 +72,9 @@ def lib():
         L.aura_material_scores.restype = C.c_int32
         L.aura_material_scores.argtypes = [vp, i64, i32, vp, i32, i32, vp, i32, C.POINTER(_ParamsT), vp, vp, vp,
                                            vp, C.c_size_t, vp]
+        L.aura_fuse_scores.restype = C.c_int32
+        L.aura_fuse_scores.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32, vp, i32, i32, vp,
+                                       i32, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.aura_property_integrate.restype = C.c_int32
         L.aura_property_integrate.argtypes = [vp, i64, i32, i32, vp, vp, f32, vp, i32, vp, vp, vp, i32, vp, vp,
                                               vp, C.c_size_t, vp]
@@ -206,6 +209,29 @@ def material_scores(fused, temb, y, params: Params, scores, prop=None, label=Non
                                       scores.data_ptr(), _ptr(prop), _ptr(label), _ptr(workspace),
                                       0 if workspace is None else workspace.numel(), _stream()),
            "aura_material_scores")
+
+
+def fuse_scores_workspace_bytes(views: "Views", N: int, K: int, B: int = 1) -> int:
+    """Workspace size of fuse_scores for these views and K materials."""
+    f = views.feat
+    return workspace_bytes(CALL_FUSE_SCORES, N=N, B=B, D=f.shape[3], K=K, n_views=f.shape[0], Hf=f.shape[1],
+                           Wf=f.shape[2], feat_dtype=_TORCH_DTYPE[f.dtype])
+
+
+def fuse_scores(views: Views, params: Params, xyz, temb, y, fused, scores, count=None, prop=None, label=None,
+                pt_offsets=None, view_offsets=None, workspace=None):
+    """fuse_features followed by material_scores in one call; fused, count, scores, prop, label filled in place."""
+    xyz = _dev(xyz, torch.float32, "xyz")
+    _dev(fused, torch.float32, "fused")
+    temb = _dev(temb, torch.float32, "temb")
+    po, vo, B = _objects(pt_offsets, view_offsets)
+    v, p = views.c(), params.c()
+    K = temb.shape[0]
+    P = 0 if y is None else y.shape[1]
+    _check(lib().aura_fuse_scores(C.byref(v), C.byref(p), xyz.data_ptr(), xyz.shape[0], _hptr(po), _hptr(vo), B,
+                                  temb.data_ptr(), F32, K, _ptr(y), P, fused.data_ptr(), _ptr(count),
+                                  scores.data_ptr(), _ptr(prop), _ptr(label), _ptr(workspace),
+                                  0 if workspace is None else workspace.numel(), _stream()), "aura_fuse_scores")
 
 
 def property_integrate(prop, mass, p_index=0, count=None, vol=None, vol_uniform=1.0, pt_offsets=None, xyz=None,

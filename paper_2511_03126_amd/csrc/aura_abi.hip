@@ -9,6 +9,7 @@
 #include "../../include/aura_fuse.h"
 #include "fuse_args.hpp"
 #include "launch.hpp"
+#include "tile_scores.hpp"
 
 namespace {
 
@@ -126,6 +127,33 @@ static bool tile_path(int32_t dtype, int32_t D, int32_t Hf, int32_t Wf, int32_t 
   return aura::fuse_tile_supported(dtype, D, Hf, Wf, feat_bytes);
 }
 
+// Workspace of aura_fuse_scores: the fusion workspace, then (where the scores come from per-cell
+// similarities) the factor and similarity arrays, then the workspace of aura_material_scores.
+struct FuseScoresLayout {
+  bool tile;        // fusion on the matrix cores
+  bool by_cells;    // scores from per-cell similarities (needs tile and fewer cells than points)
+  size_t fuse_off, cells_off, scores_off, total;
+};
+
+static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static FuseScoresLayout fuse_scores_layout(int64_t N, int32_t B, int32_t n_views, int32_t Hf, int32_t Wf, int32_t D,
+                                           int32_t dtype, int32_t K) {
+  FuseScoresLayout l{};
+  const int64_t n_cells = (int64_t)n_views * Hf * Wf;
+  l.tile = tile_path(dtype, D, Hf, Wf, n_views);
+  l.by_cells = l.tile && n_cells <= N;
+  size_t off = 0;
+  l.fuse_off = off;
+  if (l.tile) off += round256(aura::fuse_tile_workspace_bytes(N, B, n_views));
+  l.cells_off = off;
+  if (l.by_cells) off += round256(aura::tile_scores_workspace_bytes(N, n_cells, K));
+  l.scores_off = off;
+  off += round256(aura::scores_workspace_bytes(D, K));
+  l.total = off;
+  return l;
+}
+
 aura_status_t aura_workspace_bytes(int32_t call, const aura_sizes_t* sz, size_t* bytes) {
   if (!bytes || !sz) return AURA_ERR_NULL;
   *bytes = 0;
@@ -147,6 +175,13 @@ aura_status_t aura_workspace_bytes(int32_t call, const aura_sizes_t* sz, size_t*
     if (sz->feat_dtype != AURA_F32 && sz->feat_dtype != AURA_BF16 && sz->feat_dtype != AURA_F16) return AURA_ERR_DTYPE;
     if (tile_path(sz->feat_dtype, sz->D, sz->Hf, sz->Wf, sz->n_views))
       *bytes = aura::fuse_tile_workspace_bytes(sz->N, sz->B, sz->n_views);
+    return AURA_OK;
+  }
+  if (call == AURA_CALL_FUSE_SCORES) {
+    if (sz->N < 0 || sz->B < 1 || sz->n_views < 1 || sz->Hf < 1 || sz->Wf < 1 || sz->D < 1 || sz->K < 1) return AURA_ERR_SHAPE;
+    if (sz->feat_dtype != AURA_F32 && sz->feat_dtype != AURA_BF16 && sz->feat_dtype != AURA_F16) return AURA_ERR_DTYPE;
+    if (sz->K > 128) return AURA_ERR_UNSUPPORTED;
+    *bytes = fuse_scores_layout(sz->N, sz->B, sz->n_views, sz->Hf, sz->Wf, sz->D, sz->feat_dtype, sz->K).total;
     return AURA_OK;
   }
   return AURA_ERR_UNSUPPORTED;
@@ -214,6 +249,67 @@ aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t*
     return aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only, tile ? &tws : nullptr,
                                       tab, n, max_pts, st);
   });
+}
+
+aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* params,
+                               const float* xyz, int64_t N,
+                               const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                               const void* temb, int32_t temb_dtype, int32_t K, const float* y, int32_t P,
+                               float* fused, int32_t* count, float* scores, float* prop, int32_t* label,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+  aura_status_t s = check_views(views, params, true);
+  if (s != AURA_OK) return s;
+  if (!temb) return AURA_ERR_NULL;
+  if (N < 0 || K < 1 || P < 0) return AURA_ERR_SHAPE;
+  if (temb_dtype != AURA_F32) return temb_dtype == AURA_BF16 || temb_dtype == AURA_F16 ? AURA_ERR_UNSUPPORTED : AURA_ERR_DTYPE;
+  if (prop && (!y || P < 1)) return AURA_ERR_NULL;
+  if (!(params->temperature > 0.0f)) return AURA_ERR_SHAPE;
+  if (K > 128 || P > 8) return AURA_ERR_UNSUPPORTED;
+  std::vector<aura::ObjRange> objs;
+  int max_views = 0;
+  s = check_objects(N, views->n_views, pt_offsets, view_offsets, B, &objs, &max_views);
+  if (s != AURA_OK) return s;
+  if (N == 0) return AURA_OK;
+  if (!xyz || !fused || !scores) return AURA_ERR_NULL;
+  if (!aligned(fused, 16)) return AURA_ERR_ALIGN;
+  FuseScoresLayout lay = fuse_scores_layout(N, B, views->n_views, views->Hf, views->Wf, views->D, views->feat_dtype, K);
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < lay.total) return AURA_ERR_WORKSPACE;
+  char* wbase = static_cast<char*>(workspace);
+  if (params->flags & AURA_FUSE_GATHER) lay.tile = lay.by_cells = false;
+
+  const aura::VisArgs va = vis_args(views, params);
+  aura::FeatArgs fa{};
+  fa.feat = views->feat;
+  fa.Hf = views->Hf;
+  fa.Wf = views->Wf;
+  fa.D = views->D;
+  fa.dtype = views->feat_dtype;
+  fa.pitch_x = (float)views->W / (float)views->Wf;
+  fa.pitch_y = (float)views->H / (float)views->Hf;
+  const int mean_only = (params->flags & AURA_FUSE_MEAN_ONLY) ? 1 : 0;
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  const float* t32 = static_cast<const float*>(temb);
+  const int64_t n_cells = (int64_t)views->n_views * views->Hf * views->Wf;
+
+  aura::TileWs tws{};
+  aura::TileScoreWs sws{};
+  if (lay.tile) tws = aura::fuse_tile_workspace(wbase + lay.fuse_off, N, B, views->n_views);
+  if (lay.by_cells) {
+    sws = aura::tile_scores_workspace(wbase + lay.cells_off, N, n_cells, K);
+    s = hip_status(aura::launch_cell_scores(fa, n_cells, t32, K, sws, st));
+    if (s != AURA_OK) return s;
+  }
+  s = for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts, int obj_base) {
+    tws.obj_base = obj_base;
+    hipError_t e = aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only,
+                                              lay.tile ? &tws : nullptr, tab, n, max_pts, st, lay.by_cells ? sws.factor : nullptr);
+    if (e != hipSuccess || !lay.by_cells) return e;
+    return aura::launch_tile_scores(fa, tws, sws, fused, t32, K, y, P, params->temperature, scores, prop, label, tab, n,
+                                    max_pts, st);
+  });
+  if (s != AURA_OK || lay.by_cells) return s;
+  return hip_status(aura::launch_material_scores(fused, N, views->D, t32, K, y, P, params->temperature, scores, prop,
+                                                 label, wbase + lay.scores_off, st));
 }
 
 aura_status_t aura_material_scores(const float* fused, int64_t N, int32_t D,

@@ -15,6 +15,7 @@ struct FuseArgs {
   int* out_count;
   float norm_eps;
   int mean_only;
+  float* out_factor;   // tile path only, may be nullptr: [N] factor applied to each point's raw tile product
 };
 
 // ---- workspace of the tile path ------------------------------------------------------------

@@ -566,6 +566,7 @@ struct ProdArgs {
   unsigned* counters;   // [objects of the launch][8]
   int quota;
   float* fused;
+  float* factor;        // [N] or nullptr: what each point's raw tile product was multiplied by
   float norm_eps;
   int mean_only;
 };
@@ -747,6 +748,13 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
       const float normed = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
       factor = a.mean_only ? inv : normed;
     }
+    {   // the factor of every point of the tile, for the scoring kernel (lanes 0..31 of the first wave; all
+        // other lanes, and every lane when no factor array was given, fall outside the buffer)
+      const int rows_f = a.factor ? min(kTilePts, ob.n_pts - blk * kTilePts) : 0;
+      const __amdgpu_buffer_rsrc_t fout = __builtin_amdgcn_make_buffer_rsrc(a.factor + (a.factor ? ob.pt_begin + blk * kTilePts : 0), 0,
+                                                                            rows_f * 4, 0x00020000);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_int(factor), fout, tid < kTilePts ? 4 * tid : 0x7ffffff0, 0, 0);
+    }
     {
       // Buffer stores: the wave's part of the tile (rows of D floats, starting at a wave-uniform
       // address) is described by a buffer resource whose size covers the rows that exist, so a lane
@@ -837,7 +845,7 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProdArgs pa{static_cast<const char*>(a.feat.feat), a.feat.D, ws.hdr, ws.steps, ws.counters + (size_t)ws.obj_base * kXcd,
-              ws.quota, a.fused, a.norm_eps, a.mean_only};
+              ws.quota, a.fused, a.out_factor, a.norm_eps, a.mean_only};
   // several objects in one launch share the machine: fewer workgroups per object
   const int groups = std::max(kXcd, std::min(max_tiles, (kProdGroupsMax / n_obj + kXcd - 1) / kXcd * kXcd));
   hipLaunchKernelGGL((k_tile_product<DT, S, H, PF>), dim3(std::min(groups, max_tiles), n_obj), dim3(kWave * S), 0, stream, pa, tab);

@@ -26,7 +26,8 @@ struct TileWs;
 // tile_ws == nullptr: per-point gather kernel; otherwise the matrix-core tile path with that workspace.
 hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const float* xyz, float* fused,
                                 int* out_count, float norm_eps, int mean_only, const TileWs* tile_ws,
-                                const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream);
+                                const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream,
+                                float* out_factor = nullptr);   // tile path only: see FuseArgs::out_factor
 
 size_t scores_workspace_bytes(int D, int K);
 hipError_t launch_material_scores(const float* fused, long long N, int D, const float* temb, int K,

@@ -14,6 +14,7 @@
 // the workspace, already in the per-lane operand order, and stay resident in L2.
 #include "aura_device.hpp"
 #include "launch.hpp"
+#include "scores_epilogue.hpp"
 
 namespace aura {
 
@@ -124,65 +125,8 @@ __global__ __launch_bounds__(256) void k_material_scores(ScoreArgs a) {
     }
   }
 
-  // Accumulator element r of tile mt in this lane is material mt*32 + 8*(r/4) + 4*g + r%4 of point n.
   if (!valid) return;   // no cross-lane traffic below except with lane ^ 32, which holds the same point
-  float* __restrict__ srow = a.scores + n * a.K;
-  const bool vec_store = (a.K & 3) == 0 && ((reinterpret_cast<uintptr_t>(a.scores) & 15) == 0);
-  float best = -INFINITY;
-  int bidx = 0;
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-      const int m0 = mt * kTileM + 8 * q + 4 * g;
-      if (vec_store) {
-        if (m0 < a.K) {
-          f32x4 v = {acc[mt][4 * q], acc[mt][4 * q + 1], acc[mt][4 * q + 2], acc[mt][4 * q + 3]};
-          *reinterpret_cast<f32x4*>(srow + m0) = v;
-        }
-      } else {
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-          if (m0 + e < a.K) srow[m0 + e] = acc[mt][4 * q + e];
-      }
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        const float sc = acc[mt][4 * q + e];
-        if (m0 + e < a.K && sc > best) { best = sc; bidx = m0 + e; }   // ascending m: lowest index wins ties
-      }
-    }
-  {
-    const float ob = __shfl_xor(best, 32, kWave);
-    const int oi = __shfl_xor(bidx, 32, kWave);
-    if (ob > best || (ob == best && oi < bidx)) { best = ob; bidx = oi; }
-  }
-  if (a.label && g == 0) a.label[n] = bidx;
-  if (!a.prop) return;
-
-  float den = 0.0f, num[kMaxP];
-#pragma unroll
-  for (int p = 0; p < kMaxP; ++p) num[p] = 0.0f;
-#pragma unroll
-  for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-      const int m = mt * kTileM + 8 * (r / 4) + 4 * g + (r & 3);
-      if (m < a.K) {
-        const float e = expf((acc[mt][r] - best) * a.inv_T);
-        den += e;
-#pragma unroll
-        for (int p = 0; p < kMaxP; ++p)
-          if (p < a.P) num[p] = __builtin_fmaf(e, ys[m * a.P + p], num[p]);
-      }
-    }
-  den += __shfl_xor(den, 32, kWave);
-#pragma unroll
-  for (int p = 0; p < kMaxP; ++p) {
-    if (p < a.P) {
-      const float t = num[p] + __shfl_xor(num[p], 32, kWave);
-      if (g == 0) a.prop[n * a.P + p] = t / den;
-    }
-  }
+  finish_scores<MT>(acc, n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label);
 }
 
 static int tiles_m(int K) { return (K + kTileM - 1) / kTileM; }

@@ -1,0 +1,283 @@
+// aura_fuse_scores, scoring part (Sec. 3.4.1) on top of the matrix-core fusion path.
+//
+// The similarity omega_k = <f, t_k> is linear in the feature, and the fused feature of Eq. 2 is a
+// weighted sum of feature cells, f_i = s_i * sum_c w[i][c] F[c] (s_i: 1 / (count * norm)).  Hence
+//     omega[i][k] = s_i * sum_c w[i][c] * G[c][k],      G[c][k] = <F[c], t_k>,
+// i.e. the same tile product as the fusion itself, but over K "channels" instead of D.  Where a call
+// has fewer feature cells than points, G is cheap (one small dense product per call) and the scores
+// never need the fused rows to be read back from memory:
+//
+//   k_cell_scores   G = F . T^T for every cell of every view, on the matrix cores, fp32 accumulate, the
+//                   text embeddings split into two 16-bit terms; stored as two 16-bit terms per value.
+//   k_tile_scores   one wave per 32-point tile: omega^T = G^T . W^T over the tile's k-steps as written
+//                   by the prepare kernel (its weight operand is exactly the B operand here), three
+//                   partial products per k-step (hi*hi, hi*lo, lo*hi), times the point's factor s_i that the
+//                   product kernel left in the workspace; then the shared epilogue (scores, label, Eq. 4).
+//
+// A tile that the prepare kernel fused by itself (no k-steps) is scored from its fused rows.
+#include "aura_device.hpp"
+#include "fuse_args.hpp"
+#include "launch.hpp"
+#include "scores_epilogue.hpp"
+#include "tile_scores.hpp"
+
+namespace aura {
+
+typedef __bf16 ts_bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 ts_f16x8 __attribute__((ext_vector_type(8)));
+typedef float ts_f32x4 __attribute__((ext_vector_type(4)));
+typedef float ts_f32x16 __attribute__((ext_vector_type(16)));
+typedef uint32_t ts_u32x4 __attribute__((ext_vector_type(4)));
+
+template <int DT>
+__device__ __forceinline__ ts_f32x16 ts_mma(ts_u32x4 a, ts_u32x4 b, ts_f32x16 c) {
+  if constexpr (DT == 1)
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(ts_bf16x8, a), __builtin_bit_cast(ts_bf16x8, b), c, 0, 0, 0);
+  else
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(ts_f16x8, a), __builtin_bit_cast(ts_f16x8, b), c, 0, 0, 0);
+}
+
+// x = hi + lo with both terms in the 16-bit type of the feature maps; returns hi | lo << 16.
+template <int DT>
+__device__ __forceinline__ uint32_t split_pack(float x) {
+  if constexpr (DT == 1) {
+    const __bf16 h = (__bf16)x;
+    const __bf16 l = (__bf16)(x - (float)h);
+    return (uint32_t)__builtin_bit_cast(uint16_t, h) | ((uint32_t)__builtin_bit_cast(uint16_t, l) << 16);
+  } else {
+    const _Float16 h = (_Float16)x;
+    const _Float16 l = (_Float16)(x - (float)h);
+    return (uint32_t)__builtin_bit_cast(uint16_t, h) | ((uint32_t)__builtin_bit_cast(uint16_t, l) << 16);
+  }
+}
+
+// ------------------------------------------------------------------------------------ G = F . T^T
+
+struct CellArgs {
+  const char* feat;     // [n_cells][D] 16-bit
+  long long n_cells;
+  int D, K, Kpad;
+  const float* temb;    // [K][D] fp32
+  uint32_t* G;          // [n_cells][Kpad]: hi | lo << 16
+};
+
+// One wave per 32 cells, all materials.  A operand: lane (cell i = l % 32, kg = l / 32) holds channels
+// 16 s + 8 kg .. + 7 of cell i (16 contiguous bytes of the stored map); B operand: the same channels of
+// material n = l % 32, split on the fly.
+template <int DT, int MT>
+__global__ __launch_bounds__(256) void k_cell_scores(CellArgs a) {
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const long long c0 = ((long long)blockIdx.x * 4 + wave) * 32;
+  if (c0 >= a.n_cells) return;
+  const int i = lane & 31, kg = lane >> 5;
+  const long long cell = min(c0 + i, a.n_cells - 1);
+  const char* __restrict__ frow = a.feat + cell * a.D * 2 + kg * 16;
+  const float* __restrict__ trow[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt) trow[mt] = a.temb + (long long)min(mt * 32 + i, a.K - 1) * a.D + kg * 8;
+
+  ts_f32x16 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
+
+  for (int s = 0; s < a.D / 16; ++s) {
+    const ts_u32x4 fa = *reinterpret_cast<const ts_u32x4*>(frow + s * 32);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const ts_f32x4 t0 = *reinterpret_cast<const ts_f32x4*>(trow[mt] + s * 16);
+      const ts_f32x4 t1 = *reinterpret_cast<const ts_f32x4*>(trow[mt] + s * 16 + 4);
+      const float t[8] = {t0[0], t0[1], t0[2], t0[3], t1[0], t1[1], t1[2], t1[3]};
+      ts_u32x4 bh, bl;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const uint32_t p0 = split_pack<DT>(t[2 * q]), p1 = split_pack<DT>(t[2 * q + 1]);
+        bh[q] = __builtin_amdgcn_perm(p1, p0, 0x05040100u);
+        bl[q] = __builtin_amdgcn_perm(p1, p0, 0x07060302u);
+      }
+      acc[mt] = ts_mma<DT>(fa, bh, acc[mt]);
+      acc[mt] = ts_mma<DT>(fa, bl, acc[mt]);
+    }
+  }
+  // element r of the lane: cell c0 + 8 (r / 4) + 4 kg + r % 4, material 32 mt + i (0 beyond K)
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const long long c = c0 + 8 * (r >> 2) + 4 * kg + (r & 3);
+      const float v = (mt * 32 + i < a.K) ? acc[mt][r] : 0.0f;
+      if (c < a.n_cells) a.G[c * a.Kpad + mt * 32 + i] = split_pack<DT>(v);
+    }
+}
+
+// ------------------------------------------------------------------------------------ per-tile scores
+
+struct TileScoreArgs {
+  const TileHdr* hdr;
+  const TileStep* steps;
+  int quota;
+  const uint32_t* G;
+  int Kpad;
+  uint32_t row_units;    // D / 256
+  const float* factor;   // [N]
+  const float* fused;    // [N][D], for tiles without k-steps
+  const float* temb;     // [K][D]
+  int D, K, P;
+  const float* y;
+  float inv_T;
+  float* scores;
+  float* prop;
+  int* label;
+};
+
+// Byte offset of a cell row (a multiple of 512 * units, units = D / 256 in 1..6) -> cell index.
+__device__ __forceinline__ uint32_t cell_index(uint32_t off, uint32_t units) {
+  const uint32_t q = off >> 9;
+  switch (units) {
+    case 1: return q;
+    case 2: return q >> 1;
+    case 3: return (uint32_t)(((unsigned long long)q * 0xAAAAAAABull) >> 33);
+    case 4: return q >> 2;
+    default: return (uint32_t)(((unsigned long long)(q >> 1) * 0xAAAAAAABull) >> 33);   // 6
+  }
+}
+
+template <int DT, int MT>
+__global__ __launch_bounds__(256) void k_tile_scores(TileScoreArgs a, ObjTable tab) {
+  __shared__ float ys[kScoreMaxK * kScoreMaxP];
+  if (a.prop) {
+    for (int t = threadIdx.x; t < a.K * a.P; t += blockDim.x) ys[t] = a.y[t];
+  }
+  __syncthreads();
+
+  const ObjRange ob = tab.o[blockIdx.y];
+  const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int tile = blockIdx.x * 4 + wave;
+  if (tile >= nblk) return;
+  const int pt = lane & 31, g = lane >> 5;
+  const int li = tile * kTilePts + pt;
+  const bool valid = li < ob.n_pts;
+  const long long n = ob.pt_begin + (valid ? li : ob.n_pts - 1);
+  const int nsteps = a.hdr[ob.tile_begin + tile].nsteps;
+
+  ts_f32x16 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
+
+  if (nsteps >= 0) {
+    const TileStep* __restrict__ st = a.steps + (long long)(ob.tile_begin + tile) * a.quota;
+    for (int s = 0; s < nsteps; ++s) {
+      const ts_u32x4 w_hi = st[s].a_hi[lane], w_lo = st[s].a_lo[lane];
+      const ts_u32x4 c0 = *reinterpret_cast<const ts_u32x4*>(&st[s].cell[8 * g]);
+      const ts_u32x4 c1 = *reinterpret_cast<const ts_u32x4*>(&st[s].cell[8 * g + 4]);
+      uint32_t gv[MT][8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const uint32_t ci = cell_index(e < 4 ? c0[e] : c1[e - 4], a.row_units);
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) gv[mt][e] = a.G[(long long)ci * a.Kpad + mt * 32 + pt];
+      }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        ts_u32x4 g_hi, g_lo;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          g_hi[q] = __builtin_amdgcn_perm(gv[mt][2 * q + 1], gv[mt][2 * q], 0x05040100u);
+          g_lo[q] = __builtin_amdgcn_perm(gv[mt][2 * q + 1], gv[mt][2 * q], 0x07060302u);
+        }
+        acc[mt] = ts_mma<DT>(g_hi, w_hi, acc[mt]);
+        acc[mt] = ts_mma<DT>(g_hi, w_lo, acc[mt]);
+        acc[mt] = ts_mma<DT>(g_lo, w_hi, acc[mt]);
+      }
+    }
+    const float f = a.factor[n];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mt][r] *= f;
+  } else {
+    // no k-steps: plain dot products of the point's fused row with the embeddings of the lane's materials
+    const float* __restrict__ row = a.fused + n * a.D;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = mt * kScoreTileM + 8 * (r >> 2) + 4 * g + (r & 3);
+        float dot = 0.0f;
+        if (m < a.K) {
+          const float* __restrict__ t = a.temb + (long long)m * a.D;
+#pragma unroll 1
+          for (int d = 0; d < a.D; ++d) dot = __builtin_fmaf(row[d], t[d], dot);
+        }
+        acc[mt][r] = dot;
+      }
+  }
+  if (!valid) return;
+  finish_scores<MT>(acc, n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label);
+}
+
+// ------------------------------------------------------------------------------------ host
+
+static size_t ts_round256(size_t x) { return (x + 255) & ~(size_t)255; }
+static int ts_kpad(int K) {
+  int mt = (K + 31) / 32;
+  if (mt == 3) mt = 4;
+  return mt * 32;
+}
+
+size_t tile_scores_workspace_bytes(long long N, long long n_cells, int K) {
+  return ts_round256((size_t)N * sizeof(float)) + ts_round256((size_t)n_cells * ts_kpad(K) * sizeof(uint32_t));
+}
+
+TileScoreWs tile_scores_workspace(void* workspace, long long N, long long n_cells, int K) {
+  TileScoreWs ws;
+  char* base = static_cast<char*>(workspace);
+  ws.factor = reinterpret_cast<float*>(base);
+  base += ts_round256((size_t)N * sizeof(float));
+  ws.G = reinterpret_cast<uint32_t*>(base);
+  ws.Kpad = ts_kpad(K);
+  return ws;
+}
+
+template <int DT>
+static hipError_t launch_cells(const CellArgs& a, hipStream_t stream) {
+  const dim3 grid((unsigned)((a.n_cells + 127) / 128)), block(256);
+  switch (a.Kpad / 32) {
+    case 1: hipLaunchKernelGGL((k_cell_scores<DT, 1>), grid, block, 0, stream, a); break;
+    case 2: hipLaunchKernelGGL((k_cell_scores<DT, 2>), grid, block, 0, stream, a); break;
+    default: hipLaunchKernelGGL((k_cell_scores<DT, 4>), grid, block, 0, stream, a); break;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_cell_scores(const FeatArgs& feat, long long n_cells, const float* temb, int K, const TileScoreWs& ws,
+                              hipStream_t stream) {
+  CellArgs a{static_cast<const char*>(feat.feat), n_cells, feat.D, K, ws.Kpad, temb, ws.G};
+  return feat.dtype == 1 ? launch_cells<1>(a, stream) : launch_cells<2>(a, stream);
+}
+
+template <int DT>
+static hipError_t launch_ts(const TileScoreArgs& a, const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream) {
+  const int max_tiles = (max_pts + kTilePts - 1) / kTilePts;
+  const dim3 grid((unsigned)((max_tiles + 3) / 4), (unsigned)n_obj), block(256);
+  switch (a.Kpad / 32) {
+    case 1: hipLaunchKernelGGL((k_tile_scores<DT, 1>), grid, block, 0, stream, a, tab); break;
+    case 2: hipLaunchKernelGGL((k_tile_scores<DT, 2>), grid, block, 0, stream, a, tab); break;
+    default: hipLaunchKernelGGL((k_tile_scores<DT, 4>), grid, block, 0, stream, a, tab); break;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_tile_scores(const FeatArgs& feat, const TileWs& tws, const TileScoreWs& ws, const float* fused,
+                              const float* temb, int K, const float* y, int P, float temperature, float* scores,
+                              float* prop, int* label, const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream) {
+  TileScoreArgs a{tws.hdr, tws.steps, tws.quota, ws.G, ws.Kpad, (uint32_t)(feat.D / 256), ws.factor, fused, temb,
+                  feat.D, K, P, y, 1.0f / temperature, scores, prop, label};
+  return feat.dtype == 1 ? launch_ts<1>(a, tab, n_obj, max_pts, stream) : launch_ts<2>(a, tab, n_obj, max_pts, stream);
+}
+
+}  // namespace aura

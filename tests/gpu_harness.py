@@ -45,6 +45,8 @@ class DeviceScene:
         self.ws_fuse = torch.empty(nb, dtype=torch.uint8, device=dev) if nb else None
         self.ws_scores = torch.empty(aura.workspace_bytes(binding.CALL_MATERIAL_SCORES, D=s.D, K=s.K),
                                      dtype=torch.uint8, device=dev)
+        self.ws_fuse_scores = torch.empty(aura.fuse_scores_workspace_bytes(self.views, N, s.K, s.B), dtype=torch.uint8,
+                                          device=dev)
         self.ws_mass = torch.empty(aura.workspace_bytes(binding.CALL_PROPERTY_INTEGRATE, N=N, B=s.B, G=s.G),
                                    dtype=torch.uint8, device=dev)
 
@@ -60,6 +62,11 @@ class DeviceScene:
         aura.material_scores(self.fused, self.temb, self.y, self.params, self.scores, self.prop, self.label,
                              self.ws_scores)
 
+    def fuse_scores(self):
+        aura.fuse_scores(self.views, self.params, self.xyz, self.temb, self.y, self.fused, self.scores,
+                         count=self.count_fuse, prop=self.prop, label=self.label, pt_offsets=self.pt_offsets,
+                         view_offsets=self.view_offsets, workspace=self.ws_fuse_scores)
+
     def property_integrate(self):
         s = self.scene
         aura.property_integrate(self.prop, self.mass, p_index=0, count=self.count_fuse, vol_uniform=s.vol_uniform,
@@ -68,11 +75,23 @@ class DeviceScene:
                                 n_used=self.n_used, workspace=self.ws_mass)
 
     def step(self):
-        """One pass of the whole path."""
+        """One pass of the whole path, one library call per stage."""
         self.project_visibility()
         self.fuse_features()
         self.material_scores()
         self.property_integrate()
+
+    def step_combined(self):
+        """One pass of the whole path with fusion and scoring in one call."""
+        self.project_visibility()
+        self.fuse_scores()
+        self.property_integrate()
+
+    def clear_outputs(self):
+        for t in (self.fused, self.scores, self.prop, self.mass):
+            t.fill_(float("nan"))
+        for t in (self.count_fuse, self.label, self.n_used):
+            t.fill_(-7)
 
     def results(self):
         torch.cuda.synchronize()

@@ -30,7 +30,7 @@ def test_every_declared_function_is_exported(B):
     names = _declared_functions()
     assert {"aura_project_visibility", "aura_fuse_features", "aura_material_scores", "aura_property_integrate",
             "aura_workspace_bytes", "aura_version", "aura_strerror", "aura_last_hip_error",
-            "aura_calibration_copy", "aura_calibration_fill"} <= set(names)
+            "aura_calibration_copy", "aura_calibration_fill", "aura_fuse_scores"} <= set(names)
     for n in names:
         assert hasattr(B.lib(), n), n
 
@@ -70,6 +70,18 @@ def test_workspace_sizes(B):
         fuse(D=768, feat_dtype=9)
     assert e.value.status == -3
     assert B.lib().aura_workspace_bytes(B.CALL_FUSE_FEATURES, None, C.byref(C.c_size_t())) == -1
+    # fusion + scoring in one call: fusion scratch, then (fewer cells than points, matrix-core fusion) one
+    # factor per point and one packed similarity per cell and padded material, then the scoring scratch
+    both = lambda **kw: B.workspace_bytes(B.CALL_FUSE_SCORES, **{**dict(N=200_000, B=1, n_views=16, Hf=32, Wf=32, K=33), **kw})
+    r256 = lambda x: -(-x // 256) * 256
+    sc = lambda D, K: B.workspace_bytes(B.CALL_MATERIAL_SCORES, D=D, K=K)
+    assert both(D=512, feat_dtype=B.F32) == r256(sc(512, 33))
+    assert both(D=768, feat_dtype=B.BF16) == (r256(fuse(D=768, feat_dtype=B.BF16)) + r256(200_000 * 4)
+                                              + r256(16 * 32 * 32 * 64 * 4) + r256(sc(768, 33)))
+    assert both(D=768, feat_dtype=B.BF16, N=1000) == r256(fuse(D=768, feat_dtype=B.BF16, N=1000)) + r256(sc(768, 33))
+    with pytest.raises(B.AuraError) as e:
+        both(D=768, feat_dtype=B.BF16, K=129)
+    assert e.value.status == -7
 
 
 def _views(B, **kw):
@@ -131,6 +143,28 @@ def test_argument_validation_returns_status_codes(B):
     assert ms(ws=C.c_void_p(0x1010)) == -5
     cold = B.Params(temperature=0.0).c()
     assert ms(par=cold) == -2
+
+    fs = lambda v=None, N=10, K=8, P=1, temb=fake, dt=B.F32, y=fake, fused=fake, scores=fake, prop=fake, \
+        ws=C.c_void_p(0x1000), wsb=1 << 30, par=p: L.aura_fuse_scores(
+            C.byref(v if v is not None else _views(B)), C.byref(par), fake, N, None, None, 1, temb, dt, K, y, P, fused, None,
+            scores, prop, None, ws, wsb, None)
+    assert fs(temb=None) == -1
+    assert fs(fused=None) == -1
+    assert fs(scores=None) == -1
+    assert fs(y=None) == -1                                                # prop wanted but no y
+    assert fs(v=_views(B, feat=None)) == -1
+    assert fs(v=_views(B, feat_dtype=7)) == -3
+    assert fs(dt=5) == -3
+    assert fs(dt=B.F16) == -7
+    assert fs(K=0) == -2
+    assert fs(K=129) == -7
+    assert fs(P=9) == -7
+    assert fs(par=cold) == -2
+    assert fs(fused=C.c_void_p(0x1004)) == -4
+    assert fs(ws=None) == -5
+    assert fs(wsb=16) == -5
+    assert fs(ws=C.c_void_p(0x1010)) == -5
+    assert fs(N=0, fused=None, scores=None) == 0
 
     cc = lambda dst=fake, src=fake, n=1024: L.aura_calibration_copy(dst, src, n, None)
     assert cc(dst=None) == -1 and cc(src=None) == -1

@@ -44,18 +44,20 @@ def test_full_path_matches_oracle_on_reduced_scenes(H, orc, name, kw):
     s = make_scene(name, **kw)
     print(f"\n[{name} {kw}] N={s.N} V={s.n_views} B={s.B} D={s.D} K={s.K} dtype={s.feat_dtype}", flush=True)
     d = H.DeviceScene(s, want_uvz=True)
-    d.step()
-    gpu = d.results()
     ref = H.oracle_points(orc, s, want_uvz=True)
-    rep = H.compare_points(gpu, ref, s)
-    rep["mass_rel"] = _mass_check(H, orc, s, gpu, ref["prop"], ref["count_fuse"])
-    rep["visible_frac"] = float(ref["vis"].mean())
-    print(rep, flush=True)
-    # the run is deterministic: a second pass gives the same bits
-    d.step()
-    again = d.results()
-    for k in ("vis", "count", "fused", "scores", "prop", "label", "mass", "n_used"):
-        assert np.array_equal(gpu[k].view(np.uint8), again[k].view(np.uint8)), k
+    for step in (d.step, d.step_combined):      # one call per stage; fusion and scoring in one call
+        d.clear_outputs()
+        step()
+        gpu = d.results()
+        rep = H.compare_points(gpu, ref, s)
+        rep["mass_rel"] = _mass_check(H, orc, s, gpu, ref["prop"], ref["count_fuse"])
+        rep["visible_frac"] = float(ref["vis"].mean())
+        print(step.__name__, rep, flush=True)
+        # the run is deterministic: a second pass gives the same bits
+        step()
+        again = d.results()
+        for k in ("vis", "count", "fused", "scores", "prop", "label", "mass", "n_used"):
+            assert np.array_equal(gpu[k].view(np.uint8), again[k].view(np.uint8)), k
 
 
 FULL = ["c1", "c2", "c3", "c4", "c5"]
@@ -70,8 +72,14 @@ def test_full_size_configs_on_sampled_points(H, orc, name):
     s = make_scene(name)
     print(f"\n[{name} full] N={s.N} V={s.n_views} B={s.B} pv={s.point_views}", flush=True)
     d = H.DeviceScene(s)
+    d.step_combined()        # the launch configuration the benchmark times
+    _check_full_size(H, orc, s, d.results(), name)
+    d.clear_outputs()
     d.step()
-    gpu = d.results()
+    _check_full_size(H, orc, s, d.results(), name)
+
+
+def _check_full_size(H, orc, s, gpu, name):
     rng = np.random.default_rng(99)
     reps = []
     for b in range(0, s.B, max(1, s.B // 4)):
@@ -138,6 +146,26 @@ def test_material_counts_and_property_columns(H, orc, K, P):
     _mass_check(H, orc, s, gpu, ref["prop"], ref["count_fuse"])
 
 
+@pytest.mark.parametrize("K,P,dtype", [(1, 1, "bf16"), (12, 1, "f16"), (31, 3, "bf16"), (33, 2, "f16"), (64, 1, "bf16"),
+                                       (100, 8, "bf16"), (128, 2, "f16")])
+def test_combined_call_scores_from_cell_similarities(H, orc, K, P, dtype):
+    """aura_fuse_scores where it scores through per-cell similarities (16-bit maps on the matrix cores,
+    fewer cells than points), over the material-tile counts and both 16-bit types; ragged last tile."""
+    s = _custom_scene(N=1100 + K, V=4, D=256 if K < 64 else 512, K=K, P=P, dtype=dtype)
+    assert s.n_views * s.Hf * s.Wf <= s.N
+    d = H.DeviceScene(s)
+    d.step_combined()
+    gpu = d.results()
+    ref = H.oracle_points(orc, s)
+    print(H.compare_points(gpu, ref, s), flush=True)
+    _mass_check(H, orc, s, gpu, ref["prop"], ref["count_fuse"])
+    # against the two separate calls: the same sums in another order
+    d.fuse_features(); d.material_scores()
+    sep = d.results()
+    assert np.abs(sep["scores"] - gpu["scores"]).max() <= 2e-5
+    assert np.array_equal(sep["fused"].view(np.uint32), gpu["fused"].view(np.uint32))
+
+
 def test_scores_kernel_alone_on_random_unit_rows(H, orc):
     # isolates the matrix-core contraction: random unit rows, D not a multiple of the 32-channel step
     import paper_2511_03126_amd as aura
@@ -174,9 +202,12 @@ def test_unsorted_points_on_the_matrix_core_path(H, orc, name, kw):
     s = make_scene(name, order="random", **kw)
     d = H.DeviceScene(s)
     assert d.ws_fuse is not None
+    ref = H.oracle_points(orc, s)
+    d.step_combined()        # tiles without k-steps are scored from their fused rows
+    print(H.compare_points(d.results(), ref, s), flush=True)
+    d.clear_outputs()
     d.step()
     gpu = d.results()
-    ref = H.oracle_points(orc, s)
     print(H.compare_points(gpu, ref, s), flush=True)
     # tile headers (144 bytes each, at the start of the workspace): a k-step count of -1 marks the gather
     ntile = int(np.sum((np.diff(s.pt_offsets) + 31) // 32))
