@@ -61,7 +61,13 @@ constexpr int kViewBatch = 32;                 // views handled per pass over th
 constexpr int kPrepThreads = 256;
 constexpr int kSlots = kPrepThreads / kTilePts;   // views processed side by side (one per half wave)
 constexpr int kNIT = kViewBatch / kSlots;      // (point, view) pairs per thread and batch
-constexpr int kChunkSteps = 12;                // k-steps of the weight matrix held in LDS
+#ifndef AURA_CHUNK
+#define AURA_CHUNK 12
+#endif
+#ifndef AURA_PREP_WPE
+#define AURA_PREP_WPE 4
+#endif
+constexpr int kChunkSteps = AURA_CHUNK;        // k-steps of the weight matrix held in LDS
 constexpr int kChunk = kChunkSteps * kStepCells;
 constexpr int kPitch = kChunk + 8;             // row pitch in 16-bit elements (rows start 4 banks apart)
 constexpr int kHalf = 128;                     // channels of one half wave's row piece: 32 lanes x 4 channels
@@ -224,7 +230,7 @@ __device__ __forceinline__ void gather_tile(const FuseArgs& a, const ObjRange& o
 
 // DT: 1 bf16, 2 fp16 feature maps (decides the 16-bit format of the weights).
 template <int DT>
-__global__ __launch_bounds__(kPrepThreads) __attribute__((amdgpu_waves_per_eu(4)))
+__global__ __launch_bounds__(kPrepThreads) __attribute__((amdgpu_waves_per_eu(AURA_PREP_WPE)))
 void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
   __shared__ int s_win[kViewBatch][2];                 // first cell (x, y) of the view's map
   __shared__ int s_mode[kViewBatch];                   // 0 nothing seen, 1 cell map, 2 private entries

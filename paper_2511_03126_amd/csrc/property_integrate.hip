@@ -10,7 +10,9 @@
 // that no sum can overflow.
 //
 // All traffic is a few bytes per point plus one sweep over the voxel arrays: the call is a small
-// fraction of the fusion pass and is bound by launch latency for small inputs.
+// fraction of the fusion pass and is bound by launch latency for small inputs.  Grid mode is four
+// launches: (1) zero the voxel arrays and take the largest |prop| per slice of points, (2) bin,
+// (3) per-voxel means summed per slice of voxels, (4) the slices added in a fixed order.
 #include "aura_device.hpp"
 #include "launch.hpp"
 
@@ -43,18 +45,13 @@ struct MassArgs {
   int G;
   double* part_sum;        // [total slices]
   long long* part_used;    // [total slices]
-  unsigned* absmax_bits;   // [1]
+  unsigned* absmax_part;   // [slices of points]: largest |prop| bits per slice (grid mode)
+  int n_absmax;            // number of valid entries of absmax_part
   long long* vox_sum;      // [B * G^3] fixed point
   int* vox_cnt;            // [B * G^3]
   int obj_base;            // index of the table's first object within the call
   int n_points_bits;       // ceil(log2(N + 1)), for the fixed-point scale
 };
-
-__global__ void k_fill_zero(uint32_t* p, long long n_words) {
-  long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  long long stride = (long long)gridDim.x * blockDim.x;
-  for (; i < n_words; i += stride) p[i] = 0u;
-}
 
 __device__ __forceinline__ double block_sum(double v, double* sh) {
   v = wave_sum(v);
@@ -106,8 +103,19 @@ __global__ __launch_bounds__(kMassBlock) void k_mass_points(MassArgs a, MassTabl
 
 // ---------------------------------------------------------------- grid mode
 
-// Largest |prop| over the used points, as the bit pattern of a non-negative float (monotone).
-__global__ __launch_bounds__(kMassBlock) void k_mass_absmax(MassArgs a, MassTable tab) {
+// Launch 1 of grid mode.  Every workgroup zeroes its share of the voxel arrays;
+// workgroup (x, object) with x below the object's slice count also writes the largest |prop| over the used
+// points of its slice, as the bit pattern of a non-negative float (monotone), into its slot.
+typedef uint32_t mass_u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(kMassBlock) void k_mass_prepare(MassArgs a, MassTable tab, uint32_t* zero_from, long long zero_vecs) {
+  {
+    mass_u32x4* __restrict__ z = reinterpret_cast<mass_u32x4*>(zero_from);   // 256-byte aligned, a multiple of 256 bytes
+    const long long nthreads = (long long)gridDim.x * gridDim.y * kMassBlock;
+    long long i = ((long long)blockIdx.y * gridDim.x + blockIdx.x) * kMassBlock + threadIdx.x;
+    for (; i < zero_vecs; i += nthreads) z[i] = mass_u32x4{0u, 0u, 0u, 0u};
+  }
+  __shared__ unsigned shm[kMassBlock / kWave];
   const MassObjDev ob = tab.o[blockIdx.y];
   if ((int)blockIdx.x >= ob.n_slices) return;
   const int begin = blockIdx.x * kMassPtsPerBlock;
@@ -120,7 +128,27 @@ __global__ __launch_bounds__(kMassBlock) void k_mass_absmax(MassArgs a, MassTabl
   }
 #pragma unroll
   for (int o = kWave / 2; o > 0; o >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, o, kWave));
-  if (threadIdx.x % kWave == 0 && m != 0) atomicMax(a.absmax_bits, m);
+  if (threadIdx.x % kWave == 0) shm[threadIdx.x / kWave] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kMassBlock / kWave; ++w) m = max(m, shm[w]);
+    a.absmax_part[ob.slice_begin + blockIdx.x] = m;
+  }
+}
+
+// Largest |prop| of the call from the per-slice maxima (every workgroup that needs the scale does this).
+__device__ __forceinline__ unsigned call_absmax(const MassArgs& a, unsigned* sh) {
+  unsigned m = 0;
+  for (int j = threadIdx.x; j < a.n_absmax; j += kMassBlock) m = max(m, a.absmax_part[j]);
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, o, kWave));
+  if (threadIdx.x % kWave == 0) sh[threadIdx.x / kWave] = m;
+  __syncthreads();
+  m = sh[0];
+#pragma unroll
+  for (int w = 1; w < kMassBlock / kWave; ++w) m = max(m, sh[w]);
+  return m;
 }
 
 // Power-of-two scale s with |x| * 2^s * (number of points) < 2^62 for every used x.
@@ -140,37 +168,59 @@ __device__ __forceinline__ int voxel_axis(float x, float lo, float inv_h, int G)
 }
 
 __global__ __launch_bounds__(kMassBlock) void k_mass_bin(MassArgs a, MassTable tab) {
+  __shared__ unsigned shm[kMassBlock / kWave];
   const MassObjDev ob = tab.o[blockIdx.y];
   if ((int)blockIdx.x >= ob.n_slices) return;
   const int begin = blockIdx.x * kMassPtsPerBlock;
   const int end = min(begin + kMassPtsPerBlock, ob.n_pts);
-  const int shift = fixed_point_shift(*a.absmax_bits, a.n_points_bits);
+  const int shift = fixed_point_shift(call_absmax(a, shm), a.n_points_bits);
   const float inv_h = 1.0f / ob.h;
   const long long G = a.G;
   const long long vox0 = (long long)(a.obj_base + blockIdx.y) * G * G * G;
-  for (int li = begin + threadIdx.x; li < end; li += kMassBlock) {
-    const long long i = ob.pt_begin + li;
-    if (a.count && a.count[i] <= 0) continue;
-    const int ix = voxel_axis(a.xyz[3 * i], ob.lo[0], inv_h, a.G);
-    const int iy = voxel_axis(a.xyz[3 * i + 1], ob.lo[1], inv_h, a.G);
-    const int iz = voxel_axis(a.xyz[3 * i + 2], ob.lo[2], inv_h, a.G);
-    const long long vidx = vox0 + ((long long)iz * G + iy) * G + ix;
-    const long long q = __double2ll_rn(ldexp((double)a.prop[i * a.P + a.p_index], shift));
-    atomicAdd(reinterpret_cast<unsigned long long*>(a.vox_sum + vidx), (unsigned long long)q);
-    atomicAdd(a.vox_cnt + vidx, 1);
+  const int lane = threadIdx.x % kWave;
+  for (int l0 = begin; l0 < end; l0 += kMassBlock) {   // uniform trip count: the lanes of a wave exchange values below
+    const int li = l0 + threadIdx.x;
+    const long long i = ob.pt_begin + min(li, end - 1);
+    const bool used = li < end && !(a.count && a.count[i] <= 0);
+    long long vidx = -1 - lane;   // unused lanes: a voxel id no neighbour shares
+    long long q = 0;
+    if (used) {
+      const int ix = voxel_axis(a.xyz[3 * i], ob.lo[0], inv_h, a.G);
+      const int iy = voxel_axis(a.xyz[3 * i + 1], ob.lo[1], inv_h, a.G);
+      const int iz = voxel_axis(a.xyz[3 * i + 2], ob.lo[2], inv_h, a.G);
+      vidx = vox0 + ((long long)iz * G + iy) * G + ix;
+      q = __double2ll_rn(ldexp((double)a.prop[i * a.P + a.p_index], shift));
+    }
+    // Spatially sorted points fall into the same voxel in runs: the lanes of a run add up (integers: the
+    // order does not matter) and its last lane issues one pair of atomics for the whole run.
+    const long long prev = __shfl_up(vidx, 1, kWave), next = __shfl_down(vidx, 1, kWave);
+    const bool head = lane == 0 || prev != vidx, tail = lane == kWave - 1 || next != vidx;
+    int start = head ? lane : 0;   // lane of the run's first member
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) start = max(start, __shfl_up(start, o, kWave));
+#pragma unroll
+    for (int o = 1; o < kWave; o <<= 1) {
+      const long long up = __shfl_up(q, o, kWave);
+      if (lane - o >= start) q += up;
+    }
+    if (used && tail) {
+      atomicAdd(reinterpret_cast<unsigned long long*>(a.vox_sum + vidx), (unsigned long long)q);
+      atomicAdd(a.vox_cnt + vidx, lane - start + 1);
+    }
   }
 }
 
-// Sum of per-voxel means over one slice of an object's voxels.
+// Launch 3 of grid mode: sum of per-voxel means over one slice of an object's voxels.
 __global__ __launch_bounds__(kMassBlock) void k_mass_voxels(MassArgs a, MassTable tab) {
   __shared__ double shd[kMassBlock / kWave];
   __shared__ long long shl[kMassBlock / kWave];
+  __shared__ unsigned shm[kMassBlock / kWave];
   const MassObjDev ob = tab.o[blockIdx.y];
   const long long G3 = (long long)a.G * a.G * a.G;
   const long long vox0 = (long long)(a.obj_base + blockIdx.y) * G3;
   const long long begin = (long long)blockIdx.x * kVoxPerBlock;
   const long long end = min(begin + (long long)kVoxPerBlock, G3);
-  const int shift = fixed_point_shift(*a.absmax_bits, a.n_points_bits);
+  const int shift = fixed_point_shift(call_absmax(a, shm), a.n_points_bits);
   double s = 0.0;
   long long used = 0;
   for (long long j = begin + threadIdx.x; j < end; j += kMassBlock) {
@@ -222,11 +272,11 @@ static long long max_slices(long long N, int B, int G) {
 }
 
 size_t integrate_workspace_bytes(long long N, int B, int G) {
-  size_t bytes = 256;                                          // absmax word
-  bytes += align256((size_t)max_slices(N, B, G) * sizeof(double));
+  size_t bytes = align256((size_t)max_slices(N, B, G) * sizeof(double));
   bytes += align256((size_t)max_slices(N, B, G) * sizeof(long long));
   if (G > 0) {
     size_t vox = (size_t)B * G * G * G;
+    bytes += align256((size_t)(slices_points(N) + B) * sizeof(unsigned));                       // per-slice maxima
     bytes += align256(vox * sizeof(long long)) + align256(vox * sizeof(int));
   }
   return bytes;
@@ -241,74 +291,72 @@ hipError_t launch_property_integrate(const float* prop, int P, int p_index, cons
   MassArgs a{};
   a.prop = prop; a.P = P; a.p_index = p_index; a.count = count; a.vol = vol; a.vol_uniform = vol_uniform;
   a.xyz = xyz; a.G = G;
-  a.absmax_bits = reinterpret_cast<unsigned*>(ws);
-  size_t off = 256;
+  size_t off = 0;
   const long long nsl = max_slices(N, B, G);
   a.part_sum = reinterpret_cast<double*>(ws + off);     off += align256((size_t)nsl * sizeof(double));
   a.part_used = reinterpret_cast<long long*>(ws + off); off += align256((size_t)nsl * sizeof(long long));
   const size_t vox = G > 0 ? (size_t)B * G * G * G : 0;
+  size_t zero_begin = 0, zero_end = 0;   // the voxel sums and the voxel counts must start at zero
   if (G > 0) {
+    a.absmax_part = reinterpret_cast<unsigned*>(ws + off); off += align256((size_t)(slices_points(N) + B) * sizeof(unsigned));
+    zero_begin = off;
     a.vox_sum = reinterpret_cast<long long*>(ws + off); off += align256(vox * sizeof(long long));
     a.vox_cnt = reinterpret_cast<int*>(ws + off);       off += align256(vox * sizeof(int));
+    zero_end = off;
   }
   a.n_points_bits = 1;
   while (a.n_points_bits < 40 && (1ll << a.n_points_bits) <= N) ++a.n_points_bits;
+  for (int b = 0; b < B; ++b) a.n_absmax += (int)slices_points(objs[b].n_pts);
 
-  // the absmax word, the voxel sums and the voxel counts must start at zero
-  if (G > 0) {
-    const long long words = (long long)(off / 4);
-    const int blocks = (int)((words + 256 * 8 - 1) / (256 * 8) < 65535 ? (words + 256 * 8 - 1) / (256 * 8) : 65535);
-    hipLaunchKernelGGL(k_fill_zero, dim3(blocks), dim3(256), 0, stream, reinterpret_cast<uint32_t*>(ws), words);
-    hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-
-  int slice_cursor = 0;
-  struct Chunk { MassTable tab; int n_obj; int obj_base; int max_slices; };
-  // objects go to the device in tables of kMaxObjPerLaunch; grid mode needs every object's absmax
+  // objects go to the device in tables of kMaxObjPerLaunch; grid mode needs every object's maxima
   // and bins finished before any voxel is read, so the passes run over all tables one after another
   const int n_chunks = (B + kMaxObjPerLaunch - 1) / kMaxObjPerLaunch;
-  for (int pass = 0; pass < (G > 0 ? 4 : 2); ++pass) {
-    slice_cursor = 0;
+  const int n_passes = G > 0 ? 4 : 2;
+  for (int pass = 0; pass < n_passes; ++pass) {
+    int pt_cursor = 0, vox_cursor = 0;
     for (int c = 0; c < n_chunks; ++c) {
-      Chunk ch{};
-      ch.obj_base = c * kMaxObjPerLaunch;
-      ch.n_obj = B - ch.obj_base < kMaxObjPerLaunch ? B - ch.obj_base : kMaxObjPerLaunch;
+      MassTable tab{};
+      const int obj_base = c * kMaxObjPerLaunch;
+      const int n_obj = B - obj_base < kMaxObjPerLaunch ? B - obj_base : kMaxObjPerLaunch;
+      const bool by_voxels = G > 0 && pass >= 2;
       int max_pt_slices = 0;
-      for (int t = 0; t < ch.n_obj; ++t) {
-        const MassObj& o = objs[ch.obj_base + t];
-        MassObjDev& d = ch.tab.o[t];
+      for (int t = 0; t < n_obj; ++t) {
+        const MassObj& o = objs[obj_base + t];
+        MassObjDev& d = tab.o[t];
         d.pt_begin = o.pt_begin; d.n_pts = o.n_pts;
         d.lo[0] = o.lo[0]; d.lo[1] = o.lo[1]; d.lo[2] = o.lo[2]; d.h = o.h;
         const int pt_slices = (int)slices_points(o.n_pts);
         max_pt_slices = pt_slices > max_pt_slices ? pt_slices : max_pt_slices;
-        d.n_slices = pt_slices;
-        d.slice_begin = slice_cursor;
-        slice_cursor += G > 0 ? (int)slices_voxels(G) : pt_slices;
+        d.n_slices = by_voxels ? (int)slices_voxels(G) : pt_slices;
+        d.slice_begin = by_voxels ? vox_cursor : pt_cursor;
+        pt_cursor += pt_slices;
+        vox_cursor += G > 0 ? (int)slices_voxels(G) : 0;
       }
-      a.obj_base = ch.obj_base;
+      a.obj_base = obj_base;
       dim3 block(kMassBlock);
       if (G == 0) {
         if (pass == 0) {
           if (max_pt_slices > 0)
-            hipLaunchKernelGGL(k_mass_points, dim3(max_pt_slices, ch.n_obj), block, 0, stream, a, ch.tab);
+            hipLaunchKernelGGL(k_mass_points, dim3(max_pt_slices, n_obj), block, 0, stream, a, tab);
         } else {
-          hipLaunchKernelGGL(k_mass_final, dim3(ch.n_obj), block, 0, stream, a, ch.tab, mass, n_used);
+          hipLaunchKernelGGL(k_mass_final, dim3(n_obj), block, 0, stream, a, tab, mass, n_used);
         }
+      } else if (pass == 0) {
+        // the first table's launch also zeroes (16 bytes per thread and trip): give it enough workgroups
+        const long long zero_vecs = c == 0 ? (long long)((zero_end - zero_begin) / 16) : 0;
+        int gx = max_pt_slices > 1 ? max_pt_slices : 1;
+        if (c == 0) {
+          const long long want = (zero_vecs / (8 * kMassBlock) + n_obj) / n_obj;
+          gx = (int)(want > gx ? (want < 4096 ? want : 4096) : gx);
+        }
+        hipLaunchKernelGGL(k_mass_prepare, dim3(gx, n_obj), block, 0, stream, a, tab,
+                           reinterpret_cast<uint32_t*>(ws + zero_begin), zero_vecs);
+      } else if (pass == 1) {
+        if (max_pt_slices > 0) hipLaunchKernelGGL(k_mass_bin, dim3(max_pt_slices, n_obj), block, 0, stream, a, tab);
+      } else if (pass == 2) {
+        hipLaunchKernelGGL(k_mass_voxels, dim3((int)slices_voxels(G), n_obj), block, 0, stream, a, tab);
       } else {
-        if (pass == 0) {
-          if (max_pt_slices > 0)
-            hipLaunchKernelGGL(k_mass_absmax, dim3(max_pt_slices, ch.n_obj), block, 0, stream, a, ch.tab);
-        } else if (pass == 1) {
-          if (max_pt_slices > 0)
-            hipLaunchKernelGGL(k_mass_bin, dim3(max_pt_slices, ch.n_obj), block, 0, stream, a, ch.tab);
-        } else {
-          for (int t = 0; t < ch.n_obj; ++t) ch.tab.o[t].n_slices = (int)slices_voxels(G);
-          if (pass == 2)
-            hipLaunchKernelGGL(k_mass_voxels, dim3((int)slices_voxels(G), ch.n_obj), block, 0, stream, a, ch.tab);
-          else
-            hipLaunchKernelGGL(k_mass_final, dim3(ch.n_obj), block, 0, stream, a, ch.tab, mass, n_used);
-        }
+        hipLaunchKernelGGL(k_mass_final, dim3(n_obj), block, 0, stream, a, tab, mass, n_used);
       }
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
