@@ -61,14 +61,16 @@ struct CellArgs {
   uint32_t* G;          // [n_cells][Kpad]: hi | lo << 16
 };
 
-// One wave per 32 cells, all materials.  A operand: lane (cell i = l % 32, kg = l / 32) holds channels
-// 16 s + 8 kg .. + 7 of cell i (16 contiguous bytes of the stored map); B operand: the same channels of
-// material n = l % 32, split on the fly.
+// One workgroup of four waves per 32 cells, all materials; wave w takes every fourth group of 16 channels
+// (the sum over channels is a short chain of dependent steps: four waves make it four times shorter) and
+// the four partial results are added through LDS in a fixed order.  A operand: lane (cell i = l % 32,
+// kg = l / 32) holds channels 16 s + 8 kg .. + 7 of cell i (16 contiguous bytes of the stored map);
+// B operand: the same channels of material n = l % 32, split on the fly.
 template <int DT, int MT>
 __global__ __launch_bounds__(256) void k_cell_scores(CellArgs a) {
+  __shared__ float s_part[3][MT][16][kWave];
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-  const long long c0 = ((long long)blockIdx.x * 4 + wave) * 32;
-  if (c0 >= a.n_cells) return;
+  const long long c0 = (long long)blockIdx.x * 32;
   const int i = lane & 31, kg = lane >> 5;
   const long long cell = min(c0 + i, a.n_cells - 1);
   const char* __restrict__ frow = a.feat + cell * a.D * 2 + kg * 16;
@@ -82,7 +84,7 @@ __global__ __launch_bounds__(256) void k_cell_scores(CellArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
 
-  for (int s = 0; s < a.D / 16; ++s) {
+  for (int s = wave; s < a.D / 16; s += 4) {
     const ts_u32x4 fa = *reinterpret_cast<const ts_u32x4*>(frow + s * 32);
 #pragma unroll
     for (int mt = 0; mt < MT; ++mt) {
@@ -100,13 +102,22 @@ __global__ __launch_bounds__(256) void k_cell_scores(CellArgs a) {
       acc[mt] = ts_mma<DT>(fa, bl, acc[mt]);
     }
   }
+  if (wave > 0) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_part[wave - 1][mt][r][lane] = acc[mt][r];
+  }
+  __syncthreads();
+  if (wave > 0) return;
   // element r of the lane: cell c0 + 8 (r / 4) + 4 kg + r % 4, material 32 mt + i (0 beyond K)
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const long long c = c0 + 8 * (r >> 2) + 4 * kg + (r & 3);
-      const float v = (mt * 32 + i < a.K) ? acc[mt][r] : 0.0f;
+      const float sum = ((acc[mt][r] + s_part[0][mt][r][lane]) + s_part[1][mt][r][lane]) + s_part[2][mt][r][lane];
+      const float v = (mt * 32 + i < a.K) ? sum : 0.0f;
       if (c < a.n_cells) a.G[c * a.Kpad + mt * 32 + i] = split_pack<DT>(v);
     }
 }
@@ -245,7 +256,7 @@ TileScoreWs tile_scores_workspace(void* workspace, long long N, long long n_cell
 
 template <int DT>
 static hipError_t launch_cells(const CellArgs& a, hipStream_t stream) {
-  const dim3 grid((unsigned)((a.n_cells + 127) / 128)), block(256);
+  const dim3 grid((unsigned)((a.n_cells + 31) / 32)), block(256);
   switch (a.Kpad / 32) {
     case 1: hipLaunchKernelGGL((k_cell_scores<DT, 1>), grid, block, 0, stream, a); break;
     case 2: hipLaunchKernelGGL((k_cell_scores<DT, 2>), grid, block, 0, stream, a); break;
