@@ -32,8 +32,8 @@ def fuse_algorithmic_bytes(s):
 # profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_prepare + k_tile_product, each
 # scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
 # the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = None
-TRAFFIC_SOURCE_SHA256 = ""
+TRAFFIC_C2_BYTES = 847454618
+TRAFFIC_SOURCE_SHA256 = "11d1a44bc4da34b208f287825b393cd931edd853e95bb34bcee340ade1045c83"
 
 
 def measured_traffic():
@@ -72,8 +72,12 @@ def cpu_baseline(scene, seconds_target=15.0):
     n = int(min(p1, max(n, n * seconds_target / max(t, 1e-3))))
     n = min(n, 400_000)
     t = run(n)
-    return {"value": n * v1 / t, "unit": "point-views/s", "cores": orc.max_threads(), "kind": "oracle",
-            "sample": f"first {n} points of object 0 x {v1} views, whole path, {t:.1f} s"}
+    reps = 1
+    while t < 0.7 * seconds_target and reps < 64:     # the whole object is quicker than the target: repeat it
+        t += run(n)
+        reps += 1
+    return {"value": reps * n * v1 / t, "unit": "point-views/s", "cores": orc.max_threads(), "kind": "oracle",
+            "sample": f"first {n} points of object 0 x {v1} views, whole path, {reps} passes, {t:.1f} s"}
 
 
 CAL_BYTES = 256 << 20   # size of the calibration copy (read) and of its destination (write)
