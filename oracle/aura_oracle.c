@@ -16,6 +16,9 @@
  *   kernel regression rho(s)               Sec. 3.4.1 Eq. 4, T from Sec. 4 "Parameters"
  *   integration to mass                    Sec. 3.4.2 (each query point is the centre of a
  *                                          voxel; property times voxel volume, summed)
+ *   densification omega(q)                 Sec. 3.4.1 Eq. 5 (k nearest source points by cosine
+ *                                          similarity of the fused features, similarity-weighted
+ *                                          mean of their material vectors, then Eq. 4)
  *
  * Precision.  All sums, weights and outputs are double.  The few quantities that
  * DECIDE an integer (which depth texel is read, whether a point passes the depth
@@ -418,5 +421,92 @@ int orc_property_integrate(const double* prop, int64_t N, int P, int p_index,
   }
   free(vsum);
   free(vcnt);
+  return 0;
+}
+
+/* ---------------------------------------------------------------- exported: Eq. 5 (densification)
+ * For every query q: phi_j = cosine similarity of fq[q] and fs[j] (0 when either vector is zero); N_k(q) =
+ * the k sources with the largest phi (of equal values the lower index first; k is cut to Ns);
+ *     wq[q][m] = sum_{j in N_k} phi_j ws[j][m] / sum_{j in N_k} phi_j
+ * (when |sum phi| < 1e-12 the vector of the nearest source is taken).  Then Eq. 4 on wq[q]:
+ * prop[q][p] = sum_m softmax_m(wq/T) y[m][p]; label = argmax_m wq (lowest index on ties).
+ * nn_idx / nn_sim [Nq][k]: the neighbours in selection order (-1 / 0 beyond Ns); gap[q] = phi of the k-th
+ * neighbour minus the largest phi left out (+inf when nothing is left out).                              */
+int orc_knn_densify(const double* fq, int64_t Nq, const double* fs, int Ns, int D, const double* ws, int K, int k,
+                    const float* y, int P, float T,
+                    double* wq, double* prop, int32_t* label, int32_t* nn_idx, double* nn_sim, double* gap) {
+  if (!fq || !fs || !ws || !wq) return -1;
+  if (Nq < 0 || Ns < 1 || D < 1 || K < 1 || k < 1 || P < 0 || (prop && (!y || P < 1)) || !(T > 0.0f)) return -2;
+  const int ke = k < Ns ? k : Ns;
+  double* snorm = (double*)malloc(sizeof(double) * (size_t)Ns);
+  if (!snorm) return -3;
+  for (int j = 0; j < Ns; ++j) {
+    double ss = 0.0;
+    for (int c = 0; c < D; ++c) ss += fs[(int64_t)j * D + c] * fs[(int64_t)j * D + c];
+    snorm[j] = sqrt(ss);
+  }
+#pragma omp parallel
+  {
+    double* phi = (double*)malloc(sizeof(double) * (size_t)Ns);
+    char* taken = (char*)malloc((size_t)Ns);
+#pragma omp for schedule(dynamic, 64)
+    for (int64_t q = 0; q < Nq; ++q) {
+      const double* f = fq + q * D;
+      double qq = 0.0;
+      for (int c = 0; c < D; ++c) qq += f[c] * f[c];
+      const double qn = sqrt(qq);
+      for (int j = 0; j < Ns; ++j) {
+        double dot = 0.0;
+        for (int c = 0; c < D; ++c) dot += f[c] * fs[(int64_t)j * D + c];
+        phi[j] = (qn > 0.0 && snorm[j] > 0.0) ? dot / (qn * snorm[j]) : 0.0;
+        taken[j] = 0;
+      }
+      double* w = wq + q * K;
+      for (int m = 0; m < K; ++m) w[m] = 0.0;
+      double den = 0.0;
+      int first = -1;
+      double kth = 0.0;
+      for (int t = 0; t < k; ++t) {
+        int best = -1;
+        if (t < ke) {
+          for (int j = 0; j < Ns; ++j)
+            if (!taken[j] && (best < 0 || phi[j] > phi[best])) best = j;   /* ascending j: the lower index wins ties */
+          taken[best] = 1;
+          if (t == 0) first = best;
+          kth = phi[best];
+          den += phi[best];
+          for (int m = 0; m < K; ++m) w[m] += phi[best] * ws[(int64_t)best * K + m];
+        }
+        if (nn_idx) nn_idx[q * k + t] = best;
+        if (nn_sim) nn_sim[q * k + t] = best >= 0 ? phi[best] : 0.0;
+      }
+      if (gap) {
+        double rest = -INFINITY;
+        for (int j = 0; j < Ns; ++j) if (!taken[j] && phi[j] > rest) rest = phi[j];
+        gap[q] = (ke < Ns) ? kth - rest : INFINITY;
+      }
+      if (fabs(den) < 1e-12) {
+        for (int m = 0; m < K; ++m) w[m] = ws[(int64_t)first * K + m];
+      } else {
+        for (int m = 0; m < K; ++m) w[m] /= den;
+      }
+      int top = 0;
+      for (int m = 1; m < K; ++m) if (w[m] > w[top]) top = m;
+      if (label) label[q] = top;
+      if (prop) {
+        double z = 0.0;
+        for (int p = 0; p < P; ++p) prop[q * P + p] = 0.0;
+        for (int m = 0; m < K; ++m) {
+          const double e = exp((w[m] - w[top]) / (double)T);
+          z += e;
+          for (int p = 0; p < P; ++p) prop[q * P + p] += e * (double)y[(int64_t)m * P + p];
+        }
+        for (int p = 0; p < P; ++p) prop[q * P + p] /= z;
+      }
+    }
+    free(phi);
+    free(taken);
+  }
+  free(snorm);
   return 0;
 }

@@ -189,3 +189,27 @@ def property_integrate(prop, p_index=0, count=None, vol=None, vol_uniform=1.0, p
                                       _p(grid_h), C.c_int(G), _p(mass), _p(n_used))
     _check(rc, "property_integrate")
     return {"mass": mass, "n_used": n_used}
+
+
+def knn_densify(fq, fs, ws, k, y=None, T=0.1):
+    """Eq. 5: material vectors of the queries from their k nearest sources in feature space, then Eq. 4."""
+    fq = np.ascontiguousarray(fq, dtype=np.float64)
+    fs = np.ascontiguousarray(fs, dtype=np.float64)
+    ws = np.ascontiguousarray(ws, dtype=np.float64)
+    Nq, D = fq.shape
+    Ns, K = ws.shape
+    if fs.shape != (Ns, D):
+        raise ValueError("fs must be [Ns][D]")
+    y = None if y is None else _f32(y).reshape(K, -1)
+    P = 0 if y is None else y.shape[1]
+    wq = np.zeros((Nq, K), np.float64)
+    prop = np.zeros((Nq, P), np.float64) if y is not None else None
+    label = np.zeros(Nq, np.int32)
+    nn_idx = np.zeros((Nq, k), np.int32)
+    nn_sim = np.zeros((Nq, k), np.float64)
+    gap = np.zeros(Nq, np.float64)
+    rc = lib().orc_knn_densify(_p(fq), C.c_int64(Nq), _p(fs), C.c_int(Ns), C.c_int(D), _p(ws), C.c_int(K), C.c_int(k),
+                               _p(y), C.c_int(P), C.c_float(T), _p(wq), _p(prop), _p(label), _p(nn_idx), _p(nn_sim),
+                               _p(gap))
+    _check(rc, "knn_densify")
+    return {"wq": wq, "prop": prop, "label": label, "nn_idx": nn_idx, "nn_sim": nn_sim, "gap": gap}
