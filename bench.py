@@ -46,6 +46,34 @@ def measured_traffic():
     return TRAFFIC_C2_BYTES if digest == TRAFFIC_SOURCE_SHA256 else None
 
 
+def time_densify(torch, d, s, reps, n_sources=150, k=5):
+    """The step after the hot path (Sec. 3.4.1 Eq. 5): every point of the scene as a query, its fused row as the
+    feature, 150 evenly spaced points as sources with their scores.  HBM bound on reading the query features."""
+    import paper_2511_03126_amd as aura
+    from paper_2511_03126_amd import binding
+    ns = min(n_sources, s.N)
+    src = torch.linspace(0, s.N - 1, ns, device=d.dev).long()
+    fs, ws = d.fused[src].contiguous(), d.scores[src].contiguous()
+    wq, prop = torch.empty_like(d.scores), torch.empty_like(d.prop)
+    label = torch.empty_like(d.label)
+    work = torch.empty(aura.workspace_bytes(binding.CALL_KNN_DENSIFY, D=s.D, Ns=ns), dtype=torch.uint8, device=d.dev)
+    run = lambda: aura.knn_densify(d.fused, fs, ws, k, d.y, d.params, wq, prop, label, None, work)
+    for _ in range(2):
+        run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    nbytes = 4 * s.N * s.D + 4 * ns * s.D + 4 * ns * s.K + 4 * s.N * s.K + 4 * s.N * s.P + 4 * s.N
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    return {"call": "aura_knn_densify", "queries": s.N, "sources": ns, "k": k, "ms": ms, "bound": "hbm",
+            "algorithmic_bytes": nbytes, "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": gbps / HBM_PEAK_GBPS}
+
+
 def cpu_baseline(scene, seconds_target=15.0):
     """The oracle, as it stands, on a contiguous sample of the scene's first object."""
     import numpy as np
@@ -173,6 +201,7 @@ def main():
     kernel = "aura_fuse_features: " + (f"k_tile_prepare + k_tile_product<{s.feat_dtype}, {s.D // 256} waves>" if tile
                                        else "k_fuse_gather")
     traffic = measured_traffic() if (tile and args.workload == "c2") else None
+    densify = time_densify(torch, d, s, max(args.steps // 2, 5))
     out = {
         "metric": "fused point-views/sec", "value": pv / (ms_per_step * 1e-3), "unit": "point-views/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -186,6 +215,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes": fuse_bytes, "avg_launch_ms": fuse_ms},
+        "densify": densify,
         "calibration": calibration,
     }
     if not args.no_cpu_baseline:

@@ -9,6 +9,7 @@
  *                             by the cosine similarity of Sec. 3.4.1)
  *   aura_material_scores      Sec. 3.4.1: similarity omega_k and the kernel regression of Eq. 4
  *   aura_fuse_scores          the two calls above in one (Eq. 2, then Sec. 3.4.1 / Eq. 4)
+ *   aura_knn_densify          Sec. 3.4.1 Eq. 5: feature-space k-NN densification, then Eq. 4
  *   aura_property_integrate   Sec. 3.4.2: voxel integration over volumes (mass)
  *
  * General rules
@@ -69,7 +70,7 @@ enum {
 
 /* Which call a workspace size is asked for. */
 enum { AURA_CALL_MATERIAL_SCORES = 1, AURA_CALL_PROPERTY_INTEGRATE = 2, AURA_CALL_FUSE_FEATURES = 3,
-       AURA_CALL_FUSE_SCORES = 4 };
+       AURA_CALL_FUSE_SCORES = 4, AURA_CALL_KNN_DENSIFY = 5 };
 
 /* Problem sizes for aura_workspace_bytes; fields a call does not list are ignored. */
 typedef struct aura_sizes_t {
@@ -80,6 +81,7 @@ typedef struct aura_sizes_t {
   int32_t feat_dtype;   /* AURA_F32 | AURA_BF16 | AURA_F16                                     */
   int32_t K;            /* candidate materials                                                 */
   int32_t G;            /* voxels per axis of the integration grid, 0 = point-volume mode      */
+  int32_t Ns;           /* source points of aura_knn_densify                                   */
 } aura_sizes_t;
 
 /* One set of calibrated views (Sec. 3.1: poses, Depth_v and F_v for v in V). */
@@ -126,6 +128,7 @@ int32_t aura_last_hip_error(void);
  *   AURA_CALL_PROPERTY_INTEGRATE  N, B, G
  *   AURA_CALL_FUSE_FEATURES       N, B, n_views, Hf, Wf, D, feat_dtype
  *   AURA_CALL_FUSE_SCORES         N, B, n_views, Hf, Wf, D, feat_dtype, K
+ *   AURA_CALL_KNN_DENSIFY         D, Ns
  * Errors: AURA_ERR_NULL (sizes, bytes), AURA_ERR_SHAPE, AURA_ERR_DTYPE, AURA_ERR_UNSUPPORTED
  * (unknown call, or sizes beyond the limits of the call).
  */
@@ -231,6 +234,35 @@ aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* p
                                const void* temb, int32_t temb_dtype, int32_t K, const float* y, int32_t P,
                                float* fused, int32_t* count, float* scores, float* prop, int32_t* label,
                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sec. 3.4.1 Eq. 5, densification.  Ns sparse source points carry material vectors ws[j] (the K numbers
+ * that Eq. 4 consumes, e.g. the scores of aura_material_scores at those points); every dense query point
+ * gets the similarity-weighted mean of the vectors of its k nearest sources in feature space:
+ *     phi_j = cosine similarity of fq[i] and fs[j]  (0 when either vector is zero),
+ *     N_k(i) = the k sources with the largest phi (of equal values the lower index first; k is cut to Ns),
+ *     wq[i][m] = sum_{j in N_k(i)} phi_j ws[j][m] / sum_{j in N_k(i)} phi_j.
+ * Eq. 5 is taken as printed: the weights are the similarities themselves, negative ones included; when the
+ * sum of the weights is below 1e-12 in magnitude the vector of the nearest source is returned.  Then Eq. 4 on
+ * wq[i] when y is given: prop[i][p] = sum_m softmax_m(wq[i] / T) y[m][p]; label[i] = argmax_m wq[i][m].
+ * The paper does not print its k: it is an argument.
+ *
+ *   fq  [device] [Nq][D] fp32 features of the queries (e.g. the rows of aura_fuse_features)
+ *   fs  [device] [Ns][D] fp32 features of the source points       ws [device] [Ns][K] fp32
+ *   y   [device] [K][P] fp32 or NULL      wq [device] [Nq][K] fp32
+ *   prop [device] [Nq][P] fp32 or NULL (needs y)   label [device] [Nq] int32 or NULL
+ *   nn_idx [device] [Nq][k] int32 or NULL: the neighbours in selection order (-1 beyond Ns)
+ *   workspace [device] aura_workspace_bytes(AURA_CALL_KNN_DENSIFY, ...) bytes, 256-byte aligned
+ * The similarities run on the matrix cores with each fp32 operand split into two bf16 terms (error of a
+ * similarity near 1e-6), so which of two sources closer than that is "nearer" may differ from an exact
+ * evaluation.
+ * Limits: 1 <= Ns <= 256, 1 <= k <= 16, 1 <= K <= 128, 1 <= P <= 8.
+ * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_WORKSPACE, AURA_ERR_UNSUPPORTED, AURA_ERR_HIP.
+ */
+aura_status_t aura_knn_densify(const float* fq, int64_t Nq, int32_t D, const float* fs, int32_t Ns,
+                               const float* ws, int32_t K, int32_t k, const float* y, int32_t P,
+                               const aura_params_t* params, float* wq, float* prop, int32_t* label,
+                               int32_t* nn_idx, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Sec. 3.4.2 "voxel integration over volumes".  Each point is the centre of a voxel; the

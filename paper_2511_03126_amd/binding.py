@@ -16,7 +16,7 @@ _LIB_PATH = Path(__file__).resolve().parent / "libaura_fuse.so"
 
 F32, BF16, F16 = 0, 1, 2
 VIS_FRUSTUM_ONLY, FUSE_MEAN_ONLY, FUSE_GATHER = 1, 2, 4
-CALL_MATERIAL_SCORES, CALL_PROPERTY_INTEGRATE, CALL_FUSE_FEATURES, CALL_FUSE_SCORES = 1, 2, 3, 4
+CALL_MATERIAL_SCORES, CALL_PROPERTY_INTEGRATE, CALL_FUSE_FEATURES, CALL_FUSE_SCORES, CALL_KNN_DENSIFY = 1, 2, 3, 4, 5
 
 _TORCH_DTYPE = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 
@@ -38,7 +38,7 @@ class _ViewsT(C.Structure):
 
 class _SizesT(C.Structure):
     _fields_ = [("N", C.c_int64), ("B", C.c_int32), ("n_views", C.c_int32), ("Hf", C.c_int32), ("Wf", C.c_int32),
-                ("D", C.c_int32), ("feat_dtype", C.c_int32), ("K", C.c_int32), ("G", C.c_int32)]
+                ("D", C.c_int32), ("feat_dtype", C.c_int32), ("K", C.c_int32), ("G", C.c_int32), ("Ns", C.c_int32)]
 
 
 class _ParamsT(C.Structure):
@@ -75,6 +75,9 @@ def lib():
         L.aura_fuse_scores.restype = C.c_int32
         L.aura_fuse_scores.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32, vp, i32, i32, vp,
                                        i32, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.aura_knn_densify.restype = C.c_int32
+        L.aura_knn_densify.argtypes = [vp, i64, i32, vp, i32, vp, i32, i32, vp, i32, C.POINTER(_ParamsT), vp, vp, vp, vp,
+                                       vp, C.c_size_t, vp]
         L.aura_property_integrate.restype = C.c_int32
         L.aura_property_integrate.argtypes = [vp, i64, i32, i32, vp, vp, f32, vp, i32, vp, vp, vp, i32, vp, vp,
                                               vp, C.c_size_t, vp]
@@ -153,9 +156,9 @@ def _check(status, what):
 
 
 def workspace_bytes(call: int, N: int = 0, B: int = 1, D: int = 1, K: int = 1, G: int = 0, n_views: int = 1,
-                    Hf: int = 1, Wf: int = 1, feat_dtype: int = F32) -> int:
+                    Hf: int = 1, Wf: int = 1, feat_dtype: int = F32, Ns: int = 1) -> int:
     out = C.c_size_t(0)
-    sz = _SizesT(N, B, n_views, Hf, Wf, D, feat_dtype, K, G)
+    sz = _SizesT(N, B, n_views, Hf, Wf, D, feat_dtype, K, G, Ns)
     _check(lib().aura_workspace_bytes(call, C.byref(sz), C.byref(out)), "aura_workspace_bytes")
     return int(out.value)
 
@@ -232,6 +235,20 @@ def fuse_scores(views: Views, params: Params, xyz, temb, y, fused, scores, count
                                   temb.data_ptr(), F32, K, _ptr(y), P, fused.data_ptr(), _ptr(count),
                                   scores.data_ptr(), _ptr(prop), _ptr(label), _ptr(workspace),
                                   0 if workspace is None else workspace.numel(), _stream()), "aura_fuse_scores")
+
+
+def knn_densify(fq, fs, ws, k, y, params: Params, wq, prop=None, label=None, nn_idx=None, workspace=None):
+    """wq [Nq][K], prop [Nq][P], label [Nq], nn_idx [Nq][k] are filled in place; workspace is a uint8 device tensor."""
+    fq = _dev(fq, torch.float32, "fq")
+    fs = _dev(fs, torch.float32, "fs")
+    ws = _dev(ws, torch.float32, "ws")
+    Nq, D = fq.shape
+    Ns, K = ws.shape
+    P = 0 if y is None else y.shape[1]
+    p = params.c()
+    _check(lib().aura_knn_densify(fq.data_ptr(), Nq, D, fs.data_ptr(), Ns, ws.data_ptr(), K, k, _ptr(y), P, C.byref(p),
+                                  wq.data_ptr(), _ptr(prop), _ptr(label), _ptr(nn_idx), _ptr(workspace),
+                                  0 if workspace is None else workspace.numel(), _stream()), "aura_knn_densify")
 
 
 def property_integrate(prop, mass, p_index=0, count=None, vol=None, vol_uniform=1.0, pt_offsets=None, xyz=None,

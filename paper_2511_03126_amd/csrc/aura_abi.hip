@@ -177,6 +177,12 @@ aura_status_t aura_workspace_bytes(int32_t call, const aura_sizes_t* sz, size_t*
       *bytes = aura::fuse_tile_workspace_bytes(sz->N, sz->B, sz->n_views);
     return AURA_OK;
   }
+  if (call == AURA_CALL_KNN_DENSIFY) {
+    if (sz->D < 1 || sz->Ns < 1) return AURA_ERR_SHAPE;
+    if (sz->Ns > 256) return AURA_ERR_UNSUPPORTED;
+    *bytes = aura::knn_workspace_bytes(sz->D, sz->Ns);
+    return AURA_OK;
+  }
   if (call == AURA_CALL_FUSE_SCORES) {
     if (sz->N < 0 || sz->B < 1 || sz->n_views < 1 || sz->Hf < 1 || sz->Wf < 1 || sz->D < 1 || sz->K < 1) return AURA_ERR_SHAPE;
     if (sz->feat_dtype != AURA_F32 && sz->feat_dtype != AURA_BF16 && sz->feat_dtype != AURA_F16) return AURA_ERR_DTYPE;
@@ -330,6 +336,22 @@ aura_status_t aura_material_scores(const float* fused, int64_t N, int32_t D,
   return hip_status(aura::launch_material_scores(fused, N, D, static_cast<const float*>(temb), K, y, P,
                                                  params->temperature, scores, prop, label, workspace,
                                                  static_cast<hipStream_t>(stream)));
+}
+
+aura_status_t aura_knn_densify(const float* fq, int64_t Nq, int32_t D, const float* fs, int32_t Ns,
+                               const float* ws, int32_t K, int32_t k, const float* y, int32_t P,
+                               const aura_params_t* params, float* wq, float* prop, int32_t* label,
+                               int32_t* nn_idx, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!params || !fs || !ws) return AURA_ERR_NULL;
+  if (Nq < 0 || D < 1 || Ns < 1 || K < 1 || k < 1 || P < 0) return AURA_ERR_SHAPE;
+  if (prop && (!y || P < 1)) return AURA_ERR_NULL;
+  if (!(params->temperature > 0.0f)) return AURA_ERR_SHAPE;
+  if (!aura::knn_supported(Ns, K, k, P)) return AURA_ERR_UNSUPPORTED;
+  if (Nq == 0) return AURA_OK;
+  if (!fq || !wq) return AURA_ERR_NULL;
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < aura::knn_workspace_bytes(D, Ns)) return AURA_ERR_WORKSPACE;
+  return hip_status(aura::launch_knn_densify(fq, Nq, D, fs, Ns, ws, K, k, y, P, params->temperature, wq, prop, label,
+                                             nn_idx, workspace, static_cast<hipStream_t>(stream)));
 }
 
 aura_status_t aura_property_integrate(const float* prop, int64_t N, int32_t P, int32_t p_index,

@@ -47,6 +47,13 @@ hipError_t launch_property_integrate(const float* prop, int P, int p_index, cons
                                      float vol_uniform, const MassObj* objs, int B, const float* xyz, int G,
                                      float* mass, long long* n_used, void* workspace, hipStream_t stream);
 
+// Sec. 3.4.1 Eq. 5 (knn_densify.hip).
+bool knn_supported(int Ns, int K, int k, int P);
+size_t knn_workspace_bytes(int D, int Ns);
+hipError_t launch_knn_densify(const float* fq, long long Nq, int D, const float* fs, int Ns, const float* ws, int K,
+                              int k, const float* y, int P, float temperature, float* wq, float* prop, int* label,
+                              int* nn_idx, void* workspace, hipStream_t stream);
+
 hipError_t launch_calibration_copy(void* dst, const void* src, size_t bytes, hipStream_t stream);
 hipError_t launch_calibration_fill(void* dst, size_t bytes, uint32_t value, hipStream_t stream);
 

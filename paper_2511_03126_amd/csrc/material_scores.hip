@@ -14,6 +14,7 @@
 // the workspace, already in the per-lane operand order, and stay resident in L2.
 #include "aura_device.hpp"
 #include "launch.hpp"
+#include "scores_core.hpp"
 #include "scores_epilogue.hpp"
 
 namespace aura {
@@ -41,10 +42,6 @@ struct ScoreArgs {
   int steps;               // S = ceil(D / 32)
 };
 
-// Channel held by (macro step s, half j, lane group g, element e): the same map is used for both
-// operands, so any order works as long as it is this one on both sides.
-__device__ __forceinline__ int chan_of(int s, int j, int g, int e) { return s * kStepK + g * 16 + j * 8 + e; }
-
 __global__ __launch_bounds__(256) void k_split_embeddings(const float* __restrict__ temb, int K, int D, int MT,
                                                           int steps, __bf16* __restrict__ out) {
   long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;   // one thread per (slot, lane)
@@ -59,7 +56,7 @@ __global__ __launch_bounds__(256) void k_split_embeddings(const float* __restric
   __bf16* lo = out + ((((long long)(s * MT + mt) * 2 + j) * 2 + 1) * kWave + lane) * 8;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    int c = chan_of(s, j, g, e);
+    int c = score_chan_of(s, j, g, e);
     float x = (m < K && c < D) ? temb[(long long)m * D + c] : 0.0f;
     __bf16 h = (__bf16)x;
     hi[e] = h;
@@ -89,44 +86,22 @@ __global__ __launch_bounds__(256) void k_material_scores(ScoreArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
 
-  for (int s = 0; s < a.steps; ++s) {
-    const int c0 = s * kStepK + g * 16;
-    float b[16];
-    if (ROWS_ALIGNED && c0 + 16 <= a.D) {
-#pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        f32x4 v = *reinterpret_cast<const f32x4*>(row + c0 + 4 * q);
-        b[4 * q] = v[0]; b[4 * q + 1] = v[1]; b[4 * q + 2] = v[2]; b[4 * q + 3] = v[3];
-      }
-    } else {
-#pragma unroll
-      for (int e = 0; e < 16; ++e) b[e] = (c0 + e < a.D) ? row[c0 + e] : 0.0f;
-    }
-    bf16x8 bh[2], bl[2];
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        float x = b[8 * j + e];
-        __bf16 h = (__bf16)x;
-        bh[j][e] = h;
-        bl[j][e] = (__bf16)(x - (float)h);
-      }
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-#pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const bf16x8* slot = a.a_split + ((long long)(s * MT + mt) * 2 + j) * 2 * kWave + lane;
-        const bf16x8 ah = slot[0], al = slot[kWave];
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh[j], acc[mt], 0, 0, 0);
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl[j], acc[mt], 0, 0, 0);
-        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh[j], acc[mt], 0, 0, 0);
-      }
-    }
-  }
+  score_products<MT, ROWS_ALIGNED, false>(row, a.D, a.steps, a.a_split, lane, acc);
 
   if (!valid) return;   // no cross-lane traffic below except with lane ^ 32, which holds the same point
   finish_scores<MT>(acc, n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label);
+}
+
+size_t split_embeddings_bytes(int D, int MT) {
+  return (size_t)((D + kStepK - 1) / kStepK) * MT * 2 * 2 * kWave * 8 * sizeof(__bf16);
+}
+
+hipError_t launch_split_embeddings(const float* emb, int n_rows, int D, int MT, void* out, hipStream_t stream) {
+  const int S = (D + kStepK - 1) / kStepK;
+  const long long total = (long long)S * MT * 2 * kWave;
+  hipLaunchKernelGGL(k_split_embeddings, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, stream, emb, n_rows, D,
+                     MT, S, static_cast<__bf16*>(out));
+  return hipGetLastError();
 }
 
 static int tiles_m(int K) { return (K + kTileM - 1) / kTileM; }

@@ -30,7 +30,7 @@ def test_every_declared_function_is_exported(B):
     names = _declared_functions()
     assert {"aura_project_visibility", "aura_fuse_features", "aura_material_scores", "aura_property_integrate",
             "aura_workspace_bytes", "aura_version", "aura_strerror", "aura_last_hip_error",
-            "aura_calibration_copy", "aura_calibration_fill", "aura_fuse_scores"} <= set(names)
+            "aura_calibration_copy", "aura_calibration_fill", "aura_fuse_scores", "aura_knn_densify"} <= set(names)
     for n in names:
         assert hasattr(B.lib(), n), n
 
@@ -165,6 +165,31 @@ def test_argument_validation_returns_status_codes(B):
     assert fs(wsb=16) == -5
     assert fs(ws=C.c_void_p(0x1010)) == -5
     assert fs(N=0, fused=None, scores=None) == 0
+
+    kd = lambda Nq=10, D=64, Ns=20, K=8, k=3, P=1, fq=fake, fs=fake, ws_=fake, y=fake, wq=fake, prop=fake, \
+        ws=C.c_void_p(0x1000), wsb=1 << 24, par=p: L.aura_knn_densify(fq, Nq, D, fs, Ns, ws_, K, k, y, P, C.byref(par), wq, prop,
+                                                                    None, None, ws, wsb, None)
+    assert kd(fs=None) == -1
+    assert kd(ws_=None) == -1
+    assert kd(fq=None) == -1
+    assert kd(wq=None) == -1
+    assert kd(y=None) == -1
+    assert kd(D=0) == -2
+    assert kd(Ns=0) == -2
+    assert kd(k=0) == -2
+    assert kd(par=cold) == -2
+    assert kd(Ns=257) == -7
+    assert kd(k=17) == -7
+    assert kd(K=129) == -7
+    assert kd(P=9) == -7
+    assert kd(ws=None) == -5
+    assert kd(wsb=16) == -5
+    assert kd(ws=C.c_void_p(0x1010)) == -5
+    assert kd(Nq=0, fq=None, wq=None) == 0
+    assert B.workspace_bytes(B.CALL_KNN_DENSIFY, D=768, Ns=150) == 24 * 6 * 2 * 2 * 64 * 16 + 768
+    with pytest.raises(B.AuraError) as e:
+        B.workspace_bytes(B.CALL_KNN_DENSIFY, D=768, Ns=300)
+    assert e.value.status == -7
 
     cc = lambda dst=fake, src=fake, n=1024: L.aura_calibration_copy(dst, src, n, None)
     assert cc(dst=None) == -1 and cc(src=None) == -1
