@@ -2,8 +2,8 @@
 """Benchmark of the fusion hot path on one MI355X.
 
 One step = one pass of the whole path over one synthetic scene already resident in HBM:
-aura_project_visibility -> aura_fuse_scores (fusion, then scoring) -> aura_property_integrate
-(--staged: aura_fuse_features and aura_material_scores as two calls instead).
+aura_fuse_scores (visibility mask and view counts, fusion, scoring) -> aura_property_integrate
+(--staged: aura_project_visibility, aura_fuse_features, aura_material_scores, aura_property_integrate).
 Prints ONE JSON line: whole-path throughput in fused point-views per second, the roofline figure
 of the dominant call (the fusion, HBM bound on writing the fused rows) measured with events on the
 launch stream inside the timed region, and the CPU oracle timed on a bounded sample of the same workload.
@@ -32,8 +32,8 @@ def fuse_algorithmic_bytes(s):
 # profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_prepare + k_tile_product, each
 # scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
 # the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = 847454618
-TRAFFIC_SOURCE_SHA256 = "11d1a44bc4da34b208f287825b393cd931edd853e95bb34bcee340ade1045c83"
+TRAFFIC_C2_BYTES = 868381559
+TRAFFIC_SOURCE_SHA256 = "c2e696eeb85b2abb02da7971125b42c887b6b450399ab4aa3a0299ea9c4dc2e8"
 
 
 def measured_traffic():
@@ -157,8 +157,8 @@ def main():
         names = ["project_visibility", "fuse_features", "material_scores", "property_integrate"]
         calls = [d.project_visibility, d.fuse_features, d.material_scores, d.property_integrate]
     else:
-        names = ["project_visibility", "fuse_scores", "property_integrate"]
-        calls = [d.project_visibility, d.fuse_scores, d.property_integrate]
+        names = ["fuse_scores", "property_integrate"]       # the mask and view counts come out of the fusion
+        calls = [d.fuse_scores_vis, d.property_integrate]
     for _ in range(max(args.warmup, 0)):
         for call in calls:
             call()
@@ -209,7 +209,7 @@ def main():
         "config": {"workload": f"{args.workload}: N={s.N} points, B={s.B} objects, {s.n_views} views {s.H}x{s.W}, "
                                f"feature grid {s.Hf}x{s.Wf}x{s.D} {s.feat_dtype}, K={s.K} materials, P={s.P}, "
                                f"mass grid G={s.G}", "point_views": pv,
-                   "visible_fraction": float(gpu["vis"].mean()), "unseen_points": float((gpu["count"] == 0).mean()),
+                   "visible_fraction": float(gpu["vis"].mean()), "unseen_points": float((gpu["count_fuse"] == 0).mean()),
                    "order": s.meta["order"], "seed": s.meta["seed"]},
         "calls_ms": call_ms,
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,

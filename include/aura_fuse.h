@@ -207,8 +207,8 @@ aura_status_t aura_material_scores(const float* fused, int64_t N, int32_t D,
                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Sec. 3.1 Eq. 2 followed by Sec. 3.4.1 / Eq. 4 in one call: everything aura_fuse_features writes
- * (fused, count) and everything aura_material_scores writes (scores, prop, label) for the same
+ * Sec. 3.1 Eq. 1 and 2 followed by Sec. 3.4.1 / Eq. 4 in one call: everything aura_fuse_features writes
+ * (fused, count), optionally the mask of aura_project_visibility, and everything aura_material_scores writes (scores, prop, label) for the same
  * points, with the arguments and rules of those two calls.
  *
  * The similarity omega_k = <f, t_k> is linear in f, and the fused feature is a weighted sum of
@@ -222,6 +222,8 @@ aura_status_t aura_material_scores(const float* fused, int64_t N, int32_t D,
  * call is exactly the two calls in sequence.
  *
  *   fused  [device] [N][D] fp32, 16-byte aligned (required)    count [device] [N] int32 or NULL
+ *   vis    [device] [N][vis_pitch] uint8 or NULL: the mask of Eq. 1 exactly as aura_project_visibility writes it
+ *          (the fusion evaluates it anyway), vis_pitch >= the largest per-object view count
  *   temb   [device] [K][D] fp32 (temb_dtype must be AURA_F32)  y     [device] [K][P] fp32 or NULL
  *   scores [device] [N][K] fp32   prop [device] [N][P] fp32 or NULL (needs y)   label [device] [N] or NULL
  *   workspace [device] aura_workspace_bytes(AURA_CALL_FUSE_SCORES, ...) bytes, 256-byte aligned (required)
@@ -232,7 +234,8 @@ aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* p
                                const float* xyz, int64_t N,
                                const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
                                const void* temb, int32_t temb_dtype, int32_t K, const float* y, int32_t P,
-                               float* fused, int32_t* count, float* scores, float* prop, int32_t* label,
+                               float* fused, int32_t* count, uint8_t* vis, int32_t vis_pitch,
+                               float* scores, float* prop, int32_t* label,
                                void* workspace, size_t workspace_bytes, void* stream);
 
 /*

@@ -74,7 +74,7 @@ def lib():
                                            vp, C.c_size_t, vp]
         L.aura_fuse_scores.restype = C.c_int32
         L.aura_fuse_scores.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32, vp, i32, i32, vp,
-                                       i32, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+                                       i32, vp, vp, vp, i32, vp, vp, vp, vp, C.c_size_t, vp]
         L.aura_knn_densify.restype = C.c_int32
         L.aura_knn_densify.argtypes = [vp, i64, i32, vp, i32, vp, i32, i32, vp, i32, C.POINTER(_ParamsT), vp, vp, vp, vp,
                                        vp, C.c_size_t, vp]
@@ -222,8 +222,9 @@ def fuse_scores_workspace_bytes(views: "Views", N: int, K: int, B: int = 1) -> i
 
 
 def fuse_scores(views: Views, params: Params, xyz, temb, y, fused, scores, count=None, prop=None, label=None,
-                pt_offsets=None, view_offsets=None, workspace=None):
-    """fuse_features followed by material_scores in one call; fused, count, scores, prop, label filled in place."""
+                pt_offsets=None, view_offsets=None, workspace=None, vis=None):
+    """fuse_features followed by material_scores in one call; fused, count, scores, prop, label (and the
+    visibility mask vis [N][vis_pitch] uint8, if given) filled in place."""
     xyz = _dev(xyz, torch.float32, "xyz")
     _dev(fused, torch.float32, "fused")
     temb = _dev(temb, torch.float32, "temb")
@@ -233,7 +234,7 @@ def fuse_scores(views: Views, params: Params, xyz, temb, y, fused, scores, count
     P = 0 if y is None else y.shape[1]
     _check(lib().aura_fuse_scores(C.byref(v), C.byref(p), xyz.data_ptr(), xyz.shape[0], _hptr(po), _hptr(vo), B,
                                   temb.data_ptr(), F32, K, _ptr(y), P, fused.data_ptr(), _ptr(count),
-                                  scores.data_ptr(), _ptr(prop), _ptr(label), _ptr(workspace),
+                                  _ptr(vis), 0 if vis is None else vis.shape[1], scores.data_ptr(), _ptr(prop), _ptr(label), _ptr(workspace),
                                   0 if workspace is None else workspace.numel(), _stream()), "aura_fuse_scores")
 
 

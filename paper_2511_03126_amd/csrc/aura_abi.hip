@@ -261,7 +261,8 @@ aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* p
                                const float* xyz, int64_t N,
                                const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
                                const void* temb, int32_t temb_dtype, int32_t K, const float* y, int32_t P,
-                               float* fused, int32_t* count, float* scores, float* prop, int32_t* label,
+                               float* fused, int32_t* count, uint8_t* vis, int32_t vis_pitch,
+                               float* scores, float* prop, int32_t* label,
                                void* workspace, size_t workspace_bytes, void* stream) {
   aura_status_t s = check_views(views, params, true);
   if (s != AURA_OK) return s;
@@ -275,6 +276,7 @@ aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* p
   int max_views = 0;
   s = check_objects(N, views->n_views, pt_offsets, view_offsets, B, &objs, &max_views);
   if (s != AURA_OK) return s;
+  if (vis && (vis_pitch < max_views || vis_pitch < 1)) return AURA_ERR_SHAPE;
   if (N == 0) return AURA_OK;
   if (!xyz || !fused || !scores) return AURA_ERR_NULL;
   if (!aligned(fused, 16)) return AURA_ERR_ALIGN;
@@ -307,8 +309,13 @@ aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* p
   }
   s = for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts, int obj_base) {
     tws.obj_base = obj_base;
-    hipError_t e = aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only,
-                                              lay.tile ? &tws : nullptr, tab, n, max_pts, st, lay.by_cells ? sws.factor : nullptr);
+    hipError_t e = hipSuccess;
+    if (vis && !lay.tile)   // the gather kernel does not write the mask: the visibility kernel does
+      e = aura::launch_project_visibility(va, xyz, vis, vis_pitch, nullptr, nullptr, tab, n, max_pts, st);
+    if (e != hipSuccess) return e;
+    e = aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only,
+                                   lay.tile ? &tws : nullptr, tab, n, max_pts, st, lay.by_cells ? sws.factor : nullptr,
+                                   vis, vis_pitch);
     if (e != hipSuccess || !lay.by_cells) return e;
     return aura::launch_tile_scores(fa, tws, sws, fused, t32, K, y, P, params->temperature, scores, prop, label, tab, n,
                                     max_pts, st);

@@ -16,6 +16,8 @@ struct FuseArgs {
   float norm_eps;
   int mean_only;
   float* out_factor;   // tile path only, may be nullptr: [N] factor applied to each point's raw tile product
+  uint8_t* out_vis;    // tile path only, may be nullptr: [N][vis_pitch] visibility mask (Eq. 1), as aura_project_visibility
+  int vis_pitch;
 };
 
 // ---- workspace of the tile path ------------------------------------------------------------

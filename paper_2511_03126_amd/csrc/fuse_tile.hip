@@ -164,6 +164,7 @@ __device__ __forceinline__ void gather_tile(const FuseArgs& a, const ObjRange& o
           const Proj p = project(a.vis.cam + (long long)v * 16, x, y, z);
           const float* dv = a.vis.depth ? a.vis.depth + (long long)v * a.vis.H * a.vis.W : nullptr;
           seen = visible(a.vis, dv, p);
+          if (a.out_vis && cb == 0) a.out_vis[i * a.vis_pitch + vb + lane] = seen ? 1 : 0;
           if (seen) {
             const Tap tx = tap_axis(p.u, a.feat.pitch_x, Wf), ty = tap_axis(p.v, a.feat.pitch_y, Hf);
             x0 = tx.i0; ax = tx.a;
@@ -308,6 +309,26 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
     }
     if (my_cnt) atomicAdd(&s_cnt[p], my_cnt);
     __syncthreads();
+    if (a.out_vis && tid < kTilePts && p_valid) {
+      // the mask of Eq. 1 for this batch of views, from the per-view bit masks: point tid's bytes, four per store
+      // where the row pitch allows
+      uint8_t* __restrict__ vrow = a.out_vis + (ob.pt_begin + li0 + tid) * a.vis_pitch + vb0;
+      if ((a.vis_pitch & 3) == 0) {
+        for (int v4 = 0; v4 < nvb; v4 += 4) {
+          uint32_t w = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (v4 + e < nvb) w |= ((s_vmask[v4 + e] >> tid) & 1u) << (8 * e);
+          if (v4 + 4 <= nvb) {
+            *reinterpret_cast<uint32_t*>(vrow + v4) = w;
+          } else {
+            for (int e = 0; v4 + e < nvb; ++e) vrow[v4 + e] = (uint8_t)((w >> (8 * e)) & 1u);
+          }
+        }
+      } else {
+        for (int v = 0; v < nvb; ++v) vrow[v] = (uint8_t)((s_vmask[v] >> tid) & 1u);
+      }
+    }
 
     // ---- B: mark the touched cells of every view that uses a map
 #pragma unroll
@@ -440,6 +461,9 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
     }
   }
 
+  if (a.out_vis && tid < kTilePts && li0 + tid < ob.n_pts) {   // mask columns beyond the object's views
+    for (int j = ob.n_views; j < a.vis_pitch; ++j) a.out_vis[(ob.pt_begin + li0 + tid) * a.vis_pitch + j] = 0;
+  }
   __syncthreads();
   if (exhausted) {
     if (tid == 0) hdr->nsteps = -1;

@@ -27,7 +27,8 @@ struct TileWs;
 hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const float* xyz, float* fused,
                                 int* out_count, float norm_eps, int mean_only, const TileWs* tile_ws,
                                 const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream,
-                                float* out_factor = nullptr);   // tile path only: see FuseArgs::out_factor
+                                float* out_factor = nullptr,    // tile path only: see FuseArgs::out_factor
+                                uint8_t* out_vis = nullptr, int vis_pitch = 0);   // tile path only: see FuseArgs::out_vis
 
 size_t scores_workspace_bytes(int D, int K);
 hipError_t launch_material_scores(const float* fused, long long N, int D, const float* temb, int K,

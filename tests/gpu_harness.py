@@ -62,10 +62,14 @@ class DeviceScene:
         aura.material_scores(self.fused, self.temb, self.y, self.params, self.scores, self.prop, self.label,
                              self.ws_scores)
 
-    def fuse_scores(self):
+    def fuse_scores(self, with_vis=False):
         aura.fuse_scores(self.views, self.params, self.xyz, self.temb, self.y, self.fused, self.scores,
                          count=self.count_fuse, prop=self.prop, label=self.label, pt_offsets=self.pt_offsets,
-                         view_offsets=self.view_offsets, workspace=self.ws_fuse_scores)
+                         view_offsets=self.view_offsets, workspace=self.ws_fuse_scores,
+                         vis=self.vis if with_vis else None)
+
+    def fuse_scores_vis(self):
+        self.fuse_scores(with_vis=True)
 
     def property_integrate(self):
         s = self.scene
@@ -82,16 +86,18 @@ class DeviceScene:
         self.property_integrate()
 
     def step_combined(self):
-        """One pass of the whole path with fusion and scoring in one call."""
-        self.project_visibility()
-        self.fuse_scores()
+        """One pass of the whole path with visibility mask, fusion and scoring in one call (the mask and the view
+        counts come out of the fusion; `count` is filled from its count output)."""
+        self.fuse_scores(with_vis=True)
+        self.count.copy_(self.count_fuse)
         self.property_integrate()
 
     def clear_outputs(self):
         for t in (self.fused, self.scores, self.prop, self.mass):
             t.fill_(float("nan"))
-        for t in (self.count_fuse, self.label, self.n_used):
+        for t in (self.count_fuse, self.count, self.label, self.n_used):
             t.fill_(-7)
+        self.vis.fill_(9)      # uvz (debug output of aura_project_visibility alone) is left as it is
 
     def results(self):
         torch.cuda.synchronize()

@@ -144,10 +144,10 @@ def test_argument_validation_returns_status_codes(B):
     cold = B.Params(temperature=0.0).c()
     assert ms(par=cold) == -2
 
-    fs = lambda v=None, N=10, K=8, P=1, temb=fake, dt=B.F32, y=fake, fused=fake, scores=fake, prop=fake, \
+    fs = lambda v=None, N=10, K=8, P=1, temb=fake, dt=B.F32, y=fake, fused=fake, scores=fake, prop=fake, vis=None, pitch=0, \
         ws=C.c_void_p(0x1000), wsb=1 << 30, par=p: L.aura_fuse_scores(
             C.byref(v if v is not None else _views(B)), C.byref(par), fake, N, None, None, 1, temb, dt, K, y, P, fused, None,
-            scores, prop, None, ws, wsb, None)
+            vis, pitch, scores, prop, None, ws, wsb, None)
     assert fs(temb=None) == -1
     assert fs(fused=None) == -1
     assert fs(scores=None) == -1
@@ -165,6 +165,7 @@ def test_argument_validation_returns_status_codes(B):
     assert fs(wsb=16) == -5
     assert fs(ws=C.c_void_p(0x1010)) == -5
     assert fs(N=0, fused=None, scores=None) == 0
+    assert fs(vis=fake, pitch=3) == -2                                     # fewer mask columns than views
 
     kd = lambda Nq=10, D=64, Ns=20, K=8, k=3, P=1, fq=fake, fs=fake, ws_=fake, y=fake, wq=fake, prop=fake, \
         ws=C.c_void_p(0x1000), wsb=1 << 24, par=p: L.aura_knn_densify(fq, Nq, D, fs, Ns, ws_, K, k, y, P, C.byref(par), wq, prop,
