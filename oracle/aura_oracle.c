@@ -19,6 +19,8 @@
  *   densification omega(q)                 Sec. 3.4.1 Eq. 5 (k nearest source points by cosine
  *                                          similarity of the fused features, similarity-weighted
  *                                          mean of their material vectors, then Eq. 4)
+ *   thickness-based integration            Sec. 3.4.2 (voxel b_adap x b_adap x theta per point, correction
+ *                                          factor lambda) and the centre of mass it gives
  *
  * Precision.  All sums, weights and outputs are double.  The few quantities that
  * DECIDE an integer (which depth texel is read, whether a point passes the depth
@@ -508,5 +510,74 @@ int orc_knn_densify(const double* fq, int64_t Nq, const double* fs, int Ns, int 
     free(taken);
   }
   free(snorm);
+  return 0;
+}
+
+/* ---------------------------------------------------------------- exported: Sec. 3.4.2, thickness-based integration
+ * Every point s of object b is the centre of a voxel b_adap x b_adap x theta:
+ *     A_bar  = (L * scale_factor)^2 / N_b          (area one point stands for; N_b = all points of the object)
+ *     b_adap = sqrt(A_bar)
+ *     zeta(s) = [ sum_k exp(omega_k[s] / T) y_k theta_k / sum_k exp(omega_k[s] / T) ] * b_adap^2 * lambda
+ * and the object-level value is the sum of zeta over the object's used points (count == NULL or count[i] > 0).
+ * L: box_len[b] when given, else the longest side of the axis-aligned bounding box of all the object's points.
+ * The centre of mass named in Sec. 2.1 / 3.4 is the zeta-weighted mean position, sum zeta x / sum zeta
+ * (zero when the sum is zero).
+ * omega [N][K], y_col [K] (the property column: density for mass), theta [K], xyz [N][3].
+ * Outputs: zeta [N] or NULL (0 for unused points), total [B], com [B][3] or NULL, b_adap [B] or NULL,
+ * n_used [B] or NULL.                                                                                   */
+int orc_thickness_integrate(const double* omega, int64_t N, int K, const float* y_col, const float* theta,
+                            const float* xyz, const int32_t* count, const int64_t* pt_offsets, int B,
+                            const float* box_len, float T, float lambda, float scale_factor,
+                            double* zeta, double* total, double* com, double* b_adap, int64_t* n_used) {
+  if (!omega || !y_col || !theta || !xyz || !total) return -1;
+  if (N < 0 || K < 1 || B < 1 || !(T > 0.0f)) return -2;
+  if (!pt_offsets && B != 1) return -1;
+  if (pt_offsets) {
+    if (pt_offsets[0] != 0 || pt_offsets[B] != N) return -2;
+    for (int b = 0; b < B; ++b) if (pt_offsets[b + 1] < pt_offsets[b]) return -2;
+  }
+  for (int b = 0; b < B; ++b) {
+    const int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
+    double L = 0.0;
+    if (box_len) {
+      L = (double)box_len[b];
+    } else {
+      for (int a = 0; a < 3; ++a) {
+        double lo = INFINITY, hi = -INFINITY;
+        for (int64_t i = p0; i < p1; ++i) {
+          const double v = (double)xyz[3 * i + a];
+          if (v < lo) lo = v;
+          if (v > hi) hi = v;
+        }
+        if (p1 > p0 && hi - lo > L) L = hi - lo;
+      }
+    }
+    const double side = L * (double)scale_factor;
+    const double area = p1 > p0 ? side * side / (double)(p1 - p0) : 0.0;
+    double m = 0.0, mx[3] = {0.0, 0.0, 0.0};
+    int64_t used = 0;
+    for (int64_t i = p0; i < p1; ++i) {
+      if (zeta) zeta[i] = 0.0;
+      if (count && count[i] <= 0) continue;
+      const double* w = omega + i * K;
+      double top = w[0];
+      for (int k = 1; k < K; ++k) if (w[k] > top) top = w[k];
+      double num = 0.0, den = 0.0;
+      for (int k = 0; k < K; ++k) {
+        const double e = exp((w[k] - top) / (double)T);     /* the common factor exp(top / T) cancels */
+        num += e * (double)y_col[k] * (double)theta[k];
+        den += e;
+      }
+      const double z = num / den * area * (double)lambda;
+      if (zeta) zeta[i] = z;
+      m += z;
+      for (int a = 0; a < 3; ++a) mx[a] += z * (double)xyz[3 * i + a];
+      ++used;
+    }
+    total[b] = m;
+    if (com) for (int a = 0; a < 3; ++a) com[3 * b + a] = m != 0.0 ? mx[a] / m : 0.0;
+    if (b_adap) b_adap[b] = sqrt(area);
+    if (n_used) n_used[b] = used;
+  }
   return 0;
 }

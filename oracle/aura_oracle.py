@@ -213,3 +213,27 @@ def knn_densify(fq, fs, ws, k, y=None, T=0.1):
                                _p(gap))
     _check(rc, "knn_densify")
     return {"wq": wq, "prop": prop, "label": label, "nn_idx": nn_idx, "nn_sim": nn_sim, "gap": gap}
+
+
+def thickness_integrate(omega, y_col, theta, xyz, count=None, pt_offsets=None, box_len=None, T=0.1, lam=0.6,
+                        scale_factor=1.0):
+    """Sec. 3.4.2: thickness-based voxel integration (voxel b_adap x b_adap x theta_k, factor lambda) and the
+    centre of mass of the integrated quantity."""
+    omega = np.ascontiguousarray(omega, dtype=np.float64)
+    N, K = omega.shape
+    y_col, theta = _f32(y_col).reshape(K), _f32(theta).reshape(K)
+    xyz = _f32(xyz).reshape(N, 3)
+    po = None if pt_offsets is None else np.ascontiguousarray(pt_offsets, dtype=np.int64)
+    B = 1 if po is None else len(po) - 1
+    count = None if count is None else np.ascontiguousarray(count, dtype=np.int32)
+    box_len = None if box_len is None else _f32(box_len).reshape(B)
+    zeta = np.zeros(N, np.float64)
+    total = np.zeros(B, np.float64)
+    com = np.zeros((B, 3), np.float64)
+    b_adap = np.zeros(B, np.float64)
+    n_used = np.zeros(B, np.int64)
+    rc = lib().orc_thickness_integrate(_p(omega), C.c_int64(N), C.c_int(K), _p(y_col), _p(theta), _p(xyz), _p(count),
+                                       _p(po), C.c_int(B), _p(box_len), C.c_float(T), C.c_float(lam),
+                                       C.c_float(scale_factor), _p(zeta), _p(total), _p(com), _p(b_adap), _p(n_used))
+    _check(rc, "thickness_integrate")
+    return {"zeta": zeta, "mass": total, "com": com, "b_adap": b_adap, "n_used": n_used}
