@@ -74,6 +74,34 @@ def time_densify(torch, d, s, reps, n_sources=150, k=5):
             "frac": gbps / HBM_PEAK_GBPS}
 
 
+def time_thickness(torch, d, s, reps):
+    """Sec. 3.4.2, thickness-based integration and centre of mass over the scene's scores (three small launches;
+    reads the score rows, the positions and the view counts once)."""
+    import paper_2511_03126_amd as aura
+    from paper_2511_03126_amd import binding
+    from workloads.scenes import material_thickness
+    theta = torch.from_numpy(material_thickness(s.K, s.meta["seed"])).to(d.dev)
+    total, com = torch.empty(s.B, device=d.dev), torch.empty((s.B, 3), device=d.dev)
+    work = torch.empty(aura.workspace_bytes(binding.CALL_THICKNESS_INTEGRATE, N=s.N, B=s.B), dtype=torch.uint8, device=d.dev)
+    run = lambda: aura.thickness_integrate(d.scores, d.y, theta, d.xyz, d.params, total, p_index=0, count=d.count_fuse,
+                                           pt_offsets=None if d.single else s.pt_offsets, lam=0.6, scale_factor=1.0,
+                                           com=com, workspace=work)
+    for _ in range(2):
+        run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    nbytes = 4 * s.N * s.K + 2 * 12 * s.N + 4 * s.N       # positions are read by the box pass and by the point pass
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    return {"call": "aura_thickness_integrate", "ms": ms, "bound": "hbm", "algorithmic_bytes": nbytes, "achieved": gbps,
+            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": gbps / HBM_PEAK_GBPS, "mass": total.cpu().tolist(),
+            "centre_of_mass": com.cpu().tolist()[0]}
+
+
 def cpu_baseline(scene, seconds_target=15.0):
     """The oracle, as it stands, on a contiguous sample of the scene's first object."""
     import numpy as np
@@ -202,6 +230,7 @@ def main():
                                        else "k_fuse_gather")
     traffic = measured_traffic() if (tile and args.workload == "c2") else None
     densify = time_densify(torch, d, s, max(args.steps // 2, 5))
+    thickness = time_thickness(torch, d, s, max(args.steps // 2, 5))
     out = {
         "metric": "fused point-views/sec", "value": pv / (ms_per_step * 1e-3), "unit": "point-views/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -216,6 +245,7 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes": fuse_bytes, "avg_launch_ms": fuse_ms},
         "densify": densify,
+        "thickness_integrate": thickness,
         "calibration": calibration,
     }
     if not args.no_cpu_baseline:

@@ -11,6 +11,8 @@
  *   aura_fuse_scores          the two calls above in one (Eq. 2, then Sec. 3.4.1 / Eq. 4)
  *   aura_knn_densify          Sec. 3.4.1 Eq. 5: feature-space k-NN densification, then Eq. 4
  *   aura_property_integrate   Sec. 3.4.2: voxel integration over volumes (mass)
+ *   aura_thickness_integrate  Sec. 3.4.2: thickness-based integration (b_adap x b_adap x theta voxels, factor
+ *                             lambda) and the centre of mass of Sec. 2.1 / 3.4
  *
  * General rules
  *   - Plain C ABI.  Every function returns an aura_status_t (0 = AURA_OK, negative = error);
@@ -70,7 +72,8 @@ enum {
 
 /* Which call a workspace size is asked for. */
 enum { AURA_CALL_MATERIAL_SCORES = 1, AURA_CALL_PROPERTY_INTEGRATE = 2, AURA_CALL_FUSE_FEATURES = 3,
-       AURA_CALL_FUSE_SCORES = 4, AURA_CALL_KNN_DENSIFY = 5 };
+       AURA_CALL_FUSE_SCORES = 4, AURA_CALL_KNN_DENSIFY = 5,
+       AURA_CALL_THICKNESS_INTEGRATE = 6 };
 
 /* Problem sizes for aura_workspace_bytes; fields a call does not list are ignored. */
 typedef struct aura_sizes_t {
@@ -129,6 +132,7 @@ int32_t aura_last_hip_error(void);
  *   AURA_CALL_FUSE_FEATURES       N, B, n_views, Hf, Wf, D, feat_dtype
  *   AURA_CALL_FUSE_SCORES         N, B, n_views, Hf, Wf, D, feat_dtype, K
  *   AURA_CALL_KNN_DENSIFY         D, Ns
+ *   AURA_CALL_THICKNESS_INTEGRATE N, B
  * Errors: AURA_ERR_NULL (sizes, bytes), AURA_ERR_SHAPE, AURA_ERR_DTYPE, AURA_ERR_UNSUPPORTED
  * (unknown call, or sizes beyond the limits of the call).
  */
@@ -293,6 +297,35 @@ aura_status_t aura_property_integrate(const float* prop, int64_t N, int32_t P, i
                                       const float* xyz, const float* grid_lo, const float* grid_h, int32_t G,
                                       float* mass, int64_t* n_used,
                                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sec. 3.4.2, thickness-based integration.  Every point s of object b is the centre of a voxel
+ * b_adap x b_adap x theta_k, where b_adap^2 = A_bar = (L * scale_factor)^2 / N_b is the area one point stands
+ * for (N_b: all points of the object):
+ *     zeta[s]  = sum_k softmax_k(scores[s] / T)_k * y[k][p_index] * theta[k] * b_adap^2 * lambda
+ *     total[b] = sum of zeta over the object's used points (count NULL or count[i] > 0): the mass when
+ *                column p_index of y holds densities
+ *     com[b]   = sum zeta[s] xyz[s] / total[b], the centre of mass (Sec. 2.1 names it among the integral
+ *                estimates; zero when total[b] is 0)
+ * L is box_len[b] when box_len is given, else the longest side of the axis-aligned bounding box of all the
+ * object's points (the paper says "characteristic length of its bounding box" without choosing one).
+ * T = params->temperature; the paper takes T = 0.1 and lambda = 0.6.  fp32 per point, fp64 sums in a fixed order.
+ *
+ *   scores [device] [N][K] fp32       y [device] [K][P] fp32       theta [device] [K] fp32
+ *   xyz    [device] [N][3] fp32       count [device] [N] int32 or NULL
+ *   pt_offsets [host] [B+1] int64 or NULL (B == 1)     box_len [host] [B] fp32 (>= 0) or NULL
+ *   zeta   [device] [N] fp32 or NULL (0 for unused points)         total [device] [B] fp32
+ *   com    [device] [B][3] fp32 or NULL   b_adap [device] [B] fp32 or NULL   n_used [device] [B] int64 or NULL
+ *   workspace [device] aura_workspace_bytes(AURA_CALL_THICKNESS_INTEGRATE, ...) bytes, 256-byte aligned
+ * Limits: K <= 128, B <= 4096.  scores must be finite.
+ * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_WORKSPACE, AURA_ERR_UNSUPPORTED, AURA_ERR_HIP.
+ */
+aura_status_t aura_thickness_integrate(const float* scores, int64_t N, int32_t K, const float* y, int32_t P,
+                                       int32_t p_index, const float* theta, const float* xyz, const int32_t* count,
+                                       const int64_t* pt_offsets, int32_t B, const float* box_len,
+                                       const aura_params_t* params, float lambda, float scale_factor,
+                                       float* zeta, float* total, float* com, float* b_adap, int64_t* n_used,
+                                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Bandwidth calibration (not part of the method).  A plain copy of `bytes` bytes from src to dst,

@@ -17,6 +17,7 @@ _LIB_PATH = Path(__file__).resolve().parent / "libaura_fuse.so"
 F32, BF16, F16 = 0, 1, 2
 VIS_FRUSTUM_ONLY, FUSE_MEAN_ONLY, FUSE_GATHER = 1, 2, 4
 CALL_MATERIAL_SCORES, CALL_PROPERTY_INTEGRATE, CALL_FUSE_FEATURES, CALL_FUSE_SCORES, CALL_KNN_DENSIFY = 1, 2, 3, 4, 5
+CALL_THICKNESS_INTEGRATE = 6
 
 _TORCH_DTYPE = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 
@@ -82,6 +83,9 @@ def lib():
         L.aura_property_integrate.argtypes = [vp, i64, i32, i32, vp, vp, f32, vp, i32, vp, vp, vp, i32, vp, vp,
                                               vp, C.c_size_t, vp]
         L.aura_calibration_copy.restype = C.c_int32
+        L.aura_thickness_integrate.restype = C.c_int32
+        L.aura_thickness_integrate.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp, vp, vp, i32, vp, C.POINTER(_ParamsT),
+                                               f32, f32, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.aura_calibration_copy.argtypes = [vp, vp, C.c_size_t, vp]
         L.aura_calibration_fill.restype = C.c_int32
         L.aura_calibration_fill.argtypes = [vp, C.c_size_t, C.c_uint32, vp]
@@ -265,6 +269,26 @@ def property_integrate(prop, mass, p_index=0, count=None, vol=None, vol_uniform=
                                          _ptr(n_used), _ptr(workspace),
                                          0 if workspace is None else workspace.numel(), _stream()),
            "aura_property_integrate")
+
+
+def thickness_integrate(scores, y, theta, xyz, params: "Params", total, p_index=0, count=None, pt_offsets=None,
+                        box_len=None, lam=0.6, scale_factor=1.0, zeta=None, com=None, b_adap=None, n_used=None,
+                        workspace=None):
+    """Sec. 3.4.2, thickness-based integration: total [B] f32 (and zeta [N], com [B][3], b_adap [B] f32, n_used [B]
+    int64 when given) are filled in place."""
+    scores = _dev(scores, torch.float32, "scores")
+    N, K = scores.shape
+    y = _dev(y, torch.float32, "y")
+    P = y.shape[1]
+    po = _host(pt_offsets, np.int64)
+    B = 1 if po is None else len(po) - 1
+    bl = _host(box_len, np.float32)
+    p = params.c()
+    _check(lib().aura_thickness_integrate(scores.data_ptr(), N, K, y.data_ptr(), P, p_index, _ptr(theta), _ptr(xyz),
+                                          _ptr(count), _hptr(po), B, _hptr(bl), C.byref(p), lam, scale_factor,
+                                          _ptr(zeta), total.data_ptr(), _ptr(com), _ptr(b_adap), _ptr(n_used),
+                                          _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()),
+           "aura_thickness_integrate")
 
 
 def calibration_copy(dst, src):

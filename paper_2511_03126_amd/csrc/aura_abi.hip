@@ -183,6 +183,12 @@ aura_status_t aura_workspace_bytes(int32_t call, const aura_sizes_t* sz, size_t*
     *bytes = aura::knn_workspace_bytes(sz->D, sz->Ns);
     return AURA_OK;
   }
+  if (call == AURA_CALL_THICKNESS_INTEGRATE) {
+    if (sz->N < 0 || sz->B < 1) return AURA_ERR_SHAPE;
+    if (sz->B > 4096) return AURA_ERR_UNSUPPORTED;
+    *bytes = aura::thickness_workspace_bytes(sz->N, sz->B);
+    return AURA_OK;
+  }
   if (call == AURA_CALL_FUSE_SCORES) {
     if (sz->N < 0 || sz->B < 1 || sz->n_views < 1 || sz->Hf < 1 || sz->Wf < 1 || sz->D < 1 || sz->K < 1) return AURA_ERR_SHAPE;
     if (sz->feat_dtype != AURA_F32 && sz->feat_dtype != AURA_BF16 && sz->feat_dtype != AURA_F16) return AURA_ERR_DTYPE;
@@ -396,6 +402,40 @@ aura_status_t aura_property_integrate(const float* prop, int64_t N, int32_t P, i
   return hip_status(aura::launch_property_integrate(prop, P, p_index, count, vol, vol_uniform, objs.data(), B, xyz, G,
                                                     mass, reinterpret_cast<long long*>(n_used), workspace,
                                                     static_cast<hipStream_t>(stream)));
+}
+
+aura_status_t aura_thickness_integrate(const float* scores, int64_t N, int32_t K, const float* y, int32_t P, int32_t p_index,
+                                       const float* theta, const float* xyz, const int32_t* count,
+                                       const int64_t* pt_offsets, int32_t B, const float* box_len,
+                                       const aura_params_t* params, float lambda, float scale_factor,
+                                       float* zeta, float* total, float* com, float* b_adap, int64_t* n_used,
+                                       void* workspace, size_t workspace_bytes, void* stream) {
+  if (!params || !total) return AURA_ERR_NULL;
+  if (N < 0 || K < 1 || P < 1 || p_index < 0 || p_index >= P || B < 1) return AURA_ERR_SHAPE;
+  if (!(params->temperature > 0.0f) || !(lambda == lambda) || !(scale_factor >= 0.0f)) return AURA_ERR_SHAPE;
+  if (!pt_offsets && B != 1) return AURA_ERR_NULL;
+  if (B > 4096 || !aura::thickness_supported(K)) return AURA_ERR_UNSUPPORTED;
+  std::vector<aura::ThickObj> objs((size_t)B);
+  for (int b = 0; b < B; ++b) {
+    const int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
+    if (p1 < p0 || p0 < 0 || p1 > N || p1 - p0 > 0x7fffffff) return AURA_ERR_SHAPE;
+    if ((b == 0 && p0 != 0) || (b == B - 1 && p1 != N)) return AURA_ERR_SHAPE;
+    aura::ThickObj& o = objs[(size_t)b];
+    o.pt_begin = p0;
+    o.n_pts = (int)(p1 - p0);
+    o.box_len = -1.0f;
+    if (box_len) {
+      if (!(box_len[b] >= 0.0f)) return AURA_ERR_SHAPE;
+      o.box_len = box_len[b];
+    }
+  }
+  if (N > 0 && (!scores || !y || !theta || !xyz)) return AURA_ERR_NULL;
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < aura::thickness_workspace_bytes(N, B))
+    return AURA_ERR_WORKSPACE;
+  return hip_status(aura::launch_thickness_integrate(scores, K, y, P, p_index, theta, xyz, count, objs.data(), B,
+                                                     params->temperature, lambda, scale_factor, zeta, total, com, b_adap,
+                                                     reinterpret_cast<long long*>(n_used), workspace,
+                                                     static_cast<hipStream_t>(stream)));
 }
 
 aura_status_t aura_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {

@@ -48,6 +48,20 @@ hipError_t launch_property_integrate(const float* prop, int P, int p_index, cons
                                      float vol_uniform, const MassObj* objs, int B, const float* xyz, int G,
                                      float* mass, long long* n_used, void* workspace, hipStream_t stream);
 
+// Sec. 3.4.2, thickness-based integration and centre of mass (thickness_integrate.hip).
+struct ThickObj {
+  long long pt_begin;
+  int n_pts;
+  float box_len;   // characteristic length L of the object; < 0: longest side of its bounding box
+};
+
+bool thickness_supported(int K);
+size_t thickness_workspace_bytes(long long N, int B);
+hipError_t launch_thickness_integrate(const float* scores, int K, const float* y, int P, int p_index, const float* theta,
+                                      const float* xyz, const int* count, const ThickObj* objs, int B, float temperature,
+                                      float lambda, float scale_factor, float* zeta, float* total, float* com,
+                                      float* b_adap, long long* n_used, void* workspace, hipStream_t stream);
+
 // Sec. 3.4.1 Eq. 5 (knn_densify.hip).
 bool knn_supported(int Ns, int K, int k, int P);
 size_t knn_workspace_bytes(int D, int Ns);

@@ -192,6 +192,34 @@ def test_argument_validation_returns_status_codes(B):
         B.workspace_bytes(B.CALL_KNN_DENSIFY, D=768, Ns=300)
     assert e.value.status == -7
 
+    ti = lambda N=10, K=8, P=2, pi=0, scores=fake, y=fake, theta=fake, xyz=fake, po_=None, B_=1, blen=None, par=p, lam=0.6, \
+        scale=1.0, total=fake, ws=C.c_void_p(0x1000), wsb=1 << 20: L.aura_thickness_integrate(
+            scores, N, K, y, P, pi, theta, xyz, None, po_, B_, blen, C.byref(par) if par is not None else None, lam, scale,
+            None, total, None, None, None, ws, wsb, None)
+    assert ti(scores=None) == -1 and ti(y=None) == -1 and ti(theta=None) == -1 and ti(xyz=None) == -1
+    assert ti(total=None) == -1
+    assert ti(par=None) == -1
+    assert ti(K=0) == -2
+    assert ti(pi=2) == -2                                                  # property column outside y
+    assert ti(N=-1) == -2
+    assert ti(par=cold) == -2
+    assert ti(scale=-1.0) == -2
+    assert ti(K=129) == -7
+    assert ti(B_=2) == -1                                                  # two objects need offsets
+    assert ti(po_=hp(po), B_=2, N=11) == -2
+    assert ti(po_=hp(bad), B_=2, N=5) == -2
+    assert ti(blen=hp(np.array([-1.0], np.float32))) == -2                 # a given length must not be negative
+    assert ti(ws=None) == -5
+    assert ti(wsb=16) == -5
+    assert ti(ws=C.c_void_p(0x1010)) == -5
+    r256 = lambda x: -(-x // 256) * 256
+    slices = -(-200_000 // 256) + 3
+    assert B.workspace_bytes(B.CALL_THICKNESS_INTEGRATE, N=200_000, B=3) == (r256(slices * 24) + r256(slices * 32)
+                                                                             + r256(slices * 8) + 256)
+    with pytest.raises(B.AuraError) as e:
+        B.workspace_bytes(B.CALL_THICKNESS_INTEGRATE, N=10, B=5000)
+    assert e.value.status == -7
+
     cc = lambda dst=fake, src=fake, n=1024: L.aura_calibration_copy(dst, src, n, None)
     assert cc(dst=None) == -1 and cc(src=None) == -1
     assert cc(n=1000) == -2                                                # not a multiple of 16 bytes

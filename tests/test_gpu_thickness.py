@@ -1,0 +1,144 @@
+"""GPU parity of aura_thickness_integrate (Sec. 3.4.2: thickness-based integration, centre of mass) against the
+CPU oracle on the same seeded inputs.  Bar: per-point zeta, totals, centres of mass and b_adap within 1e-5
+relative (fp32 per-point arithmetic against fp64; the sums themselves are fp64 on both sides), n_used exact, and
+two runs bit for bit the same."""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+GOLD = os.path.join(os.path.dirname(__file__), "golden", "thickness_cases.txt")
+
+
+def _run_gpu(scores, y, theta, xyz, count=None, pt_offsets=None, box_len=None, T=0.1, lam=0.6, scale=1.0, p_index=0,
+             want=("zeta", "com", "b_adap", "n_used")):
+    import paper_2511_03126_amd as aura
+    from paper_2511_03126_amd import binding
+    dev = "cuda:0"
+    N, K = scores.shape
+    B = 1 if pt_offsets is None else len(pt_offsets) - 1
+    t = lambda a, dt=np.float32: torch.from_numpy(np.ascontiguousarray(a, dtype=dt)).to(dev)
+    out = dict(total=torch.full((B,), float("nan"), device=dev),
+               zeta=torch.full((N,), float("nan"), device=dev) if "zeta" in want else None,
+               com=torch.full((B, 3), float("nan"), device=dev) if "com" in want else None,
+               b_adap=torch.full((B,), float("nan"), device=dev) if "b_adap" in want else None,
+               n_used=torch.full((B,), -7, dtype=torch.int64, device=dev) if "n_used" in want else None)
+    work = torch.empty(aura.workspace_bytes(binding.CALL_THICKNESS_INTEGRATE, N=N, B=B), dtype=torch.uint8, device=dev)
+    work.fill_(0xA5)
+    y = np.asarray(y, np.float32)
+    y = y[:, None] if y.ndim == 1 else y
+    aura.thickness_integrate(t(scores).reshape(N, K), t(y), t(theta), t(xyz).reshape(N, 3), aura.Params(temperature=T),
+                             out["total"], p_index=p_index, count=None if count is None else t(count, np.int32),
+                             pt_offsets=pt_offsets, box_len=box_len, lam=lam, scale_factor=scale, zeta=out["zeta"],
+                             com=out["com"], b_adap=out["b_adap"], n_used=out["n_used"], workspace=work)
+    torch.cuda.synchronize()
+    return {k: (None if v is None else v.cpu().numpy()) for k, v in out.items()}
+
+
+def _compare(g, ref, xyz):
+    assert np.array_equal(g["n_used"], ref["n_used"])
+    scale_z = np.abs(ref["zeta"]).max(initial=0.0) or 1.0
+    assert np.abs(g["zeta"] - ref["zeta"]).max(initial=0.0) <= TOL * scale_z
+    assert ((g["zeta"] == 0) == (ref["zeta"] == 0)).all()
+    assert np.allclose(g["total"], ref["mass"], rtol=TOL, atol=0)
+    assert np.allclose(g["b_adap"], ref["b_adap"], rtol=TOL, atol=0)
+    extent = np.abs(xyz).max(initial=1.0)
+    assert np.abs(g["com"] - ref["com"]).max(initial=0.0) <= TOL * extent
+
+
+def _inputs(sizes, K, seed, P=2):
+    rng = np.random.default_rng(seed)
+    N = int(sum(sizes))
+    po = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    xyz = np.concatenate([rng.normal(size=(n, 3)) * rng.uniform(0.1, 1.0, 3) + rng.uniform(-2, 2, 3) for n in sizes]
+                         + [np.zeros((0, 3))]).astype(np.float32)
+    scores = rng.uniform(-0.2, 0.45, (N, K)).astype(np.float32)
+    y = rng.uniform(100, 8000, (K, P)).astype(np.float32)
+    from workloads.scenes import material_thickness
+    theta = material_thickness(K, seed)
+    count = ((rng.uniform(size=N) < 0.85) * rng.integers(1, 9, N)).astype(np.int32)
+    return po, xyz, scores, y, theta, count
+
+
+@pytest.mark.parametrize("K", [1, 3, 4, 5, 12, 16, 24, 32, 33, 64, 65, 100, 128])
+def test_material_counts(orc, K):
+    po, xyz, scores, y, theta, count = _inputs([5003], K, 100 + K)
+    g = _run_gpu(scores, y, theta, xyz, count=count, T=0.1, lam=0.6, scale=1.3, p_index=0)
+    ref = orc.thickness_integrate(scores, y[:, 0], theta, xyz, count=count, T=0.1, lam=0.6, scale_factor=1.3)
+    _compare(g, ref, xyz)
+
+
+@pytest.mark.parametrize("sizes", [[1], [2], [255], [256], [257], [4097, 0, 1, 700, 2048], [0], [0, 0], [300] * 70])
+def test_object_layouts(orc, sizes):
+    """Ragged slices, empty objects, a single point, more objects than one launch table holds."""
+    po, xyz, scores, y, theta, count = _inputs(sizes, 12, 7 + len(sizes) + sizes[0])
+    g = _run_gpu(scores, y, theta, xyz, count=count, pt_offsets=po if len(sizes) > 1 else None, p_index=1)
+    ref = orc.thickness_integrate(scores, y[:, 1], theta, xyz, count=count, pt_offsets=po)
+    _compare(g, ref, xyz)
+
+
+def test_given_length_no_count_and_optional_outputs(orc):
+    po, xyz, scores, y, theta, _ = _inputs([900, 2100], 32, 5)
+    box_len = np.array([2.5, 0.75], np.float32)
+    g = _run_gpu(scores, y, theta, xyz, pt_offsets=po, box_len=box_len, lam=0.5, scale=2.0)
+    ref = orc.thickness_integrate(scores, y[:, 0], theta, xyz, pt_offsets=po, box_len=box_len, lam=0.5, scale_factor=2.0)
+    _compare(g, ref, xyz)
+    assert np.allclose(g["b_adap"], 2.0 * box_len / np.sqrt([900, 2100]), rtol=1e-6)
+    only = _run_gpu(scores, y, theta, xyz, pt_offsets=po, box_len=box_len, lam=0.5, scale=2.0, want=())
+    assert np.array_equal(only["total"], g["total"])
+
+
+def test_hand_worked_cases_on_the_gpu():
+    """The paper-side fixtures, through the library (fp32 scores: 1e-6 instead of 1e-12)."""
+    vec = lambda text: np.array([[float(x) for x in part.split()] for part in text.split(";")], np.float64)
+    opt = lambda text: None if text.strip() == "-" else vec(text)[0]
+    for line in [l for l in open(GOLD) if l.strip() and not l.startswith("#")]:
+        name, par, pts, om, y, th, cnt, blen, total, com, b = [c.strip() for c in line.split("|")]
+        T, lam, scale = [float(x) for x in par.split()]
+        g = _run_gpu(vec(om).astype(np.float32), vec(y)[0], vec(th)[0], vec(pts), count=opt(cnt), box_len=opt(blen), T=T,
+                     lam=lam, scale=scale)
+        assert np.allclose(g["total"], float(total), rtol=2e-6, atol=1e-30), (name, g["total"])
+        assert np.allclose(g["com"][0], vec(com)[0], rtol=2e-6, atol=1e-6), (name, g["com"])
+        assert np.allclose(g["b_adap"], float(b), rtol=2e-6, atol=1e-30), (name, g["b_adap"])
+
+
+def test_reproducible_bit_for_bit():
+    po, xyz, scores, y, theta, count = _inputs([30000, 12345], 32, 9)
+    a = _run_gpu(scores, y, theta, xyz, count=count, pt_offsets=po)
+    b = _run_gpu(scores, y, theta, xyz, count=count, pt_offsets=po)
+    for k in a:
+        assert np.array_equal(a[k].view(np.uint8), b[k].view(np.uint8)), k
+
+
+@pytest.mark.parametrize("name", ["c1", "c2"])
+def test_after_the_hot_path(orc, name):
+    """Full size, in the configuration the benchmark times: the scores come from aura_fuse_scores on the device,
+    the oracle integrates the same fp32 scores."""
+    import gpu_harness as H
+    from workloads.scenes import make_scene, material_thickness
+    import paper_2511_03126_amd as aura
+    from paper_2511_03126_amd import binding
+    s = make_scene(name)
+    d = H.DeviceScene(s)
+    d.fuse_scores()
+    theta = material_thickness(s.K, s.meta["seed"])
+    total = torch.empty(s.B, device=d.dev)
+    com = torch.empty((s.B, 3), device=d.dev)
+    zeta = torch.empty(s.N, device=d.dev)
+    b_adap = torch.empty(s.B, device=d.dev)
+    n_used = torch.empty(s.B, dtype=torch.int64, device=d.dev)
+    work = torch.empty(aura.workspace_bytes(binding.CALL_THICKNESS_INTEGRATE, N=s.N, B=s.B), dtype=torch.uint8, device=d.dev)
+    aura.thickness_integrate(d.scores, d.y, torch.from_numpy(theta).to(d.dev), d.xyz, d.params, total, p_index=0,
+                             count=d.count_fuse, pt_offsets=None if d.single else s.pt_offsets, lam=0.6, scale_factor=1.0,
+                             zeta=zeta, com=com, b_adap=b_adap, n_used=n_used, workspace=work)
+    torch.cuda.synchronize()
+    g = dict(total=total.cpu().numpy(), com=com.cpu().numpy(), zeta=zeta.cpu().numpy(), b_adap=b_adap.cpu().numpy(),
+             n_used=n_used.cpu().numpy())
+    ref = orc.thickness_integrate(d.scores.cpu().numpy(), s.y[:, 0], theta, s.xyz, count=d.count_fuse.cpu().numpy(),
+                                  pt_offsets=None if d.single else s.pt_offsets, T=s.temperature, lam=0.6)
+    _compare(g, ref, s.xyz)
+    assert g["total"][0] > 0 and np.isfinite(g["com"]).all()

@@ -354,6 +354,13 @@ def _materials(rng, K, D, P):
     return proto, y
 
 
+def material_thickness(K: int, seed: int) -> np.ndarray:
+    """Thickness theta_k of each candidate material in scene units (2 mm to 5 cm, as a language model would
+    propose for shells of everyday objects): the per-material input of the thickness-based integration."""
+    rng = np.random.default_rng([seed, 77])
+    return rng.uniform(0.002, 0.05, K).astype(np.float32)
+
+
 def _grid_for(points, G):
     lo, hi = points.min(0), points.max(0)
     h = 1.001 * max(float(np.max(hi - lo)), 1e-6) / G
