@@ -19,6 +19,8 @@
  *   densification omega(q)                 Sec. 3.4.1 Eq. 5 (k nearest source points by cosine
  *                                          similarity of the fused features, similarity-weighted
  *                                          mean of their material vectors, then Eq. 4)
+ *   view importance-based filtering        Sec. 3.2.2 (S_dist, S_angle, S_total, top-k views per point) and the
+ *                                          mean over the kept views of Sec. 3.2.3
  *   thickness-based integration            Sec. 3.4.2 (voxel b_adap x b_adap x theta per point, correction
  *                                          factor lambda) and the centre of mass it gives
  *
@@ -272,15 +274,18 @@ int orc_project_visibility(const float* cam, const float* depth, int n_views, in
 
 /* ---------------------------------------------------------------- exported: a1..a4, Eq. 2
  * fused[i] = sum_v M_vis F_v(pi(x_i,v)) / sum_v M_vis, then divided by
- * max(||.||_2, norm_eps) unless ORC_FLAG_MEAN_ONLY.  No visible view: zeros.      */
+ * max(||.||_2, norm_eps) unless ORC_FLAG_MEAN_ONLY.  No visible view: zeros.
+ * With sel_mask the weight of a pair is sel_mask[i][v] (the top-k views of Sec. 3.2.2, fused by
+ * averaging as in Sec. 3.2.3) instead of M_vis.                                    */
 int orc_fuse_features(const float* cam, const float* depth, const void* feat, int feat_dtype,
                       int n_views, int H, int W, int Hf, int Wf, int D,
                       float tau, float z_near, float norm_eps, unsigned flags,
                       const float* xyz, int64_t N, const int64_t* pt_offsets,
                       const int32_t* view_offsets, int B,
+                      const uint8_t* sel_mask /* [N][mask_pitch] or NULL */, int mask_pitch,
                       double* fused /* [N][D] */, int32_t* count /* [N] or NULL */) {
   if (!cam || !feat || !xyz || !fused) return -1;
-  if (!(flags & ORC_FLAG_FRUSTUM_ONLY) && !depth) return -1;
+  if (!(flags & ORC_FLAG_FRUSTUM_ONLY) && !depth && !sel_mask) return -1;
   if (N < 0 || n_views < 1 || H < 1 || W < 1 || Hf < 1 || Wf < 1 || D < 1) return -2;
   if (feat_dtype < 0 || feat_dtype > 2) return -3;
   int rc = check_csr(N, n_views, pt_offsets, view_offsets, B);
@@ -299,7 +304,13 @@ int orc_fuse_features(const float* cam, const float* depth, const void* feat, in
         const float* dv = depth ? depth + (int64_t)vw * H * W : NULL;
         float u, v, z;
         project_f32(cam + (int64_t)vw * 16, xyz + 3 * i, &u, &v, &z);
-        if (!visible_f32(dv, H, W, tau, z_near, frustum_only, u, v, z)) continue;
+        if (sel_mask) {
+          /* Sec. 3.2.3: the mean runs over the views selected for the point (given), not over all visible ones;
+             a selected pair must still lie in front of the camera and inside the image */
+          if (!sel_mask[i * mask_pitch + (vw - v0)] || !visible_f32(NULL, H, W, tau, z_near, 1, u, v, z)) continue;
+        } else if (!visible_f32(dv, H, W, tau, z_near, frustum_only, u, v, z)) {
+          continue;
+        }
         sample_bilinear((const char*)feat + (int64_t)vw * view_bytes, feat_dtype, Hf, Wf, D, H, W, u, v, acc);
         ++n;
       }
@@ -578,6 +589,88 @@ int orc_thickness_integrate(const double* omega, int64_t N, int K, const float* 
     if (com) for (int a = 0; a < 3; ++a) com[3 * b + a] = m != 0.0 ? mx[a] / m : 0.0;
     if (b_adap) b_adap[b] = sqrt(area);
     if (n_used) n_used[b] = used;
+  }
+  return 0;
+}
+
+/* ---------------------------------------------------------------- exported: Sec. 3.2.2, view importance-based filtering
+ * For every visible pair (Eq. 1, the fp32 decision above):
+ *     S_dist  = 1 / (1 + z),  z = depth of the point in the camera frame
+ *     S_angle = max(0, v . (-n)),  v = unit vector from the camera centre C = -R^T t to the point, n = the
+ *               point's unit normal (as given, oriented outward)
+ *     S_total = S_dist * S_angle
+ * and the k visible views with the largest S_total are kept (of equal scores the lower view index first).
+ * Scores are double.  sel_view / sel_score [N][k]: the kept views (index within the object) in rank order,
+ * -1 / 0 beyond the number of visible views; sel_mask [N][mask_pitch]: 1 for kept pairs; n_sel [N];
+ * gap [N]: S_total of the last kept view minus the largest S_total left out (+inf when nothing is left out);
+ * score_all [N][mask_pitch] or NULL: S_total of every visible pair, -1 for the others.                 */
+int orc_select_views(const float* cam, const float* depth, int n_views, int H, int W, float tau, float z_near,
+                     unsigned flags, const float* xyz, const float* normals, int64_t N,
+                     const int64_t* pt_offsets, const int32_t* view_offsets, int B, int k, int mask_pitch,
+                     int32_t* sel_view, double* sel_score, uint8_t* sel_mask, int32_t* n_sel, double* gap,
+                     double* score_all) {
+  if (!cam || !xyz || !normals || !sel_view) return -1;
+  if (!(flags & ORC_FLAG_FRUSTUM_ONLY) && !depth) return -1;
+  if (N < 0 || n_views < 1 || H < 1 || W < 1 || k < 1) return -2;
+  int rc = check_csr(N, n_views, pt_offsets, view_offsets, B);
+  if (rc) return rc;
+  const int frustum_only = (flags & ORC_FLAG_FRUSTUM_ONLY) != 0;
+  for (int b = 0; b < B; ++b) {
+    const int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
+    const int v0 = view_offsets ? view_offsets[b] : 0, v1 = view_offsets ? view_offsets[b + 1] : n_views;
+    const int nv = v1 - v0;
+    if ((sel_mask || score_all) && mask_pitch < nv) return -2;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t i = p0; i < p1; ++i) {
+      double* S = (double*)malloc(sizeof(double) * (size_t)(nv > 0 ? nv : 1));
+      char* taken = (char*)calloc((size_t)(nv > 0 ? nv : 1), 1);
+      const double x[3] = {xyz[3 * i], xyz[3 * i + 1], xyz[3 * i + 2]};
+      const double n[3] = {normals[3 * i], normals[3 * i + 1], normals[3 * i + 2]};
+      for (int j = 0; j < nv; ++j) {
+        const float* cm = cam + (int64_t)(v0 + j) * 16;
+        const float* dv = depth ? depth + (int64_t)(v0 + j) * H * W : NULL;
+        float u, v, z;
+        project_f32(cm, xyz + 3 * i, &u, &v, &z);
+        S[j] = -1.0;                                        /* not visible */
+        if (!visible_f32(dv, H, W, tau, z_near, frustum_only, u, v, z)) continue;
+        double ud, vd, zd;
+        project_f64(cm, xyz + 3 * i, &ud, &vd, &zd);
+        double ray[3], len = 0.0;
+        for (int a = 0; a < 3; ++a) {                       /* C = -R^T t: C_a = -sum_r R[r][a] t[r] */
+          const double c = -((double)cm[a] * cm[9] + (double)cm[3 + a] * cm[10] + (double)cm[6 + a] * cm[11]);
+          ray[a] = x[a] - c;
+          len += ray[a] * ray[a];
+        }
+        len = sqrt(len);
+        double dot = 0.0;
+        for (int a = 0; a < 3; ++a) dot += ray[a] / len * (-n[a]);
+        S[j] = (1.0 / (1.0 + zd)) * (dot > 0.0 ? dot : 0.0);
+      }
+      if (sel_mask) for (int j = 0; j < mask_pitch; ++j) sel_mask[i * mask_pitch + j] = 0;
+      if (score_all) for (int j = 0; j < mask_pitch; ++j) score_all[i * mask_pitch + j] = j < nv ? S[j] : -1.0;
+      int kept = 0;
+      double last = 0.0;
+      for (int r = 0; r < k; ++r) {
+        int best = -1;
+        for (int j = 0; j < nv; ++j)
+          if (!taken[j] && S[j] >= 0.0 && (best < 0 || S[j] > S[best])) best = j;
+        sel_view[i * k + r] = best;
+        if (sel_score) sel_score[i * k + r] = best >= 0 ? S[best] : 0.0;
+        if (best < 0) continue;
+        taken[best] = 1;
+        last = S[best];
+        ++kept;
+        if (sel_mask) sel_mask[i * mask_pitch + best] = 1;
+      }
+      if (n_sel) n_sel[i] = kept;
+      if (gap) {
+        double rest = -INFINITY;
+        for (int j = 0; j < nv; ++j) if (!taken[j] && S[j] >= 0.0 && S[j] > rest) rest = S[j];
+        gap[i] = (kept > 0 && rest > -INFINITY) ? last - rest : INFINITY;
+      }
+      free(S);
+      free(taken);
+    }
   }
   return 0;
 }

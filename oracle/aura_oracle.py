@@ -129,7 +129,7 @@ def project_visibility(cam, depth, xyz, tau=0.0, z_near=1e-6, flags=0, pt_offset
 
 
 def fuse_features(cam, depth, feat, feat_dtype, xyz, tau=0.0, z_near=1e-6, norm_eps=1e-12, flags=0,
-                  pt_offsets=None, view_offsets=None):
+                  pt_offsets=None, view_offsets=None, sel_mask=None):
     cam = _f32(cam).reshape(-1, 16)
     depth = _f32(depth)
     xyz = _f32(xyz).reshape(-1, 3)
@@ -142,10 +142,13 @@ def fuse_features(cam, depth, feat, feat_dtype, xyz, tau=0.0, z_near=1e-6, norm_
     po, vo, B = _csr(N, n_views, pt_offsets, view_offsets)
     fused = np.zeros((N, D), np.float64)
     count = np.zeros(N, np.int32)
+    if sel_mask is not None:
+        sel_mask = np.ascontiguousarray(sel_mask, dtype=np.uint8).reshape(N, -1)
     rc = lib().orc_fuse_features(_p(cam), _p(depth), _p(feat), C.c_int(code), C.c_int(n_views),
                                  C.c_int(H), C.c_int(W), C.c_int(Hf), C.c_int(Wf), C.c_int(D),
                                  C.c_float(tau), C.c_float(z_near), C.c_float(norm_eps), C.c_uint(flags),
-                                 _p(xyz), C.c_int64(N), _p(po), _p(vo), C.c_int(B), _p(fused), _p(count))
+                                 _p(xyz), C.c_int64(N), _p(po), _p(vo), C.c_int(B), _p(sel_mask),
+                                 C.c_int(0 if sel_mask is None else sel_mask.shape[1]), _p(fused), _p(count))
     _check(rc, "fuse_features")
     return {"fused": fused, "count": count}
 
@@ -237,3 +240,32 @@ def thickness_integrate(omega, y_col, theta, xyz, count=None, pt_offsets=None, b
                                        C.c_float(scale_factor), _p(zeta), _p(total), _p(com), _p(b_adap), _p(n_used))
     _check(rc, "thickness_integrate")
     return {"zeta": zeta, "mass": total, "com": com, "b_adap": b_adap, "n_used": n_used}
+
+
+def select_views(cam, depth, xyz, normals, k, tau=0.0, z_near=1e-6, flags=0, pt_offsets=None, view_offsets=None,
+                 mask_pitch=None, H=None, W=None):
+    """Sec. 3.2.2: S_total = S_dist * S_angle of every visible pair, the k best views per point."""
+    cam = _f32(cam).reshape(-1, 16)
+    depth = _f32(depth)
+    xyz = _f32(xyz).reshape(-1, 3)
+    normals = _f32(normals).reshape(-1, 3)
+    n_views = cam.shape[0]
+    if depth is not None:
+        _, H, W = depth.shape
+    N = xyz.shape[0]
+    po, vo, B = _csr(N, n_views, pt_offsets, view_offsets)
+    if mask_pitch is None:
+        mask_pitch = n_views if vo is None else int(np.diff(vo).max())
+    sel_view = np.zeros((N, k), np.int32)
+    sel_score = np.zeros((N, k), np.float64)
+    sel_mask = np.zeros((N, mask_pitch), np.uint8)
+    n_sel = np.zeros(N, np.int32)
+    gap = np.zeros(N, np.float64)
+    score_all = np.zeros((N, mask_pitch), np.float64)
+    rc = lib().orc_select_views(_p(cam), _p(depth), C.c_int(n_views), C.c_int(H), C.c_int(W), C.c_float(tau),
+                                C.c_float(z_near), C.c_uint(flags), _p(xyz), _p(normals), C.c_int64(N), _p(po), _p(vo),
+                                C.c_int(B), C.c_int(k), C.c_int(mask_pitch), _p(sel_view), _p(sel_score), _p(sel_mask),
+                                _p(n_sel), _p(gap), _p(score_all))
+    _check(rc, "select_views")
+    return {"sel_view": sel_view, "sel_score": sel_score, "sel_mask": sel_mask, "n_sel": n_sel, "gap": gap,
+            "score_all": score_all}

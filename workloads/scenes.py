@@ -361,6 +361,23 @@ def material_thickness(K: int, seed: int) -> np.ndarray:
     return rng.uniform(0.002, 0.05, K).astype(np.float32)
 
 
+def synthetic_normals(xyz: np.ndarray, pt_offsets: np.ndarray, seed: int, noise: float = 0.2) -> np.ndarray:
+    """Unit "outward" normals for a scene's points: the direction from the object's centroid to the point, perturbed
+    by Gaussian noise and renormalised (stands in for normals estimated from the reconstructed cloud)."""
+    rng = np.random.default_rng([seed, 91])
+    out = np.empty_like(xyz, dtype=np.float32)
+    for b in range(len(pt_offsets) - 1):
+        s_ = slice(int(pt_offsets[b]), int(pt_offsets[b + 1]))
+        if s_.stop == s_.start:
+            continue
+        d = xyz[s_].astype(np.float64) - xyz[s_].astype(np.float64).mean(0)
+        d /= np.maximum(np.linalg.norm(d, axis=1, keepdims=True), 1e-12)
+        d += noise * rng.standard_normal(d.shape)
+        d /= np.maximum(np.linalg.norm(d, axis=1, keepdims=True), 1e-12)
+        out[s_] = d.astype(np.float32)
+    return out
+
+
 def _grid_for(points, G):
     lo, hi = points.min(0), points.max(0)
     h = 1.001 * max(float(np.max(hi - lo)), 1e-6) / G
