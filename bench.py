@@ -32,8 +32,8 @@ def fuse_algorithmic_bytes(s):
 # profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_prepare + k_tile_product, each
 # scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
 # the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = 868381559
-TRAFFIC_SOURCE_SHA256 = "c2e696eeb85b2abb02da7971125b42c887b6b450399ab4aa3a0299ea9c4dc2e8"
+TRAFFIC_C2_BYTES = 869158382
+TRAFFIC_SOURCE_SHA256 = "cb020442f182d2aa4c0a7d80036c4a02ed42b90ce86010d5967d61fb4b9d90f0"
 
 
 def measured_traffic():
@@ -102,6 +102,35 @@ def time_thickness(torch, d, s, reps):
             "centre_of_mass": com.cpu().tolist()[0]}
 
 
+def time_selection(torch, d, s, reps, k=3):
+    """Sec. 3.2.2 / 3.2.3: the k = 3 most important views of every point, then the fusion over the kept views."""
+    import paper_2511_03126_amd as aura
+    from workloads.scenes import synthetic_normals
+    nrm = torch.from_numpy(synthetic_normals(s.xyz, s.pt_offsets, s.meta["seed"])).to(d.dev)
+    sel_view = torch.empty((s.N, k), dtype=torch.int32, device=d.dev)
+    sel_score = torch.empty((s.N, k), device=d.dev)
+    sel_mask = torch.empty((s.N, s.vis_pitch), dtype=torch.uint8, device=d.dev)
+    fused = torch.empty_like(d.fused)
+    count = torch.empty_like(d.count_fuse)
+    select = lambda: aura.select_views(d.views, d.params, d.xyz, nrm, k, sel_view, sel_score, sel_mask, None, d.pt_offsets,
+                                       d.view_offsets)
+    fuse = lambda: aura.fuse_selected(d.views, d.params, d.xyz, sel_mask, fused, count, d.pt_offsets, d.view_offsets,
+                                      d.ws_fuse)
+    out = {"k": k}
+    for name, fn in (("aura_select_views_ms", select), ("aura_fuse_selected_ms", fuse)):
+        for _ in range(2):
+            fn()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        out[name] = e0.elapsed_time(e1) / reps
+    out["mean_views_kept"] = float(count.float().mean())
+    return out
+
+
 def cpu_baseline(scene, seconds_target=15.0):
     """The oracle, as it stands, on a contiguous sample of the scene's first object."""
     import numpy as np
@@ -168,6 +197,8 @@ def main():
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--staged", action="store_true", help="fusion and scoring as two library calls")
+    ap.add_argument("--hot-path-only", action="store_true",
+                    help="skip the calls beyond the hot path (densification, thickness integration, view selection)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on exactly one GPU (the path shards by points; see DESIGN.md); "
@@ -229,8 +260,11 @@ def main():
     kernel = "aura_fuse_features: " + (f"k_tile_prepare + k_tile_product<{s.feat_dtype}, {s.D // 256} waves>" if tile
                                        else "k_fuse_gather")
     traffic = measured_traffic() if (tile and args.workload == "c2") else None
-    densify = time_densify(torch, d, s, max(args.steps // 2, 5))
-    thickness = time_thickness(torch, d, s, max(args.steps // 2, 5))
+    extras = {}
+    if not args.hot_path_only:
+        extras = {"densify": time_densify(torch, d, s, max(args.steps // 2, 5)),
+                  "thickness_integrate": time_thickness(torch, d, s, max(args.steps // 2, 5)),
+                  "view_selection": time_selection(torch, d, s, max(args.steps // 2, 5))}
     out = {
         "metric": "fused point-views/sec", "value": pv / (ms_per_step * 1e-3), "unit": "point-views/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
@@ -244,8 +278,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes": fuse_bytes, "avg_launch_ms": fuse_ms},
-        "densify": densify,
-        "thickness_integrate": thickness,
+        **extras,
         "calibration": calibration,
     }
     if not args.no_cpu_baseline:

@@ -8,6 +8,8 @@
  *   aura_fuse_features        Sec. 3.1 "Feature Aggregation", Eq. 2 (+ L2 normalisation, implied
  *                             by the cosine similarity of Sec. 3.4.1)
  *   aura_material_scores      Sec. 3.4.1: similarity omega_k and the kernel regression of Eq. 4
+ *   aura_select_views         Sec. 3.2.2: view importance scores and the top-k views per point
+ *   aura_fuse_selected        Sec. 3.2.3: Eq. 2 over the kept views only
  *   aura_fuse_scores          the two calls above in one (Eq. 2, then Sec. 3.4.1 / Eq. 4)
  *   aura_knn_densify          Sec. 3.4.1 Eq. 5: feature-space k-NN densification, then Eq. 4
  *   aura_property_integrate   Sec. 3.4.2: voxel integration over volumes (mass)
@@ -297,6 +299,43 @@ aura_status_t aura_property_integrate(const float* prop, int64_t N, int32_t P, i
                                       const float* xyz, const float* grid_lo, const float* grid_h, int32_t G,
                                       float* mass, int64_t* n_used,
                                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sec. 3.2.2 "View Importance-based Filtering".  For every visible pair (Eq. 1, as aura_project_visibility):
+ *     S_dist = 1 / (1 + z)             z: depth of the point in the camera frame
+ *     S_angle = max(0, v . (-n))       v: unit vector from the camera centre to the point, n: unit normal of the point
+ *     S_total = S_dist * S_angle
+ * and the k visible views with the largest S_total are kept for the point (of equal scores the lower view index
+ * first; a visible view that sees the back of the surface has score 0 and is kept only when fewer than k views score
+ * higher).  The paper keeps k = 3.  Scores are fp32.
+ *
+ *   xyz, normals [device] [N][3] fp32 (normals of unit length, oriented outward)
+ *   pt_offsets, view_offsets [host] as in aura_project_visibility
+ *   sel_view  [device] [N][k] int32: kept views in rank order, as indices within the object; -1 beyond the visible ones
+ *   sel_score [device] [N][k] fp32 or NULL: their S_total (0 beyond)
+ *   sel_mask  [device] [N][mask_pitch] uint8 or NULL: 1 for kept pairs, 0 elsewhere; mask_pitch >= views per object
+ *   n_sel     [device] [N] int32 or NULL: number of kept views, min(k, visible views)
+ * Limits: 1 <= k <= 8.
+ * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_UNSUPPORTED, AURA_ERR_HIP.
+ */
+aura_status_t aura_select_views(const aura_views_t* views, const aura_params_t* params, const float* xyz,
+                                const float* normals, int64_t N, const int64_t* pt_offsets,
+                                const int32_t* view_offsets, int32_t B, int32_t k, int32_t* sel_view, float* sel_score,
+                                uint8_t* sel_mask, int32_t mask_pitch, int32_t* n_sel, void* stream);
+
+/*
+ * Sec. 3.2.3: the features of the kept views are fused by averaging.  aura_fuse_features with the weight of a pair
+ * taken from sel_mask (e.g. the output of aura_select_views) instead of Eq. 1: fused[i] = mean over
+ * {v : sel_mask[i][v] != 0} of F_v(pi(x_i, v)), then L2 normalisation as in aura_fuse_features.  The depth maps are
+ * not read (views->depth may be NULL); a kept pair that projects behind the camera or outside the image is ignored.
+ * count [N] (or NULL) receives the number of views that entered the mean.  Everything else, the workspace
+ * (AURA_CALL_FUSE_FEATURES) included, as for aura_fuse_features.
+ *   sel_mask [device] [N][mask_pitch] uint8, mask_pitch >= views per object
+ */
+aura_status_t aura_fuse_selected(const aura_views_t* views, const aura_params_t* params, const float* xyz, int64_t N,
+                                 const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                                 const uint8_t* sel_mask, int32_t mask_pitch, float* fused, int32_t* count,
+                                 void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Sec. 3.4.2, thickness-based integration.  Every point s of object b is the centre of a voxel

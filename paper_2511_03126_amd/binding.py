@@ -83,6 +83,12 @@ def lib():
         L.aura_property_integrate.argtypes = [vp, i64, i32, i32, vp, vp, f32, vp, i32, vp, vp, vp, i32, vp, vp,
                                               vp, C.c_size_t, vp]
         L.aura_calibration_copy.restype = C.c_int32
+        L.aura_select_views.restype = C.c_int32
+        L.aura_select_views.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, vp, i64, vp, vp, i32, i32, vp, vp, vp,
+                                        i32, vp, vp]
+        L.aura_fuse_selected.restype = C.c_int32
+        L.aura_fuse_selected.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32, vp, i32, vp, vp,
+                                         vp, C.c_size_t, vp]
         L.aura_thickness_integrate.restype = C.c_int32
         L.aura_thickness_integrate.argtypes = [vp, i64, i32, vp, i32, i32, vp, vp, vp, vp, i32, vp, C.POINTER(_ParamsT),
                                                f32, f32, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
@@ -269,6 +275,34 @@ def property_integrate(prop, mass, p_index=0, count=None, vol=None, vol_uniform=
                                          _ptr(n_used), _ptr(workspace),
                                          0 if workspace is None else workspace.numel(), _stream()),
            "aura_property_integrate")
+
+
+def select_views(views: "Views", params: "Params", xyz, normals, k, sel_view, sel_score=None, sel_mask=None, n_sel=None,
+                 pt_offsets=None, view_offsets=None):
+    """Sec. 3.2.2: sel_view [N][k] int32 (and sel_score [N][k] f32, sel_mask [N][pitch] uint8, n_sel [N] int32 when
+    given) are filled in place."""
+    xyz = _dev(xyz, torch.float32, "xyz")
+    normals = _dev(normals, torch.float32, "normals")
+    po, vo, B = _objects(pt_offsets, view_offsets)
+    v, p = views.c(), params.c()
+    _check(lib().aura_select_views(C.byref(v), C.byref(p), xyz.data_ptr(), normals.data_ptr(), xyz.shape[0], _hptr(po),
+                                   _hptr(vo), B, k, sel_view.data_ptr(), _ptr(sel_score), _ptr(sel_mask),
+                                   0 if sel_mask is None else sel_mask.shape[1], _ptr(n_sel), _stream()),
+           "aura_select_views")
+
+
+def fuse_selected(views: "Views", params: "Params", xyz, sel_mask, fused, count=None, pt_offsets=None, view_offsets=None,
+                  workspace=None):
+    """Sec. 3.2.3: Eq. 2 over the views marked in sel_mask [N][pitch] uint8; fused [N][D] f32 and count [N] int32
+    are filled in place."""
+    xyz = _dev(xyz, torch.float32, "xyz")
+    _dev(sel_mask, torch.uint8, "sel_mask")
+    po, vo, B = _objects(pt_offsets, view_offsets)
+    v, p = views.c(), params.c()
+    _check(lib().aura_fuse_selected(C.byref(v), C.byref(p), xyz.data_ptr(), xyz.shape[0], _hptr(po), _hptr(vo), B,
+                                    sel_mask.data_ptr(), sel_mask.shape[1], fused.data_ptr(), _ptr(count),
+                                    _ptr(workspace), 0 if workspace is None else workspace.numel(), _stream()),
+           "aura_fuse_selected")
 
 
 def thickness_integrate(scores, y, theta, xyz, params: "Params", total, p_index=0, count=None, pt_offsets=None,

@@ -221,11 +221,32 @@ aura_status_t aura_project_visibility(const aura_views_t* views, const aura_para
   });
 }
 
+// aura_fuse_features and aura_fuse_selected: the same launches, the second with a given selection of views.
+static aura_status_t fuse_features_impl(const aura_views_t* views, const aura_params_t* params, const float* xyz, int64_t N,
+                                        const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                                        const uint8_t* sel_mask, int32_t mask_pitch, float* fused, int32_t* count,
+                                        void* workspace, size_t workspace_bytes, void* stream);
+
 aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t* params,
                                  const float* xyz, int64_t N,
                                  const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
                                  float* fused, int32_t* count,
                                  void* workspace, size_t workspace_bytes, void* stream) {
+  return fuse_features_impl(views, params, xyz, N, pt_offsets, view_offsets, B, nullptr, 0, fused, count, workspace,
+                            workspace_bytes, stream);
+}
+
+static aura_status_t fuse_features_impl(const aura_views_t* views, const aura_params_t* params, const float* xyz, int64_t N,
+                                        const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                                        const uint8_t* sel_mask, int32_t mask_pitch, float* fused, int32_t* count,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  // with a given selection the depth maps are not read
+  aura_params_t par_sel;
+  if (sel_mask && params) {
+    par_sel = *params;
+    par_sel.flags |= AURA_VIS_FRUSTUM_ONLY;
+    params = &par_sel;
+  }
   aura_status_t s = check_views(views, params, true);
   if (s != AURA_OK) return s;
   if (N < 0) return AURA_ERR_SHAPE;
@@ -233,6 +254,7 @@ aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t*
   int max_views = 0;
   s = check_objects(N, views->n_views, pt_offsets, view_offsets, B, &objs, &max_views);
   if (s != AURA_OK) return s;
+  if (sel_mask && mask_pitch < max_views) return AURA_ERR_SHAPE;
   if (N == 0) return AURA_OK;
   if (!xyz || !fused) return AURA_ERR_NULL;
   if (!aligned(fused, 16)) return AURA_ERR_ALIGN;
@@ -259,7 +281,40 @@ aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t*
   return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts, int obj_base) {
     tws.obj_base = obj_base;
     return aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only, tile ? &tws : nullptr,
-                                      tab, n, max_pts, st);
+                                      tab, n, max_pts, st, nullptr, nullptr, 0, sel_mask, mask_pitch);
+  });
+}
+
+aura_status_t aura_fuse_selected(const aura_views_t* views, const aura_params_t* params, const float* xyz, int64_t N,
+                                 const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                                 const uint8_t* sel_mask, int32_t mask_pitch, float* fused, int32_t* count,
+                                 void* workspace, size_t workspace_bytes, void* stream) {
+  if (!views || !params) return AURA_ERR_NULL;
+  if (N > 0 && !sel_mask) return AURA_ERR_NULL;
+  return fuse_features_impl(views, params, xyz, N, pt_offsets, view_offsets, B, sel_mask, mask_pitch, fused, count,
+                            workspace, workspace_bytes, stream);
+}
+
+aura_status_t aura_select_views(const aura_views_t* views, const aura_params_t* params, const float* xyz,
+                                const float* normals, int64_t N, const int64_t* pt_offsets,
+                                const int32_t* view_offsets, int32_t B, int32_t k, int32_t* sel_view, float* sel_score,
+                                uint8_t* sel_mask, int32_t mask_pitch, int32_t* n_sel, void* stream) {
+  aura_status_t s = check_views(views, params, false);
+  if (s != AURA_OK) return s;
+  if (N < 0 || k < 1) return AURA_ERR_SHAPE;
+  if (k > aura::kSelectMaxK) return AURA_ERR_UNSUPPORTED;
+  std::vector<aura::ObjRange> objs;
+  int max_views = 0;
+  s = check_objects(N, views->n_views, pt_offsets, view_offsets, B, &objs, &max_views);
+  if (s != AURA_OK) return s;
+  if (sel_mask && mask_pitch < max_views) return AURA_ERR_SHAPE;
+  if (N == 0) return AURA_OK;
+  if (!xyz || !normals || !sel_view) return AURA_ERR_NULL;
+  const aura::VisArgs va = vis_args(views, params);
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts, int) {
+    return aura::launch_select_views(va, xyz, normals, k, sel_view, sel_score, sel_mask, mask_pitch, n_sel, tab, n,
+                                     max_pts, st);
   });
 }
 

@@ -18,7 +18,14 @@ struct FuseArgs {
   float* out_factor;   // tile path only, may be nullptr: [N] factor applied to each point's raw tile product
   uint8_t* out_vis;    // tile path only, may be nullptr: [N][vis_pitch] visibility mask (Eq. 1), as aura_project_visibility
   int vis_pitch;
+  const uint8_t* in_mask;   // may be nullptr: [N][in_mask_pitch], the views kept for each point (Sec. 3.2.2); given, it
+  int in_mask_pitch;        // takes the place of the depth test (the caller passes no depth maps then)
 };
+
+// Whether view `local_view` (index within the object) takes part in the mean of point i.
+__device__ __forceinline__ bool view_kept(const FuseArgs& a, long long i, int local_view) {
+  return !a.in_mask || a.in_mask[i * a.in_mask_pitch + local_view] != 0;
+}
 
 // ---- workspace of the tile path ------------------------------------------------------------
 // A tile is 32 consecutive points of one object.  The prepare kernel turns a tile into a list of

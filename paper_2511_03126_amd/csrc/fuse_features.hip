@@ -133,7 +133,7 @@ __global__ __launch_bounds__(kFuseWaves* kWave) void k_fuse_gather(FuseArgs a, O
           const int v = ob.view_begin + vb + lane;
           const Proj p = project(a.vis.cam + (long long)v * 16, x, y, z);
           const float* dv = a.vis.depth ? a.vis.depth + (long long)v * a.vis.H * a.vis.W : nullptr;
-          seen = visible(a.vis, dv, p);
+          seen = visible(a.vis, dv, p) && view_kept(a, i, vb + lane);
           if (seen) {
             const Tap tx = tap_axis(p.u, a.feat.pitch_x, Wf), ty = tap_axis(p.v, a.feat.pitch_y, Hf);
             x0 = tx.i0; ax = tx.a;
@@ -244,10 +244,10 @@ static hipError_t dispatch_d(const FuseArgs& a, const ObjTable& tab, int n_obj, 
 hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const float* xyz, float* fused,
                                 int* out_count, float norm_eps, int mean_only, const TileWs* tile_ws,
                                 const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream, float* out_factor,
-                                uint8_t* out_vis, int vis_pitch) {
+                                uint8_t* out_vis, int vis_pitch, const uint8_t* in_mask, int in_mask_pitch) {
   if (n_obj == 0 || max_pts == 0) return hipSuccess;
   FuseArgs a{vis, feat, xyz, fused, out_count, norm_eps, mean_only, tile_ws ? out_factor : nullptr,
-             tile_ws ? out_vis : nullptr, vis_pitch};
+             tile_ws ? out_vis : nullptr, vis_pitch, in_mask, in_mask_pitch};
   if (tile_ws) return launch_fuse_tile(a, *tile_ws, tab, n_obj, max_pts, stream);
   switch (feat.dtype) {
     case 0: return dispatch_d<0>(a, tab, n_obj, max_pts, stream);

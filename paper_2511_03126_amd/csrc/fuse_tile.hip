@@ -163,7 +163,7 @@ __device__ __forceinline__ void gather_tile(const FuseArgs& a, const ObjRange& o
           const int v = ob.view_begin + vb + lane;
           const Proj p = project(a.vis.cam + (long long)v * 16, x, y, z);
           const float* dv = a.vis.depth ? a.vis.depth + (long long)v * a.vis.H * a.vis.W : nullptr;
-          seen = visible(a.vis, dv, p);
+          seen = visible(a.vis, dv, p) && view_kept(a, i, vb + lane);
           if (a.out_vis && cb == 0) a.out_vis[i * a.vis_pitch + vb + lane] = seen ? 1 : 0;
           if (seen) {
             const Tap tx = tap_axis(p.u, a.feat.pitch_x, Wf), ty = tap_axis(p.v, a.feat.pitch_y, Hf);
@@ -229,8 +229,10 @@ __device__ __forceinline__ void gather_tile(const FuseArgs& a, const ObjRange& o
   }
 }
 
-// DT: 1 bf16, 2 fp16 feature maps (decides the 16-bit format of the weights).
-template <int DT>
+// DT: 1 bf16, 2 fp16 feature maps (decides the 16-bit format of the weights).  SEL: the views of each point are
+// given (FuseArgs::in_mask) instead of decided by the depth test; a variant of its own so that the usual path does
+// not carry the test.
+template <int DT, bool SEL>
 __global__ __launch_bounds__(kPrepThreads) __attribute__((amdgpu_waves_per_eu(AURA_PREP_WPE)))
 void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
   __shared__ int s_win[kViewBatch][2];                 // first cell (x, y) of the view's map
@@ -284,7 +286,8 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
       const bool fr = in_frustum(a.vis, pj);
       float dep = 1.0f;
       if (a.vis.depth) dep = a.vis.depth[(long long)v * a.vis.H * a.vis.W + (fr ? depth_texel(a.vis, pj) : 0)];
-      const bool seen = vl < nvb && p_valid && fr && (a.vis.frustum_only || passes_depth(a.vis, pj, dep));
+      bool seen = vl < nvb && p_valid && fr && (a.vis.frustum_only || passes_depth(a.vis, pj, dep));
+      if constexpr (SEL) seen = seen && view_kept(a, ip, vb0 + min(vl, nvb - 1));
       s16x2 lo2 = {0x7fff, 0x7fff}, hi2 = {-1, -1};   // (x, y) of the first / second cell
       if (seen) {
         const Tap tx = tap_axis(pj.u, a.feat.pitch_x, Wf), ty = tap_axis(pj.v, a.feat.pitch_y, Hf);
@@ -871,7 +874,10 @@ template <int DT, int S, int H, int PF>
 static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
                               hipStream_t stream) {
   const int max_tiles = (max_pts + kTilePts - 1) / kTilePts;
-  hipLaunchKernelGGL((k_tile_prepare<DT>), dim3(max_tiles, n_obj), dim3(kPrepThreads), 0, stream, a, ws, tab);
+  if (a.in_mask)
+    hipLaunchKernelGGL((k_tile_prepare<DT, true>), dim3(max_tiles, n_obj), dim3(kPrepThreads), 0, stream, a, ws, tab);
+  else
+    hipLaunchKernelGGL((k_tile_prepare<DT, false>), dim3(max_tiles, n_obj), dim3(kPrepThreads), 0, stream, a, ws, tab);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   ProdArgs pa{static_cast<const char*>(a.feat.feat), a.feat.D, ws.hdr, ws.steps, ws.counters + (size_t)ws.obj_base * kXcd,

@@ -28,7 +28,14 @@ hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const 
                                 int* out_count, float norm_eps, int mean_only, const TileWs* tile_ws,
                                 const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream,
                                 float* out_factor = nullptr,    // tile path only: see FuseArgs::out_factor
-                                uint8_t* out_vis = nullptr, int vis_pitch = 0);   // tile path only: see FuseArgs::out_vis
+                                uint8_t* out_vis = nullptr, int vis_pitch = 0,    // tile path only: see FuseArgs::out_vis
+                                const uint8_t* in_mask = nullptr, int in_mask_pitch = 0);   // see FuseArgs::in_mask
+
+// Sec. 3.2.2, view importance-based filtering (select_views.hip).
+constexpr int kSelectMaxK = 8;
+hipError_t launch_select_views(const VisArgs& vis, const float* xyz, const float* normals, int k, int* sel_view,
+                               float* sel_score, uint8_t* sel_mask, int mask_pitch, int* n_sel, const ObjTable& tab,
+                               int n_obj, int max_pts, hipStream_t stream);
 
 size_t scores_workspace_bytes(int D, int K);
 hipError_t launch_material_scores(const float* fused, long long N, int D, const float* temb, int K,

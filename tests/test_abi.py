@@ -192,6 +192,30 @@ def test_argument_validation_returns_status_codes(B):
         B.workspace_bytes(B.CALL_KNN_DENSIFY, D=768, Ns=300)
     assert e.value.status == -7
 
+    sv = lambda v=None, N=10, k=3, xyz=fake, nrm=fake, sel=fake, mask=None, pitch=0, po_=None, vo_=None, B_=1: \
+        L.aura_select_views(C.byref(v if v is not None else _views(B)), C.byref(p), xyz, nrm, N, po_, vo_, B_, k, sel, None,
+                            mask, pitch, None, None)
+    assert sv(xyz=None) == -1 and sv(nrm=None) == -1 and sv(sel=None) == -1
+    assert sv(v=_views(B, cam=None)) == -1
+    assert sv(v=_views(B, depth=None)) == -1                               # the depth test needs depth maps
+    assert sv(k=0) == -2
+    assert sv(k=9) == -7
+    assert sv(N=-1) == -2
+    assert sv(mask=fake, pitch=3) == -2                                    # fewer mask columns than views
+    assert sv(po_=hp(po), vo_=None, B_=2) == -1
+    assert sv(N=0, xyz=None, nrm=None, sel=None) == 0
+
+    fsel = lambda v=None, N=10, xyz=fake, mask=fake, pitch=4, fused=fake, ws=None, wsb=0: L.aura_fuse_selected(
+        C.byref(v if v is not None else _views(B)), C.byref(p), xyz, N, None, None, 1, mask, pitch, fused, None, ws, wsb, None)
+    assert fsel(mask=None) == -1
+    assert fsel(xyz=None) == -1 and fsel(fused=None) == -1
+    assert fsel(pitch=3) == -2
+    assert fsel(v=_views(B, feat=None)) == -1
+    assert fsel(v=_views(B, feat_dtype=7)) == -3
+    assert fsel(fused=C.c_void_p(0x1004)) == -4
+    assert fsel(v=_views(B, **half), ws=C.c_void_p(0x1000), wsb=64) == -5
+    assert fsel(N=0, xyz=None, mask=None, fused=None) == 0
+
     ti = lambda N=10, K=8, P=2, pi=0, scores=fake, y=fake, theta=fake, xyz=fake, po_=None, B_=1, blen=None, par=p, lam=0.6, \
         scale=1.0, total=fake, ws=C.c_void_p(0x1000), wsb=1 << 20: L.aura_thickness_integrate(
             scores, N, K, y, P, pi, theta, xyz, None, po_, B_, blen, C.byref(par) if par is not None else None, lam, scale,

@@ -1,0 +1,150 @@
+"""GPU parity of aura_select_views (Sec. 3.2.2) and aura_fuse_selected (Sec. 3.2.3) against the CPU oracle on the
+same seeded inputs.
+
+Selection: which views are visible is bit-exact (Eq. 1); scores within 1e-5 (fp32 against fp64); the kept views
+identical, in order, wherever the oracle's scores around the cut and between consecutive kept views are further apart
+than the accuracy of an fp32 score (pairs inside that margin may swap: they must be rare and the library's choice must
+still be k visible views whose oracle scores are the k largest up to the margin).  Fusion over a selection: both
+sides get the ORACLE's selection; fused rows to the bar of the hot path, counts exact."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+SCORE_TOL = 1e-5
+
+
+def _scene(name, **kw):
+    from workloads.scenes import make_scene, synthetic_normals
+    s = make_scene(name, **kw)
+    return s, synthetic_normals(s.xyz, s.pt_offsets, s.meta["seed"])
+
+
+def _gpu_select(d, s, nrm, k, want_all=True):
+    import paper_2511_03126_amd as aura
+    N = s.N
+    sel_view = torch.full((N, k), -7, dtype=torch.int32, device=d.dev)
+    sel_score = torch.full((N, k), float("nan"), device=d.dev) if want_all else None
+    sel_mask = torch.full((N, s.vis_pitch), 9, dtype=torch.uint8, device=d.dev) if want_all else None
+    n_sel = torch.full((N,), -7, dtype=torch.int32, device=d.dev) if want_all else None
+    aura.select_views(d.views, d.params, d.xyz, torch.from_numpy(nrm).to(d.dev), k, sel_view, sel_score, sel_mask, n_sel,
+                      d.pt_offsets, d.view_offsets)
+    torch.cuda.synchronize()
+    f = lambda t: None if t is None else t.cpu().numpy()
+    return dict(sel_view=f(sel_view), sel_score=f(sel_score), sel_mask=f(sel_mask), n_sel=f(n_sel))
+
+
+def _check_selection(g, ref, k):
+    assert np.array_equal(g["n_sel"], ref["n_sel"])                      # the visible views are the same: Eq. 1
+    assert np.abs(g["sel_score"] - ref["sel_score"]).max(initial=0.0) <= SCORE_TOL
+    # mask = exactly the kept views
+    assert np.array_equal(g["sel_mask"].sum(1), g["n_sel"]) and g["sel_mask"].max(initial=0) <= 1
+    rows, cols = np.nonzero(g["sel_view"] >= 0)
+    assert g["sel_mask"][rows, g["sel_view"][rows, cols]].all()
+    assert ((g["sel_view"] >= 0).sum(1) == g["n_sel"]).all()
+    # identical ranking away from near-ties
+    d = -np.diff(ref["sel_score"], axis=1)
+    both = (ref["sel_view"][:, 1:] >= 0) if k > 1 else np.zeros((len(d), 0), bool)
+    last = np.take_along_axis(ref["sel_score"], np.maximum(ref["n_sel"] - 1, 0)[:, None], 1)[:, 0]
+    # scores of exactly 0 (views that see the back of the surface) are 0 on both sides and go by view index
+    cut_clear = (ref["gap"] > SCORE_TOL) | ((ref["gap"] == 0) & (last == 0))
+    clear = cut_clear & ((d > SCORE_TOL) | ((d == 0) & (ref["sel_score"][:, 1:] == 0)) | ~both).all(1)
+    assert clear.mean() > 0.97, f"too many near-ties: {1 - clear.mean():.4f}"
+    assert np.array_equal(g["sel_view"][clear], ref["sel_view"][clear])
+    assert np.array_equal(g["sel_mask"][clear], ref["sel_mask"][clear])
+    # inside the margin: every kept view is visible and scores, by the oracle, within the margin of the oracle's choice
+    for i in np.nonzero(~clear)[0]:
+        kept = g["sel_view"][i][g["sel_view"][i] >= 0]
+        assert len(set(kept.tolist())) == len(kept)
+        s_or = ref["score_all"][i, kept]
+        assert (s_or >= 0).all()
+        assert np.abs(np.sort(s_or)[::-1] - ref["sel_score"][i, :len(kept)]).max(initial=0.0) <= 2 * SCORE_TOL
+
+
+@pytest.mark.parametrize("name,kw,k", [("c1", {}, 3), ("c1", {}, 1), ("c1", {}, 8), ("c2", dict(n_points=30_011), 3),
+                                       ("c5", dict(n_points=3_001, n_objects=5), 2), ("c5", dict(n_points=3_001, n_objects=70), 3),
+                                       ("c1", dict(n_points=7_001, overrides=dict(dtype="f16", V=12)), 5)])
+def test_selection_matches_oracle(orc, name, kw, k):
+    import gpu_harness as H
+    s, nrm = _scene(name, **kw)
+    d = H.DeviceScene(s)
+    g = _gpu_select(d, s, nrm, k)
+    ref = orc.select_views(s.cam, s.depth, s.xyz, nrm, k, tau=s.tau, z_near=s.z_near, pt_offsets=d.pt_offsets,
+                           view_offsets=d.view_offsets, mask_pitch=s.vis_pitch)
+    _check_selection(g, ref, k)
+    only = _gpu_select(d, s, nrm, k, want_all=False)
+    assert np.array_equal(only["sel_view"], g["sel_view"])
+
+
+def test_hand_worked_rig_on_the_gpu():
+    """Cameras on a line at known distances: S_total = 1 / (1 + distance), nearest first; equal distances by index; a
+    camera behind the surface scores 0 and comes last."""
+    import paper_2511_03126_amd as aura
+    dev = "cuda:0"
+    cam = lambda zc, flip=False: np.array(([-1, 0, 0, 0, 1, 0, 0, 0, -1] if flip else [1, 0, 0, 0, 1, 0, 0, 0, 1])
+                                          + [0, 0, (zc if flip else -zc)] + [100, 100, 500, 500], np.float32)
+    # camera centres at z = -2, -2, -1 looking along +z; one at z = +1 looking back along -z (R = diag(-1, 1, -1))
+    cams = np.stack([cam(1.0, flip=True), cam(-2.0), cam(-2.0), cam(-1.0)])
+    views = aura.Views(cam=torch.from_numpy(cams).to(dev), depth=None, feat=None, H=1000, W=1000)
+    params = aura.Params(flags=1)   # frustum only
+    xyz = torch.tensor([[0.0, 0.0, 0.0]], device=dev)
+    nrm = torch.tensor([[0.0, 0.0, -1.0]], device=dev)
+    sel_view = torch.empty((1, 4), dtype=torch.int32, device=dev)
+    sel_score = torch.empty((1, 4), device=dev)
+    aura.select_views(views, params, xyz, nrm, 4, sel_view, sel_score)
+    torch.cuda.synchronize()
+    assert sel_view.cpu().tolist() == [[3, 1, 2, 0]]
+    assert np.allclose(sel_score.cpu().numpy(), [[0.5, 1 / 3, 1 / 3, 0.0]], rtol=1e-6)
+
+
+@pytest.mark.parametrize("name,kw,k", [("c1", {}, 3), ("c2", dict(n_points=30_011), 3), ("c2", dict(n_points=30_011), 1),
+                                       ("c5", dict(n_points=3_001, n_objects=5), 2), ("c1", dict(n_points=7_001, overrides=dict(dtype="f16", V=12, D=512)), 3)])
+def test_fusion_over_the_oracle_selection(orc, name, kw, k):
+    import gpu_harness as H
+    import paper_2511_03126_amd as aura
+    s, nrm = _scene(name, **kw)
+    d = H.DeviceScene(s)
+    sel = orc.select_views(s.cam, s.depth, s.xyz, nrm, k, tau=s.tau, z_near=s.z_near, pt_offsets=d.pt_offsets,
+                           view_offsets=d.view_offsets, mask_pitch=s.vis_pitch)
+    ref = orc.fuse_features(s.cam, s.depth, s.feat, s.feat_dtype, s.xyz, tau=s.tau, z_near=s.z_near,
+                            pt_offsets=d.pt_offsets, view_offsets=d.view_offsets, sel_mask=sel["sel_mask"])
+    mask = torch.from_numpy(sel["sel_mask"]).to(d.dev)
+    for ws in ([d.ws_fuse, None] if d.ws_fuse is not None else [None]):     # matrix-core path and gather path
+        d.fused.fill_(float("nan"))
+        d.count_fuse.fill_(-7)
+        aura.fuse_selected(d.views, d.params, d.xyz, mask, d.fused, d.count_fuse, d.pt_offsets, d.view_offsets, ws)
+        torch.cuda.synchronize()
+        fg = d.fused.cpu().numpy().astype(np.float64)
+        assert np.array_equal(d.count_fuse.cpu().numpy(), ref["count"])
+        assert np.array_equal(ref["count"], sel["n_sel"])
+        nr = np.linalg.norm(ref["fused"], axis=1)
+        err = np.linalg.norm(fg - ref["fused"], axis=1) / np.maximum(nr, 1e-12)
+        err[(nr == 0) & (np.linalg.norm(fg, axis=1) == 0)] = 0.0
+        assert err.max() <= H.tol_for(s), f"fused rel err {err.max()}"
+
+
+def test_full_size_pipeline_c2(orc):
+    """C2 at full size: select on the device, fuse over the device's own selection; the oracle selects and fuses on its
+    own.  Points whose selection is unambiguous (all but a few near-ties) must agree to the bar of the hot path."""
+    import gpu_harness as H
+    import paper_2511_03126_amd as aura
+    s, nrm = _scene("c2")
+    d = H.DeviceScene(s)
+    g = _gpu_select(d, s, nrm, 3)
+    mask = torch.from_numpy(g["sel_mask"]).to(d.dev)
+    aura.fuse_selected(d.views, d.params, d.xyz, mask, d.fused, d.count_fuse, None, None, d.ws_fuse)
+    torch.cuda.synchronize()
+    ref_sel = orc.select_views(s.cam, s.depth, s.xyz, nrm, 3, tau=s.tau, z_near=s.z_near, mask_pitch=s.vis_pitch)
+    _check_selection(g, ref_sel, 3)
+    same = (g["sel_mask"] == ref_sel["sel_mask"]).all(1)
+    assert same.mean() > 0.99
+    rng = np.random.default_rng(3)
+    idx = np.sort(rng.choice(np.nonzero(same)[0], 4000, replace=False))
+    ref = orc.fuse_features(s.cam, s.depth, s.feat, s.feat_dtype, s.xyz[idx], tau=s.tau, z_near=s.z_near,
+                            sel_mask=ref_sel["sel_mask"][idx])
+    fg = d.fused.cpu().numpy()[idx].astype(np.float64)
+    err = np.linalg.norm(fg - ref["fused"], axis=1) / np.maximum(np.linalg.norm(ref["fused"], axis=1), 1e-12)
+    err[np.linalg.norm(ref["fused"], axis=1) == 0] = 0.0
+    assert err.max() <= H.tol_for(s)
+    assert np.array_equal(d.count_fuse.cpu().numpy()[idx], ref["count"])

@@ -116,8 +116,9 @@ def test_reproducible_bit_for_bit():
 
 @pytest.mark.parametrize("name", ["c1", "c2"])
 def test_after_the_hot_path(orc, name):
-    """Full size, in the configuration the benchmark times: the scores come from aura_fuse_scores on the device,
-    the oracle integrates the same fp32 scores."""
+    """Full size, in the configuration the benchmark times: the device integrates the scores of aura_fuse_scores, the
+    oracle integrates the scores of its own fusion and scoring of the same scene.  Bar: that of the hot path
+    (1e-4 for fp32 maps, 2e-2 for bf16 maps), since the scores differ by the rounding of the fused rows."""
     import gpu_harness as H
     from workloads.scenes import make_scene, material_thickness
     import paper_2511_03126_amd as aura
@@ -136,9 +137,14 @@ def test_after_the_hot_path(orc, name):
                              count=d.count_fuse, pt_offsets=None if d.single else s.pt_offsets, lam=0.6, scale_factor=1.0,
                              zeta=zeta, com=com, b_adap=b_adap, n_used=n_used, workspace=work)
     torch.cuda.synchronize()
-    g = dict(total=total.cpu().numpy(), com=com.cpu().numpy(), zeta=zeta.cpu().numpy(), b_adap=b_adap.cpu().numpy(),
-             n_used=n_used.cpu().numpy())
-    ref = orc.thickness_integrate(d.scores.cpu().numpy(), s.y[:, 0], theta, s.xyz, count=d.count_fuse.cpu().numpy(),
+    pts = H.oracle_points(orc, s)
+    ref = orc.thickness_integrate(pts["scores"], s.y[:, 0], theta, s.xyz, count=pts["count_fuse"],
                                   pt_offsets=None if d.single else s.pt_offsets, T=s.temperature, lam=0.6)
-    _compare(g, ref, s.xyz)
-    assert g["total"][0] > 0 and np.isfinite(g["com"]).all()
+    tol = H.tol_for(s)
+    g_zeta = zeta.cpu().numpy()
+    assert np.array_equal(n_used.cpu().numpy(), ref["n_used"])
+    assert np.abs(g_zeta - ref["zeta"]).max() <= tol * np.abs(ref["zeta"]).max()
+    assert np.allclose(total.cpu().numpy(), ref["mass"], rtol=tol)
+    assert np.allclose(b_adap.cpu().numpy(), ref["b_adap"], rtol=1e-5)
+    assert np.abs(com.cpu().numpy() - ref["com"]).max() <= tol * np.abs(s.xyz).max()
+    assert ref["mass"][0] > 0
