@@ -19,6 +19,8 @@
  *   densification omega(q)                 Sec. 3.4.1 Eq. 5 (k nearest source points by cosine
  *                                          similarity of the fused features, similarity-weighted
  *                                          mean of their material vectors, then Eq. 4)
+ *   adaptive sampling                      Sec. 3.2.1 (voxel size from the boundary box volume and N_target, voxel
+ *                                          down-sampling to the mean position per occupied voxel)
  *   view importance-based filtering        Sec. 3.2.2 (S_dist, S_angle, S_total, top-k views per point) and the
  *                                          mean over the kept views of Sec. 3.2.3
  *   thickness-based integration            Sec. 3.4.2 (voxel b_adap x b_adap x theta per point, correction
@@ -672,5 +674,88 @@ int orc_select_views(const float* cam, const float* depth, int n_views, int H, i
       free(taken);
     }
   }
+  return 0;
+}
+
+/* ---------------------------------------------------------------- exported: Sec. 3.2.1, adaptive sampling
+ * Voxel size from the volume of the boundary box and the wanted number of points,
+ *     s_voxel = cbrt(V_bound / N_target),
+ * then standard voxel down-sampling: the box is cut into cubes of side s_voxel and every occupied cube is
+ * replaced by the mean position of its points.
+ * Decision arithmetic (fp32, so that an fp32 implementation bins every point alike): extents e = hi - lo,
+ * s = (float)cbrt((double)e_x * e_y * e_z / N_target); a flat box (volume 0) takes the longest extent in place of
+ * the cube root of the volume, s = e_max / cbrt(N_target), and a box of one point s = 1; cubes per axis
+ * n = floor(e / s) + 1; a point's cube per axis clamp(floor((x - lo) / s), 0, n - 1).                     */
+int orc_voxel_grid(const float* box_lo, const float* box_hi, int n_target, float* s_voxel, int32_t* dims) {
+  if (!box_lo || !box_hi || !s_voxel || !dims) return -1;
+  if (n_target < 1) return -2;
+  float e[3], emax = 0.0f;
+  for (int a = 0; a < 3; ++a) {
+    e[a] = box_hi[a] - box_lo[a];
+    if (!(e[a] >= 0.0f)) return -2;
+    if (e[a] > emax) emax = e[a];
+  }
+  float s = (float)cbrt((double)e[0] * (double)e[1] * (double)e[2] / (double)n_target);
+  if (!(s > 0.0f)) s = (float)((double)emax / cbrt((double)n_target));
+  if (!(s > 0.0f)) s = 1.0f;
+  *s_voxel = s;
+  for (int a = 0; a < 3; ++a) {
+    float q = floorf(e[a] / s);
+    if (q > 2.0e9f) return -7;
+    dims[a] = (int32_t)q + 1;
+  }
+  return 0;
+}
+
+/* out_xyz / out_count: the occupied cubes of object 0 in the order of their index (z * ny + y) * nx + x, then those
+ * of object 1, ...; out_offsets [B+1] their ranges; voxel_of_point [N]: position of the point's cube in that list.
+ * Returns the number of occupied cubes through *n_out; out arrays hold out_capacity entries (cubes beyond are
+ * counted but not written).                                                                              */
+int orc_voxel_downsample(const float* xyz, int64_t N, const int64_t* pt_offsets, int B, const float* box_lo,
+                         const float* box_hi, int n_target, double* out_xyz, int32_t* out_count, int64_t out_capacity,
+                         int64_t* out_offsets, int64_t* voxel_of_point) {
+  if (!xyz || !box_lo || !box_hi || !out_xyz || !out_offsets) return -1;
+  if (N < 0 || B < 1 || n_target < 1) return -2;
+  if (!pt_offsets && B != 1) return -1;
+  int64_t total = 0;
+  for (int b = 0; b < B; ++b) {
+    const int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
+    float s;
+    int32_t d[3];
+    int rc = orc_voxel_grid(box_lo + 3 * b, box_hi + 3 * b, n_target, &s, d);
+    if (rc) return rc;
+    const int64_t cells = (int64_t)d[0] * d[1] * d[2];
+    double* sum = (double*)calloc((size_t)cells * 3, sizeof(double));
+    int32_t* cnt = (int32_t*)calloc((size_t)cells, sizeof(int32_t));
+    int64_t* slot = (int64_t*)malloc((size_t)cells * sizeof(int64_t));
+    int64_t* cell_of = (int64_t*)malloc((size_t)(p1 > p0 ? p1 - p0 : 1) * sizeof(int64_t));
+    if (!sum || !cnt || !slot || !cell_of) { free(sum); free(cnt); free(slot); free(cell_of); return -5; }
+    for (int64_t i = p0; i < p1; ++i) {
+      int64_t idx = 0;
+      for (int a = 2; a >= 0; --a) {
+        float t = xyz[3 * i + a] - box_lo[3 * b + a];
+        float fl = floorf(t / s);
+        int q = (fl >= (float)(d[a] - 1)) ? d[a] - 1 : ((fl > 0.0f) ? (int)fl : 0);
+        idx = idx * d[a] + q;
+      }
+      cell_of[i - p0] = idx;
+      for (int a = 0; a < 3; ++a) sum[3 * idx + a] += (double)xyz[3 * i + a];
+      cnt[idx] += 1;
+    }
+    out_offsets[b] = total;
+    for (int64_t c = 0; c < cells; ++c) {
+      slot[c] = -1;
+      if (cnt[c] == 0) continue;
+      slot[c] = total;
+      if (total < out_capacity) {
+        for (int a = 0; a < 3; ++a) out_xyz[3 * total + a] = sum[3 * c + a] / (double)cnt[c];
+        if (out_count) out_count[total] = cnt[c];
+      }
+      ++total;
+    }
+    if (voxel_of_point) for (int64_t i = p0; i < p1; ++i) voxel_of_point[i] = slot[cell_of[i - p0]];
+    free(sum); free(cnt); free(slot); free(cell_of);
+  }
+  out_offsets[B] = total;
   return 0;
 }

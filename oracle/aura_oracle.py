@@ -269,3 +269,36 @@ def select_views(cam, depth, xyz, normals, k, tau=0.0, z_near=1e-6, flags=0, pt_
     _check(rc, "select_views")
     return {"sel_view": sel_view, "sel_score": sel_score, "sel_mask": sel_mask, "n_sel": n_sel, "gap": gap,
             "score_all": score_all}
+
+
+def voxel_grid(box_lo, box_hi, n_target):
+    """Sec. 3.2.1: s_voxel = cbrt(V_bound / N_target) and the number of voxels per axis."""
+    lo, hi = _f32(box_lo).reshape(3), _f32(box_hi).reshape(3)
+    s = C.c_float(0.0)
+    dims = np.zeros(3, np.int32)
+    _check(lib().orc_voxel_grid(_p(lo), _p(hi), C.c_int(n_target), C.byref(s), _p(dims)), "voxel_grid")
+    return float(s.value), dims
+
+
+def voxel_downsample(xyz, n_target, box_lo=None, box_hi=None, pt_offsets=None, capacity=None):
+    """Sec. 3.2.1: adaptive voxel down-sampling; the box defaults to the bounding box of each object's points."""
+    xyz = _f32(xyz).reshape(-1, 3)
+    N = xyz.shape[0]
+    po = None if pt_offsets is None else np.ascontiguousarray(pt_offsets, dtype=np.int64)
+    B = 1 if po is None else len(po) - 1
+    if box_lo is None:
+        rng = [(0, N)] if po is None else [(int(po[b]), int(po[b + 1])) for b in range(B)]
+        box_lo = np.stack([xyz[a:b].min(0) if b > a else np.zeros(3, np.float32) for a, b in rng])
+        box_hi = np.stack([xyz[a:b].max(0) if b > a else np.zeros(3, np.float32) for a, b in rng])
+    lo, hi = _f32(box_lo).reshape(B, 3), _f32(box_hi).reshape(B, 3)
+    cap = N if capacity is None else int(capacity)
+    out_xyz = np.zeros((max(cap, 1), 3), np.float64)
+    out_count = np.zeros(max(cap, 1), np.int32)
+    out_offsets = np.zeros(B + 1, np.int64)
+    voxel_of_point = np.zeros(max(N, 1), np.int64)
+    _check(lib().orc_voxel_downsample(_p(xyz), C.c_int64(N), _p(po), C.c_int(B), _p(lo), _p(hi), C.c_int(n_target),
+                                      _p(out_xyz), _p(out_count), C.c_int64(cap), _p(out_offsets), _p(voxel_of_point)),
+           "voxel_downsample")
+    M = min(int(out_offsets[B]), cap)
+    return {"xyz": out_xyz[:M], "count": out_count[:M], "offsets": out_offsets, "voxel_of_point": voxel_of_point[:N],
+            "box_lo": lo, "box_hi": hi}
