@@ -131,6 +131,32 @@ def time_selection(torch, d, s, reps, k=3):
     return out
 
 
+def time_downsample(torch, d, s, reps, n_target=150):
+    """Sec. 3.2.1: adaptive voxel down-sampling of the scene's points to about 150 source points per object."""
+    import numpy as np
+    import paper_2511_03126_amd as aura
+    po = s.pt_offsets
+    lo = np.stack([s.xyz[po[b]:po[b + 1]].min(0) for b in range(s.B)]).astype(np.float32)
+    hi = np.stack([s.xyz[po[b]:po[b + 1]].max(0) for b in range(s.B)]).astype(np.float32)
+    cap = 64 * n_target * s.B
+    out_xyz = torch.empty((cap, 3), device=d.dev)
+    out_offsets = torch.empty(s.B + 1, dtype=torch.int32, device=d.dev)
+    vop = torch.empty(s.N, dtype=torch.int32, device=d.dev)
+    work = torch.empty(aura.voxel_workspace_bytes(lo, hi, n_target), dtype=torch.uint8, device=d.dev)
+    run = lambda: aura.voxel_downsample(d.xyz, lo, hi, n_target, out_xyz, out_offsets, None, vop,
+                                        pt_offsets=None if d.single else po, workspace=work)
+    for _ in range(2):
+        run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    return {"call": "aura_voxel_downsample", "n_target": n_target, "ms": e0.elapsed_time(e1) / reps,
+            "sampled_points": int(out_offsets[-1].item())}
+
+
 def cpu_baseline(scene, seconds_target=15.0):
     """The oracle, as it stands, on a contiguous sample of the scene's first object."""
     import numpy as np
@@ -264,7 +290,8 @@ def main():
     if not args.hot_path_only:
         extras = {"densify": time_densify(torch, d, s, max(args.steps // 2, 5)),
                   "thickness_integrate": time_thickness(torch, d, s, max(args.steps // 2, 5)),
-                  "view_selection": time_selection(torch, d, s, max(args.steps // 2, 5))}
+                  "view_selection": time_selection(torch, d, s, max(args.steps // 2, 5)),
+                  "voxel_downsample": time_downsample(torch, d, s, max(args.steps // 2, 5))}
     out = {
         "metric": "fused point-views/sec", "value": pv / (ms_per_step * 1e-3), "unit": "point-views/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

@@ -8,6 +8,7 @@
  *   aura_fuse_features        Sec. 3.1 "Feature Aggregation", Eq. 2 (+ L2 normalisation, implied
  *                             by the cosine similarity of Sec. 3.4.1)
  *   aura_material_scores      Sec. 3.4.1: similarity omega_k and the kernel regression of Eq. 4
+ *   aura_voxel_downsample     Sec. 3.2.1: adaptive voxel size and voxel down-sampling of the point cloud
  *   aura_select_views         Sec. 3.2.2: view importance scores and the top-k views per point
  *   aura_fuse_selected        Sec. 3.2.3: Eq. 2 over the kept views only
  *   aura_fuse_scores          the two calls above in one (Eq. 2, then Sec. 3.4.1 / Eq. 4)
@@ -299,6 +300,40 @@ aura_status_t aura_property_integrate(const float* prop, int64_t N, int32_t P, i
                                       const float* xyz, const float* grid_lo, const float* grid_h, int32_t G,
                                       float* mass, int64_t* n_used,
                                       void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sec. 3.2.1 "Adaptive Sampling".  The voxel size follows the object instead of being fixed,
+ *     s_voxel = cbrt(V_bound / N_target),
+ * V_bound the volume of the boundary box of the point cloud and N_target the wanted number of points (the paper takes
+ * about 150); the box is cut into cubes of side s_voxel and every occupied cube is replaced by the mean position of
+ * its points (standard voxel down-sampling).
+ * Arithmetic that decides an integer is fp32: extents e = hi - lo; s_voxel = (float)cbrt((double)e_x e_y e_z /
+ * N_target); a box without volume takes e_max / cbrt(N_target), a box of one point 1; cubes per axis
+ * floor(e / s_voxel) + 1; a point's cube per axis clamp(floor((x - lo) / s_voxel), 0, cubes - 1).  Sums are exact
+ * (64-bit fixed point), so the result does not depend on the order of the points.
+ *
+ * aura_voxel_grid (host only, no GPU work): s_voxel and the cubes per axis (dims[3]) of one box.
+ * aura_voxel_workspace_bytes: workspace of aura_voxel_downsample for these boxes.
+ * aura_voxel_downsample:
+ *   xyz [device] [N][3] fp32          pt_offsets [host] [B+1] int64 or NULL (B == 1)
+ *   box_lo, box_hi [host] [B][3] fp32: the boundary box of every object (hi >= lo).  Points outside it fall into its
+ *           border cubes; they may lie up to one box extent outside.
+ *   out_xyz [device] [out_capacity][3] fp32: the sampled points, object after object, inside an object in the order
+ *           of the cube index (z * ny + y) * nx + x          out_count [device] [out_capacity] int32 or NULL: points per cube
+ *   out_offsets [device] [B+1] int32: range of every object in the list; out_offsets[B] is the number of occupied
+ *           cubes even when it exceeds out_capacity (the cubes beyond it are not written)
+ *   voxel_of_point [device] [N] int32 or NULL: list position of the point's cube
+ *   workspace [device] aura_voxel_workspace_bytes(...) bytes, 256-byte aligned
+ * Limits: B <= 64; the grids of a call hold at most 2^24 cubes in all (every object rounded up to 2048).
+ * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_WORKSPACE, AURA_ERR_UNSUPPORTED, AURA_ERR_HIP.
+ */
+aura_status_t aura_voxel_grid(const float* box_lo, const float* box_hi, int32_t n_target, float* s_voxel, int32_t* dims);
+aura_status_t aura_voxel_workspace_bytes(const float* box_lo, const float* box_hi, int32_t B, int32_t n_target,
+                                         size_t* bytes);
+aura_status_t aura_voxel_downsample(const float* xyz, int64_t N, const int64_t* pt_offsets, int32_t B,
+                                    const float* box_lo, const float* box_hi, int32_t n_target, float* out_xyz,
+                                    int32_t* out_count, int64_t out_capacity, int32_t* out_offsets,
+                                    int32_t* voxel_of_point, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Sec. 3.2.2 "View Importance-based Filtering".  For every visible pair (Eq. 1, as aura_project_visibility):

@@ -83,6 +83,12 @@ def lib():
         L.aura_property_integrate.argtypes = [vp, i64, i32, i32, vp, vp, f32, vp, i32, vp, vp, vp, i32, vp, vp,
                                               vp, C.c_size_t, vp]
         L.aura_calibration_copy.restype = C.c_int32
+        L.aura_voxel_grid.restype = C.c_int32
+        L.aura_voxel_grid.argtypes = [vp, vp, i32, C.POINTER(C.c_float), vp]
+        L.aura_voxel_workspace_bytes.restype = C.c_int32
+        L.aura_voxel_workspace_bytes.argtypes = [vp, vp, i32, i32, C.POINTER(C.c_size_t)]
+        L.aura_voxel_downsample.restype = C.c_int32
+        L.aura_voxel_downsample.argtypes = [vp, i64, vp, i32, vp, vp, i32, vp, vp, i64, vp, vp, vp, C.c_size_t, vp]
         L.aura_select_views.restype = C.c_int32
         L.aura_select_views.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, vp, i64, vp, vp, i32, i32, vp, vp, vp,
                                         i32, vp, vp]
@@ -275,6 +281,37 @@ def property_integrate(prop, mass, p_index=0, count=None, vol=None, vol_uniform=
                                          _ptr(n_used), _ptr(workspace),
                                          0 if workspace is None else workspace.numel(), _stream()),
            "aura_property_integrate")
+
+
+def voxel_grid(box_lo, box_hi, n_target):
+    """Sec. 3.2.1 (host only): s_voxel and the voxels per axis of one boundary box."""
+    lo, hi = _host(box_lo, np.float32), _host(box_hi, np.float32)
+    s, dims = C.c_float(0.0), np.zeros(3, np.int32)
+    _check(lib().aura_voxel_grid(_hptr(lo), _hptr(hi), n_target, C.byref(s), _hptr(dims)), "aura_voxel_grid")
+    return float(s.value), dims
+
+
+def voxel_workspace_bytes(box_lo, box_hi, n_target):
+    lo, hi = _host(box_lo, np.float32).reshape(-1, 3), _host(box_hi, np.float32).reshape(-1, 3)
+    out = C.c_size_t(0)
+    _check(lib().aura_voxel_workspace_bytes(_hptr(lo), _hptr(hi), lo.shape[0], n_target, C.byref(out)),
+           "aura_voxel_workspace_bytes")
+    return int(out.value)
+
+
+def voxel_downsample(xyz, box_lo, box_hi, n_target, out_xyz, out_offsets, out_count=None, voxel_of_point=None,
+                     pt_offsets=None, workspace=None):
+    """Sec. 3.2.1: out_xyz [capacity][3] f32, out_offsets [B+1] int32 (and out_count [capacity], voxel_of_point [N]
+    int32 when given) are filled in place; the boxes are host arrays [B][3]."""
+    xyz = _dev(xyz, torch.float32, "xyz")
+    lo, hi = _host(box_lo, np.float32).reshape(-1, 3), _host(box_hi, np.float32).reshape(-1, 3)
+    po = _host(pt_offsets, np.int64)
+    B = 1 if po is None else len(po) - 1
+    _check(lib().aura_voxel_downsample(_ptr(xyz), xyz.shape[0], _hptr(po), B, _hptr(lo), _hptr(hi), n_target,
+                                       _ptr(out_xyz), _ptr(out_count), 0 if out_xyz is None else out_xyz.shape[0],
+                                       out_offsets.data_ptr(), _ptr(voxel_of_point), _ptr(workspace),
+                                       0 if workspace is None else workspace.numel(), _stream()),
+           "aura_voxel_downsample")
 
 
 def select_views(views: "Views", params: "Params", xyz, normals, k, sel_view, sel_score=None, sel_mask=None, n_sel=None,

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <cmath>
 #include <vector>
 
 #include "../../include/aura_fuse.h"
@@ -491,6 +492,82 @@ aura_status_t aura_thickness_integrate(const float* scores, int64_t N, int32_t K
                                                      params->temperature, lambda, scale_factor, zeta, total, com, b_adap,
                                                      reinterpret_cast<long long*>(n_used), workspace,
                                                      static_cast<hipStream_t>(stream)));
+}
+
+aura_status_t aura_voxel_grid(const float* box_lo, const float* box_hi, int32_t n_target, float* s_voxel, int32_t* dims) {
+  if (!box_lo || !box_hi || !s_voxel || !dims) return AURA_ERR_NULL;
+  if (n_target < 1) return AURA_ERR_SHAPE;
+  for (int a = 0; a < 3; ++a)
+    if (!(box_hi[a] >= box_lo[a])) return AURA_ERR_SHAPE;
+  int d[3];
+  if (!aura::voxel_grid(box_lo, box_hi, n_target, s_voxel, d)) return AURA_ERR_UNSUPPORTED;
+  dims[0] = d[0]; dims[1] = d[1]; dims[2] = d[2];
+  return AURA_OK;
+}
+
+// Grids of the objects of a call; total = cubes of all objects, each object padded as the kernels lay them out.
+static aura_status_t voxel_objects(const float* box_lo, const float* box_hi, int32_t B, int32_t n_target,
+                                   std::vector<aura::VoxObj>* objs, long long* total, float* max_abs) {
+  if (!box_lo || !box_hi) return AURA_ERR_NULL;
+  if (B < 1 || n_target < 1) return AURA_ERR_SHAPE;
+  if (B > aura::kMaxObjPerLaunch) return AURA_ERR_UNSUPPORTED;
+  objs->assign((size_t)B, aura::VoxObj{});
+  *total = 0;
+  *max_abs = 0.0f;
+  for (int b = 0; b < B; ++b) {
+    aura::VoxObj& o = (*objs)[(size_t)b];
+    for (int a = 0; a < 3; ++a) {
+      const float lo = box_lo[3 * b + a], hi = box_hi[3 * b + a];
+      if (!(hi >= lo)) return AURA_ERR_SHAPE;
+      o.lo[a] = lo;
+      // points up to one box extent outside the box still sum without overflow
+      const float reach = std::max(std::fabs(lo - (hi - lo)), std::fabs(hi + (hi - lo)));
+      *max_abs = std::max(*max_abs, reach);
+    }
+    if (!aura::voxel_grid(box_lo + 3 * b, box_hi + 3 * b, n_target, &o.s, o.dims)) return AURA_ERR_UNSUPPORTED;
+    *total += aura::voxel_padded_cells((long long)o.dims[0] * o.dims[1] * o.dims[2]);
+    if (*total > aura::kVoxelMaxCells) return AURA_ERR_UNSUPPORTED;
+  }
+  return AURA_OK;
+}
+
+aura_status_t aura_voxel_workspace_bytes(const float* box_lo, const float* box_hi, int32_t B, int32_t n_target,
+                                         size_t* bytes) {
+  if (!bytes) return AURA_ERR_NULL;
+  *bytes = 0;
+  std::vector<aura::VoxObj> objs;
+  long long total = 0;
+  float max_abs = 0.0f;
+  const aura_status_t s = voxel_objects(box_lo, box_hi, B, n_target, &objs, &total, &max_abs);
+  if (s != AURA_OK) return s;
+  *bytes = aura::voxel_workspace_bytes(total);
+  return AURA_OK;
+}
+
+aura_status_t aura_voxel_downsample(const float* xyz, int64_t N, const int64_t* pt_offsets, int32_t B,
+                                    const float* box_lo, const float* box_hi, int32_t n_target, float* out_xyz,
+                                    int32_t* out_count, int64_t out_capacity, int32_t* out_offsets,
+                                    int32_t* voxel_of_point, void* workspace, size_t workspace_bytes, void* stream) {
+  if (N < 0 || out_capacity < 0) return AURA_ERR_SHAPE;
+  if (!pt_offsets && B != 1) return AURA_ERR_NULL;
+  std::vector<aura::VoxObj> objs;
+  long long total = 0;
+  float max_abs = 0.0f;
+  const aura_status_t s = voxel_objects(box_lo, box_hi, B, n_target, &objs, &total, &max_abs);
+  if (s != AURA_OK) return s;
+  for (int b = 0; b < B; ++b) {
+    const int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
+    if (p1 < p0 || p0 < 0 || p1 > N || p1 - p0 > 0x7fffffff) return AURA_ERR_SHAPE;
+    if ((b == 0 && p0 != 0) || (b == B - 1 && p1 != N)) return AURA_ERR_SHAPE;
+    objs[(size_t)b].pt_begin = p0;
+    objs[(size_t)b].n_pts = (int)(p1 - p0);
+  }
+  if (!out_offsets || (out_capacity > 0 && !out_xyz) || (N > 0 && !xyz)) return AURA_ERR_NULL;
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < aura::voxel_workspace_bytes(total))
+    return AURA_ERR_WORKSPACE;
+  return hip_status(aura::launch_voxel_downsample(xyz, objs.data(), B, max_abs, N, out_xyz, out_count, out_capacity,
+                                                  out_offsets, voxel_of_point, workspace,
+                                                  static_cast<hipStream_t>(stream)));
 }
 
 aura_status_t aura_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {

@@ -69,6 +69,22 @@ hipError_t launch_thickness_integrate(const float* scores, int K, const float* y
                                       float lambda, float scale_factor, float* zeta, float* total, float* com,
                                       float* b_adap, long long* n_used, void* workspace, hipStream_t stream);
 
+// Sec. 3.2.1, adaptive voxel down-sampling (voxel_downsample.hip).
+constexpr long long kVoxelMaxCells = 1ll << 24;   // cubes of all objects of a call, each object padded to 2048
+struct VoxObj {
+  long long pt_begin;
+  int n_pts;
+  float lo[3];
+  float s;
+  int dims[3];
+};
+bool voxel_grid(const float* lo, const float* hi, int n_target, float* s_out, int* dims);
+long long voxel_padded_cells(long long cells);
+size_t voxel_workspace_bytes(long long padded_cells);
+hipError_t launch_voxel_downsample(const float* xyz, const VoxObj* objs, int B, float max_abs, long long n_points,
+                                   float* out_xyz, int* out_count, long long capacity, int* out_offsets,
+                                   int* voxel_of_point, void* workspace, hipStream_t stream);
+
 // Sec. 3.4.1 Eq. 5 (knn_densify.hip).
 bool knn_supported(int Ns, int K, int k, int P);
 size_t knn_workspace_bytes(int D, int Ns);

@@ -216,6 +216,29 @@ def test_argument_validation_returns_status_codes(B):
     assert fsel(v=_views(B, **half), ws=C.c_void_p(0x1000), wsb=64) == -5
     assert fsel(N=0, xyz=None, mask=None, fused=None) == 0
 
+    box = lambda lo, hi: (hp(np.array(lo, np.float32)), hp(np.array(hi, np.float32)))
+    keep = [np.array([0, 0, 0], np.float32), np.array([2, 2, 2], np.float32), np.array([2, 2, 1], np.float32)]
+    s_out, dims = C.c_float(0), np.zeros(3, np.int32)
+    assert L.aura_voxel_grid(hp(keep[0]), hp(keep[1]), 8, C.byref(s_out), hp(dims)) == 0
+    assert s_out.value == 1.0 and list(dims) == [3, 3, 3]
+    assert L.aura_voxel_grid(None, hp(keep[1]), 8, C.byref(s_out), hp(dims)) == -1
+    assert L.aura_voxel_grid(hp(keep[1]), hp(keep[2]), 8, C.byref(s_out), hp(dims)) == -2   # upper corner below lower
+    assert L.aura_voxel_grid(hp(keep[0]), hp(keep[1]), 0, C.byref(s_out), hp(dims)) == -2
+    big = np.array([1e4, 1e4, 1e-20], np.float32)
+    assert L.aura_voxel_grid(hp(keep[0]), hp(big), 150, C.byref(s_out), hp(dims)) == -7        # too many voxels
+    nb = C.c_size_t(0)
+    assert L.aura_voxel_workspace_bytes(hp(keep[0]), hp(keep[1]), 1, 8, C.byref(nb)) == 0
+    assert nb.value == 2048 * 32 + 2048 * 4 + 256 + 256
+    assert L.aura_voxel_workspace_bytes(hp(keep[0]), hp(keep[1]), 65, 8, C.byref(nb)) == -7    # more than 64 objects
+    vd = lambda N=10, xyz=fake, lo=keep[0], hi=keep[1], nt=8, out=fake, cap=10, offs=fake, po_=None, B_=1, \
+        ws=C.c_void_p(0x1000), wsb=1 << 20: L.aura_voxel_downsample(xyz, N, po_, B_, hp(lo), hp(hi), nt, out, None, cap, offs,
+                                                                  None, ws, wsb, None)
+    assert vd(xyz=None) == -1 and vd(out=None) == -1 and vd(offs=None) == -1
+    assert vd(N=-1) == -2 and vd(nt=0) == -2 and vd(cap=-1) == -2
+    assert vd(lo=keep[1], hi=keep[2]) == -2
+    assert vd(B_=2) == -1
+    assert vd(ws=None) == -5 and vd(wsb=16) == -5 and vd(ws=C.c_void_p(0x1010)) == -5
+
     ti = lambda N=10, K=8, P=2, pi=0, scores=fake, y=fake, theta=fake, xyz=fake, po_=None, B_=1, blen=None, par=p, lam=0.6, \
         scale=1.0, total=fake, ws=C.c_void_p(0x1000), wsb=1 << 20: L.aura_thickness_integrate(
             scores, N, K, y, P, pi, theta, xyz, None, po_, B_, blen, C.byref(par) if par is not None else None, lam, scale,
