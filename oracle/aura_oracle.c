@@ -23,6 +23,8 @@
  *                                          down-sampling to the mean position per occupied voxel)
  *   view importance-based filtering        Sec. 3.2.2 (S_dist, S_angle, S_total, top-k views per point) and the
  *                                          mean over the kept views of Sec. 3.2.3
+ *   multi-scale patches                    Sec. 3.2.3 (squares of several sizes around the projection in each kept view,
+ *                                          resampled into one batch for the encoder; the encoder itself is not here)
  *   thickness-based integration            Sec. 3.4.2 (voxel b_adap x b_adap x theta per point, correction
  *                                          factor lambda) and the centre of mass it gives
  *
@@ -757,5 +759,72 @@ int orc_voxel_downsample(const float* xyz, int64_t N, const int64_t* pt_offsets,
     free(sum); free(cnt); free(slot); free(cell_of);
   }
   out_offsets[B] = total;
+  return 0;
+}
+
+/* ---------------------------------------------------------------- exported: Sec. 3.2.3, multi-scale patches
+ * For point s, each of its kept views v (sel_view, index within the object; -1: none) and each scale l (side of
+ * the square in pixels, e.g. 20, 40, 60): the patch P_v^(l)(s) is the l x l square of view v's image centred at the
+ * projection pi(s, v) = (u, v), resampled to R x R for the encoder.  The image is read as a continuous field
+ * (bilinear between pixel centres at integer + 0.5, the border pixel repeated outside the image); output pixel
+ * (i, j) samples it at
+ *     x = u - l/2 + (j + 0.5) l / R,   y = v - l/2 + (i + 0.5) l / R
+ * and is stored channel-first as (value / 255 - mean[c]) * inv_std[c].
+ * images [n_views][H][W][3] uint8; out [M][k][L][3][R][R] double; valid [M][k] or NULL.
+ * The projection is the fp32 chain of project_f32; everything after it is double.                          */
+int orc_patch_batch(const float* cam, int n_views, int H, int W, const uint8_t* images, const float* xyz, int64_t M,
+                    const int64_t* pt_offsets, const int32_t* view_offsets, int B, const int32_t* sel_view, int k,
+                    const float* scales, int L, int R, const float* mean, const float* inv_std, double* out,
+                    uint8_t* valid) {
+  if (!cam || !images || !xyz || !sel_view || !scales || !out) return -1;
+  if (M < 0 || n_views < 1 || H < 1 || W < 1 || k < 1 || L < 1 || R < 1) return -2;
+  int rc = check_csr(M, n_views, pt_offsets, view_offsets, B);
+  if (rc) return rc;
+  const int64_t plane = (int64_t)R * R;
+  for (int b = 0; b < B; ++b) {
+    const int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : M;
+    const int v0 = view_offsets ? view_offsets[b] : 0, v1 = view_offsets ? view_offsets[b + 1] : n_views;
+#pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t s = p0; s < p1; ++s) {
+      for (int r = 0; r < k; ++r) {
+        const int sv = sel_view[s * k + r];
+        double* o = out + (s * k + r) * (int64_t)L * 3 * plane;
+        const int ok = sv >= 0 && sv < v1 - v0;
+        if (valid) valid[s * k + r] = (uint8_t)ok;
+        if (!ok) {
+          for (int64_t e = 0; e < (int64_t)L * 3 * plane; ++e) o[e] = 0.0;
+          continue;
+        }
+        const uint8_t* img = images + (int64_t)(v0 + sv) * H * W * 3;
+        float uf, vf, zf;
+        project_f32(cam + (int64_t)(v0 + sv) * 16, xyz + 3 * s, &uf, &vf, &zf);
+        for (int l = 0; l < L; ++l) {
+          const double side = (double)scales[l];
+          for (int i = 0; i < R; ++i) {
+            for (int j = 0; j < R; ++j) {
+              const double x = (double)uf - 0.5 * side + ((double)j + 0.5) * side / (double)R;
+              const double y = (double)vf - 0.5 * side + ((double)i + 0.5) * side / (double)R;
+              /* pixel centres at integer + 0.5: texel coordinates g = x - 0.5, clamped to the image */
+              double gx = x - 0.5, gy = y - 0.5;
+              if (gx < 0.0) gx = 0.0;
+              if (gx > (double)(W - 1)) gx = (double)(W - 1);
+              if (gy < 0.0) gy = 0.0;
+              if (gy > (double)(H - 1)) gy = (double)(H - 1);
+              const int x0 = (int)floor(gx), y0 = (int)floor(gy);
+              const int x1 = x0 + 1 < W ? x0 + 1 : W - 1, y1 = y0 + 1 < H ? y0 + 1 : H - 1;
+              const double ax = gx - (double)x0, ay = gy - (double)y0;
+              for (int c = 0; c < 3; ++c) {
+                const double t00 = img[((int64_t)y0 * W + x0) * 3 + c], t01 = img[((int64_t)y0 * W + x1) * 3 + c];
+                const double t10 = img[((int64_t)y1 * W + x0) * 3 + c], t11 = img[((int64_t)y1 * W + x1) * 3 + c];
+                const double val = (1.0 - ay) * ((1.0 - ax) * t00 + ax * t01) + ay * ((1.0 - ax) * t10 + ax * t11);
+                const double mu = mean ? (double)mean[c] : 0.0, is = inv_std ? (double)inv_std[c] : 1.0;
+                o[((int64_t)l * 3 + c) * plane + (int64_t)i * R + j] = (val / 255.0 - mu) * is;
+              }
+            }
+          }
+        }
+      }
+    }
+  }
   return 0;
 }

@@ -302,3 +302,25 @@ def voxel_downsample(xyz, n_target, box_lo=None, box_hi=None, pt_offsets=None, c
     M = min(int(out_offsets[B]), cap)
     return {"xyz": out_xyz[:M], "count": out_count[:M], "offsets": out_offsets, "voxel_of_point": voxel_of_point[:N],
             "box_lo": lo, "box_hi": hi}
+
+
+def patch_batch(cam, images, xyz, sel_view, scales, R, mean=None, inv_std=None, pt_offsets=None, view_offsets=None):
+    """Sec. 3.2.3: the multi-scale patches of every (point, kept view) as one batch [M][k][L][3][R][R]."""
+    cam = _f32(cam).reshape(-1, 16)
+    images = np.ascontiguousarray(images, dtype=np.uint8)
+    n_views, H, W, _ = images.shape
+    xyz = _f32(xyz).reshape(-1, 3)
+    M = xyz.shape[0]
+    sel_view = np.ascontiguousarray(sel_view, dtype=np.int32).reshape(M, -1)
+    k = sel_view.shape[1]
+    scales = _f32(scales).reshape(-1)
+    L = len(scales)
+    po, vo, B = _csr(M, n_views, pt_offsets, view_offsets)
+    mean, inv_std = _f32(mean), _f32(inv_std)
+    out = np.zeros((M, k, L, 3, R, R), np.float64)
+    valid = np.zeros((M, k), np.uint8)
+    rc = lib().orc_patch_batch(_p(cam), C.c_int(n_views), C.c_int(H), C.c_int(W), _p(images), _p(xyz), C.c_int64(M),
+                               _p(po), _p(vo), C.c_int(B), _p(sel_view), C.c_int(k), _p(scales), C.c_int(L), C.c_int(R),
+                               _p(mean), _p(inv_std), _p(out), _p(valid))
+    _check(rc, "patch_batch")
+    return {"patches": out, "valid": valid}
