@@ -157,6 +157,38 @@ def time_downsample(torch, d, s, reps, n_target=150):
             "sampled_points": int(out_offsets[-1].item())}
 
 
+def time_patches(torch, d, s, reps, M=150, k=3, R=224, half=False):
+    """Sec. 3.2.3: the encoder batch of M source points x k views x 3 scales (20, 40, 60 pixels) at R x R.  HBM bound on
+    writing the batch."""
+    import numpy as np
+    import paper_2511_03126_amd as aura
+    from workloads.scenes import synthetic_images, synthetic_normals
+    images = torch.from_numpy(synthetic_images(s.n_views, s.H, s.W, s.meta["seed"])).to(d.dev)
+    idx = np.linspace(0, int(s.pt_offsets[1]) - 1, M).astype(np.int64)
+    xyz = d.xyz[torch.from_numpy(idx).to(d.dev)].contiguous()
+    nrm = torch.from_numpy(synthetic_normals(s.xyz, s.pt_offsets, s.meta["seed"])[idx]).to(d.dev)
+    v1 = int(s.view_offsets[1])
+    views = aura.Views(cam=d.views.cam[:v1], depth=d.views.depth[:v1])
+    sel = torch.empty((M, k), dtype=torch.int32, device=d.dev)
+    aura.select_views(views, d.params, xyz, nrm, k, sel)
+    out = torch.empty((M, k, 3, 3, R, R), dtype=torch.float16 if half else torch.float32, device=d.dev)
+    run = lambda: aura.patch_batch(views.cam, images[:v1], xyz, sel, [20.0, 40.0, 60.0], out)
+    for _ in range(2):
+        run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / reps
+    nbytes = out.numel() * out.element_size()
+    gbps = nbytes / (ms * 1e-3) / 1e9
+    return {"call": "aura_patch_batch", "patches": M * k * 3, "resolution": R, "out_dtype": "f16" if half else "f32",
+            "ms": ms, "bound": "hbm", "algorithmic_bytes": nbytes, "achieved": gbps, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+            "frac": gbps / HBM_PEAK_GBPS}
+
+
 def cpu_baseline(scene, seconds_target=15.0):
     """The oracle, as it stands, on a contiguous sample of the scene's first object."""
     import numpy as np
@@ -291,7 +323,9 @@ def main():
         extras = {"densify": time_densify(torch, d, s, max(args.steps // 2, 5)),
                   "thickness_integrate": time_thickness(torch, d, s, max(args.steps // 2, 5)),
                   "view_selection": time_selection(torch, d, s, max(args.steps // 2, 5)),
-                  "voxel_downsample": time_downsample(torch, d, s, max(args.steps // 2, 5))}
+                  "voxel_downsample": time_downsample(torch, d, s, max(args.steps // 2, 5)),
+                  "patch_batch": time_patches(torch, d, s, max(args.steps // 2, 5)),
+                  "patch_batch_f16": time_patches(torch, d, s, max(args.steps // 2, 5), half=True)}
     out = {
         "metric": "fused point-views/sec", "value": pv / (ms_per_step * 1e-3), "unit": "point-views/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,

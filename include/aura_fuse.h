@@ -11,6 +11,7 @@
  *   aura_voxel_downsample     Sec. 3.2.1: adaptive voxel size and voxel down-sampling of the point cloud
  *   aura_select_views         Sec. 3.2.2: view importance scores and the top-k views per point
  *   aura_fuse_selected        Sec. 3.2.3: Eq. 2 over the kept views only
+ *   aura_patch_batch          Sec. 3.2.3: the multi-scale image patches of the kept views as one batch for the encoder
  *   aura_fuse_scores          the two calls above in one (Eq. 2, then Sec. 3.4.1 / Eq. 4)
  *   aura_knn_densify          Sec. 3.4.1 Eq. 5: feature-space k-NN densification, then Eq. 4
  *   aura_property_integrate   Sec. 3.4.2: voxel integration over volumes (mass)
@@ -371,6 +372,30 @@ aura_status_t aura_fuse_selected(const aura_views_t* views, const aura_params_t*
                                  const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
                                  const uint8_t* sel_mask, int32_t mask_pitch, float* fused, int32_t* count,
                                  void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sec. 3.2.3 "Multi-scale Feature Fusion": the patches P_v^(l)(s).  For every source point s, each of its kept views
+ * (sel_view, as written by aura_select_views: index within the object, -1 = none) and each scale l, the l x l pixel
+ * square of the view's image centred at the projection pi(s, v) = (u, v) is resampled to R x R and written
+ * channel-first into one batch for the image encoder (the paper uses three scales of 20, 40 and 60 pixels; the
+ * encoder is not part of this library).  The image is read as a continuous field: bilinear between pixel centres at
+ * integer + 0.5, the border pixel repeated outside the image; output pixel (i, j) samples it at
+ *     x = u - l/2 + (j + 0.5) l / R,    y = v - l/2 + (i + 0.5) l / R
+ * and stores (value / 255 - mean[c]) * inv_std[c].  A missing view gives a patch of zeros and valid = 0.
+ *
+ *   cam    [device] [n_views][16] fp32 as in aura_views_t           images [device] [n_views][H][W][3] uint8
+ *   xyz    [device] [M][3] fp32             pt_offsets, view_offsets [host] as in aura_project_visibility
+ *   sel_view [device] [M][k] int32          scales [host] [L] fp32 (> 0)
+ *   mean, inv_std [host] [3] fp32 or NULL (0 and 1)
+ *   out    [device] [M][k][L][3][R][R] of out_dtype (AURA_F32 or AURA_F16)       valid [device] [M][k] uint8 or NULL
+ * Limits: L <= 8; M_b * k * L * ceil(R / 32) < 2^31 per object.
+ * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_DTYPE, AURA_ERR_ALIGN, AURA_ERR_UNSUPPORTED, AURA_ERR_HIP.
+ */
+aura_status_t aura_patch_batch(const float* cam, int32_t n_views, int32_t H, int32_t W, const uint8_t* images,
+                               const float* xyz, int64_t M, const int64_t* pt_offsets, const int32_t* view_offsets,
+                               int32_t B, const int32_t* sel_view, int32_t k, const float* scales, int32_t L, int32_t R,
+                               const float* mean, const float* inv_std, void* out, int32_t out_dtype, uint8_t* valid,
+                               void* stream);
 
 /*
  * Sec. 3.4.2, thickness-based integration.  Every point s of object b is the centre of a voxel

@@ -89,6 +89,9 @@ def lib():
         L.aura_voxel_workspace_bytes.argtypes = [vp, vp, i32, i32, C.POINTER(C.c_size_t)]
         L.aura_voxel_downsample.restype = C.c_int32
         L.aura_voxel_downsample.argtypes = [vp, i64, vp, i32, vp, vp, i32, vp, vp, i64, vp, vp, vp, C.c_size_t, vp]
+        L.aura_patch_batch.restype = C.c_int32
+        L.aura_patch_batch.argtypes = [vp, i32, i32, i32, vp, vp, i64, vp, vp, i32, vp, i32, vp, i32, i32, vp, vp, vp, i32,
+                                       vp, vp]
         L.aura_select_views.restype = C.c_int32
         L.aura_select_views.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, vp, i64, vp, vp, i32, i32, vp, vp, vp,
                                         i32, vp, vp]
@@ -312,6 +315,25 @@ def voxel_downsample(xyz, box_lo, box_hi, n_target, out_xyz, out_offsets, out_co
                                        out_offsets.data_ptr(), _ptr(voxel_of_point), _ptr(workspace),
                                        0 if workspace is None else workspace.numel(), _stream()),
            "aura_voxel_downsample")
+
+
+def patch_batch(cam, images, xyz, sel_view, scales, out, mean=None, inv_std=None, valid=None, pt_offsets=None,
+                view_offsets=None):
+    """Sec. 3.2.3: out [M][k][L][3][R][R] (float32 or float16) and valid [M][k] uint8 are filled in place; images
+    [V][H][W][3] uint8 and cam [V][16] f32 are device tensors, scales / mean / inv_std host arrays."""
+    cam = _dev(cam, torch.float32, "cam")
+    images = _dev(images, torch.uint8, "images")
+    xyz = _dev(xyz, torch.float32, "xyz")
+    sel_view = _dev(sel_view, torch.int32, "sel_view")
+    if not (out.is_cuda and out.is_contiguous() and out.dtype in (torch.float32, torch.float16)):
+        raise TypeError("out must be a contiguous device tensor of float32 or float16")
+    sc, mu, isd = _host(scales, np.float32), _host(mean, np.float32), _host(inv_std, np.float32)
+    po, vo, B = _objects(pt_offsets, view_offsets)
+    V, H, W, _ = images.shape
+    M, k = sel_view.shape
+    _check(lib().aura_patch_batch(cam.data_ptr(), V, H, W, images.data_ptr(), _ptr(xyz), M, _hptr(po), _hptr(vo), B,
+                                  sel_view.data_ptr(), k, _hptr(sc), len(sc), out.shape[-1], _hptr(mu), _hptr(isd),
+                                  out.data_ptr(), _TORCH_DTYPE[out.dtype], _ptr(valid), _stream()), "aura_patch_batch")
 
 
 def select_views(views: "Views", params: "Params", xyz, normals, k, sel_view, sel_score=None, sel_mask=None, n_sel=None,

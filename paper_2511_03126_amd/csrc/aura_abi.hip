@@ -494,6 +494,37 @@ aura_status_t aura_thickness_integrate(const float* scores, int64_t N, int32_t K
                                                      static_cast<hipStream_t>(stream)));
 }
 
+aura_status_t aura_patch_batch(const float* cam, int32_t n_views, int32_t H, int32_t W, const uint8_t* images,
+                               const float* xyz, int64_t M, const int64_t* pt_offsets, const int32_t* view_offsets,
+                               int32_t B, const int32_t* sel_view, int32_t k, const float* scales, int32_t L, int32_t R,
+                               const float* mean, const float* inv_std, void* out, int32_t out_dtype, uint8_t* valid,
+                               void* stream) {
+  if (M < 0 || n_views < 1 || H < 1 || W < 1 || k < 1 || L < 1 || R < 1) return AURA_ERR_SHAPE;
+  if ((int64_t)H * W * 3 > 0x7fffffff) return AURA_ERR_SHAPE;
+  if (out_dtype != AURA_F32 && out_dtype != AURA_F16) return out_dtype == AURA_BF16 ? AURA_ERR_UNSUPPORTED : AURA_ERR_DTYPE;
+  if (!scales) return AURA_ERR_NULL;
+  if (!aura::patch_batch_supported(L)) return AURA_ERR_UNSUPPORTED;
+  for (int l = 0; l < L; ++l)
+    if (!(scales[l] > 0.0f)) return AURA_ERR_SHAPE;
+  if (inv_std)
+    for (int c = 0; c < 3; ++c)
+      if (!(inv_std[c] == inv_std[c])) return AURA_ERR_SHAPE;
+  std::vector<aura::ObjRange> objs;
+  int max_views = 0;
+  const aura_status_t s = check_objects(M, n_views, pt_offsets, view_offsets, B, &objs, &max_views);
+  if (s != AURA_OK) return s;
+  if (M == 0) return AURA_OK;
+  if (!cam || !images || !xyz || !sel_view || !out) return AURA_ERR_NULL;
+  if (!aligned(out, out_dtype == AURA_F16 ? 2 : 4)) return AURA_ERR_ALIGN;
+  for (const aura::ObjRange& o : objs)
+    if ((int64_t)o.n_pts * k * L * ((R + 31) / 32) > 0x7fffffff) return AURA_ERR_UNSUPPORTED;   // one workgroup per 32 rows
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts, int) {
+    return aura::launch_patch_batch(cam, images, H, W, xyz, sel_view, k, scales, L, R, mean, inv_std, out,
+                                    out_dtype == AURA_F16, valid, tab, n, max_pts, st);
+  });
+}
+
 aura_status_t aura_voxel_grid(const float* box_lo, const float* box_hi, int32_t n_target, float* s_voxel, int32_t* dims) {
   if (!box_lo || !box_hi || !s_voxel || !dims) return AURA_ERR_NULL;
   if (n_target < 1) return AURA_ERR_SHAPE;

@@ -85,6 +85,13 @@ hipError_t launch_voxel_downsample(const float* xyz, const VoxObj* objs, int B, 
                                    float* out_xyz, int* out_count, long long capacity, int* out_offsets,
                                    int* voxel_of_point, void* workspace, hipStream_t stream);
 
+// Sec. 3.2.3, multi-scale patches for the image encoder (patch_batch.hip).
+bool patch_batch_supported(int L);
+hipError_t launch_patch_batch(const float* cam, const uint8_t* images, int H, int W, const float* xyz, const int* sel_view,
+                              int k, const float* scales, int L, int R, const float* mean, const float* inv_std,
+                              void* out, bool half, uint8_t* valid, const ObjTable& tab, int n_obj, int max_pts,
+                              hipStream_t stream);
+
 // Sec. 3.4.1 Eq. 5 (knn_densify.hip).
 bool knn_supported(int Ns, int K, int k, int P);
 size_t knn_workspace_bytes(int D, int Ns);

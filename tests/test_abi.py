@@ -239,6 +239,20 @@ def test_argument_validation_returns_status_codes(B):
     assert vd(B_=2) == -1
     assert vd(ws=None) == -5 and vd(wsb=16) == -5 and vd(ws=C.c_void_p(0x1010)) == -5
 
+    sc3 = np.array([20, 40, 60], np.float32)
+    pb = lambda cam=fake, V=4, H=32, W=32, img=fake, xyz=fake, M=10, sel=fake, k=3, sc=sc3, L=3, R=16, out=fake, dt=B.F32: \
+        L_.aura_patch_batch(cam, V, H, W, img, xyz, M, None, None, 1, sel, k, None if sc is None else hp(sc), L, R, None, None,
+                            out, dt, None, None)
+    L_ = L
+    assert pb(cam=None) == -1 and pb(img=None) == -1 and pb(xyz=None) == -1 and pb(sel=None) == -1 and pb(out=None) == -1
+    assert pb(sc=None) == -1
+    assert pb(V=0) == -2 and pb(k=0) == -2 and pb(L=0) == -2 and pb(R=0) == -2 and pb(M=-1) == -2
+    assert pb(sc=np.array([20, 0, 60], np.float32)) == -2
+    assert pb(L=9, sc=np.ones(9, np.float32)) == -7
+    assert pb(dt=B.BF16) == -7 and pb(dt=9) == -3
+    assert pb(out=C.c_void_p(0x1002)) == -4
+    assert pb(M=0, xyz=None, sel=None, out=None) == 0
+
     ti = lambda N=10, K=8, P=2, pi=0, scores=fake, y=fake, theta=fake, xyz=fake, po_=None, B_=1, blen=None, par=p, lam=0.6, \
         scale=1.0, total=fake, ws=C.c_void_p(0x1000), wsb=1 << 20: L.aura_thickness_integrate(
             scores, N, K, y, P, pi, theta, xyz, None, po_, B_, blen, C.byref(par) if par is not None else None, lam, scale,

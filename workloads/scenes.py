@@ -361,6 +361,22 @@ def material_thickness(K: int, seed: int) -> np.ndarray:
     return rng.uniform(0.002, 0.05, K).astype(np.float32)
 
 
+def synthetic_images(n_views: int, H: int, W: int, seed: int) -> np.ndarray:
+    """[n_views][H][W][3] uint8 pictures: smooth colour gradients and blobs plus pixel noise (stand in for the RGB
+    captures that the patches of Sec. 3.2.3 are cut from)."""
+    rng = np.random.default_rng([seed, 55])
+    yy, xx = np.mgrid[0:H, 0:W].astype(np.float32)
+    out = np.empty((n_views, H, W, 3), np.uint8)
+    for v in range(n_views):
+        img = np.empty((H, W, 3), np.float32)
+        for c in range(3):
+            fx, fy, ph = rng.uniform(0.01, 0.08, 2).tolist() + [rng.uniform(0, 6.28)]
+            img[..., c] = 128 + 70 * np.sin(fx * xx + fy * yy + ph) + 30 * np.sin(3.1 * fx * yy - 2.3 * fy * xx)
+        img += rng.normal(0, 12, img.shape).astype(np.float32)
+        out[v] = np.clip(np.rint(img), 0, 255).astype(np.uint8)
+    return out
+
+
 def synthetic_normals(xyz: np.ndarray, pt_offsets: np.ndarray, seed: int, noise: float = 0.2) -> np.ndarray:
     """Unit "outward" normals for a scene's points: the direction from the object's centroid to the point, perturbed
     by Gaussian noise and renormalised (stands in for normals estimated from the reconstructed cloud)."""
