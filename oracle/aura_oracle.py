@@ -2,8 +2,10 @@
 
 TEST INFRASTRUCTURE ONLY: imported by tests/, by the smoke check and by the
 benchmark's cpu_baseline leg.  Nothing here touches the GPU library, and the GPU
-library never imports this module.  Arrays in, numpy arrays out; all arithmetic
-is in the C file (see its header for the passages of the paper each part follows).
+library never imports this module.  Arrays in, numpy arrays out; the arithmetic
+is in the C file (see its header for the passages of the paper each part follows),
+except estimate_normals, which is written out here with numpy (float64 covariance,
+numpy.linalg.eigh).
 """
 from __future__ import annotations
 
@@ -324,3 +326,52 @@ def patch_batch(cam, images, xyz, sel_view, scales, R, mean=None, inv_std=None, 
                                _p(mean), _p(inv_std), _p(out), _p(valid))
     _check(rc, "patch_batch")
     return {"patches": out, "valid": valid}
+
+
+def estimate_normals(xyz, queries, centre, k, pt_offsets=None, q_offsets=None):
+    """Sec. 3.2.2 ("we begin by estimating normal vectors for the sampled sparse point cloud"): for every query the
+    plane through its k nearest points of the object's cloud, i.e. the eigenvector of the smallest eigenvalue of their
+    covariance, turned to point away from the object's centre.
+
+    Which points are nearest is decided in fp32 with one fixed operation order, d = (dx * dx + dy * dy) + dz * dz with
+    dx = p_x - q_x and every operation rounded to fp32 (numpy float32 arithmetic), and of equal distances the lower
+    index first, so that an fp32 implementation selects the same neighbours; means, covariance (numpy, float64) and the eigenvectors (numpy.linalg.eigh) are double.
+    Returns normals [M][3], the neighbour indices [M][k] (within the object, -1 beyond its size), the eigenvalues
+    [M][3] ascending, and the gap between the k-th distance and the next one."""
+    xyz = _f32(xyz).reshape(-1, 3)
+    queries = _f32(queries).reshape(-1, 3)
+    N, M = len(xyz), len(queries)
+    po = np.array([0, N], np.int64) if pt_offsets is None else np.asarray(pt_offsets, np.int64)
+    qo = np.array([0, M], np.int64) if q_offsets is None else np.asarray(q_offsets, np.int64)
+    B = len(po) - 1
+    centre = _f32(centre).reshape(B, 3)
+    normals = np.zeros((M, 3), np.float64)
+    nn = np.full((M, k), -1, np.int64)
+    evals = np.zeros((M, 3), np.float64)
+    gap = np.full(M, np.inf)
+    for b in range(B):
+        P = xyz[po[b]:po[b + 1]]
+        for m in range(int(qo[b]), int(qo[b + 1])):
+            q = queries[m]
+            if len(P) == 0:
+                continue
+            d = P - q                                                    # fp32 throughout
+            t = (d[:, 0] * d[:, 0] + d[:, 1] * d[:, 1]) + d[:, 2] * d[:, 2]
+            assert t.dtype == np.float32
+            order = np.argsort(t, kind="stable")
+            kk = min(k, len(P))
+            sel = order[:kk]
+            nn[m, :kk] = sel
+            if kk < len(P):
+                gap[m] = float(t[order[kk]]) - float(t[order[kk - 1]])
+            pts = P[sel].astype(np.float64)
+            c = pts.mean(0)
+            cov = (pts - c).T @ (pts - c) / kk
+            w, v = np.linalg.eigh(cov)
+            n = v[:, 0]
+            out = q.astype(np.float64) - centre[b].astype(np.float64)
+            if n @ out < 0:
+                n = -n
+            normals[m] = n
+            evals[m] = w
+    return {"normals": normals, "nn_idx": nn, "evals": evals, "gap": gap}
