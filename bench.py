@@ -189,6 +189,32 @@ def time_patches(torch, d, s, reps, M=150, k=3, R=224, half=False):
             "frac": gbps / HBM_PEAK_GBPS}
 
 
+def time_normals(torch, d, s, reps, n_target=150, k=30):
+    """Sec. 3.2.2: normals of the ~150 sampled points of the first object from their 30 nearest points of its cloud."""
+    import numpy as np
+    import paper_2511_03126_amd as aura
+    p1 = int(s.pt_offsets[1])
+    lo, hi = s.xyz[:p1].min(0, keepdims=True), s.xyz[:p1].max(0, keepdims=True)
+    cloud = d.xyz[:p1]
+    q = torch.empty((64 * n_target, 3), device=d.dev)
+    off = torch.empty(2, dtype=torch.int32, device=d.dev)
+    work = torch.empty(aura.voxel_workspace_bytes(lo, hi, n_target), dtype=torch.uint8, device=d.dev)
+    aura.voxel_downsample(cloud, lo, hi, n_target, q, off, workspace=work)
+    q = q[: int(off[1].item())].contiguous()
+    centre = s.xyz[:p1].mean(0, keepdims=True).astype(np.float32)
+    normals = torch.empty_like(q)
+    run = lambda: aura.estimate_normals(cloud, q, centre, k, normals)
+    for _ in range(2):
+        run()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    return {"call": "aura_estimate_normals", "queries": int(q.shape[0]), "cloud": p1, "k": k, "ms": e0.elapsed_time(e1) / reps}
+
+
 def cpu_baseline(scene, seconds_target=15.0):
     """The oracle, as it stands, on a contiguous sample of the scene's first object."""
     import numpy as np
@@ -324,6 +350,7 @@ def main():
                   "thickness_integrate": time_thickness(torch, d, s, max(args.steps // 2, 5)),
                   "view_selection": time_selection(torch, d, s, max(args.steps // 2, 5)),
                   "voxel_downsample": time_downsample(torch, d, s, max(args.steps // 2, 5)),
+                  "estimate_normals": time_normals(torch, d, s, max(args.steps // 2, 5)),
                   "patch_batch": time_patches(torch, d, s, max(args.steps // 2, 5)),
                   "patch_batch_f16": time_patches(torch, d, s, max(args.steps // 2, 5), half=True)}
     out = {

@@ -9,6 +9,7 @@
  *                             by the cosine similarity of Sec. 3.4.1)
  *   aura_material_scores      Sec. 3.4.1: similarity omega_k and the kernel regression of Eq. 4
  *   aura_voxel_downsample     Sec. 3.2.1: adaptive voxel size and voxel down-sampling of the point cloud
+ *   aura_estimate_normals     Sec. 3.2.2: normals of the sampled points (input of the view importance score)
  *   aura_select_views         Sec. 3.2.2: view importance scores and the top-k views per point
  *   aura_fuse_selected        Sec. 3.2.3: Eq. 2 over the kept views only
  *   aura_patch_batch          Sec. 3.2.3: the multi-scale image patches of the kept views as one batch for the encoder
@@ -335,6 +336,27 @@ aura_status_t aura_voxel_downsample(const float* xyz, int64_t N, const int64_t* 
                                     const float* box_lo, const float* box_hi, int32_t n_target, float* out_xyz,
                                     int32_t* out_count, int64_t out_capacity, int32_t* out_offsets,
                                     int32_t* voxel_of_point, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sec. 3.2.2: "we begin by estimating normal vectors for the sampled sparse point cloud".  For every query point q of
+ * object b: the k points of the object's cloud nearest to q; the normal is the unit eigenvector of the smallest
+ * eigenvalue of their covariance (the plane through them), with the sign that points away from centre[b]
+ * ("oriented outward"; when it is at right angles to q - centre the sign is arbitrary).  The paper names no
+ * neighbourhood size: k is an argument.
+ * Which points are nearest is decided on the fp32 distance d = (dx dx + dy dy) + dz dz, dx = p_x - q_x, every
+ * operation rounded to fp32; of equal distances the lower index first.  Sums, covariance and eigenvectors are fp64.
+ * An object with fewer than k points uses all of them; without points the normal is 0.
+ *
+ *   xyz [device] [N][3] fp32: the clouds          pt_offsets [host] [B+1] int64 or NULL (B == 1)
+ *   queries [device] [M][3] fp32                   q_offsets  [host] [B+1] int64 or NULL (with pt_offsets)
+ *   centre [host] [B][3] fp32: a point inside every object (e.g. the centroid of its cloud)
+ *   normals [device] [M][3] fp32                   evals [device] [M][3] fp32 or NULL: eigenvalues, ascending
+ * Limits: B <= 4096.
+ * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_UNSUPPORTED, AURA_ERR_HIP.
+ */
+aura_status_t aura_estimate_normals(const float* xyz, int64_t N, const int64_t* pt_offsets, const float* queries, int64_t M,
+                                    const int64_t* q_offsets, int32_t B, const float* centre, int32_t k, float* normals,
+                                    float* evals, void* stream);
 
 /*
  * Sec. 3.2.2 "View Importance-based Filtering".  For every visible pair (Eq. 1, as aura_project_visibility):

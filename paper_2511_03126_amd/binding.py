@@ -92,6 +92,8 @@ def lib():
         L.aura_patch_batch.restype = C.c_int32
         L.aura_patch_batch.argtypes = [vp, i32, i32, i32, vp, vp, i64, vp, vp, i32, vp, i32, vp, i32, i32, vp, vp, vp, i32,
                                        vp, vp]
+        L.aura_estimate_normals.restype = C.c_int32
+        L.aura_estimate_normals.argtypes = [vp, i64, vp, vp, i64, vp, i32, vp, i32, vp, vp, vp]
         L.aura_select_views.restype = C.c_int32
         L.aura_select_views.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, vp, i64, vp, vp, i32, i32, vp, vp, vp,
                                         i32, vp, vp]
@@ -334,6 +336,18 @@ def patch_batch(cam, images, xyz, sel_view, scales, out, mean=None, inv_std=None
     _check(lib().aura_patch_batch(cam.data_ptr(), V, H, W, images.data_ptr(), _ptr(xyz), M, _hptr(po), _hptr(vo), B,
                                   sel_view.data_ptr(), k, _hptr(sc), len(sc), out.shape[-1], _hptr(mu), _hptr(isd),
                                   out.data_ptr(), _TORCH_DTYPE[out.dtype], _ptr(valid), _stream()), "aura_patch_batch")
+
+
+def estimate_normals(xyz, queries, centre, k, normals, evals=None, pt_offsets=None, q_offsets=None):
+    """Sec. 3.2.2: normals [M][3] f32 (and evals [M][3] f32 when given) are filled in place; centre is a host array
+    [B][3]."""
+    xyz = _dev(xyz, torch.float32, "xyz")
+    queries = _dev(queries, torch.float32, "queries")
+    po, qo = _host(pt_offsets, np.int64), _host(q_offsets, np.int64)
+    B = 1 if po is None else len(po) - 1
+    ce = _host(centre, np.float32).reshape(B, 3)
+    _check(lib().aura_estimate_normals(_ptr(xyz), xyz.shape[0], _hptr(po), _ptr(queries), queries.shape[0], _hptr(qo), B,
+                                       _hptr(ce), k, normals.data_ptr(), _ptr(evals), _stream()), "aura_estimate_normals")
 
 
 def select_views(views: "Views", params: "Params", xyz, normals, k, sel_view, sel_score=None, sel_mask=None, n_sel=None,

@@ -494,6 +494,40 @@ aura_status_t aura_thickness_integrate(const float* scores, int64_t N, int32_t K
                                                      static_cast<hipStream_t>(stream)));
 }
 
+aura_status_t aura_estimate_normals(const float* xyz, int64_t N, const int64_t* pt_offsets, const float* queries, int64_t M,
+                                    const int64_t* q_offsets, int32_t B, const float* centre, int32_t k, float* normals,
+                                    float* evals, void* stream) {
+  if (N < 0 || M < 0 || B < 1 || k < 1) return AURA_ERR_SHAPE;
+  if ((pt_offsets == nullptr) != (q_offsets == nullptr)) return AURA_ERR_NULL;
+  if (!pt_offsets && B != 1) return AURA_ERR_NULL;
+  if (!centre) return AURA_ERR_NULL;
+  if (B > 4096) return AURA_ERR_UNSUPPORTED;
+  std::vector<aura::NrmObj> objs((size_t)B);
+  for (int b = 0; b < B; ++b) {
+    const int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
+    const int64_t q0 = q_offsets ? q_offsets[b] : 0, q1 = q_offsets ? q_offsets[b + 1] : M;
+    if (p1 < p0 || q1 < q0 || p0 < 0 || q0 < 0 || p1 > N || q1 > M) return AURA_ERR_SHAPE;
+    if (p1 - p0 > 0x7fffffff || q1 > 0x7fffffff) return AURA_ERR_SHAPE;
+    if (b == 0 && (p0 != 0 || q0 != 0)) return AURA_ERR_SHAPE;
+    if (b == B - 1 && (p1 != N || q1 != M)) return AURA_ERR_SHAPE;
+    aura::NrmObj& o = objs[(size_t)b];
+    o.pt_begin = p0; o.n_pts = (int)(p1 - p0); o.q_begin = (int)q0; o.n_q = (int)(q1 - q0);
+    for (int c = 0; c < 3; ++c) {
+      if (!(centre[3 * b + c] == centre[3 * b + c])) return AURA_ERR_SHAPE;
+      o.centre[c] = centre[3 * b + c];
+    }
+  }
+  if (M == 0) return AURA_OK;
+  if (!queries || !normals || (N > 0 && !xyz)) return AURA_ERR_NULL;
+  for (int base = 0; base < B; base += aura::kMaxObjPerLaunch) {
+    const int n = std::min(aura::kMaxObjPerLaunch, B - base);
+    const aura_status_t s = hip_status(aura::launch_estimate_normals(xyz, queries, objs.data() + base, n, k, normals, evals,
+                                                                     static_cast<hipStream_t>(stream)));
+    if (s != AURA_OK) return s;
+  }
+  return AURA_OK;
+}
+
 aura_status_t aura_patch_batch(const float* cam, int32_t n_views, int32_t H, int32_t W, const uint8_t* images,
                                const float* xyz, int64_t M, const int64_t* pt_offsets, const int32_t* view_offsets,
                                int32_t B, const int32_t* sel_view, int32_t k, const float* scales, int32_t L, int32_t R,

@@ -92,6 +92,17 @@ hipError_t launch_patch_batch(const float* cam, const uint8_t* images, int H, in
                               void* out, bool half, uint8_t* valid, const ObjTable& tab, int n_obj, int max_pts,
                               hipStream_t stream);
 
+// Sec. 3.2.2, normals of the sampled points (estimate_normals.hip).
+struct NrmObj {
+  long long pt_begin;
+  int n_pts;
+  int q_begin;
+  int n_q;
+  float centre[3];
+};
+hipError_t launch_estimate_normals(const float* xyz, const float* queries, const NrmObj* objs, int n_obj, int k,
+                                   float* normals, float* evals, hipStream_t stream);
+
 // Sec. 3.4.1 Eq. 5 (knn_densify.hip).
 bool knn_supported(int Ns, int K, int k, int P);
 size_t knn_workspace_bytes(int D, int Ns);

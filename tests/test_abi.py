@@ -239,6 +239,19 @@ def test_argument_validation_returns_status_codes(B):
     assert vd(B_=2) == -1
     assert vd(ws=None) == -5 and vd(wsb=16) == -5 and vd(ws=C.c_void_p(0x1010)) == -5
 
+    ctr = np.zeros((2, 3), np.float32)
+    qo2 = np.array([0, 1, 3], np.int64)
+    en = lambda xyz=fake, N=10, po_=None, q=fake, M=3, qo_=None, B_=1, c=ctr, k=8, nrm=fake: L.aura_estimate_normals(
+        xyz, N, po_, q, M, qo_, B_, None if c is None else hp(c), k, nrm, None, None)
+    assert en(xyz=None) == -1 and en(q=None) == -1 and en(nrm=None) == -1 and en(c=None) == -1
+    assert en(k=0) == -2 and en(N=-1) == -2 and en(M=-1) == -2
+    assert en(B_=2) == -1                                                  # two objects need both offset arrays
+    assert en(po_=hp(po), B_=2) == -1
+    assert en(po_=hp(po), qo_=hp(qo2), B_=2, N=11) == -2
+    assert en(po_=hp(po), qo_=hp(qo2), B_=2, M=4) == -2
+    assert en(c=np.full((1, 3), np.nan, np.float32)) == -2
+    assert en(M=0, q=None, nrm=None) == 0
+
     sc3 = np.array([20, 40, 60], np.float32)
     pb = lambda cam=fake, V=4, H=32, W=32, img=fake, xyz=fake, M=10, sel=fake, k=3, sc=sc3, L=3, R=16, out=fake, dt=B.F32: \
         L_.aura_patch_batch(cam, V, H, W, img, xyz, M, None, None, 1, sel, k, None if sc is None else hp(sc), L, R, None, None,
