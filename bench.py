@@ -32,7 +32,7 @@ def fuse_algorithmic_bytes(s):
 # profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_prepare + k_tile_product, each
 # scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
 # the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = 869158382
+TRAFFIC_C2_BYTES = 869406603
 TRAFFIC_SOURCE_SHA256 = "cb020442f182d2aa4c0a7d80036c4a02ed42b90ce86010d5967d61fb4b9d90f0"
 
 
