@@ -18,7 +18,7 @@
 
 namespace aura {
 
-constexpr int kNrmBlock = 256;
+constexpr int kNrmBlock = 1024;   // a sweep over the cloud is shared by 16 waves
 constexpr int kNrmBins = 2048;
 
 struct NrmObjDev {
@@ -77,8 +77,8 @@ __device__ uint32_t radix_select(int n, int want, Key key, Eligible eligible, ui
         if (cand[e] && (kv[e] & mask) == prefix) atomicAdd(&s_hist[(kv[e] >> shift) & (uint32_t)(nb - 1)], 1u);
     }
     __syncthreads();
-    // the bin that holds the remaining-th candidate: thread t sums bins 8 t .. 8 t + 7, a scan over the threads finds
-    // the thread, which then walks its 8 bins
+    // the bin that holds the remaining-th candidate: thread t sums its kPer consecutive bins, a scan over the threads
+    // finds the thread, which then walks its bins
     constexpr int kPer = kNrmBins / kNrmBlock;
     uint32_t mine = 0;
 #pragma unroll
