@@ -285,7 +285,7 @@ def main():
                     help="skip the calls beyond the hot path (densification, thickness integration, view selection)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on exactly one GPU (the path shards by points; see DESIGN.md); "
+        sys.exit("bench.py: this library runs on exactly one GPU (the path would shard by points, one GPU each); "
                  "use --gpus 1")
 
     import torch

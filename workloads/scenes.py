@@ -70,7 +70,7 @@ class Scene:
 
 
 PRESETS = {
-    # BASELINE configs, index 0..4
+    # the five benchmark configurations, index 0..4
     "c1": dict(index=0, N=20_000, n_ell=1, V=8, radius=2.5, HW=224, f=250.0, grid=16, D=512, dtype="f32",
                K=12, parts=3, P=1, sigma=0.3, G=64, footprint=1, axes=(0.3, 1.0)),
     "c2": dict(index=1, N=200_000, n_ell=4, V=16, radius=3.0, HW=448, f=500.0, grid=32, D=768, dtype="bf16",
