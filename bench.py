@@ -339,6 +339,22 @@ def main():
     e1.record()
     torch.cuda.synchronize()
     fuse_ms = e0.elapsed_time(e1) / fuse_reps
+    # the same call one at a time (its own pair of events): spread of the launches, and a second figure with the
+    # caches flushed by a 512 MiB fill before every call (maps, depth and workspace then come from HBM)
+    def one_by_one(flush):
+        big = torch.empty(512 << 20, dtype=torch.uint8, device="cuda") if flush else None
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(fuse_reps)]
+        from paper_2511_03126_amd import binding
+        for a, b in pairs:
+            if flush:
+                binding.calibration_fill(big, 1)
+            a.record()
+            d.fuse_features()
+            b.record()
+        torch.cuda.synchronize()
+        t = sorted(a.elapsed_time(b) for a, b in pairs)
+        return {"min_ms": t[0], "median_ms": t[len(t) // 2], "max_ms": t[-1]}
+    warm_each, cold_each = one_by_one(False), one_by_one(True)
     fuse_bytes = fuse_algorithmic_bytes(s)
     achieved = fuse_bytes / (fuse_ms * 1e-3) / 1e9
     kernel = "aura_fuse_features: " + (f"k_tile_prepare + k_tile_product<{s.feat_dtype}, {s.D // 256} waves>" if tile
@@ -360,12 +376,15 @@ def main():
         "config": {"workload": f"{args.workload}: N={s.N} points, B={s.B} objects, {s.n_views} views {s.H}x{s.W}, "
                                f"feature grid {s.Hf}x{s.Wf}x{s.D} {s.feat_dtype}, K={s.K} materials, P={s.P}, "
                                f"mass grid G={s.G}", "point_views": pv,
+                   "visible_point_views_per_s": float(gpu["vis"].mean()) * pv / (ms_per_step * 1e-3),
                    "visible_fraction": float(gpu["vis"].mean()), "unseen_points": float((gpu["count_fuse"] == 0).mean()),
                    "order": s.meta["order"], "seed": s.meta["seed"]},
         "calls_ms": call_ms,
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "algorithmic_bytes": fuse_bytes, "avg_launch_ms": fuse_ms},
+                     "algorithmic_bytes": fuse_bytes, "avg_launch_ms": fuse_ms, "launches": fuse_reps,
+                     "single_launches": warm_each, "single_launches_caches_flushed": cold_each,
+                     "frac_caches_flushed": fuse_bytes / (cold_each["median_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS},
         **extras,
         "calibration": calibration,
     }
