@@ -224,29 +224,40 @@ def cpu_baseline(scene, seconds_target=15.0):
     v1 = int(s.view_offsets[1])
     cam, depth, feat = s.cam[:v1], s.depth[:v1], s.feat[:v1]
 
+    stages = {"project_visibility": 0.0, "fuse_features": 0.0, "material_scores": 0.0, "property_integrate": 0.0}
+
     def run(n):
         xyz = s.xyz[:n]
-        t0 = time.perf_counter()
+        t = [time.perf_counter()]
         pv = orc.project_visibility(cam, depth, xyz, tau=s.tau, z_near=s.z_near)
+        t.append(time.perf_counter())
         fu = orc.fuse_features(cam, depth, feat, s.feat_dtype, xyz, tau=s.tau, z_near=s.z_near)
+        t.append(time.perf_counter())
         sc = orc.material_scores(fu["fused"], s.temb, s.y, T=s.temperature)
+        t.append(time.perf_counter())
         orc.property_integrate(sc["prop"], 0, fu["count"], vol_uniform=s.vol_uniform, xyz=xyz,
                                grid_lo=None if s.G == 0 else s.grid_lo[:1], grid_h=None if s.G == 0 else s.grid_h[:1],
                                G=s.G)
+        t.append(time.perf_counter())
         del pv
-        return time.perf_counter() - t0
+        for name, a, b in zip(stages, t[:-1], t[1:]):
+            stages[name] += b - a
+        return t[-1] - t[0]
 
     n = min(p1, 2000)
     t = run(n)                       # also warms the library up
     n = int(min(p1, max(n, n * seconds_target / max(t, 1e-3))))
     n = min(n, 400_000)
+    for name in stages:
+        stages[name] = 0.0           # the sizing run above does not count
     t = run(n)
     reps = 1
     while t < 0.7 * seconds_target and reps < 64:     # the whole object is quicker than the target: repeat it
         t += run(n)
         reps += 1
     return {"value": reps * n * v1 / t, "unit": "point-views/s", "cores": orc.max_threads(), "kind": "oracle",
-            "sample": f"first {n} points of object 0 x {v1} views, whole path, {reps} passes, {t:.1f} s"}
+            "sample": f"first {n} points of object 0 x {v1} views, whole path, {reps} passes, {t:.1f} s",
+            "stage_seconds": {k: round(v, 3) for k, v in stages.items()}}
 
 
 CAL_BYTES = 256 << 20   # size of the calibration copy (read) and of its destination (write)
@@ -384,7 +395,8 @@ def main():
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
                      "algorithmic_bytes": fuse_bytes, "avg_launch_ms": fuse_ms, "launches": fuse_reps,
                      "single_launches": warm_each, "single_launches_caches_flushed": cold_each,
-                     "frac_caches_flushed": fuse_bytes / (cold_each["median_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+                     "frac_caches_flushed": fuse_bytes / (cold_each["median_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                     "frac_of_fill_kernel": achieved / calibration["fill_GBps"]},
         **extras,
         "calibration": calibration,
     }
