@@ -70,9 +70,11 @@ enum {
                                   camera and inside the image                                  */
   AURA_FUSE_MEAN_ONLY = 2u,    /* aura_fuse_features returns the plain mean of Eq. 2 without the
                                   L2 normalisation                                             */
-  AURA_FUSE_GATHER = 4u        /* aura_fuse_features uses the per-point gather kernel even where the
+  AURA_FUSE_GATHER = 4u,       /* aura_fuse_features uses the per-point gather kernel even where the
                                   matrix-core kernels apply (16-bit maps, D a multiple of 256).
                                   Meant for point sets that are not spatially sorted            */
+  AURA_FUSE_TWO_KERNELS = 8u   /* the matrix-core fusion runs as two kernels (lists, then products) even where
+                                  its one-kernel form applies; same results bit for bit        */
 };
 
 /* Which call a workspace size is asked for. */
@@ -117,7 +119,7 @@ typedef struct aura_params_t {
   float z_near;         /* points with camera-frame z <= z_near are invisible (e.g. 1e-6)      */
   float temperature;    /* T of Eq. 4, > 0; the paper uses 0.1                                  */
   float norm_eps;       /* L2 normalisation divides by max(norm, norm_eps) (e.g. 1e-12)        */
-  uint32_t flags;       /* AURA_VIS_FRUSTUM_ONLY | AURA_FUSE_MEAN_ONLY | AURA_FUSE_GATHER       */
+  uint32_t flags;       /* AURA_VIS_FRUSTUM_ONLY | AURA_FUSE_MEAN_ONLY | AURA_FUSE_GATHER | ...    */
 } aura_params_t;
 
 /* Library version as major * 10000 + minor * 100 + patch. */

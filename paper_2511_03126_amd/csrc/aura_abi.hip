@@ -282,7 +282,8 @@ static aura_status_t fuse_features_impl(const aura_views_t* views, const aura_pa
   return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts, int obj_base) {
     tws.obj_base = obj_base;
     return aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only, tile ? &tws : nullptr,
-                                      tab, n, max_pts, st, nullptr, nullptr, 0, sel_mask, mask_pitch);
+                                      tab, n, max_pts, st, nullptr, nullptr, 0, sel_mask, mask_pitch,
+                                      (params->flags & AURA_FUSE_TWO_KERNELS) ? 1 : 0);
   });
 }
 
@@ -377,7 +378,7 @@ aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* p
     if (e != hipSuccess) return e;
     e = aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only,
                                    lay.tile ? &tws : nullptr, tab, n, max_pts, st, lay.by_cells ? sws.factor : nullptr,
-                                   vis, vis_pitch);
+                                   vis, vis_pitch, nullptr, 0, (params->flags & AURA_FUSE_TWO_KERNELS) ? 1 : 0);
     if (e != hipSuccess || !lay.by_cells) return e;
     return aura::launch_tile_scores(fa, tws, sws, fused, t32, K, y, P, params->temperature, scores, prop, label, tab, n,
                                     max_pts, st);

@@ -51,7 +51,9 @@ struct Proj {
 
 // pi(x, v) and proj_depth: Xc = R x + t as a chain of fused multiply-adds starting from t, one
 // IEEE division per pixel coordinate, one fused multiply-add with the focal length.
-__device__ __forceinline__ Proj project(const float* __restrict__ c, float x, float y, float z) {
+// CamPtr: a pointer to the 16 floats of a camera row in any address space (memory or LDS).
+template <typename CamPtr>
+__device__ __forceinline__ Proj project(CamPtr c, float x, float y, float z) {
 #pragma clang fp contract(off)
   float xc = __builtin_fmaf(c[2], z, __builtin_fmaf(c[1], y, __builtin_fmaf(c[0], x, c[9])));
   float yc = __builtin_fmaf(c[5], z, __builtin_fmaf(c[4], y, __builtin_fmaf(c[3], x, c[10])));

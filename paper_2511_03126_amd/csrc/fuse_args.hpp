@@ -20,6 +20,7 @@ struct FuseArgs {
   int vis_pitch;
   const uint8_t* in_mask;   // may be nullptr: [N][in_mask_pitch], the views kept for each point (Sec. 3.2.2); given, it
   int in_mask_pitch;        // takes the place of the depth test (the caller passes no depth maps then)
+  int two_kernels;          // tile path: keep the prepare and the product kernel apart (AURA_FUSE_TWO_KERNELS)
 };
 
 // Whether view `local_view` (index within the object) takes part in the mean of point i.

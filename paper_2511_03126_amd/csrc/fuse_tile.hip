@@ -137,12 +137,11 @@ struct PairRec {
 // The slow way out when a tile needs more k-steps than it owns: the workgroup fuses its 32 points by a
 // per-point gather (wave per point, lanes over channels, 512 channels per sweep).
 template <int DT>
-__device__ __forceinline__ void gather_tile(const FuseArgs& a, const ObjRange& ob, int li0, int tid) {
-  const int wave = tid / kWave, lane = tid % kWave;
+__device__ __forceinline__ void gather_tile(const FuseArgs& a, const ObjRange& ob, int li0, int wave, int n_waves, int lane) {
   const int D = a.feat.D, Hf = a.feat.Hf, Wf = a.feat.Wf;
   const long long view_bytes = (long long)Hf * Wf * D * 2;
-  for (int k = 0; k < kTilePts / (kPrepThreads / kWave); ++k) {
-    const int li = li0 + wave * (kTilePts / (kPrepThreads / kWave)) + k;
+  for (int k = 0; k < kTilePts / n_waves; ++k) {
+    const int li = li0 + wave * (kTilePts / n_waves) + k;
     if (li >= ob.n_pts) break;
     const long long i = ob.pt_begin + li;
     const float x = a.xyz[3 * i], y = a.xyz[3 * i + 1], z = a.xyz[3 * i + 2];
@@ -470,7 +469,7 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
   __syncthreads();
   if (exhausted) {
     if (tid == 0) hdr->nsteps = -1;
-    gather_tile<DT>(a, ob, li0, tid);
+    gather_tile<DT>(a, ob, li0, tid / kWave, kPrepThreads / kWave, lane);
     return;
   }
   if (tid == 0) hdr->nsteps = used;
@@ -628,6 +627,7 @@ struct ProdArgs {
 // a counter (tiles differ in length, a fixed split leaves a tail), so that at any time the tiles in
 // flight on an XCD are neighbours and share cell rows in its L2.
 constexpr int kXcd = 8;
+constexpr int kFusedGroupsMax = 512;  // one-kernel form: two workgroups per compute unit
 constexpr int kProdGroupsMax = 768;   // two workgroups fit a compute unit at a time; the rest take over as the first run out of tiles
 
 // The opening reads of a tile whose k-steps are staged at `sb` (n of them, possibly none): the rows of its
@@ -832,6 +832,489 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
   }
 }
 
+// ------------------------------------------------------------------------------------ one kernel
+//
+// k_tile_fused: the product kernel with one more wave per workgroup, the producer, that does the prepare kernel's work
+// for the workgroup's NEXT tile while the S product waves multiply the current one.  The producer writes the k-steps
+// straight into the other LDS buffer, in the layout the product waves read (no trip through memory, unless the scoring
+// kernel wants them), so the projection -> depth read -> list -> weight chain of a tile hides behind the stores of the
+// tile before it.  The tile's one barrier is shared: after it the buffer the products came from belongs to the producer
+// and the buffer it filled belongs to the product waves.  The producer has no barrier of its own: it is one wave, and
+// orders its LDS traffic with wave-level fences.  Tiles go to workgroups through the per-XCD counters as before; the
+// producer asks for a ticket one tile ahead.  A tile whose list does not fit the buffer is fused by the producer itself
+// (per-point gather): the launch code only takes this kernel where that is rare.
+
+constexpr int kPBatch = 16;   // views per pass of the producer wave: two per trip, one per half wave
+constexpr int kCamRows = 32;  // camera rows of the object kept in LDS for the producer
+constexpr int kOneKernelViews = 8;
+
+typedef const float __attribute__((address_space(3))) * lds_floats;
+
+struct ProducerScratch {
+  uint32_t bits[kPBatch][kWinSide];   // map of touched cells per view, row = word
+  uint16_t wbase[kPBatch][kWinSide];  // set bits before each row
+  int base[kPBatch + 1];              // first list index of each view
+  int win[kPBatch][2];
+  int mode[kPBatch];
+  uint32_t vmask[kPBatch];
+};
+
+struct TileSlot {    // what the product waves need to know about a staged tile
+  int tile;          // index within the object; -1: no further tile
+  int nsteps;        // -1: fused by the producer
+  int pad_[2];
+  int cnt[kTilePts];
+};
+
+// Orders the producer wave's LDS traffic for the compiler.  The LDS unit handles the instructions of one wave in
+// program order, so a later read by any lane sees an earlier write by any other lane of the same wave: no wait and
+// no barrier instruction is needed, only that the compiler keeps the order.
+__device__ __forceinline__ void wave_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+}
+
+// The point that lane `lane` of the producer handles in tile `blk` (lane % 32; the tile's first point where the object
+// has no such point).  Read one tile ahead so that the round trip to memory is not waited for.
+__device__ __forceinline__ float3 tile_point(const FuseArgs& a, const ObjRange& ob, int blk, int lane) {
+  blk = max(min(blk, (ob.n_pts + kTilePts - 1) / kTilePts - 1), 0);   // a ticket past the end reads a tile that exists
+  const int p = lane & 31, li0 = blk * kTilePts;
+  const long long ip = ob.pt_begin + li0 + (li0 + p < ob.n_pts ? p : 0);
+  return float3{a.xyz[3 * ip], a.xyz[3 * ip + 1], a.xyz[3 * ip + 2]};
+}
+
+// Builds tile `blk` of object `ob` into `stage` (room for `k_stage` k-steps) and `slot`.  Called by all 64 lanes of
+// the producer wave.  cam_lds: the object's camera rows in LDS.
+template <int DT, bool SEL>
+__device__ __forceinline__ void produce_tile(const FuseArgs& a, const TileWs& ws, bool keep, const ObjRange& ob, int blk,
+                                             float3 pt, char* stage, int k_stage, TileSlot* slot, ProducerScratch* sc,
+                                             lds_floats cam_lds, int lane) {
+  const int p = lane & 31, h = lane >> 5;
+  const int Hf = a.feat.Hf, Wf = a.feat.Wf;
+  const uint32_t row_bytes = (uint32_t)a.feat.D * 2u;
+  const int li0 = blk * kTilePts;
+  const bool p_valid = li0 + p < ob.n_pts;
+  const long long ip = ob.pt_begin + li0 + (p_valid ? p : 0);
+  const float px = pt.x, py = pt.y, pz = pt.z;   // read by the caller one tile ahead (tile_point)
+  TileStep* st = reinterpret_cast<TileStep*>(stage);
+  int used = 0, cnt = 0;
+  bool exhausted = false;
+
+  for (int vb0 = 0; vb0 < ob.n_views; vb0 += kPBatch) {
+    const int nvb = min(kPBatch, ob.n_views - vb0);
+    wave_sync();   // the previous batch is done with the tables
+    reinterpret_cast<u32x4*>(&sc->bits[0][0])[lane] = u32x4{0u, 0u, 0u, 0u};
+    reinterpret_cast<u32x4*>(&sc->bits[0][0])[lane + kWave] = u32x4{0u, 0u, 0u, 0u};
+
+    // ---- A: project and test; bounding box of the touched cells per view.  First every projection and the request
+    // for its depth texel (and, with a given selection, its mask byte), then the tests: the wave has nobody to hide
+    // a read behind, so the reads of all its pairs are in flight together.
+    PairRec pr[kPBatch / 2];
+    Proj pj[kPBatch / 2];
+    float dep[kPBatch / 2];
+    bool fr[kPBatch / 2], kept[kPBatch / 2];
+#pragma unroll
+    for (int it = 0; it < kPBatch / 2; ++it) {
+      dep[it] = 1.0f;
+      fr[it] = false;
+      kept[it] = true;
+      if (2 * it >= nvb) continue;   // uniform
+      const int vl = min(2 * it + h, nvb - 1);
+      const int v = ob.view_begin + vb0 + vl;
+      // the camera rows come from the LDS copy, through a pointer that says so: a generic read would wait for every
+      // read in flight, the depth texels of the trips before included
+      pj[it] = project(cam_lds + (vb0 + vl) * 16, px, py, pz);
+      fr[it] = in_frustum(a.vis, pj[it]);
+      if (a.vis.depth) dep[it] = a.vis.depth[(long long)v * a.vis.H * a.vis.W + (fr[it] ? depth_texel(a.vis, pj[it]) : 0)];
+      if constexpr (SEL) kept[it] = view_kept(a, ip, vb0 + vl);
+    }
+#pragma unroll
+    for (int it = 0; it < kPBatch / 2; ++it) {
+      pr[it].xy = -1;
+      pr[it].ax = pr[it].ay = 0.0f;
+      if (2 * it >= nvb) continue;   // uniform
+      const int vl = 2 * it + h;
+      const bool seen = vl < nvb && p_valid && fr[it] && kept[it] && (a.vis.frustum_only || passes_depth(a.vis, pj[it], dep[it]));
+      s16x2 lo2 = {0x7fff, 0x7fff}, hi2 = {-1, -1};
+      if (seen) {
+        const Tap tx = tap_axis(pj[it].u, a.feat.pitch_x, Wf), ty = tap_axis(pj[it].v, a.feat.pitch_y, Hf);
+        pr[it].ax = tx.a;
+        pr[it].ay = ty.a;
+        pr[it].xy = (ty.i0 << 16) | tx.i0;
+        lo2 = s16x2{(short)tx.i0, (short)ty.i0};
+        hi2 = s16x2{(short)tx.i1, (short)ty.i1};
+        ++cnt;
+      }
+      const unsigned long long seen_mask = __ballot(seen);
+      lo2 = half_wave_reduce<true>(lo2);
+      hi2 = half_wave_reduce<false>(hi2);
+      if (p == kTilePts - 1 && vl < nvb) {
+        const bool any = hi2[0] >= 0;
+        const int ww = hi2[0] - lo2[0] + 1, wh = hi2[1] - lo2[1] + 1;
+        sc->win[vl][0] = lo2[0];
+        sc->win[vl][1] = lo2[1];
+        sc->mode[vl] = !any ? 0 : (ww <= kWinSide && wh <= kWinSide ? 1 : 2);
+        sc->vmask[vl] = (uint32_t)(seen_mask >> (lane & 32));
+      }
+    }
+    wave_sync();
+    if (a.out_vis && lane < kTilePts && li0 + lane < ob.n_pts) {   // the mask of Eq. 1 for this batch of views
+      uint8_t* __restrict__ vrow = a.out_vis + (ob.pt_begin + li0 + lane) * a.vis_pitch + vb0;
+      if ((a.vis_pitch & 3) == 0) {
+        for (int v4 = 0; v4 < nvb; v4 += 4) {
+          uint32_t w = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (v4 + e < nvb) w |= ((sc->vmask[v4 + e] >> lane) & 1u) << (8 * e);
+          if (v4 + 4 <= nvb) {
+            *reinterpret_cast<uint32_t*>(vrow + v4) = w;
+          } else {
+            for (int e = 0; v4 + e < nvb; ++e) vrow[v4 + e] = (uint8_t)((w >> (8 * e)) & 1u);
+          }
+        }
+      } else {
+        for (int v = 0; v < nvb; ++v) vrow[v] = (uint8_t)((sc->vmask[v] >> lane) & 1u);
+      }
+    }
+
+    // ---- B: mark the touched cells of every view that uses a map
+#pragma unroll
+    for (int it = 0; it < kPBatch / 2; ++it) {
+      if (pr[it].xy < 0) continue;
+      const int vl = 2 * it + h;
+      if (sc->mode[vl] != 1) continue;
+      const int x0 = pr[it].xy & 0xffff, y0 = pr[it].xy >> 16;
+      const int bit = (y0 - sc->win[vl][1]) * kWinSide + (x0 - sc->win[vl][0]);
+      const bool has_x1 = x0 + 1 < Wf, has_y1 = y0 + 1 < Hf;
+      atomicOr(&sc->bits[vl][bit >> 5], 1u << (bit & 31));
+      if (has_x1) atomicOr(&sc->bits[vl][(bit + 1) >> 5], 1u << ((bit + 1) & 31));
+      if (has_y1) atomicOr(&sc->bits[vl][(bit + kWinSide) >> 5], 1u << ((bit + kWinSide) & 31));
+      if (has_x1 && has_y1) atomicOr(&sc->bits[vl][(bit + kWinSide + 1) >> 5], 1u << ((bit + kWinSide + 1) & 31));
+    }
+    wave_sync();
+    {   // list length of every view, exclusive scan over the views
+      int n = 0;
+      if (lane < nvb) {
+        if (sc->mode[lane] == 1) {
+#pragma unroll 8
+          for (int w = 0; w < kWinSide; ++w) {
+            sc->wbase[lane][w] = (uint16_t)n;
+            n += __popc(sc->bits[lane][w]);
+          }
+        } else if (sc->mode[lane] == 2) {
+          n = 4 * __popc(sc->vmask[lane]);
+        }
+      }
+      int inc = n;
+#pragma unroll
+      for (int o = 1; o < kPBatch; o <<= 1) {
+        const int up = __shfl_up(inc, o, kWave);
+        if (lane >= o) inc += up;
+      }
+      if (lane < kPBatch) sc->base[lane] = inc - n;
+      if (lane == kPBatch - 1) sc->base[kPBatch] = inc;
+    }
+    wave_sync();
+    const int L = sc->base[kPBatch];
+    const int nsteps = (L + kStepCells - 1) / kStepCells;
+    if (used + nsteps > k_stage) {   // uniform
+      exhausted = true;
+      break;
+    }
+    TileStep* __restrict__ out = st + used;
+    used += nsteps;
+
+    // ---- C: zero weights, the cells of the list, then the weights in the operand layout
+    for (int q = lane; q < nsteps * 128; q += kWave)
+      reinterpret_cast<u32x4*>(reinterpret_cast<char*>(&out[q >> 7]) + 64)[q & 127] = u32x4{0u, 0u, 0u, 0u};
+    if (lane < nsteps * kStepCells - L) {   // entries that pad the last k-step point at a cell that exists
+      const int idx = L + lane;
+      out[idx >> 4].cell[idx & 15] = (uint32_t)((ob.view_begin + vb0) * Hf * Wf) * row_bytes;
+    }
+    {   // cells of the views with a map: lane = (view, eight rows of the map)
+      const int vl = lane >> 2;
+      if (vl < nvb && sc->mode[vl] == 1) {
+        const int cell0 = (ob.view_begin + vb0 + vl) * Hf + sc->win[vl][1], wx = sc->win[vl][0];
+        for (int w = 8 * (lane & 3); w < 8 * (lane & 3) + 8; ++w) {
+          uint32_t bits = sc->bits[vl][w];
+          int q = sc->base[vl] + sc->wbase[vl][w];
+          while (bits) {
+            const int b = __builtin_ctz(bits);
+            bits &= bits - 1;
+            out[q >> 4].cell[q & 15] = (uint32_t)((cell0 + w) * Wf + wx + b) * row_bytes;
+            ++q;
+          }
+        }
+      }
+    }
+    wave_sync();   // the zeros are in place before the weights land
+    // list positions of the four cells of every pair first (LDS reads only), then the stores: with both in one loop
+    // the reads of a pair would wait behind the stores of the pair before it
+    int idx[kPBatch / 2][4];
+#pragma unroll
+    for (int it = 0; it < kPBatch / 2; ++it) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) idx[it][k] = 0;
+      if (pr[it].xy < 0) continue;
+      const int vl = 2 * it + h;
+      const int x0 = pr[it].xy & 0xffff, y0 = pr[it].xy >> 16;
+      const bool has_x1 = x0 + 1 < Wf, has_y1 = y0 + 1 < Hf;
+      const bool on[4] = {true, has_x1, has_y1, has_x1 && has_y1};
+      if (sc->mode[vl] == 1) {
+        const int bit = (y0 - sc->win[vl][1]) * kWinSide + (x0 - sc->win[vl][0]);
+        const int bs[4] = {bit, bit + 1, bit + kWinSide, bit + kWinSide + 1};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const int b = on[k] ? bs[k] : bit;
+          idx[it][k] = sc->base[vl] + sc->wbase[vl][b >> 5] + __popc(sc->bits[vl][b >> 5] & ((1u << (b & 31)) - 1u));
+        }
+      } else {
+        const int first = sc->base[vl] + 4 * __popc(sc->vmask[vl] & ((1u << p) - 1u));
+#pragma unroll
+        for (int k = 0; k < 4; ++k) idx[it][k] = -1 - (first + k);   // negative: a private entry, its cell is still to be written
+      }
+    }
+    wave_sync();
+#pragma unroll
+    for (int it = 0; it < kPBatch / 2; ++it) {
+      if (pr[it].xy < 0) continue;
+      const int vl = 2 * it + h;
+      const int x0 = pr[it].xy & 0xffff, y0 = pr[it].xy >> 16;
+      const float ax = pr[it].ax, ay = pr[it].ay;
+      const bool has_x1 = x0 + 1 < Wf, has_y1 = y0 + 1 < Hf;
+      const float wgt[4] = {(1.0f - ax) * (1.0f - ay), ax * (1.0f - ay), (1.0f - ax) * ay, ax * ay};
+      const bool on[4] = {true, has_x1, has_y1, has_x1 && has_y1};
+      if (idx[it][0] < 0) {
+        const int cell0 = (ob.view_begin + vb0 + vl) * Hf;
+        const int x1 = has_x1 ? x0 + 1 : x0, y1 = has_y1 ? y0 + 1 : y0;
+        const int cx[4] = {x0, x1, x0, x1}, cy[4] = {y0, y0, y1, y1};
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          idx[it][k] = -1 - idx[it][k];
+          out[idx[it][k] >> 4].cell[idx[it][k] & 15] = (uint32_t)((cell0 + cy[k]) * Wf + cx[k]) * row_bytes;
+        }
+      }
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        if (on[k]) {
+          uint16_t hi, lo;
+          split_weight<DT>(wgt[k], hi, lo);
+          const int c = idx[it][k] & 15;
+          TileStep* stp = out + (idx[it][k] >> 4);
+          reinterpret_cast<uint16_t*>(&stp->a_hi[(c >> 3) * kTilePts + p])[c & 7] = hi;
+          reinterpret_cast<uint16_t*>(&stp->a_lo[(c >> 3) * kTilePts + p])[c & 7] = lo;
+        }
+      }
+    }
+  }
+
+  if (a.out_vis && lane < kTilePts && li0 + lane < ob.n_pts) {   // mask columns beyond the object's views
+    for (int j = ob.n_views; j < a.vis_pitch; ++j) a.out_vis[(ob.pt_begin + li0 + lane) * a.vis_pitch + j] = 0;
+  }
+  const int total = cnt + __shfl_xor(cnt, 32, kWave);   // views that see point lane % 32
+  wave_sync();
+  if (lane == 0) {
+    slot->tile = blk;
+    slot->nsteps = exhausted ? -1 : used;
+  }
+  if (lane < kTilePts) slot->cnt[lane] = total;
+  if (exhausted) {
+    gather_tile<DT>(a, ob, li0, 0, 1, lane);   // writes the rows and the counts of the tile itself
+  } else if (a.out_count && lane < kTilePts && li0 + lane < ob.n_pts) {
+    a.out_count[ob.pt_begin + li0 + lane] = total;
+  }
+  if (keep) {   // the scoring kernel reads the k-steps and the header from memory
+    TileHdr* __restrict__ hdr = ws.hdr + ob.tile_begin + blk;
+    if (lane == 0) hdr->nsteps = exhausted ? -1 : used;
+    if (lane < kTilePts) hdr->cnt[lane] = total;
+    if (!exhausted) {
+      u32x4* __restrict__ dst = reinterpret_cast<u32x4*>(ws.steps + (long long)(ob.tile_begin + blk) * ws.quota);
+      const u32x4* src = reinterpret_cast<const u32x4*>(stage);
+      for (int q = lane; q < used * (int)(sizeof(TileStep) / 16); q += kWave) dst[q] = src[q];
+    }
+  }
+}
+
+template <int DT, int S, int H, int PF, bool SEL>
+__global__ __launch_bounds__(kWave* (S + 1)) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
+  constexpr int kSpan = kHalf * H;
+  constexpr int kStage = stage_steps_for<S * H / 2>();
+  __shared__ __attribute__((aligned(16))) char s_steps[2][kStage * sizeof(TileStep)];
+  __shared__ TileSlot s_slot[2];
+  __shared__ __attribute__((aligned(16))) ProducerScratch s_sc;
+  __shared__ float s_ss[2][S][kTilePts];
+  __shared__ __attribute__((aligned(16))) float s_cam[kCamRows][16];   // the object's camera rows, for the producer
+
+  const ObjRange ob = tab.o[blockIdx.y];
+  const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
+  const int groups = min(nblk, (int)gridDim.x);
+  if ((int)blockIdx.x >= groups) return;
+  const int xcd = blockIdx.x % kXcd, per = nblk / kXcd, rem = nblk % kXcd;
+  const int r0 = xcd * per + min(xcd, rem), len = per + (xcd < rem ? 1 : 0);
+  unsigned* __restrict__ ctr = a.counters + blockIdx.y * kXcd + xcd;
+
+  const int tid = threadIdx.x, lane = tid % kWave;
+  const int span = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave index; wave S is the producer
+  const bool producer = span == S;
+  const lds_floats cam_lds = (lds_floats)&s_cam[0][0];   // the launch code takes this kernel for up to kCamRows views
+  if (producer) {
+    for (int q = lane; q < ob.n_views * 16; q += kWave) s_cam[q >> 4][q & 15] = fa.vis.cam[(long long)ob.view_begin * 16 + q];
+    wave_sync();
+  }
+  const int m = lane & 31, g = lane >> 5;
+  const int D = a.D;
+  const uint32_t lane_off = (uint32_t)(span * kSpan + 4 * m) * 2u;
+
+  // producer: tickets one tile ahead (the counters are zeroed by the launch that precedes this kernel)
+  // the answer stays in a vector register and is only read one tile later, so nobody waits for the round trip
+  auto ticket = [&]() {
+    int t = 0;
+    if (lane == 0) t = (int)atomicAdd(ctr, 1u);
+    return t;
+  };
+  if (producer) {
+    // tickets and points run ahead of the tile being built: the ticket of tile i + 2 is asked for and the points of tile
+    // i + 1 are read before tile i is built, and both are only looked at after it
+    const int t0 = __builtin_amdgcn_readfirstlane(ticket());
+    int t1_raw = ticket();
+    if (t0 < len) {
+      produce_tile<DT, SEL>(fa, ws, keep != 0, ob, r0 + t0, tile_point(fa, ob, r0 + t0, lane), s_steps[0], kStage, &s_slot[0],
+                            &s_sc, cam_lds, lane);
+    } else if (lane == 0) {
+      s_slot[0].tile = -1;
+      s_slot[0].nsteps = 0;
+    }
+    int t = __builtin_amdgcn_readfirstlane(t1_raw);            // the next tile to build
+    float3 pt = tile_point(fa, ob, r0 + t, lane);
+    int t_raw = t < len ? ticket() : len;                       // the one after it
+    __syncthreads();
+    // Two loops with the same number of barriers: one trip per tile, ended by the barrier after which the buffers change
+    // hands.  Both leave when the slot they look at says that there is no further tile (written before the last barrier,
+    // so every wave of the workgroup sees the same value).
+    int buf = 0;
+    while (s_slot[buf].tile >= 0) {
+      if (t < len) {
+        produce_tile<DT, SEL>(fa, ws, keep != 0, ob, r0 + t, pt, s_steps[buf ^ 1], kStage, &s_slot[buf ^ 1], &s_sc, cam_lds, lane);
+        t = __builtin_amdgcn_readfirstlane(t_raw);
+        pt = tile_point(fa, ob, r0 + t, lane);
+        if (t < len) t_raw = ticket();
+      } else if (lane == 0) {
+        s_slot[buf ^ 1].tile = -1;
+        s_slot[buf ^ 1].nsteps = 0;
+      }
+      __syncthreads();
+      buf ^= 1;
+    }
+    return;
+  }
+  __syncthreads();
+
+  StepA wa[2];
+  StepC wc;
+  StepQ<H> rq[PF];
+  int buf = 0;
+  if (s_slot[0].tile >= 0)
+    open_tile<H, PF>(s_steps[0], min(max(s_slot[0].nsteps, 0), kStage), a.feat, lane_off, lane, g, wa, rq);
+
+  while (true) {
+    const int blk = s_slot[buf].tile;   // uniform over the workgroup: written before the last barrier
+    if (blk < 0) break;
+    const int n = s_slot[buf].nsteps;
+
+    const int my_cnt = s_slot[buf].cnt[m];   // views that see point (lane % 32) of this tile
+    f32x16 acc[4 * H];
+#pragma unroll
+    for (int t = 0; t < 4 * H; ++t)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
+
+    const char* sb = s_steps[buf];
+    {
+      const int cnt = max(n, 0), l0 = cnt - 1;
+      int s = 0;
+      for (; s + PF <= cnt; s += PF) {
+#pragma unroll
+        for (int j = 0; j < PF; ++j) {
+          lds_c(sb, min(s + j + PF, l0), g, wc);
+          lds_a(sb, min(s + j + 1, l0), lane, wa[(j + 1) & 1]);
+          mma_step<DT, H>(wa[j & 1], rq[j], acc);
+          __builtin_amdgcn_sched_barrier(0);
+          load_q(a.feat, wc, lane_off, rq[j]);
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < PF - 1; ++j) {
+        if (s + j < cnt) {
+          lds_a(sb, min(s + j + 1, l0), lane, wa[(j + 1) & 1]);
+          mma_step<DT, H>(wa[j & 1], rq[j], acc);
+        }
+      }
+    }
+
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int row = 8 * (r >> 2) + 4 * g + (r & 3);
+      float ss = 0.0f;
+#pragma unroll
+      for (int t = 0; t < 4 * H; ++t) ss = __builtin_fmaf(acc[t][r], acc[t][r], ss);
+      ss = half_wave_sum(ss);
+      if (m == 31) s_ss[buf][span][row] = ss;
+    }
+    __syncthreads();   // the one barrier of a tile: the sums are in LDS, the producer has staged the next tile, and
+                       // every product wave is done with this tile's buffer
+
+    float factor;
+    {
+      const float inv = my_cnt > 0 ? 1.0f / (float)my_cnt : 0.0f;
+      float tot = 0.0f;
+#pragma unroll
+      for (int w = 0; w < S; ++w) tot += s_ss[buf][w][m];
+      const float normed = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
+      factor = a.mean_only ? inv : normed;
+    }
+    {
+      const int rows_f = a.factor ? min(kTilePts, ob.n_pts - blk * kTilePts) : 0;
+      const __amdgpu_buffer_rsrc_t fout = __builtin_amdgcn_make_buffer_rsrc(a.factor + (a.factor ? ob.pt_begin + blk * kTilePts : 0), 0,
+                                                                            rows_f * 4, 0x00020000);
+      __builtin_amdgcn_raw_buffer_store_b32(__float_as_int(factor), fout, tid < kTilePts ? 4 * tid : 0x7ffffff0, 0, 0);
+    }
+    {
+      const int li0 = blk * kTilePts;
+      float* obase = a.fused + (ob.pt_begin + li0) * D + span * kSpan;
+      uint32_t row_bytes = (uint32_t)D * 4u;
+      asm volatile("" : "+s"(row_bytes));
+      const int rows = n >= 0 ? min(kTilePts, ob.n_pts - li0) : 0;
+      const __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(obase, 0, (int)(rows * row_bytes), 0x00020000);
+      const uint32_t lane_out = (uint32_t)(4 * g) * row_bytes + (uint32_t)(4 * m) * 4u;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int row0 = 8 * (r >> 2) + (r & 3);
+        const float scale = __int_as_float(__builtin_amdgcn_ds_bpermute(4 * (row0 + 4 * g), __float_as_int(factor)));
+#pragma unroll
+        for (int h = 0; h < H; ++h) {
+          const f32x4 v = {acc[4 * h][r] * scale, acc[4 * h + 1][r] * scale, acc[4 * h + 2][r] * scale, acc[4 * h + 3][r] * scale};
+          __builtin_amdgcn_raw_buffer_store_b128(__builtin_bit_cast(u32x4, v), out,
+                                                 (int)(lane_out + (uint32_t)row0 * row_bytes) + h * kHalf * 4, 0, /*streaming*/ 2);
+        }
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    buf ^= 1;
+    {
+      const int nn = s_slot[buf].tile >= 0 ? min(max(s_slot[buf].nsteps, 0), kStage) : 0;
+      open_tile<H, PF>(s_steps[buf], nn, a.feat, lane_off, lane, g, wa, rq);
+    }
+  }
+}
+
+// Clears the ticket counters of a launch's objects (the prepare kernel does it on the two-kernel path).
+__global__ void k_clear_counters(unsigned* counters, int n) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < n) counters[i] = 0u;
+}
+
 // ------------------------------------------------------------------------------------ host
 
 static long long tile_count_bound(long long N, int B) { return N / kTilePts + B; }
@@ -870,18 +1353,43 @@ bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes)
          D / 256 != 5 && feat_bytes <= 0xffffffffll;
 }
 
+// Whether the one-kernel form is taken: the lists of (nearly) all tiles must fit the LDS buffer of kStage k-steps, and
+// when the scoring kernel wants the k-steps in memory, the tile's share of the workspace as well.  Measured need on
+// spatially sorted points: 0.3 to 0.4 k-steps per view for coarse grids, up to 1 for pixel-sized cells.
+static bool one_kernel_fits(const FuseArgs& a, int k_stage, int quota, int views_per_obj) {
+  const float per_view = (a.feat.pitch_x >= 4.0f && a.feat.pitch_y >= 4.0f) ? 0.5f : 1.0f;
+  // one producer wave keeps up with the product waves for up to kOneKernelViews views per object (measured: 4 views
+  // 2.7 against 3.6 ms on 6.4 M points; 16 views on a par; 24 views slower than the two kernels)
+  return !a.two_kernels && k_stage <= quota && views_per_obj <= kOneKernelViews &&
+         (float)views_per_obj * per_view <= (float)k_stage;
+}
+
 template <int DT, int S, int H, int PF>
 static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
                               hipStream_t stream) {
   const int max_tiles = (max_pts + kTilePts - 1) / kTilePts;
+  ProdArgs pa{static_cast<const char*>(a.feat.feat), a.feat.D, ws.hdr, ws.steps, ws.counters + (size_t)ws.obj_base * kXcd,
+              ws.quota, a.fused, a.out_factor, a.norm_eps, a.mean_only};
+  int max_views = 0;
+  for (int t = 0; t < n_obj; ++t) max_views = std::max(max_views, tab.o[t].n_views);
+  if (one_kernel_fits(a, stage_steps_for<S * H / 2>(), ws.quota, max_views)) {
+    hipLaunchKernelGGL(k_clear_counters, dim3((n_obj * kXcd + 63) / 64), dim3(64), 0, stream, pa.counters, n_obj * kXcd);
+    // two workgroups fit a compute unit; several objects in one launch share the machine
+    const int groups = std::max(kXcd, std::min(max_tiles, (kFusedGroupsMax / n_obj + kXcd - 1) / kXcd * kXcd));
+    const dim3 grid(std::min(groups, max_tiles), n_obj), block(kWave * (S + 1));
+    const int keep = a.out_factor != nullptr;   // the scoring kernel follows and reads the k-steps
+    if (a.in_mask)
+      hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, true>), grid, block, 0, stream, a, pa, ws, keep, tab);
+    else
+      hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false>), grid, block, 0, stream, a, pa, ws, keep, tab);
+    return hipGetLastError();
+  }
   if (a.in_mask)
     hipLaunchKernelGGL((k_tile_prepare<DT, true>), dim3(max_tiles, n_obj), dim3(kPrepThreads), 0, stream, a, ws, tab);
   else
     hipLaunchKernelGGL((k_tile_prepare<DT, false>), dim3(max_tiles, n_obj), dim3(kPrepThreads), 0, stream, a, ws, tab);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  ProdArgs pa{static_cast<const char*>(a.feat.feat), a.feat.D, ws.hdr, ws.steps, ws.counters + (size_t)ws.obj_base * kXcd,
-              ws.quota, a.fused, a.out_factor, a.norm_eps, a.mean_only};
   // several objects in one launch share the machine: fewer workgroups per object
   const int groups = std::max(kXcd, std::min(max_tiles, (kProdGroupsMax / n_obj + kXcd - 1) / kXcd * kXcd));
   hipLaunchKernelGGL((k_tile_product<DT, S, H, PF>), dim3(std::min(groups, max_tiles), n_obj), dim3(kWave * S), 0, stream, pa, tab);

@@ -29,7 +29,8 @@ hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const 
                                 const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream,
                                 float* out_factor = nullptr,    // tile path only: see FuseArgs::out_factor
                                 uint8_t* out_vis = nullptr, int vis_pitch = 0,    // tile path only: see FuseArgs::out_vis
-                                const uint8_t* in_mask = nullptr, int in_mask_pitch = 0);   // see FuseArgs::in_mask
+                                const uint8_t* in_mask = nullptr, int in_mask_pitch = 0,     // see FuseArgs::in_mask
+                                int two_kernels = 0);                                       // see FuseArgs::two_kernels
 
 // Sec. 3.2.2, view importance-based filtering (select_views.hip).
 constexpr int kSelectMaxK = 8;

@@ -25,6 +25,8 @@ class DeviceScene:
         self.views = aura.Views(cam=torch.from_numpy(s.cam).to(dev), depth=torch.from_numpy(s.depth).to(dev),
                                 feat=_feat_tensor(s, dev))
         self.params = aura.Params(tau=s.tau, z_near=s.z_near, temperature=s.temperature, norm_eps=1e-12, flags=flags)
+        # the same with the matrix-core fusion forced into its two-kernel form (AURA_FUSE_TWO_KERNELS)
+        self.params_two = aura.Params(tau=s.tau, z_near=s.z_near, temperature=s.temperature, norm_eps=1e-12, flags=flags | 8)
         self.temb = torch.from_numpy(s.temb).to(dev)
         self.y = torch.from_numpy(s.y).to(dev)
         N, V = s.N, s.vis_pitch
@@ -54,16 +56,17 @@ class DeviceScene:
         aura.project_visibility(self.views, self.params, self.xyz, self.vis, self.count, self.uvz,
                                 self.pt_offsets, self.view_offsets)
 
-    def fuse_features(self):
-        aura.fuse_features(self.views, self.params, self.xyz, self.fused, self.count_fuse, self.pt_offsets,
-                           self.view_offsets, self.ws_fuse)
+    def fuse_features(self, two_kernels=False):
+        aura.fuse_features(self.views, self.params_two if two_kernels else self.params, self.xyz, self.fused,
+                           self.count_fuse, self.pt_offsets, self.view_offsets, self.ws_fuse)
 
     def material_scores(self):
         aura.material_scores(self.fused, self.temb, self.y, self.params, self.scores, self.prop, self.label,
                              self.ws_scores)
 
-    def fuse_scores(self, with_vis=False):
-        aura.fuse_scores(self.views, self.params, self.xyz, self.temb, self.y, self.fused, self.scores,
+    def fuse_scores(self, with_vis=False, two_kernels=False):
+        aura.fuse_scores(self.views, self.params_two if two_kernels else self.params, self.xyz, self.temb, self.y,
+                         self.fused, self.scores,
                          count=self.count_fuse, prop=self.prop, label=self.label, pt_offsets=self.pt_offsets,
                          view_offsets=self.view_offsets, workspace=self.ws_fuse_scores,
                          vis=self.vis if with_vis else None)
@@ -89,6 +92,19 @@ class DeviceScene:
         """One pass of the whole path with visibility mask, fusion and scoring in one call (the mask and the view
         counts come out of the fusion; `count` is filled from its count output)."""
         self.fuse_scores(with_vis=True)
+        self.count.copy_(self.count_fuse)
+        self.property_integrate()
+
+    def step_two_kernels(self):
+        """`step` with the matrix-core fusion as two kernels (lists, then products)."""
+        self.project_visibility()
+        self.fuse_features(two_kernels=True)
+        self.material_scores()
+        self.property_integrate()
+
+    def step_combined_two_kernels(self):
+        """`step_combined` with the matrix-core fusion as two kernels."""
+        self.fuse_scores(with_vis=True, two_kernels=True)
         self.count.copy_(self.count_fuse)
         self.property_integrate()
 
@@ -122,7 +138,7 @@ def oracle_points(orc, scene, idx=None, flags=0, want_uvz=False):
     vo = None if single else s.view_offsets
     pv = orc.project_visibility(s.cam, s.depth, xyz, tau=s.tau, z_near=s.z_near, flags=flags & 1, pt_offsets=po,
                                 view_offsets=vo, vis_pitch=s.vis_pitch, want_diag=True, want_uvz=want_uvz)
-    fu = orc.fuse_features(s.cam, s.depth, s.feat, s.feat_dtype, xyz, tau=s.tau, z_near=s.z_near, flags=flags,
+    fu = orc.fuse_features(s.cam, s.depth, s.feat, s.feat_dtype, xyz, tau=s.tau, z_near=s.z_near, flags=flags & 3,
                            pt_offsets=po, view_offsets=vo)
     sc = orc.material_scores(fu["fused"], s.temb, s.y, T=s.temperature)
     return {**pv, "fused": fu["fused"], "count_fuse": fu["count"], **sc}

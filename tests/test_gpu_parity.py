@@ -45,7 +45,8 @@ def test_full_path_matches_oracle_on_reduced_scenes(H, orc, name, kw):
     print(f"\n[{name} {kw}] N={s.N} V={s.n_views} B={s.B} D={s.D} K={s.K} dtype={s.feat_dtype}", flush=True)
     d = H.DeviceScene(s, want_uvz=True)
     ref = H.oracle_points(orc, s, want_uvz=True)
-    for step in (d.step, d.step_combined):      # one call per stage; fusion and scoring in one call
+    # one call per stage; fusion and scoring in one call; both again with the matrix-core fusion as two kernels
+    for step in (d.step, d.step_combined, d.step_two_kernels, d.step_combined_two_kernels):
         d.clear_outputs()
         step()
         gpu = d.results()
@@ -77,6 +78,16 @@ def test_full_size_configs_on_sampled_points(H, orc, name):
     d.clear_outputs()
     d.step()
     _check_full_size(H, orc, s, d.results(), name)
+    d.clear_outputs()
+    d.step_combined()
+    one = d.results()
+    d.clear_outputs()
+    d.step_combined_two_kernels()
+    two = d.results()
+    _check_full_size(H, orc, s, two, name)
+    if name == "c2":     # every list fits both forms of the matrix-core fusion: the same products in the same order
+        for k in ("vis", "count", "fused", "scores", "prop", "label", "mass", "n_used"):
+            assert np.array_equal(one[k].view(np.uint8), two[k].view(np.uint8)), k
 
 
 def _check_full_size(H, orc, s, gpu, name):
@@ -203,10 +214,12 @@ def test_unsorted_points_on_the_matrix_core_path(H, orc, name, kw):
     d = H.DeviceScene(s)
     assert d.ws_fuse is not None
     ref = H.oracle_points(orc, s)
-    d.step_combined()        # tiles without k-steps are scored from their fused rows
-    print(H.compare_points(d.results(), ref, s), flush=True)
+    for step in (d.step_combined, d.step):     # tiles without k-steps are scored from their fused rows
+        d.clear_outputs()
+        step()
+        print(H.compare_points(d.results(), ref, s), flush=True)
     d.clear_outputs()
-    d.step()
+    d.step_two_kernels()
     gpu = d.results()
     print(H.compare_points(gpu, ref, s), flush=True)
     # tile headers (144 bytes each, at the start of the workspace): a k-step count of -1 marks the gather
