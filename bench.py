@@ -29,11 +29,11 @@ def fuse_algorithmic_bytes(s):
 
 
 # HBM bytes per aura_fuse_features call on workload c2 from the rocprofv3 counter runs summarised in
-# profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_prepare + k_tile_product, each
+# profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_fused, each
 # scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
 # the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = 869406603
-TRAFFIC_SOURCE_SHA256 = "cb020442f182d2aa4c0a7d80036c4a02ed42b90ce86010d5967d61fb4b9d90f0"
+TRAFFIC_C2_BYTES = 671229127
+TRAFFIC_SOURCE_SHA256 = "30467a29123ca46f069443ac855aad0d18629b6540867f32df1c090763db3088"
 
 
 def measured_traffic():
@@ -336,10 +336,11 @@ def main():
     tile = d.ws_fuse is not None
     gpu = d.results()
 
-    # Roofline of the dominant kernels: the fusion proper (k_tile_prepare + k_tile_product, or k_fuse_gather),
-    # which write the fused rows.  Inside aura_fuse_scores they cannot be bracketed by events, so the same two
-    # kernels are timed through aura_fuse_features (same launch configuration, same workspace layout) right
-    # after the timed steps, with events on the launch stream.
+    # Roofline of the dominant work: the fusion proper (the matrix-core kernels, or k_fuse_gather), which writes
+    # the fused rows.  Inside aura_fuse_scores it cannot be bracketed by events, so it is timed through
+    # aura_fuse_features (same inputs, same workspace) right after the timed steps, with events on the launch
+    # stream.  Where the scoring kernel needs the k-steps in memory aura_fuse_scores runs the fusion as two kernels
+    # and aura_fuse_features as one (see calls_ms for the whole call).
     fuse_reps = max(args.steps, 10)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     for _ in range(3):
@@ -368,7 +369,8 @@ def main():
     warm_each, cold_each = one_by_one(False), one_by_one(True)
     fuse_bytes = fuse_algorithmic_bytes(s)
     achieved = fuse_bytes / (fuse_ms * 1e-3) / 1e9
-    kernel = "aura_fuse_features: " + (f"k_tile_prepare + k_tile_product<{s.feat_dtype}, {s.D // 256} waves>" if tile
+    kernel = "aura_fuse_features: " + (f"matrix-core fusion <{s.feat_dtype}, {s.D // 256} product waves> (k_tile_fused where the "
+                                       "one-kernel form applies, else k_tile_prepare + k_tile_product)" if tile
                                        else "k_fuse_gather")
     traffic = measured_traffic() if (tile and args.workload == "c2") else None
     extras = {}

@@ -844,7 +844,8 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
 // producer asks for a ticket one tile ahead.  A tile whose list does not fit the buffer is fused by the producer itself
 // (per-point gather): the launch code only takes this kernel where that is rare.
 
-constexpr int kPBatch = 16;   // views per pass of the producer wave: two per trip, one per half wave
+constexpr int kPBatch = 16;   // views per pass of the producer waves: two per trip, one per half wave
+constexpr int kMaxProducers = 4;
 constexpr int kCamRows = 32;  // camera rows of the object kept in LDS for the producer
 constexpr int kOneKernelViews = 8;
 
@@ -861,9 +862,9 @@ struct ProducerScratch {
 
 struct TileSlot {    // what the product waves need to know about a staged tile
   int tile;          // index within the object; -1: no further tile
-  int nsteps;        // -1: fused by the producer
+  int nsteps;        // -1: fused by the producers
   int pad_[2];
-  int cnt[kTilePts];
+  int cnt[kMaxProducers][kTilePts];   // views that see each point, per producer wave
 };
 
 // Orders the producer wave's LDS traffic for the compiler.  The LDS unit handles the instructions of one wave in
@@ -874,73 +875,131 @@ __device__ __forceinline__ void wave_sync() {
   __builtin_amdgcn_wave_barrier();
 }
 
-// The point that lane `lane` of the producer handles in tile `blk` (lane % 32; the tile's first point where the object
-// has no such point).  Read one tile ahead so that the round trip to memory is not waited for.
+// The point that lane `lane` of a producer wave handles in tile `blk` (lane % 32; the tile's first point where the
+// object has no such point).
 __device__ __forceinline__ float3 tile_point(const FuseArgs& a, const ObjRange& ob, int blk, int lane) {
-  blk = max(min(blk, (ob.n_pts + kTilePts - 1) / kTilePts - 1), 0);   // a ticket past the end reads a tile that exists
   const int p = lane & 31, li0 = blk * kTilePts;
   const long long ip = ob.pt_begin + li0 + (li0 + p < ob.n_pts ? p : 0);
   return float3{a.xyz[3 * ip], a.xyz[3 * ip + 1], a.xyz[3 * ip + 2]};
 }
 
-// Builds tile `blk` of object `ob` into `stage` (room for `k_stage` k-steps) and `slot`.  Called by all 64 lanes of
-// the producer wave.  cam_lds: the object's camera rows in LDS.
-template <int DT, bool SEL>
+// Meeting point of the NP producer waves of a workgroup (the workgroup barrier belongs to the tile hand-over, which
+// the product waves take part in).  Every wave publishes the number of the meeting after its LDS traffic and waits
+// until the others have published it too; both producers pass the same meetings in the same order.  The wait is
+// bounded: a producer that never arrives (a programming error) ends in wrong results, not in a hung machine.
+template <int NP>
+__device__ __forceinline__ void producers_meet(volatile int* flags, int w, int& seq, int lane) {
+  wave_sync();
+  if constexpr (NP > 1) {
+    ++seq;
+    if (lane == 0) flags[w] = seq;
+    for (int spins = 0; spins < (1 << 16); ++spins) {
+      bool all = true;
+#pragma unroll
+      for (int o = 0; o < NP; ++o) all = all && (flags[o] - seq >= 0);
+      if (all) break;
+      __builtin_amdgcn_s_sleep(1);
+    }
+    wave_sync();
+  }
+}
+
+// What a producer wave knows about its pairs of one batch of views before the tests: projection, whether it lands in
+// the image, the depth texel (requested, maybe still on its way) and, with a given selection, whether the view is kept.
+template <int NP>
+struct ProjectedBatch {
+  Proj pj[kPBatch / 2 / NP];
+  float dep[kPBatch / 2 / NP];
+  bool fr[kPBatch / 2 / NP], kept[kPBatch / 2 / NP];
+};
+
+// First every projection and the request for its depth texel (and mask byte), nothing that waits for them: a wave has
+// nobody to hide a read behind, so the reads of all its pairs are in flight together - and, for the first batch of a
+// tile, while the wave still works on the tile before.
+template <bool SEL, int NP>
+__device__ __forceinline__ void project_batch(const FuseArgs& a, const ObjRange& ob, int blk, float3 pt, int vb0,
+                                              lds_floats cam_lds, int w, int lane, ProjectedBatch<NP>& f) {
+  constexpr int kTrips = kPBatch / 2 / NP;
+  const int p = lane & 31, h = lane >> 5;
+  const int nvb = min(kPBatch, ob.n_views - vb0);
+  const int li0 = blk * kTilePts;
+  const long long ip = ob.pt_begin + li0 + (li0 + p < ob.n_pts ? p : 0);
+#pragma unroll
+  for (int j = 0; j < kTrips; ++j) {
+    const int it = w + NP * j;
+    f.dep[j] = 1.0f;
+    f.fr[j] = false;
+    f.kept[j] = true;
+    f.pj[j] = Proj{0.0f, 0.0f, 0.0f};
+    if (2 * it >= nvb) continue;   // uniform
+    const int vl = min(2 * it + h, nvb - 1);
+    const int v = ob.view_begin + vb0 + vl;
+    // the camera rows come from the LDS copy, through a pointer that says so: a generic read would wait for every
+    // read in flight, the depth texels of the trips before included
+    f.pj[j] = project(cam_lds + (vb0 + vl) * 16, pt.x, pt.y, pt.z);
+    f.fr[j] = in_frustum(a.vis, f.pj[j]);
+    if (a.vis.depth) f.dep[j] = a.vis.depth[(long long)v * a.vis.H * a.vis.W + (f.fr[j] ? depth_texel(a.vis, f.pj[j]) : 0)];
+    if constexpr (SEL) f.kept[j] = view_kept(a, ip, vb0 + vl);
+  }
+}
+
+// Builds tile `blk` of object `ob` into `stage` (room for `k_stage` k-steps) and `slot`.  pt: the lane's point; pre:
+// the projected first batch of views (project_batch).  Called by all 64 lanes of
+// each of the NP producer waves (w = 0 .. NP - 1), which share the views of the tile: wave w takes the trips
+// it = w, w + NP, ... (two views per trip, one per half wave).  cam_lds: the object's camera rows in LDS.
+template <int DT, bool SEL, int NP>
 __device__ __forceinline__ void produce_tile(const FuseArgs& a, const TileWs& ws, bool keep, const ObjRange& ob, int blk,
-                                             float3 pt, char* stage, int k_stage, TileSlot* slot, ProducerScratch* sc,
-                                             lds_floats cam_lds, int lane) {
+                                             float3 pt, ProjectedBatch<NP>& pre, char* stage, int k_stage,
+                                             TileSlot* slot, ProducerScratch* sc, lds_floats cam_lds, volatile int* flags,
+                                             int w, int& seq, int lane) {
+  constexpr int kTrips = kPBatch / 2 / NP;   // trips of one wave per batch of views
   const int p = lane & 31, h = lane >> 5;
   const int Hf = a.feat.Hf, Wf = a.feat.Wf;
   const uint32_t row_bytes = (uint32_t)a.feat.D * 2u;
   const int li0 = blk * kTilePts;
   const bool p_valid = li0 + p < ob.n_pts;
   const long long ip = ob.pt_begin + li0 + (p_valid ? p : 0);
-  const float px = pt.x, py = pt.y, pz = pt.z;   // read by the caller one tile ahead (tile_point)
   TileStep* st = reinterpret_cast<TileStep*>(stage);
   int used = 0, cnt = 0;
   bool exhausted = false;
 
+  // zero weights of the whole buffer, shared by the waves: complete for everybody at the first meeting, before any
+  // weight lands
+  for (int q = w * kWave + lane; q < k_stage * 128; q += NP * kWave)
+    reinterpret_cast<u32x4*>(reinterpret_cast<char*>(&st[q >> 7]) + 64)[q & 127] = u32x4{0u, 0u, 0u, 0u};
+
   for (int vb0 = 0; vb0 < ob.n_views; vb0 += kPBatch) {
     const int nvb = min(kPBatch, ob.n_views - vb0);
-    wave_sync();   // the previous batch is done with the tables
-    reinterpret_cast<u32x4*>(&sc->bits[0][0])[lane] = u32x4{0u, 0u, 0u, 0u};
-    reinterpret_cast<u32x4*>(&sc->bits[0][0])[lane + kWave] = u32x4{0u, 0u, 0u, 0u};
-
-    // ---- A: project and test; bounding box of the touched cells per view.  First every projection and the request
-    // for its depth texel (and, with a given selection, its mask byte), then the tests: the wave has nobody to hide
-    // a read behind, so the reads of all its pairs are in flight together.
-    PairRec pr[kPBatch / 2];
-    Proj pj[kPBatch / 2];
-    float dep[kPBatch / 2];
-    bool fr[kPBatch / 2], kept[kPBatch / 2];
+    if (vb0 > 0) producers_meet<NP>(flags, w, seq, lane);   // the previous batch is done with the tables
+    // the maps of this wave's views (view 2 it + h of trip it): 32 words each
 #pragma unroll
-    for (int it = 0; it < kPBatch / 2; ++it) {
-      dep[it] = 1.0f;
-      fr[it] = false;
-      kept[it] = true;
-      if (2 * it >= nvb) continue;   // uniform
-      const int vl = min(2 * it + h, nvb - 1);
-      const int v = ob.view_begin + vb0 + vl;
-      // the camera rows come from the LDS copy, through a pointer that says so: a generic read would wait for every
-      // read in flight, the depth texels of the trips before included
-      pj[it] = project(cam_lds + (vb0 + vl) * 16, px, py, pz);
-      fr[it] = in_frustum(a.vis, pj[it]);
-      if (a.vis.depth) dep[it] = a.vis.depth[(long long)v * a.vis.H * a.vis.W + (fr[it] ? depth_texel(a.vis, pj[it]) : 0)];
-      if constexpr (SEL) kept[it] = view_kept(a, ip, vb0 + vl);
+    for (int j = 0; j < kTrips; ++j) {
+      const int it = w + NP * j;
+      reinterpret_cast<u32x4*>(&sc->bits[2 * it][0])[lane & 15] = u32x4{0u, 0u, 0u, 0u};   // 16 lanes x 16 bytes = two views
     }
+    wave_sync();
+
+    // ---- A: project and test; bounding box of the touched cells per view.  The projections and the requests for the
+    // depth texels of the first batch were made a tile ago (project_batch); later batches make them here.
+    PairRec pr[kTrips];
+    if (vb0 > 0) project_batch<SEL, NP>(a, ob, blk, pt, vb0, cam_lds, w, lane, pre);
+    Proj (&pj)[kTrips] = pre.pj;
+    float (&dep)[kTrips] = pre.dep;
+    bool (&fr)[kTrips] = pre.fr, (&kept)[kTrips] = pre.kept;
 #pragma unroll
-    for (int it = 0; it < kPBatch / 2; ++it) {
-      pr[it].xy = -1;
-      pr[it].ax = pr[it].ay = 0.0f;
+    for (int j = 0; j < kTrips; ++j) {
+      const int it = w + NP * j;
+      pr[j].xy = -1;
+      pr[j].ax = pr[j].ay = 0.0f;
       if (2 * it >= nvb) continue;   // uniform
       const int vl = 2 * it + h;
-      const bool seen = vl < nvb && p_valid && fr[it] && kept[it] && (a.vis.frustum_only || passes_depth(a.vis, pj[it], dep[it]));
+      const bool seen = vl < nvb && p_valid && fr[j] && kept[j] && (a.vis.frustum_only || passes_depth(a.vis, pj[j], dep[j]));
       s16x2 lo2 = {0x7fff, 0x7fff}, hi2 = {-1, -1};
       if (seen) {
-        const Tap tx = tap_axis(pj[it].u, a.feat.pitch_x, Wf), ty = tap_axis(pj[it].v, a.feat.pitch_y, Hf);
-        pr[it].ax = tx.a;
-        pr[it].ay = ty.a;
-        pr[it].xy = (ty.i0 << 16) | tx.i0;
+        const Tap tx = tap_axis(pj[j].u, a.feat.pitch_x, Wf), ty = tap_axis(pj[j].v, a.feat.pitch_y, Hf);
+        pr[j].ax = tx.a;
+        pr[j].ay = ty.a;
+        pr[j].xy = (ty.i0 << 16) | tx.i0;
         lo2 = s16x2{(short)tx.i0, (short)ty.i0};
         hi2 = s16x2{(short)tx.i1, (short)ty.i1};
         ++cnt;
@@ -958,32 +1017,14 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const TileWs& ws
       }
     }
     wave_sync();
-    if (a.out_vis && lane < kTilePts && li0 + lane < ob.n_pts) {   // the mask of Eq. 1 for this batch of views
-      uint8_t* __restrict__ vrow = a.out_vis + (ob.pt_begin + li0 + lane) * a.vis_pitch + vb0;
-      if ((a.vis_pitch & 3) == 0) {
-        for (int v4 = 0; v4 < nvb; v4 += 4) {
-          uint32_t w = 0;
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (v4 + e < nvb) w |= ((sc->vmask[v4 + e] >> lane) & 1u) << (8 * e);
-          if (v4 + 4 <= nvb) {
-            *reinterpret_cast<uint32_t*>(vrow + v4) = w;
-          } else {
-            for (int e = 0; v4 + e < nvb; ++e) vrow[v4 + e] = (uint8_t)((w >> (8 * e)) & 1u);
-          }
-        }
-      } else {
-        for (int v = 0; v < nvb; ++v) vrow[v] = (uint8_t)((sc->vmask[v] >> lane) & 1u);
-      }
-    }
 
-    // ---- B: mark the touched cells of every view that uses a map
+    // ---- B: mark the touched cells of this wave's views that use a map
 #pragma unroll
-    for (int it = 0; it < kPBatch / 2; ++it) {
-      if (pr[it].xy < 0) continue;
-      const int vl = 2 * it + h;
+    for (int j = 0; j < kTrips; ++j) {
+      if (pr[j].xy < 0) continue;
+      const int vl = 2 * (w + NP * j) + h;
       if (sc->mode[vl] != 1) continue;
-      const int x0 = pr[it].xy & 0xffff, y0 = pr[it].xy >> 16;
+      const int x0 = pr[j].xy & 0xffff, y0 = pr[j].xy >> 16;
       const int bit = (y0 - sc->win[vl][1]) * kWinSide + (x0 - sc->win[vl][0]);
       const bool has_x1 = x0 + 1 < Wf, has_y1 = y0 + 1 < Hf;
       atomicOr(&sc->bits[vl][bit >> 5], 1u << (bit & 31));
@@ -991,73 +1032,97 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const TileWs& ws
       if (has_y1) atomicOr(&sc->bits[vl][(bit + kWinSide) >> 5], 1u << ((bit + kWinSide) & 31));
       if (has_x1 && has_y1) atomicOr(&sc->bits[vl][(bit + kWinSide + 1) >> 5], 1u << ((bit + kWinSide + 1) & 31));
     }
-    wave_sync();
-    {   // list length of every view, exclusive scan over the views
-      int n = 0;
-      if (lane < nvb) {
-        if (sc->mode[lane] == 1) {
-#pragma unroll 8
-          for (int w = 0; w < kWinSide; ++w) {
-            sc->wbase[lane][w] = (uint16_t)n;
-            n += __popc(sc->bits[lane][w]);
+    producers_meet<NP>(flags, w, seq, lane);   // the maps, boxes and masks of all views are complete
+
+    if (w == 0 && a.out_vis && lane < kTilePts && li0 + lane < ob.n_pts) {   // the mask of Eq. 1 for this batch of views
+      uint8_t* __restrict__ vrow = a.out_vis + (ob.pt_begin + li0 + lane) * a.vis_pitch + vb0;
+      if ((a.vis_pitch & 3) == 0) {
+        for (int v4 = 0; v4 < nvb; v4 += 4) {
+          uint32_t wd = 0;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (v4 + e < nvb) wd |= ((sc->vmask[v4 + e] >> lane) & 1u) << (8 * e);
+          if (v4 + 4 <= nvb) {
+            *reinterpret_cast<uint32_t*>(vrow + v4) = wd;
+          } else {
+            for (int e = 0; v4 + e < nvb; ++e) vrow[v4 + e] = (uint8_t)((wd >> (8 * e)) & 1u);
           }
-        } else if (sc->mode[lane] == 2) {
-          n = 4 * __popc(sc->vmask[lane]);
         }
+      } else {
+        for (int v = 0; v < nvb; ++v) vrow[v] = (uint8_t)((sc->vmask[v] >> lane) & 1u);
       }
-      int inc = n;
+    }
+    {   // list length of every view, exclusive scan over the views: every producer wave does it (same values).
+        // lane = (view, quarter of the map's rows): set bits before each row within the quarter, then the quarters'
+        // totals through lane exchanges
+      static_assert(kPBatch == 16 && kWinSide == 32, "lane = 16 views x 4 quarters of 8 rows");
+      const int v = lane & 15, qd = lane >> 4;
+      const bool map = v < nvb && sc->mode[v] == 1;
+      int before[8], n = 0;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        before[e] = n;
+        n += map ? __popc(sc->bits[v][8 * qd + e]) : 0;
+      }
+      const int n0 = __shfl(n, v, kWave), n1 = __shfl(n, v + 16, kWave), n2 = __shfl(n, v + 32, kWave), n3 = __shfl(n, v + 48, kWave);
+      const int off = (qd > 0 ? n0 : 0) + (qd > 1 ? n1 : 0) + (qd > 2 ? n2 : 0);
+      if (map) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sc->wbase[v][8 * qd + e] = (uint16_t)(off + before[e]);
+      }
+      int total = n0 + n1 + n2 + n3;                                   // lanes 0 .. 15: the view's list length
+      if (v < nvb && sc->mode[v] == 2) total = 4 * __popc(sc->vmask[v]);
+      int inc = lane < kPBatch ? total : 0;
 #pragma unroll
       for (int o = 1; o < kPBatch; o <<= 1) {
         const int up = __shfl_up(inc, o, kWave);
         if (lane >= o) inc += up;
       }
-      if (lane < kPBatch) sc->base[lane] = inc - n;
+      if (lane < kPBatch) sc->base[lane] = inc - total;
       if (lane == kPBatch - 1) sc->base[kPBatch] = inc;
     }
     wave_sync();
     const int L = sc->base[kPBatch];
     const int nsteps = (L + kStepCells - 1) / kStepCells;
-    if (used + nsteps > k_stage) {   // uniform
+    if (used + nsteps > k_stage) {   // uniform, and the same in every producer wave
       exhausted = true;
       break;
     }
     TileStep* __restrict__ out = st + used;
     used += nsteps;
 
-    // ---- C: zero weights, the cells of the list, then the weights in the operand layout
-    for (int q = lane; q < nsteps * 128; q += kWave)
-      reinterpret_cast<u32x4*>(reinterpret_cast<char*>(&out[q >> 7]) + 64)[q & 127] = u32x4{0u, 0u, 0u, 0u};
-    if (lane < nsteps * kStepCells - L) {   // entries that pad the last k-step point at a cell that exists
+    // ---- C: the cells of the list, then the weights in the operand layout
+    if (w == 0 && lane < nsteps * kStepCells - L) {   // entries that pad the last k-step point at a cell that exists
       const int idx = L + lane;
       out[idx >> 4].cell[idx & 15] = (uint32_t)((ob.view_begin + vb0) * Hf * Wf) * row_bytes;
     }
-    {   // cells of the views with a map: lane = (view, eight rows of the map)
-      const int vl = lane >> 2;
+    {   // cells of the views with a map: lane = (view, rows of the map); the waves share the rows
+      constexpr int kRows = 8 / NP;
+      const int vl = lane >> 2, row0 = (kWinSide / NP) * w + kRows * (lane & 3);
       if (vl < nvb && sc->mode[vl] == 1) {
         const int cell0 = (ob.view_begin + vb0 + vl) * Hf + sc->win[vl][1], wx = sc->win[vl][0];
-        for (int w = 8 * (lane & 3); w < 8 * (lane & 3) + 8; ++w) {
-          uint32_t bits = sc->bits[vl][w];
-          int q = sc->base[vl] + sc->wbase[vl][w];
+        for (int wd = row0; wd < row0 + kRows; ++wd) {
+          uint32_t bits = sc->bits[vl][wd];
+          int q = sc->base[vl] + sc->wbase[vl][wd];
           while (bits) {
             const int b = __builtin_ctz(bits);
             bits &= bits - 1;
-            out[q >> 4].cell[q & 15] = (uint32_t)((cell0 + w) * Wf + wx + b) * row_bytes;
+            out[q >> 4].cell[q & 15] = (uint32_t)((cell0 + wd) * Wf + wx + b) * row_bytes;
             ++q;
           }
         }
       }
     }
-    wave_sync();   // the zeros are in place before the weights land
     // list positions of the four cells of every pair first (LDS reads only), then the stores: with both in one loop
     // the reads of a pair would wait behind the stores of the pair before it
-    int idx[kPBatch / 2][4];
+    int idx[kTrips][4];
 #pragma unroll
-    for (int it = 0; it < kPBatch / 2; ++it) {
+    for (int j = 0; j < kTrips; ++j) {
 #pragma unroll
-      for (int k = 0; k < 4; ++k) idx[it][k] = 0;
-      if (pr[it].xy < 0) continue;
-      const int vl = 2 * it + h;
-      const int x0 = pr[it].xy & 0xffff, y0 = pr[it].xy >> 16;
+      for (int k = 0; k < 4; ++k) idx[j][k] = 0;
+      if (pr[j].xy < 0) continue;
+      const int vl = 2 * (w + NP * j) + h;
+      const int x0 = pr[j].xy & 0xffff, y0 = pr[j].xy >> 16;
       const bool has_x1 = x0 + 1 < Wf, has_y1 = y0 + 1 < Hf;
       const bool on[4] = {true, has_x1, has_y1, has_x1 && has_y1};
       if (sc->mode[vl] == 1) {
@@ -1066,32 +1131,32 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const TileWs& ws
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const int b = on[k] ? bs[k] : bit;
-          idx[it][k] = sc->base[vl] + sc->wbase[vl][b >> 5] + __popc(sc->bits[vl][b >> 5] & ((1u << (b & 31)) - 1u));
+          idx[j][k] = sc->base[vl] + sc->wbase[vl][b >> 5] + __popc(sc->bits[vl][b >> 5] & ((1u << (b & 31)) - 1u));
         }
       } else {
         const int first = sc->base[vl] + 4 * __popc(sc->vmask[vl] & ((1u << p) - 1u));
 #pragma unroll
-        for (int k = 0; k < 4; ++k) idx[it][k] = -1 - (first + k);   // negative: a private entry, its cell is still to be written
+        for (int k = 0; k < 4; ++k) idx[j][k] = -1 - (first + k);   // negative: a private entry, its cell is still to be written
       }
     }
     wave_sync();
 #pragma unroll
-    for (int it = 0; it < kPBatch / 2; ++it) {
-      if (pr[it].xy < 0) continue;
-      const int vl = 2 * it + h;
-      const int x0 = pr[it].xy & 0xffff, y0 = pr[it].xy >> 16;
-      const float ax = pr[it].ax, ay = pr[it].ay;
+    for (int j = 0; j < kTrips; ++j) {
+      if (pr[j].xy < 0) continue;
+      const int vl = 2 * (w + NP * j) + h;
+      const int x0 = pr[j].xy & 0xffff, y0 = pr[j].xy >> 16;
+      const float ax = pr[j].ax, ay = pr[j].ay;
       const bool has_x1 = x0 + 1 < Wf, has_y1 = y0 + 1 < Hf;
       const float wgt[4] = {(1.0f - ax) * (1.0f - ay), ax * (1.0f - ay), (1.0f - ax) * ay, ax * ay};
       const bool on[4] = {true, has_x1, has_y1, has_x1 && has_y1};
-      if (idx[it][0] < 0) {
+      if (idx[j][0] < 0) {
         const int cell0 = (ob.view_begin + vb0 + vl) * Hf;
         const int x1 = has_x1 ? x0 + 1 : x0, y1 = has_y1 ? y0 + 1 : y0;
         const int cx[4] = {x0, x1, x0, x1}, cy[4] = {y0, y0, y1, y1};
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
-          idx[it][k] = -1 - idx[it][k];
-          out[idx[it][k] >> 4].cell[idx[it][k] & 15] = (uint32_t)((cell0 + cy[k]) * Wf + cx[k]) * row_bytes;
+          idx[j][k] = -1 - idx[j][k];
+          out[idx[j][k] >> 4].cell[idx[j][k] & 15] = (uint32_t)((cell0 + cy[k]) * Wf + cx[k]) * row_bytes;
         }
       }
 #pragma unroll
@@ -1099,8 +1164,8 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const TileWs& ws
         if (on[k]) {
           uint16_t hi, lo;
           split_weight<DT>(wgt[k], hi, lo);
-          const int c = idx[it][k] & 15;
-          TileStep* stp = out + (idx[it][k] >> 4);
+          const int c = idx[j][k] & 15;
+          TileStep* stp = out + (idx[j][k] >> 4);
           reinterpret_cast<uint16_t*>(&stp->a_hi[(c >> 3) * kTilePts + p])[c & 7] = hi;
           reinterpret_cast<uint16_t*>(&stp->a_lo[(c >> 3) * kTilePts + p])[c & 7] = lo;
         }
@@ -1108,35 +1173,31 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const TileWs& ws
     }
   }
 
-  if (a.out_vis && lane < kTilePts && li0 + lane < ob.n_pts) {   // mask columns beyond the object's views
+  if (w == 0 && a.out_vis && lane < kTilePts && li0 + lane < ob.n_pts) {   // mask columns beyond the object's views
     for (int j = ob.n_views; j < a.vis_pitch; ++j) a.out_vis[(ob.pt_begin + li0 + lane) * a.vis_pitch + j] = 0;
   }
-  const int total = cnt + __shfl_xor(cnt, 32, kWave);   // views that see point lane % 32
+  const int mine = cnt + __shfl_xor(cnt, 32, kWave);   // views of this wave that see point lane % 32
   wave_sync();
-  if (lane == 0) {
+  if (w == 0 && lane == 0) {
     slot->tile = blk;
     slot->nsteps = exhausted ? -1 : used;
   }
-  if (lane < kTilePts) slot->cnt[lane] = total;
-  if (exhausted) {
-    gather_tile<DT>(a, ob, li0, 0, 1, lane);   // writes the rows and the counts of the tile itself
-  } else if (a.out_count && lane < kTilePts && li0 + lane < ob.n_pts) {
-    a.out_count[ob.pt_begin + li0 + lane] = total;
-  }
+  if (lane < kTilePts) slot->cnt[w][lane] = mine;
+  if (exhausted) gather_tile<DT>(a, ob, li0, w, NP, lane);   // writes the rows, the counts and the mask of the tile itself
   if (keep) {   // the scoring kernel reads the k-steps and the header from memory
-    TileHdr* __restrict__ hdr = ws.hdr + ob.tile_begin + blk;
-    if (lane == 0) hdr->nsteps = exhausted ? -1 : used;
-    if (lane < kTilePts) hdr->cnt[lane] = total;
+    if (w == 0 && lane == 0) ws.hdr[ob.tile_begin + blk].nsteps = exhausted ? -1 : used;
     if (!exhausted) {
+      producers_meet<NP>(flags, w, seq, lane);   // every wave's weights are in the buffer
       u32x4* __restrict__ dst = reinterpret_cast<u32x4*>(ws.steps + (long long)(ob.tile_begin + blk) * ws.quota);
       const u32x4* src = reinterpret_cast<const u32x4*>(stage);
-      for (int q = lane; q < used * (int)(sizeof(TileStep) / 16); q += kWave) dst[q] = src[q];
+      for (int q = w * kWave + lane; q < used * (int)(sizeof(TileStep) / 16); q += NP * kWave) dst[q] = src[q];
     }
   }
 }
 
-template <int DT, int S, int H, int PF, bool SEL>
-__global__ __launch_bounds__(kWave* (S + 1)) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// S product waves and NP producer waves per workgroup.
+template <int DT, int S, int H, int PF, bool SEL, int NP>
+__global__ __launch_bounds__(kWave* (S + NP)) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
   constexpr int kSpan = kHalf * H;
   constexpr int kStage = stage_steps_for<S * H / 2>();
@@ -1144,7 +1205,9 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
   __shared__ TileSlot s_slot[2];
   __shared__ __attribute__((aligned(16))) ProducerScratch s_sc;
   __shared__ float s_ss[2][S][kTilePts];
-  __shared__ __attribute__((aligned(16))) float s_cam[kCamRows][16];   // the object's camera rows, for the producer
+  __shared__ __attribute__((aligned(16))) float s_cam[kCamRows][16];   // the object's camera rows, for the producers
+  __shared__ int s_plan[4];      // tickets of the workgroup's tiles, k-th tile in slot k & 3
+  __shared__ int s_flags[kMaxProducers];   // meeting numbers of the producer waves
 
   const ObjRange ob = tab.o[blockIdx.y];
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
@@ -1155,59 +1218,87 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
   unsigned* __restrict__ ctr = a.counters + blockIdx.y * kXcd + xcd;
 
   const int tid = threadIdx.x, lane = tid % kWave;
-  const int span = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave index; wave S is the producer
-  const bool producer = span == S;
+  const int span = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave index; waves S .. S + NP - 1 are the producers
+  const bool producer = span >= S;
   const lds_floats cam_lds = (lds_floats)&s_cam[0][0];   // the launch code takes this kernel for up to kCamRows views
-  if (producer) {
-    for (int q = lane; q < ob.n_views * 16; q += kWave) s_cam[q >> 4][q & 15] = fa.vis.cam[(long long)ob.view_begin * 16 + q];
-    wave_sync();
-  }
   const int m = lane & 31, g = lane >> 5;
   const int D = a.D;
   const uint32_t lane_off = (uint32_t)(span * kSpan + 4 * m) * 2u;
 
-  // producer: tickets one tile ahead (the counters are zeroed by the launch that precedes this kernel)
-  // the answer stays in a vector register and is only read one tile later, so nobody waits for the round trip
-  auto ticket = [&]() {
-    int t = 0;
-    if (lane == 0) t = (int)atomicAdd(ctr, 1u);
-    return t;
-  };
   if (producer) {
-    // tickets and points run ahead of the tile being built: the ticket of tile i + 2 is asked for and the points of tile
-    // i + 1 are read before tile i is built, and both are only looked at after it
-    const int t0 = __builtin_amdgcn_readfirstlane(ticket());
-    int t1_raw = ticket();
-    if (t0 < len) {
-      produce_tile<DT, SEL>(fa, ws, keep != 0, ob, r0 + t0, tile_point(fa, ob, r0 + t0, lane), s_steps[0], kStage, &s_slot[0],
-                            &s_sc, cam_lds, lane);
-    } else if (lane == 0) {
-      s_slot[0].tile = -1;
-      s_slot[0].nsteps = 0;
+    const int w = span - S;
+    int seq = 0;
+    // The first producer wave takes the tickets (the counters are zeroed by the launch that precedes this kernel) and
+    // publishes them in s_plan, slot k & 3 for the k-th tile of the workgroup, two tiles ahead of the one being built:
+    // at the top of a trip every producer knows the tile it builds now and the one after it.  Values of len or more
+    // mean that the XCD's range is used up.
+    auto ticket = [&]() {
+      int t = 0;
+      if (lane == 0) t = (int)atomicAdd(ctr, 1u);
+      return t;
+    };
+    int t_raw = 0;   // the ticket of tile k + 3 while tile k + 1 is built (lane 0 of the first producer)
+    if (w == 0) {
+      for (int q = lane; q < ob.n_views * 16; q += kWave) s_cam[q >> 4][q & 15] = fa.vis.cam[(long long)ob.view_begin * 16 + q];
+      const int t0 = ticket(), t1 = ticket(), t2 = ticket();
+      t_raw = ticket();
+      if (lane == 0) {
+        s_plan[0] = t0;
+        s_plan[1] = t1;
+        s_plan[2] = t2;
+        for (int o = 0; o < kMaxProducers; ++o) s_flags[o] = 0;
+      }
     }
-    int t = __builtin_amdgcn_readfirstlane(t1_raw);            // the next tile to build
-    float3 pt = tile_point(fa, ob, r0 + t, lane);
-    int t_raw = t < len ? ticket() : len;                       // the one after it
+    __syncthreads();   // camera rows, the first plans and the meeting flags are in LDS
+    const int last_tile = nblk - 1;
+    // a plan past the end reads (and projects) a tile that exists; it is never built
+    auto tile_of = [&](int t) { return min(r0 + t, last_tile); };
+    ProjectedBatch<NP> pre;
+    float3 pt;   // the lane's point of the tile that the next trip builds
+    {
+      const int t0 = s_plan[0], t1 = s_plan[1];
+      const float3 pt0 = tile_point(fa, ob, tile_of(t0), lane);
+      const float3 pt1 = tile_point(fa, ob, tile_of(t1), lane);
+      project_batch<SEL, NP>(fa, ob, tile_of(t0), pt0, 0, cam_lds, w, lane, pre);
+      if (t0 < len) {
+        produce_tile<DT, SEL, NP>(fa, ws, keep != 0, ob, r0 + t0, pt0, pre, s_steps[0], kStage, &s_slot[0], &s_sc, cam_lds, s_flags,
+                                  w, seq, lane);
+      } else if (w == 0 && lane == 0) {
+        s_slot[0].tile = -1;
+        s_slot[0].nsteps = 0;
+      }
+      project_batch<SEL, NP>(fa, ob, tile_of(t1), pt1, 0, cam_lds, w, lane, pre);
+      pt = pt1;
+    }
     __syncthreads();
-    // Two loops with the same number of barriers: one trip per tile, ended by the barrier after which the buffers change
-    // hands.  Both leave when the slot they look at says that there is no further tile (written before the last barrier,
-    // so every wave of the workgroup sees the same value).
-    int buf = 0;
+    // Producers and product waves run loops with the same number of barriers: one trip per tile, ended by the barrier
+    // after which the buffers change hands.  All leave when the slot they look at says that there is no further tile
+    // (written before the last barrier, so every wave of the workgroup sees the same value).
+    int buf = 0, k = 1;   // the trip builds the k-th tile of the workgroup
     while (s_slot[buf].tile >= 0) {
+      const int t = s_plan[k & 3], tn = s_plan[(k + 1) & 3];
+      const float3 pt_next = tile_point(fa, ob, tile_of(tn), lane);   // requested now, looked at after this tile is built
       if (t < len) {
-        produce_tile<DT, SEL>(fa, ws, keep != 0, ob, r0 + t, pt, s_steps[buf ^ 1], kStage, &s_slot[buf ^ 1], &s_sc, cam_lds, lane);
-        t = __builtin_amdgcn_readfirstlane(t_raw);
-        pt = tile_point(fa, ob, r0 + t, lane);
-        if (t < len) t_raw = ticket();
-      } else if (lane == 0) {
+        produce_tile<DT, SEL, NP>(fa, ws, keep != 0, ob, r0 + t, pt, pre, s_steps[buf ^ 1], kStage, &s_slot[buf ^ 1], &s_sc, cam_lds,
+                                  s_flags, w, seq, lane);
+      } else if (w == 0 && lane == 0) {
         s_slot[buf ^ 1].tile = -1;
         s_slot[buf ^ 1].nsteps = 0;
       }
+      pt = pt_next;
+      project_batch<SEL, NP>(fa, ob, tile_of(tn), pt, 0, cam_lds, w, lane, pre);   // its depth texels arrive during the barrier
+      if (w == 0) {   // the plan of tile k + 2: its slot (k + 2) & 3 held tile k - 2, which nobody looks at any more
+        const int t3 = __builtin_amdgcn_readfirstlane(t_raw);
+        if (lane == 0) s_plan[(k + 2) & 3] = t3;
+        if (t3 < len) t_raw = ticket();
+      }
       __syncthreads();
       buf ^= 1;
+      ++k;
     }
     return;
   }
+  __syncthreads();
   __syncthreads();
 
   StepA wa[2];
@@ -1221,8 +1312,12 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
     const int blk = s_slot[buf].tile;   // uniform over the workgroup: written before the last barrier
     if (blk < 0) break;
     const int n = s_slot[buf].nsteps;
+    int my_cnt = 0;                      // views that see point (lane % 32) of this tile
+#pragma unroll
+    for (int o = 0; o < NP; ++o) my_cnt += s_slot[buf].cnt[o][m];
+    if (n >= 0 && span == 0 && tid < kTilePts && fa.out_count && blk * kTilePts + tid < ob.n_pts)
+      fa.out_count[ob.pt_begin + blk * kTilePts + tid] = my_cnt;
 
-    const int my_cnt = s_slot[buf].cnt[m];   // views that see point (lane % 32) of this tile
     f32x16 acc[4 * H];
 #pragma unroll
     for (int t = 0; t < 4 * H; ++t)
@@ -1262,7 +1357,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       ss = half_wave_sum(ss);
       if (m == 31) s_ss[buf][span][row] = ss;
     }
-    __syncthreads();   // the one barrier of a tile: the sums are in LDS, the producer has staged the next tile, and
+    __syncthreads();   // the one barrier of a tile: the sums are in LDS, the producers have staged the next tile, and
                        // every product wave is done with this tile's buffer
 
     float factor;
@@ -1270,7 +1365,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       const float inv = my_cnt > 0 ? 1.0f / (float)my_cnt : 0.0f;
       float tot = 0.0f;
 #pragma unroll
-      for (int w = 0; w < S; ++w) tot += s_ss[buf][w][m];
+      for (int wv = 0; wv < S; ++wv) tot += s_ss[buf][wv][m];
       const float normed = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
       factor = a.mean_only ? inv : normed;
     }
@@ -1353,15 +1448,16 @@ bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes)
          D / 256 != 5 && feat_bytes <= 0xffffffffll;
 }
 
-// Whether the one-kernel form is taken: the lists of (nearly) all tiles must fit the LDS buffer of kStage k-steps, and
-// when the scoring kernel wants the k-steps in memory, the tile's share of the workspace as well.  Measured need on
-// spatially sorted points: 0.3 to 0.4 k-steps per view for coarse grids, up to 1 for pixel-sized cells.
-static bool one_kernel_fits(const FuseArgs& a, int k_stage, int quota, int views_per_obj) {
+// How many producer waves the one-kernel form takes for this launch; 0: the two kernels.  The lists of (nearly) all
+// tiles must fit the LDS buffer of kStage k-steps, and when the scoring kernel wants the k-steps in memory, the
+// tile's share of the workspace as well.  Measured need on spatially sorted points: 0.3 to 0.4 k-steps per view for
+// coarse grids, up to 1 for pixel-sized cells.  One producer wave keeps up with the product waves for a few views per
+// object; beyond that four share the views of a tile and a compute unit holds one workgroup.
+static int one_kernel_producers(const FuseArgs& a, int k_stage, int quota, int views_per_obj) {
   const float per_view = (a.feat.pitch_x >= 4.0f && a.feat.pitch_y >= 4.0f) ? 0.5f : 1.0f;
-  // one producer wave keeps up with the product waves for up to kOneKernelViews views per object (measured: 4 views
-  // 2.7 against 3.6 ms on 6.4 M points; 16 views on a par; 24 views slower than the two kernels)
-  return !a.two_kernels && k_stage <= quota && views_per_obj <= kOneKernelViews &&
-         (float)views_per_obj * per_view <= (float)k_stage;
+  if (a.two_kernels || k_stage > quota || views_per_obj > kCamRows || (float)views_per_obj * per_view > (float)k_stage) return 0;
+  if (views_per_obj <= kOneKernelViews) return 1;
+  return a.out_factor ? 0 : 4;   // measured: with the k-steps also going to memory the two kernels are faster here
 }
 
 template <int DT, int S, int H, int PF>
@@ -1372,16 +1468,22 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
               ws.quota, a.fused, a.out_factor, a.norm_eps, a.mean_only};
   int max_views = 0;
   for (int t = 0; t < n_obj; ++t) max_views = std::max(max_views, tab.o[t].n_views);
-  if (one_kernel_fits(a, stage_steps_for<S * H / 2>(), ws.quota, max_views)) {
+  const int np = one_kernel_producers(a, stage_steps_for<S * H / 2>(), ws.quota, max_views);
+  if (np > 0) {
     hipLaunchKernelGGL(k_clear_counters, dim3((n_obj * kXcd + 63) / 64), dim3(64), 0, stream, pa.counters, n_obj * kXcd);
-    // two workgroups fit a compute unit; several objects in one launch share the machine
-    const int groups = std::max(kXcd, std::min(max_tiles, (kFusedGroupsMax / n_obj + kXcd - 1) / kXcd * kXcd));
-    const dim3 grid(std::min(groups, max_tiles), n_obj), block(kWave * (S + 1));
+    // with one producer wave two workgroups fit a compute unit, with four one; several objects in one launch share
+    // the machine
+    const int groups_max = np == 1 ? kFusedGroupsMax : kFusedGroupsMax / 2;
+    const int groups = std::max(kXcd, std::min(max_tiles, (groups_max / n_obj + kXcd - 1) / kXcd * kXcd));
+    const dim3 grid(std::min(groups, max_tiles), n_obj), block(kWave * (S + np));
     const int keep = a.out_factor != nullptr;   // the scoring kernel follows and reads the k-steps
-    if (a.in_mask)
-      hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, true>), grid, block, 0, stream, a, pa, ws, keep, tab);
-    else
-      hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false>), grid, block, 0, stream, a, pa, ws, keep, tab);
+    if (np == 1) {
+      if (a.in_mask) hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, true, 1>), grid, block, 0, stream, a, pa, ws, keep, tab);
+      else hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 1>), grid, block, 0, stream, a, pa, ws, keep, tab);
+    } else {
+      if (a.in_mask) hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, true, 4>), grid, block, 0, stream, a, pa, ws, keep, tab);
+      else hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 4>), grid, block, 0, stream, a, pa, ws, keep, tab);
+    }
     return hipGetLastError();
   }
   if (a.in_mask)
