@@ -958,7 +958,6 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const TileWs& ws
   const uint32_t row_bytes = (uint32_t)a.feat.D * 2u;
   const int li0 = blk * kTilePts;
   const bool p_valid = li0 + p < ob.n_pts;
-  const long long ip = ob.pt_begin + li0 + (p_valid ? p : 0);
   TileStep* st = reinterpret_cast<TileStep*>(stage);
   int used = 0, cnt = 0;
   bool exhausted = false;
@@ -1452,12 +1451,14 @@ bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes)
 // tiles must fit the LDS buffer of kStage k-steps, and when the scoring kernel wants the k-steps in memory, the
 // tile's share of the workspace as well.  Measured need on spatially sorted points: 0.3 to 0.4 k-steps per view for
 // coarse grids, up to 1 for pixel-sized cells.  One producer wave keeps up with the product waves for a few views per
-// object; beyond that four share the views of a tile and a compute unit holds one workgroup.
-static int one_kernel_producers(const FuseArgs& a, int k_stage, int quota, int views_per_obj) {
+// object; beyond that four share the views of a tile and a compute unit holds one workgroup of at most eight waves
+// (two per SIMD: a product wave needs about 250 registers).
+static int one_kernel_producers(const FuseArgs& a, int k_stage, int quota, int views_per_obj, int product_waves) {
   const float per_view = (a.feat.pitch_x >= 4.0f && a.feat.pitch_y >= 4.0f) ? 0.5f : 1.0f;
   if (a.two_kernels || k_stage > quota || views_per_obj > kCamRows || (float)views_per_obj * per_view > (float)k_stage) return 0;
   if (views_per_obj <= kOneKernelViews) return 1;
-  return a.out_factor ? 0 : 4;   // measured: with the k-steps also going to memory the two kernels are faster here
+  if (product_waves + 4 > 8) return 0;
+  return a.out_factor ? 0 : 4;   // measured: with the k-steps also going to memory the two kernels are as fast or faster here
 }
 
 template <int DT, int S, int H, int PF>
@@ -1468,7 +1469,7 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
               ws.quota, a.fused, a.out_factor, a.norm_eps, a.mean_only};
   int max_views = 0;
   for (int t = 0; t < n_obj; ++t) max_views = std::max(max_views, tab.o[t].n_views);
-  const int np = one_kernel_producers(a, stage_steps_for<S * H / 2>(), ws.quota, max_views);
+  const int np = one_kernel_producers(a, stage_steps_for<S * H / 2>(), ws.quota, max_views, S);
   if (np > 0) {
     hipLaunchKernelGGL(k_clear_counters, dim3((n_obj * kXcd + 63) / 64), dim3(64), 0, stream, pa.counters, n_obj * kXcd);
     // with one producer wave two workgroups fit a compute unit, with four one; several objects in one launch share
@@ -1480,7 +1481,7 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
     if (np == 1) {
       if (a.in_mask) hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, true, 1>), grid, block, 0, stream, a, pa, ws, keep, tab);
       else hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 1>), grid, block, 0, stream, a, pa, ws, keep, tab);
-    } else {
+    } else if constexpr (S + 4 <= 8) {
       if (a.in_mask) hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, true, 4>), grid, block, 0, stream, a, pa, ws, keep, tab);
       else hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 4>), grid, block, 0, stream, a, pa, ws, keep, tab);
     }
