@@ -221,7 +221,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2))) void k
 static size_t knn_round256(size_t x) { return (x + 255) & ~(size_t)255; }
 static int knn_source_tiles(int Ns) {
   const int mt = (Ns + 31) / 32;
-  return mt <= 2 ? mt : (mt <= 4 ? 4 : (mt <= 6 ? 6 : 8));
+  return mt <= 6 ? mt : 8;
 }
 
 bool knn_supported(int Ns, int K, int k, int P) {
@@ -269,7 +269,9 @@ hipError_t launch_knn_densify(const float* fq, long long Nq, int D, const float*
   switch (MT) {
     case 1: return launch_knn_mtk<1>(a, aligned, stream);
     case 2: return launch_knn_mtk<2>(a, aligned, stream);
+    case 3: return launch_knn_mtk<3>(a, aligned, stream);
     case 4: return launch_knn_mtk<4>(a, aligned, stream);
+    case 5: return launch_knn_mtk<5>(a, aligned, stream);
     case 6: return launch_knn_mtk<6>(a, aligned, stream);
     default: return launch_knn_mtk<8>(a, aligned, stream);
   }

@@ -70,7 +70,8 @@ def _compare(gpu, ref, ws, y, sel=None):
 
 @pytest.mark.parametrize("Nq,Ns,D,K,P,k", [
     (1, 1, 4, 1, 1, 1), (33, 5, 7, 3, 1, 16), (1000, 31, 64, 12, 2, 3), (4097, 150, 768, 32, 2, 5),
-    (777, 64, 100, 33, 1, 8), (500, 129, 130, 64, 3, 16), (300, 200, 512, 100, 8, 4), (2000, 256, 384, 128, 2, 7)])
+    (777, 64, 100, 33, 1, 8), (500, 129, 130, 64, 3, 16), (300, 200, 512, 100, 8, 4), (2000, 256, 384, 128, 2, 7),
+    (600, 70, 96, 5, 1, 4), (900, 128, 256, 32, 2, 6), (700, 190, 160, 16, 2, 5)])   # 3, 4 and 6 tiles of 32 sources
 def test_matches_oracle_on_random_clustered_features(orc, Nq, Ns, D, K, P, k):
     fq, fs, ws, y = _inputs(Nq, Ns, D, K, P, seed=Nq + Ns)
     print(f"\n[knn] Nq={Nq} Ns={Ns} D={D} K={K} P={P} k={k}", flush=True)
