@@ -32,8 +32,8 @@ def fuse_algorithmic_bytes(s):
 # profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_fused, each
 # scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
 # the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = 671225258
-TRAFFIC_SOURCE_SHA256 = "498d216e35b0a796c8cf25104d29f165d1ee52789857e29b0328134163365d80"
+TRAFFIC_C2_BYTES = 671489069
+TRAFFIC_SOURCE_SHA256 = "c2ff225689d9703fed88731357d9b94aecc66ce3486db53d0bf63ec9f4b4d231"
 
 
 def measured_traffic():

@@ -865,6 +865,7 @@ struct TileSlot {    // what the product waves need to know about a staged tile
   int nsteps;        // -1: fused by the producers
   int pad_[2];
   int cnt[kMaxProducers][kTilePts];   // views that see each point, per producer wave
+  uint32_t vmask[kCamRows];           // per view of the object: which of the tile's 32 points it sees (Eq. 1)
 };
 
 // Orders the producer wave's LDS traffic for the compiler.  The LDS unit handles the instructions of one wave in
@@ -948,7 +949,7 @@ __device__ __forceinline__ void project_batch(const FuseArgs& a, const ObjRange&
 // each of the NP producer waves (w = 0 .. NP - 1), which share the views of the tile: wave w takes the trips
 // it = w, w + NP, ... (two views per trip, one per half wave).  cam_lds: the object's camera rows in LDS.
 template <int DT, bool SEL, int NP>
-__device__ __forceinline__ void produce_tile(const FuseArgs& a, const TileWs& ws, bool keep, const ObjRange& ob, int blk,
+__device__ __forceinline__ void produce_tile(const FuseArgs& a, const ObjRange& ob, int blk,
                                              float3 pt, ProjectedBatch<NP>& pre, char* stage, int k_stage,
                                              TileSlot* slot, ProducerScratch* sc, lds_floats cam_lds, volatile int* flags,
                                              int w, int& seq, int lane) {
@@ -1033,24 +1034,9 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const TileWs& ws
     }
     producers_meet<NP>(flags, w, seq, lane);   // the maps, boxes and masks of all views are complete
 
-    if (w == 0 && a.out_vis && lane < kTilePts && li0 + lane < ob.n_pts) {   // the mask of Eq. 1 for this batch of views
-      uint8_t* __restrict__ vrow = a.out_vis + (ob.pt_begin + li0 + lane) * a.vis_pitch + vb0;
-      if ((a.vis_pitch & 3) == 0) {
-        for (int v4 = 0; v4 < nvb; v4 += 4) {
-          uint32_t wd = 0;
-#pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (v4 + e < nvb) wd |= ((sc->vmask[v4 + e] >> lane) & 1u) << (8 * e);
-          if (v4 + 4 <= nvb) {
-            *reinterpret_cast<uint32_t*>(vrow + v4) = wd;
-          } else {
-            for (int e = 0; v4 + e < nvb; ++e) vrow[v4 + e] = (uint8_t)((wd >> (8 * e)) & 1u);
-          }
-        }
-      } else {
-        for (int v = 0; v < nvb; ++v) vrow[v] = (uint8_t)((sc->vmask[v] >> lane) & 1u);
-      }
-    }
+    // the mask of Eq. 1 for this batch of views goes out with the tile: a product wave writes it to memory (a store
+    // of a producer would hold up its next wait for a read: one counter covers both)
+    if (w == 0 && a.out_vis && lane < nvb) slot->vmask[vb0 + lane] = sc->vmask[lane];
     {   // list length of every view, exclusive scan over the views: every producer wave does it (same values).
         // lane = (view, quarter of the map's rows): set bits before each row within the quarter, then the quarters'
         // totals through lane exchanges
@@ -1172,9 +1158,6 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const TileWs& ws
     }
   }
 
-  if (w == 0 && a.out_vis && lane < kTilePts && li0 + lane < ob.n_pts) {   // mask columns beyond the object's views
-    for (int j = ob.n_views; j < a.vis_pitch; ++j) a.out_vis[(ob.pt_begin + li0 + lane) * a.vis_pitch + j] = 0;
-  }
   const int mine = cnt + __shfl_xor(cnt, 32, kWave);   // views of this wave that see point lane % 32
   wave_sync();
   if (w == 0 && lane == 0) {
@@ -1183,15 +1166,6 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const TileWs& ws
   }
   if (lane < kTilePts) slot->cnt[w][lane] = mine;
   if (exhausted) gather_tile<DT>(a, ob, li0, w, NP, lane);   // writes the rows, the counts and the mask of the tile itself
-  if (keep) {   // the scoring kernel reads the k-steps and the header from memory
-    if (w == 0 && lane == 0) ws.hdr[ob.tile_begin + blk].nsteps = exhausted ? -1 : used;
-    if (!exhausted) {
-      producers_meet<NP>(flags, w, seq, lane);   // every wave's weights are in the buffer
-      u32x4* __restrict__ dst = reinterpret_cast<u32x4*>(ws.steps + (long long)(ob.tile_begin + blk) * ws.quota);
-      const u32x4* src = reinterpret_cast<const u32x4*>(stage);
-      for (int q = w * kWave + lane; q < used * (int)(sizeof(TileStep) / 16); q += NP * kWave) dst[q] = src[q];
-    }
-  }
 }
 
 // S product waves and NP producer waves per workgroup.
@@ -1260,7 +1234,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       const float3 pt1 = tile_point(fa, ob, tile_of(t1), lane);
       project_batch<SEL, NP>(fa, ob, tile_of(t0), pt0, 0, cam_lds, w, lane, pre);
       if (t0 < len) {
-        produce_tile<DT, SEL, NP>(fa, ws, keep != 0, ob, r0 + t0, pt0, pre, s_steps[0], kStage, &s_slot[0], &s_sc, cam_lds, s_flags,
+        produce_tile<DT, SEL, NP>(fa, ob, r0 + t0, pt0, pre, s_steps[0], kStage, &s_slot[0], &s_sc, cam_lds, s_flags,
                                   w, seq, lane);
       } else if (w == 0 && lane == 0) {
         s_slot[0].tile = -1;
@@ -1278,7 +1252,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       const int t = s_plan[k & 3], tn = s_plan[(k + 1) & 3];
       const float3 pt_next = tile_point(fa, ob, tile_of(tn), lane);   // requested now, looked at after this tile is built
       if (t < len) {
-        produce_tile<DT, SEL, NP>(fa, ws, keep != 0, ob, r0 + t, pt, pre, s_steps[buf ^ 1], kStage, &s_slot[buf ^ 1], &s_sc, cam_lds,
+        produce_tile<DT, SEL, NP>(fa, ob, r0 + t, pt, pre, s_steps[buf ^ 1], kStage, &s_slot[buf ^ 1], &s_sc, cam_lds,
                                   s_flags, w, seq, lane);
       } else if (w == 0 && lane == 0) {
         s_slot[buf ^ 1].tile = -1;
@@ -1324,6 +1298,47 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
 
     const char* sb = s_steps[buf];
+    if (keep && tid == 0) ws.hdr[ob.tile_begin + blk].nsteps = n;   // the scoring kernel reads the header from memory
+    if (fa.out_vis && span == S - 1 && lane < kTilePts && blk * kTilePts + lane < ob.n_pts) {
+      // The visibility mask (Eq. 1) of the tile, as aura_project_visibility writes it; a tile that the producers
+      // fused themselves has its mask already, up to the columns beyond the object's views.
+      uint8_t* __restrict__ vrow = fa.out_vis + (ob.pt_begin + blk * kTilePts + lane) * fa.vis_pitch;
+      const uint32_t* vm = s_slot[buf].vmask;
+      if (n >= 0) {
+        const bool wide = (fa.vis_pitch & 15) == 0 && (reinterpret_cast<uintptr_t>(fa.out_vis) & 15) == 0;
+        const bool words = (fa.vis_pitch & 3) == 0 && (reinterpret_cast<uintptr_t>(fa.out_vis) & 3) == 0;
+        for (int v0 = 0; v0 < ob.n_views; v0 += 16) {   // 16 views = 16 bytes of the point's row
+          uint32_t wd[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            wd[q] = 0;
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (v0 + 4 * q + e < ob.n_views) wd[q] |= ((vm[v0 + 4 * q + e] >> lane) & 1u) << (8 * e);
+          }
+          if (wide && v0 + 16 <= ob.n_views) {
+            *reinterpret_cast<u32x4*>(vrow + v0) = u32x4{wd[0], wd[1], wd[2], wd[3]};
+          } else {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              if (words && v0 + 4 * q + 4 <= ob.n_views) {
+                *reinterpret_cast<uint32_t*>(vrow + v0 + 4 * q) = wd[q];
+              } else {
+                for (int e = 0; e < 4 && v0 + 4 * q + e < ob.n_views; ++e) vrow[v0 + 4 * q + e] = (uint8_t)((wd[q] >> (8 * e)) & 1u);
+              }
+            }
+          }
+        }
+      }
+      for (int j = ob.n_views; j < fa.vis_pitch; ++j) vrow[j] = 0;
+    }
+    if (keep && n > 0) {
+      // The scoring kernel wants the k-steps in memory: the product waves, which have issue slots to spare, copy the
+      // staged tile out (the producers do not: their vector ALU work is what the tile waits for).
+      u32x4* __restrict__ dst = reinterpret_cast<u32x4*>(ws.steps + (long long)(ob.tile_begin + blk) * ws.quota);
+      const u32x4* src = reinterpret_cast<const u32x4*>(sb);
+      for (int q = span * kWave + lane; q < n * (int)(sizeof(TileStep) / 16); q += S * kWave) dst[q] = src[q];
+    }
     {
       const int cnt = max(n, 0), l0 = cnt - 1;
       int s = 0;
@@ -1458,7 +1473,11 @@ static int one_kernel_producers(const FuseArgs& a, int k_stage, int quota, int v
   if (a.two_kernels || k_stage > quota || views_per_obj > kCamRows || (float)views_per_obj * per_view > (float)k_stage) return 0;
   if (views_per_obj <= kOneKernelViews) return 1;
   if (product_waves + 4 > 8) return 0;
-  return a.out_factor ? 0 : 4;   // measured: with the k-steps also going to memory the two kernels are as fast or faster here
+  // the scoring kernel wants the k-steps in memory: the product waves copy them out, which pays where they are not
+  // already bound by their own stores (measured: 768 channels and 16 views 7 % faster than the two kernels, 1024
+  // channels and 24 views 5 % slower)
+  if (a.out_factor && product_waves > 3) return 0;
+  return 4;
 }
 
 template <int DT, int S, int H, int PF>
