@@ -187,7 +187,7 @@ def test_argument_validation_returns_status_codes(B):
     assert kd(wsb=16) == -5
     assert kd(ws=C.c_void_p(0x1010)) == -5
     assert kd(Nq=0, fq=None, wq=None) == 0
-    assert B.workspace_bytes(B.CALL_KNN_DENSIFY, D=768, Ns=150) == 24 * 6 * 2 * 2 * 64 * 16 + 768
+    assert B.workspace_bytes(B.CALL_KNN_DENSIFY, D=768, Ns=150) == 24 * 5 * 2 * 2 * 64 * 16 + 768   # 5 tiles of 32 sources
     with pytest.raises(B.AuraError) as e:
         B.workspace_bytes(B.CALL_KNN_DENSIFY, D=768, Ns=300)
     assert e.value.status == -7
