@@ -950,7 +950,7 @@ __device__ __forceinline__ void project_batch(const FuseArgs& a, const ObjRange&
 // it = w, w + NP, ... (two views per trip, one per half wave).  cam_lds: the object's camera rows in LDS.
 template <int DT, bool SEL, int NP>
 __device__ __forceinline__ void produce_tile(const FuseArgs& a, const ObjRange& ob, int blk,
-                                             float3 pt, ProjectedBatch<NP>& pre, char* stage, int k_stage,
+                                             float3 pt, ProjectedBatch<NP>& pre, char* stage, int k_stage, int& dirty,
                                              TileSlot* slot, ProducerScratch* sc, lds_floats cam_lds, volatile int* flags,
                                              int w, int& seq, int lane) {
   constexpr int kTrips = kPBatch / 2 / NP;   // trips of one wave per batch of views
@@ -963,9 +963,10 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const ObjRange& 
   int used = 0, cnt = 0;
   bool exhausted = false;
 
-  // zero weights of the whole buffer, shared by the waves: complete for everybody at the first meeting, before any
-  // weight lands
-  for (int q = w * kWave + lane; q < k_stage * 128; q += NP * kWave)
+  // zero weights, shared by the waves: complete for everybody at the first meeting, before any weight lands.  Only
+  // the k-steps that the buffer's last tile wrote (`dirty` of them; all of the buffer the first time) can hold
+  // anything but zeros.
+  for (int q = w * kWave + lane; q < dirty * 128; q += NP * kWave)
     reinterpret_cast<u32x4*>(reinterpret_cast<char*>(&st[q >> 7]) + 64)[q & 127] = u32x4{0u, 0u, 0u, 0u};
 
   for (int vb0 = 0; vb0 < ob.n_views; vb0 += kPBatch) {
@@ -1165,6 +1166,7 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const ObjRange& 
     slot->nsteps = exhausted ? -1 : used;
   }
   if (lane < kTilePts) slot->cnt[w][lane] = mine;
+  dirty = used;   // the same in every producer wave
   if (exhausted) gather_tile<DT>(a, ob, li0, w, NP, lane);   // writes the rows, the counts and the mask of the tile itself
 }
 
@@ -1227,6 +1229,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
     // a plan past the end reads (and projects) a tile that exists; it is never built
     auto tile_of = [&](int t) { return min(r0 + t, last_tile); };
     ProjectedBatch<NP> pre;
+    int dirty0 = kStage, dirty1 = kStage;   // k-steps of each stage buffer that may hold non-zero weights
     float3 pt;   // the lane's point of the tile that the next trip builds
     {
       const int t0 = s_plan[0], t1 = s_plan[1];
@@ -1234,7 +1237,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       const float3 pt1 = tile_point(fa, ob, tile_of(t1), lane);
       project_batch<SEL, NP>(fa, ob, tile_of(t0), pt0, 0, cam_lds, w, lane, pre);
       if (t0 < len) {
-        produce_tile<DT, SEL, NP>(fa, ob, r0 + t0, pt0, pre, s_steps[0], kStage, &s_slot[0], &s_sc, cam_lds, s_flags,
+        produce_tile<DT, SEL, NP>(fa, ob, r0 + t0, pt0, pre, s_steps[0], kStage, dirty0, &s_slot[0], &s_sc, cam_lds, s_flags,
                                   w, seq, lane);
       } else if (w == 0 && lane == 0) {
         s_slot[0].tile = -1;
@@ -1252,7 +1255,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       const int t = s_plan[k & 3], tn = s_plan[(k + 1) & 3];
       const float3 pt_next = tile_point(fa, ob, tile_of(tn), lane);   // requested now, looked at after this tile is built
       if (t < len) {
-        produce_tile<DT, SEL, NP>(fa, ob, r0 + t, pt, pre, s_steps[buf ^ 1], kStage, &s_slot[buf ^ 1], &s_sc, cam_lds,
+        produce_tile<DT, SEL, NP>(fa, ob, r0 + t, pt, pre, s_steps[buf ^ 1], kStage, buf ? dirty0 : dirty1, &s_slot[buf ^ 1], &s_sc, cam_lds,
                                   s_flags, w, seq, lane);
       } else if (w == 0 && lane == 0) {
         s_slot[buf ^ 1].tile = -1;
