@@ -32,8 +32,8 @@ def fuse_algorithmic_bytes(s):
 # profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_fused, each
 # scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
 # the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = 671489069
-TRAFFIC_SOURCE_SHA256 = "c2ff225689d9703fed88731357d9b94aecc66ce3486db53d0bf63ec9f4b4d231"
+TRAFFIC_C2_BYTES = 671240172
+TRAFFIC_SOURCE_SHA256 = "ef2828b1383ccaf9245281c74bb44c6b0778588ae52a8e152480ea20f9304936"
 
 
 def measured_traffic():
