@@ -6,7 +6,8 @@ aura_fuse_scores (visibility mask and view counts, fusion, scoring) -> aura_prop
 (--staged: aura_project_visibility, aura_fuse_features, aura_material_scores, aura_property_integrate).
 Prints ONE JSON line: whole-path throughput in fused point-views per second, the roofline figure
 of the dominant call (the fusion, HBM bound on writing the fused rows) measured with events on the
-launch stream inside the timed region, and the CPU oracle timed on a bounded sample of the same workload.
+launch stream in a run of its own right after the timed steps, and the CPU oracle timed on a bounded sample of the
+same workload.
 """
 import argparse
 import json
@@ -32,7 +33,7 @@ def fuse_algorithmic_bytes(s):
 # profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_fused, each
 # scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
 # the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = 671240172
+TRAFFIC_C2_BYTES = 671255725
 TRAFFIC_SOURCE_SHA256 = "ef2828b1383ccaf9245281c74bb44c6b0778588ae52a8e152480ea20f9304936"
 
 
@@ -288,7 +289,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=100,
+                    help="untimed steps before the timed ones; the GPU needs some tens of milliseconds of load to reach its clocks")
     ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--staged", action="store_true", help="fusion and scoring as two library calls")
@@ -306,31 +308,53 @@ def main():
 
     s = make_scene(args.workload)
     d = H.DeviceScene(s)
-    calibration = calibrate(torch)
     if args.staged:
         names = ["project_visibility", "fuse_features", "material_scores", "property_integrate"]
         calls = [d.project_visibility, d.fuse_features, d.material_scores, d.property_integrate]
     else:
         names = ["fuse_scores", "property_integrate"]       # the mask and view counts come out of the fusion
         calls = [d.fuse_scores_vis, d.property_integrate]
-    for _ in range(max(args.warmup, 0)):
+    for k in range(max(args.warmup, 0)):
         for call in calls:
             call()
+        if k % 16 == 15:
+            torch.cuda.synchronize()   # keeps the launch queue short: a queue that has run full once makes later launches slow
     torch.cuda.synchronize()
 
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(args.steps)]
+    # The timed region: exactly args.steps steps between two synchronisations, nothing else on the stream (events
+    # recorded between the calls slow the launches down once a few hundred of them are outstanding).
+    # Every 32 steps the host waits for the GPU (inside the timed region: the few microseconds of idle GPU count
+    # against the result): a launch queue that runs full, or hundreds of outstanding launches, make the runtime's
+    # launches several times slower, and the figure would then be the host's, not the GPU's.
     torch.cuda.synchronize()
+    waited = 0.0
     t0 = time.perf_counter()
     for k in range(args.steps):
+        if k % 32 == 0 and k > 0:
+            tw = time.perf_counter()
+            torch.cuda.synchronize()
+            waited += time.perf_counter() - tw
+        for call in calls:
+            call()
+    t_enqueued = time.perf_counter()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    # host time to enqueue one step (without the waits above): if it comes close to ms_per_step the GPU was waiting
+    # for the host
+    enqueue_ms_per_step = (t_enqueued - t0 - waited) * 1e3 / args.steps
+
+    # Time per call, from a short run of its own with an event after every call.
+    n_split = min(args.steps, 20)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(n_split)]
+    for k in range(n_split):
         ev[k][0].record()
         for c, call in enumerate(calls):
             call()
             ev[k][c + 1].record()
     torch.cuda.synchronize()
-    t1 = time.perf_counter()
-
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    call_ms = {n: sum(ev[k][c].elapsed_time(ev[k][c + 1]) for k in range(args.steps)) / args.steps
+    call_ms = {n: sum(ev[k][c].elapsed_time(ev[k][c + 1]) for k in range(n_split)) / n_split
                for c, n in enumerate(names)}
     pv = s.point_views
     tile = d.ws_fuse is not None
@@ -339,11 +363,12 @@ def main():
     # Roofline of the dominant work: the fusion proper (the matrix-core kernels, or k_fuse_gather), which writes
     # the fused rows.  Inside aura_fuse_scores it cannot be bracketed by events, so it is timed through
     # aura_fuse_features (same inputs, same workspace) right after the timed steps, with events on the launch
-    # stream.  Where the scoring kernel needs the k-steps in memory aura_fuse_scores runs the fusion as two kernels
-    # and aura_fuse_features as one (see calls_ms for the whole call).
+    # stream.  Inside aura_fuse_scores the same kernels also leave the k-steps in memory for the scoring kernel (see
+    # calls_ms for the whole call).
     fuse_reps = max(args.steps, 10)
+    fuse_warmup = max(3, min(args.warmup, 50))
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for _ in range(3):
+    for _ in range(fuse_warmup):
         d.fuse_features()
     e0.record()
     for _ in range(fuse_reps):
@@ -367,6 +392,7 @@ def main():
         t = sorted(a.elapsed_time(b) for a, b in pairs)
         return {"min_ms": t[0], "median_ms": t[len(t) // 2], "max_ms": t[-1]}
     warm_each, cold_each = one_by_one(False), one_by_one(True)
+    calibration = calibrate(torch)   # after the measurements above: its 256 MiB sweeps leave the caches full of its data
     fuse_bytes = fuse_algorithmic_bytes(s)
     achieved = fuse_bytes / (fuse_ms * 1e-3) / 1e9
     kernel = "aura_fuse_features: " + (f"matrix-core fusion <{s.feat_dtype}, {s.D // 256} product waves> (k_tile_fused where the "
@@ -392,10 +418,10 @@ def main():
                    "visible_point_views_per_s": float(gpu["vis"].mean()) * pv / (ms_per_step * 1e-3),
                    "visible_fraction": float(gpu["vis"].mean()), "unseen_points": float((gpu["count_fuse"] == 0).mean()),
                    "order": s.meta["order"], "seed": s.meta["seed"]},
-        "calls_ms": call_ms,
+        "calls_ms": call_ms, "host_enqueue_ms_per_step": enqueue_ms_per_step,
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
                      "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "algorithmic_bytes": fuse_bytes, "avg_launch_ms": fuse_ms, "launches": fuse_reps,
+                     "algorithmic_bytes": fuse_bytes, "avg_launch_ms": fuse_ms, "launches": fuse_reps, "warmup_launches": fuse_warmup,
                      "single_launches": warm_each, "single_launches_caches_flushed": cold_each,
                      "frac_caches_flushed": fuse_bytes / (cold_each["median_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                      "frac_of_fill_kernel": achieved / calibration["fill_GBps"]},
