@@ -10,6 +10,7 @@ launch stream in a run of its own right after the timed steps, and the CPU oracl
 same workload.
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -33,7 +34,7 @@ def fuse_algorithmic_bytes(s):
 # profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_fused, each
 # scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
 # the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = 671255725
+TRAFFIC_C2_BYTES = 671245716
 TRAFFIC_SOURCE_SHA256 = "ef2828b1383ccaf9245281c74bb44c6b0778588ae52a8e152480ea20f9304936"
 
 
@@ -314,26 +315,19 @@ def main():
     else:
         names = ["fuse_scores", "property_integrate"]       # the mask and view counts come out of the fusion
         calls = [d.fuse_scores_vis, d.property_integrate]
-    for k in range(max(args.warmup, 0)):
+    # Python's cyclic garbage collector is off during the warm-up and the timed steps: a full collection (it comes
+    # after a few hundred steps' worth of allocations and walks every object torch has created) stops the host for
+    # about 40 ms, the launch queue runs dry and the figure would be the host's, not the GPU's.
+    gc.collect()
+    gc.disable()
+    for _ in range(max(args.warmup, 0)):
         for call in calls:
             call()
-        if k % 16 == 15:
-            torch.cuda.synchronize()   # keeps the launch queue short: a queue that has run full once makes later launches slow
     torch.cuda.synchronize()
 
-    # The timed region: exactly args.steps steps between two synchronisations, nothing else on the stream (events
-    # recorded between the calls slow the launches down once a few hundred of them are outstanding).
-    # Every 32 steps the host waits for the GPU (inside the timed region: the few microseconds of idle GPU count
-    # against the result): a launch queue that runs full, or hundreds of outstanding launches, make the runtime's
-    # launches several times slower, and the figure would then be the host's, not the GPU's.
-    torch.cuda.synchronize()
-    waited = 0.0
+    # The timed region: exactly args.steps steps between two synchronisations, nothing else on the stream.
     t0 = time.perf_counter()
-    for k in range(args.steps):
-        if k % 32 == 0 and k > 0:
-            tw = time.perf_counter()
-            torch.cuda.synchronize()
-            waited += time.perf_counter() - tw
+    for _ in range(args.steps):
         for call in calls:
             call()
     t_enqueued = time.perf_counter()
@@ -341,9 +335,8 @@ def main():
     t1 = time.perf_counter()
 
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    # host time to enqueue one step (without the waits above): if it comes close to ms_per_step the GPU was waiting
-    # for the host
-    enqueue_ms_per_step = (t_enqueued - t0 - waited) * 1e3 / args.steps
+    # host time to enqueue one step; once the launch queue is full it is the GPU's pace, not the host's cost
+    enqueue_ms_per_step = (t_enqueued - t0) * 1e3 / args.steps
 
     # Time per call, from a short run of its own with an event after every call.
     n_split = min(args.steps, 20)
@@ -408,6 +401,7 @@ def main():
                   "estimate_normals": time_normals(torch, d, s, max(args.steps // 2, 5)),
                   "patch_batch": time_patches(torch, d, s, max(args.steps // 2, 5)),
                   "patch_batch_f16": time_patches(torch, d, s, max(args.steps // 2, 5), half=True)}
+    gc.enable()
     out = {
         "metric": "fused point-views/sec", "value": pv / (ms_per_step * 1e-3), "unit": "point-views/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
