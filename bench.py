@@ -34,8 +34,8 @@ def fuse_algorithmic_bytes(s):
 # profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_fused, each
 # scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
 # the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = 671245716
-TRAFFIC_SOURCE_SHA256 = "ef2828b1383ccaf9245281c74bb44c6b0778588ae52a8e152480ea20f9304936"
+TRAFFIC_C2_BYTES = 671259291
+TRAFFIC_SOURCE_SHA256 = "4deb2cdaea35e56dfdb020a9eda2d82e280fcba5b4aee72ed8e6e00f594dd274"
 
 
 def measured_traffic():
