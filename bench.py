@@ -34,8 +34,8 @@ def fuse_algorithmic_bytes(s):
 # profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_fused, each
 # scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
 # the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = 671259291
-TRAFFIC_SOURCE_SHA256 = "4deb2cdaea35e56dfdb020a9eda2d82e280fcba5b4aee72ed8e6e00f594dd274"
+TRAFFIC_C2_BYTES = 671147400
+TRAFFIC_SOURCE_SHA256 = "f24c7a82fbadfe618247584cad2b9328fe0c625c79cbdc95d6e3f9a634b0941e"
 
 
 def measured_traffic():

@@ -119,6 +119,11 @@ __device__ __forceinline__ float dpp_add(float v) {
   return v + __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, ROW_MASK, 0xf, false));
 }
 
+template <int CTRL>
+__device__ __forceinline__ int row_shift_add(int v) {
+  return v + __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, false);
+}
+
 __device__ __forceinline__ float half_wave_sum(float v) {
   v = dpp_add<0x111, 0xf>(v);   // row_shr:1
   v = dpp_add<0x112, 0xf>(v);   // row_shr:2
@@ -887,19 +892,23 @@ __device__ __forceinline__ float3 tile_point(const FuseArgs& a, const ObjRange& 
 // Meeting point of the NP producer waves of a workgroup (the workgroup barrier belongs to the tile hand-over, which
 // the product waves take part in).  Every wave publishes the number of the meeting after its LDS traffic and waits
 // until the others have published it too; both producers pass the same meetings in the same order.  The wait is
-// bounded: a producer that never arrives (a programming error) ends in wrong results, not in a hung machine.
+// bounded: a producer that never arrives (a programming error) ends in wrong results, not in a hung machine.  The
+// waiting waves look again as soon as the last look is back (no sleep in between: the meeting is on the tile's
+// critical path, and a look is one LDS read for all four flags).
 template <int NP>
 __device__ __forceinline__ void producers_meet(volatile int* flags, int w, int& seq, int lane) {
   wave_sync();
   if constexpr (NP > 1) {
     ++seq;
     if (lane == 0) flags[w] = seq;
+    static_assert(NP <= 4, "the four flags are read as one 16-byte vector");
+    typedef int flags4 __attribute__((ext_vector_type(4)));
     for (int spins = 0; spins < (1 << 16); ++spins) {
+      const flags4 f = *reinterpret_cast<const volatile flags4*>(flags);   // one LDS round trip per look
       bool all = true;
 #pragma unroll
-      for (int o = 0; o < NP; ++o) all = all && (flags[o] - seq >= 0);
+      for (int o = 0; o < NP; ++o) all = all && (f[o] - seq >= 0);
       if (all) break;
-      __builtin_amdgcn_s_sleep(1);
     }
     wave_sync();
   }
@@ -1058,12 +1067,13 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const ObjRange& 
       }
       int total = n0 + n1 + n2 + n3;                                   // lanes 0 .. 15: the view's list length
       if (v < nvb && sc->mode[v] == 2) total = 4 * __popc(sc->vmask[v]);
+      // running sum over the 16 views = over the first row of 16 lanes, with lane shifts inside the row (a lane without
+      // a source adds 0): no trip through the LDS unit, which every exchange between arbitrary lanes would cost
       int inc = lane < kPBatch ? total : 0;
-#pragma unroll
-      for (int o = 1; o < kPBatch; o <<= 1) {
-        const int up = __shfl_up(inc, o, kWave);
-        if (lane >= o) inc += up;
-      }
+      inc = row_shift_add<0x111>(inc);   // row_shr:1
+      inc = row_shift_add<0x112>(inc);   // row_shr:2
+      inc = row_shift_add<0x114>(inc);   // row_shr:4
+      inc = row_shift_add<0x118>(inc);   // row_shr:8
       if (lane < kPBatch) sc->base[lane] = inc - total;
       if (lane == kPBatch - 1) sc->base[kPBatch] = inc;
     }
@@ -1182,7 +1192,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
   __shared__ float s_ss[2][S][kTilePts];
   __shared__ __attribute__((aligned(16))) float s_cam[kCamRows][16];   // the object's camera rows, for the producers
   __shared__ int s_plan[4];      // tickets of the workgroup's tiles, k-th tile in slot k & 3
-  __shared__ int s_flags[kMaxProducers];   // meeting numbers of the producer waves
+  __shared__ __attribute__((aligned(16))) int s_flags[kMaxProducers];   // meeting numbers of the producer waves
 
   const ObjRange ob = tab.o[blockIdx.y];
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
