@@ -34,8 +34,8 @@ def fuse_algorithmic_bytes(s):
 # profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_fused, each
 # scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
 # the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = 671147400
-TRAFFIC_SOURCE_SHA256 = "f24c7a82fbadfe618247584cad2b9328fe0c625c79cbdc95d6e3f9a634b0941e"
+TRAFFIC_C2_BYTES = 671120393
+TRAFFIC_SOURCE_SHA256 = "63db4f76e914b9c5077bed0f61aa2c7c53b41fa1caaaf60b6282018b9fe2b1ee"
 
 
 def measured_traffic():
@@ -356,8 +356,8 @@ def main():
     # Roofline of the dominant work: the fusion proper (the matrix-core kernels, or k_fuse_gather), which writes
     # the fused rows.  Inside aura_fuse_scores it cannot be bracketed by events, so it is timed through
     # aura_fuse_features (same inputs, same workspace) right after the timed steps, with events on the launch
-    # stream.  Inside aura_fuse_scores the same kernels also leave the k-steps in memory for the scoring kernel (see
-    # calls_ms for the whole call).
+    # stream.  Inside aura_fuse_scores the same kernels also serve the scoring (a scoring wave per workgroup, or the
+    # k-steps left in memory for the scoring kernel; see calls_ms for the whole call).
     fuse_reps = max(args.steps, 10)
     fuse_warmup = max(3, min(args.warmup, 50))
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -376,10 +376,13 @@ aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* p
     if (vis && !lay.tile)   // the gather kernel does not write the mask: the visibility kernel does
       e = aura::launch_project_visibility(va, xyz, vis, vis_pitch, nullptr, nullptr, tab, n, max_pts, st);
     if (e != hipSuccess) return e;
+    const aura::TileScoring want{sws.G, sws.Kpad, K, P, t32, y, 1.0f / params->temperature, scores, prop, label};
+    bool scored = false;   // the one-kernel form of the fusion scores its tiles itself where it can
     e = aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only,
                                    lay.tile ? &tws : nullptr, tab, n, max_pts, st, lay.by_cells ? sws.factor : nullptr,
-                                   vis, vis_pitch, nullptr, 0, (params->flags & AURA_FUSE_TWO_KERNELS) ? 1 : 0);
-    if (e != hipSuccess || !lay.by_cells) return e;
+                                   vis, vis_pitch, nullptr, 0, (params->flags & AURA_FUSE_TWO_KERNELS) ? 1 : 0,
+                                   lay.by_cells ? &want : nullptr, &scored);
+    if (e != hipSuccess || !lay.by_cells || scored) return e;
     return aura::launch_tile_scores(fa, tws, sws, fused, t32, K, y, P, params->temperature, scores, prop, label, tab, n,
                                     max_pts, st);
   });

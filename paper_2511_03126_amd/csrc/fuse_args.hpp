@@ -7,6 +7,20 @@
 
 namespace aura {
 
+// Scoring request to the tile path (Sec. 3.4.1): with the similarity of every feature cell to every material at hand
+// (G, two 16-bit terms per value), the scores of a tile are one more small product over the tile's k-steps.
+struct TileScoring {
+  const uint32_t* G;    // [n_cells][Kpad]: hi | lo << 16
+  int Kpad;             // K rounded up to the matrix-core tile
+  int K, P;
+  const float* temb;    // [K][D] fp32, for tiles without k-steps
+  const float* y;       // [K][P], may be nullptr with prop
+  float inv_T;
+  float* scores;        // [N][K]
+  float* prop;          // [N][P] or nullptr
+  int* label;           // [N] or nullptr
+};
+
 struct FuseArgs {
   VisArgs vis;
   FeatArgs feat;
@@ -21,6 +35,7 @@ struct FuseArgs {
   const uint8_t* in_mask;   // may be nullptr: [N][in_mask_pitch], the views kept for each point (Sec. 3.2.2); given, it
   int in_mask_pitch;        // takes the place of the depth test (the caller passes no depth maps then)
   int two_kernels;          // tile path: keep the prepare and the product kernel apart (AURA_FUSE_TWO_KERNELS)
+  TileScoring scoring;      // tile path: scores, labels and properties wanted along with the fused rows (G == nullptr: no)
 };
 
 // Whether view `local_view` (index within the object) takes part in the mean of point i.
@@ -58,12 +73,25 @@ struct TileWs {
   int obj_base;         // index of the launch's first object within the call
 };
 
+// Byte offset of a cell row as stored in a k-step (a multiple of 512 * units, units = D / 256 in 1..6) -> cell index.
+__device__ __forceinline__ uint32_t cell_index(uint32_t off, uint32_t units) {
+  const uint32_t q = off >> 9;
+  switch (units) {
+    case 1: return q;
+    case 2: return q >> 1;
+    case 3: return (uint32_t)(((unsigned long long)q * 0xAAAAAAABull) >> 33);
+    case 4: return q >> 2;
+    default: return (uint32_t)(((unsigned long long)(q >> 1) * 0xAAAAAAABull) >> 33);   // 6
+  }
+}
+
 bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes);
 size_t fuse_tile_workspace_bytes(long long N, int B, int n_views);
 // Splits a workspace of fuse_tile_workspace_bytes(N, B, n_views) bytes into its parts.
 TileWs fuse_tile_workspace(void* workspace, long long N, int B, int n_views);
-hipError_t launch_fuse_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,  // ws.obj_base set
-                           
-                            hipStream_t stream);
+// ws.obj_base set.  *scored (may be nullptr) tells whether the launch also wrote what a.scoring asks for; if not, the
+// k-steps and the factors are in the workspace for the scoring kernel.
+hipError_t launch_fuse_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
+                            hipStream_t stream, bool* scored);
 
 }  // namespace aura

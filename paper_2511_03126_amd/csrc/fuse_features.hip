@@ -244,11 +244,14 @@ static hipError_t dispatch_d(const FuseArgs& a, const ObjTable& tab, int n_obj, 
 hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const float* xyz, float* fused,
                                 int* out_count, float norm_eps, int mean_only, const TileWs* tile_ws,
                                 const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream, float* out_factor,
-                                uint8_t* out_vis, int vis_pitch, const uint8_t* in_mask, int in_mask_pitch, int two_kernels) {
+                                uint8_t* out_vis, int vis_pitch, const uint8_t* in_mask, int in_mask_pitch, int two_kernels,
+                                const TileScoring* scoring, bool* scored) {
+  if (scored) *scored = false;
   if (n_obj == 0 || max_pts == 0) return hipSuccess;
   FuseArgs a{vis, feat, xyz, fused, out_count, norm_eps, mean_only, tile_ws ? out_factor : nullptr,
-             tile_ws ? out_vis : nullptr, vis_pitch, in_mask, in_mask_pitch, two_kernels};
-  if (tile_ws) return launch_fuse_tile(a, *tile_ws, tab, n_obj, max_pts, stream);
+             tile_ws ? out_vis : nullptr, vis_pitch, in_mask, in_mask_pitch, two_kernels,
+             tile_ws && scoring ? *scoring : TileScoring{}};
+  if (tile_ws) return launch_fuse_tile(a, *tile_ws, tab, n_obj, max_pts, stream, scored);
   switch (feat.dtype) {
     case 0: return dispatch_d<0>(a, tab, n_obj, max_pts, stream);
     case 1: return dispatch_d<1>(a, tab, n_obj, max_pts, stream);

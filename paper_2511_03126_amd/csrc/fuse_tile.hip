@@ -47,6 +47,7 @@
 #include "aura_device.hpp"
 #include "fuse_args.hpp"
 #include "launch.hpp"
+#include "scores_epilogue.hpp"
 
 namespace aura {
 
@@ -1180,9 +1181,79 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const ObjRange& 
   if (exhausted) gather_tile<DT>(a, ob, li0, w, NP, lane);   // writes the rows, the counts and the mask of the tile itself
 }
 
-// S product waves and NP producer waves per workgroup.
-template <int DT, int S, int H, int PF, bool SEL, int NP>
-__global__ __launch_bounds__(kWave* (S + NP)) __attribute__((amdgpu_waves_per_eu(2, 2)))
+// The scoring wave's part of a tile (Sec. 3.4.1): omega^T = G^T . W^T over the k-steps staged at `sb`, whose weight
+// operand is exactly the B operand here; three partial products per k-step (hi * hi, hi * lo, lo * hi).  The rows of G
+// of kScoreAhead k-steps are requested together (the wave has nobody to hide a read behind) and multiplied later.
+// Accumulator element r of lane l is material 8 (r / 4) + 4 (l / 32) + r % 4 of point l % 32, before the point's factor.
+constexpr int kScoreAhead = 8;
+
+struct ScoreRows {
+  uint32_t gv[kScoreAhead][8];
+};
+
+// What the scoring wave hands to a product wave for storing: a wave that stores to memory waits for the stores'
+// acknowledgement before its next read comes back (one counter covers both), and the scoring wave lives on its reads.
+struct __attribute__((aligned(16))) ScoreOut {
+  float scores[kTilePts * kScoreTileM];   // [32][K]
+  float prop[kTilePts * kScoreMaxP];      // [32][P]
+  int label[kTilePts];
+  int blk;                                // tile index within the object; -1: nothing to store
+  int pad_[3];
+};
+
+// Requests G for those of the k-steps s0 .. s0 + kScoreAhead - 1 that exist (n staged ones).
+__device__ __forceinline__ void request_rows(const char* sb, int n, int s0, const TileScoring& sc, uint32_t row_units, int lane,
+                                             ScoreRows& rows) {
+  const int pt = lane & 31, g = lane >> 5;
+  const TileStep* st = reinterpret_cast<const TileStep*>(sb);
+#pragma unroll
+  for (int j = 0; j < kScoreAhead; ++j) {
+    if (s0 + j >= n) break;   // uniform
+    const TileStep* sj = st + s0 + j;
+    const u32x4 c0 = *reinterpret_cast<const u32x4*>(&sj->cell[8 * g]);
+    const u32x4 c1 = *reinterpret_cast<const u32x4*>(&sj->cell[8 * g + 4]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+      rows.gv[j][e] = sc.G[(long long)cell_index(e < 4 ? c0[e] : c1[e - 4], row_units) * sc.Kpad + pt];
+  }
+}
+
+template <int DT>
+__device__ __forceinline__ void multiply_rows(const char* sb, int n, int s0, const ScoreRows& rows, int lane, f32x16& acc) {
+  const TileStep* st = reinterpret_cast<const TileStep*>(sb);
+#pragma unroll
+  for (int j = 0; j < kScoreAhead; ++j) {
+    if (s0 + j < n) {
+      const u32x4 w_hi = st[s0 + j].a_hi[lane], w_lo = st[s0 + j].a_lo[lane];
+      u32x4 g_hi, g_lo;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        g_hi[q] = __builtin_amdgcn_perm(rows.gv[j][2 * q + 1], rows.gv[j][2 * q], 0x05040100u);
+        g_lo[q] = __builtin_amdgcn_perm(rows.gv[j][2 * q + 1], rows.gv[j][2 * q], 0x07060302u);
+      }
+      acc = mma<DT>(g_hi, w_hi, acc);
+      acc = mma<DT>(g_hi, w_lo, acc);
+      acc = mma<DT>(g_lo, w_hi, acc);
+    }
+  }
+}
+
+// Stores what the scoring wave left in `o` (if anything): scores, properties and labels of the tile's points are
+// contiguous in memory.  Called by all lanes of one wave.
+__device__ __forceinline__ void store_scores(const ScoreOut& o, const TileScoring& sc, const ObjRange& ob, int lane) {
+  const int blk = o.blk;
+  if (blk < 0) return;
+  const long long p0 = ob.pt_begin + (long long)blk * kTilePts;
+  const int rows = min(kTilePts, ob.n_pts - blk * kTilePts);
+  for (int q = lane; q < rows * sc.K; q += kWave) sc.scores[p0 * sc.K + q] = o.scores[q];
+  if (sc.prop)
+    for (int q = lane; q < rows * sc.P; q += kWave) sc.prop[p0 * sc.P + q] = o.prop[q];
+  if (sc.label && lane < rows) sc.label[p0 + lane] = o.label[lane];
+}
+
+// S product waves and NP producer waves per workgroup; with SC one more wave, which scores the tiles (K <= 32).
+template <int DT, int S, int H, int PF, bool SEL, int NP, bool SC>
+__global__ __launch_bounds__(kWave* (S + NP + (SC ? 1 : 0))) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
   constexpr int kSpan = kHalf * H;
   constexpr int kStage = stage_steps_for<S * H / 2>();
@@ -1193,6 +1264,8 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
   __shared__ __attribute__((aligned(16))) float s_cam[kCamRows][16];   // the object's camera rows, for the producers
   __shared__ int s_plan[4];      // tickets of the workgroup's tiles, k-th tile in slot k & 3
   __shared__ __attribute__((aligned(16))) int s_flags[kMaxProducers];   // meeting numbers of the producer waves
+  __shared__ float s_ys[SC ? kScoreTileM * kScoreMaxP : 1];   // the property table y[K][P]
+  __shared__ ScoreOut s_out[SC ? 2 : 1];                        // scores of the tile before the last, on their way to memory
 
   const ObjRange ob = tab.o[blockIdx.y];
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
@@ -1203,8 +1276,11 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
   unsigned* __restrict__ ctr = a.counters + blockIdx.y * kXcd + xcd;
 
   const int tid = threadIdx.x, lane = tid % kWave;
-  const int span = __builtin_amdgcn_readfirstlane(tid / kWave);   // wave index; waves S .. S + NP - 1 are the producers
-  const bool producer = span >= S;
+  // Wave index: the product waves come first, then the scoring wave if there is one, then the NP producers (waves go
+  // to the four SIMDs in turn: every producer then shares its SIMD with a wave that leaves the vector ALU mostly alone).
+  const int span = __builtin_amdgcn_readfirstlane(tid / kWave);
+  constexpr int kFirstProducer = S + (SC ? 1 : 0);
+  const bool producer = span >= kFirstProducer;
   const lds_floats cam_lds = (lds_floats)&s_cam[0][0];   // the launch code takes this kernel for up to kCamRows views
   const int m = lane & 31, g = lane >> 5;
   const int D = a.D;
@@ -1215,7 +1291,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
     // producers: they go first where both are ready (measured on 1024 channels with 24 views: 12 % faster; with seven
     // waves it does not pay).
     if constexpr (S + NP >= 8) __builtin_amdgcn_s_setprio(1);
-    const int w = span - S;
+    const int w = span - kFirstProducer;
     int seq = 0;
     // The first producer wave takes the tickets (the counters are zeroed by the launch that precedes this kernel) and
     // publishes them in s_plan, slot k & 3 for the k-th tile of the workgroup, two tiles ahead of the one being built:
@@ -1288,6 +1364,85 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
     }
     return;
   }
+  if constexpr (SC) {
+    if (span == S) {
+      // The scoring wave follows the product waves through the tiles, one barrier behind.  During a tile it multiplies
+      // the staged weights with G.  After the tile's barrier the product waves' sums of squares are in LDS: the factor
+      // of every point follows as in the product waves, and the scores, labels and properties of the tile go to LDS
+      // (a product wave stores them during the next tile) while the rows of G for the next tile are on their way.
+      const TileScoring& sc = fa.scoring;
+      constexpr uint32_t row_units = S * H / 2;   // D / 256
+      if (sc.prop)
+        for (int t = lane; t < sc.K * sc.P; t += kWave) s_ys[t] = sc.y[t];
+      if (lane == 0) s_out[0].blk = s_out[1].blk = -1;
+      __syncthreads();
+      __syncthreads();
+      int buf = 0;
+      int blk_prev = -1, n_prev = 0, cnt_prev = 0;   // the tile whose products are in acc
+      f32x16 acc[1];
+      while (true) {
+        const int blk = s_slot[buf].tile;
+        const int n = blk >= 0 ? s_slot[buf].nsteps : 0;
+        int my_cnt = 0;
+#pragma unroll
+        for (int o = 0; o < NP; ++o) my_cnt += s_slot[buf].cnt[o][m];
+        ScoreRows rows;
+        if (n > 0) request_rows(s_steps[buf], n, 0, sc, row_units, lane, rows);
+
+        if (blk_prev >= 0) {   // the tile before: its sums are in the other half of s_ss
+          const int li = blk_prev * kTilePts + m;
+          const bool valid = li < ob.n_pts;
+          const long long ip = ob.pt_begin + (valid ? li : ob.n_pts - 1);
+          if (n_prev >= 0) {
+            const float inv = cnt_prev > 0 ? 1.0f / (float)cnt_prev : 0.0f;
+            float tot = 0.0f;
+#pragma unroll
+            for (int wv = 0; wv < S; ++wv) tot += s_ss[buf ^ 1][wv][m];
+            const float normed = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
+            const float factor = a.mean_only ? inv : normed;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[0][r] *= factor;
+          } else {
+            // fused by the producers before the barrier that opened that tile: plain dot products of the stored row
+            const float* __restrict__ row = a.fused + ip * D;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+              const int mat = 8 * (r >> 2) + 4 * g + (r & 3);
+              float dot = 0.0f;
+              if (mat < sc.K) {
+                const float* __restrict__ t = sc.temb + (long long)mat * D;
+#pragma unroll 1
+                for (int d = 0; d < D; ++d) dot = __builtin_fmaf(row[d], t[d], dot);
+              }
+              acc[0][r] = dot;
+            }
+          }
+          if (blk >= 0) {   // a product wave stores the results during the next tile
+            ScoreOut& o = s_out[buf ^ 1];
+            if (valid) finish_scores<1>(acc, (long long)m, g, sc.K, sc.P, sc.inv_T, s_ys, o.scores, sc.prop ? o.prop : nullptr,
+                                        sc.label ? o.label : nullptr);
+            if (lane == 0) o.blk = blk_prev;
+          } else if (valid) {   // the workgroup's last tile: nobody is left to hand it to
+            finish_scores<1>(acc, ip, g, sc.K, sc.P, sc.inv_T, s_ys, sc.scores, sc.prop, sc.label);
+          }
+        }
+        if (blk < 0) break;
+
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[0][r] = 0.0f;
+        for (int s0 = 0; s0 < n; s0 += kScoreAhead) {
+          if (s0 > 0) request_rows(s_steps[buf], n, s0, sc, row_units, lane, rows);
+          multiply_rows<DT>(s_steps[buf], n, s0, rows, lane, acc[0]);
+        }
+        __syncthreads();
+        blk_prev = blk;
+        n_prev = n;
+        cnt_prev = my_cnt;
+        buf ^= 1;
+      }
+      return;
+    }
+  }
   __syncthreads();
   __syncthreads();
 
@@ -1315,6 +1470,9 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
 
     const char* sb = s_steps[buf];
+    if constexpr (SC) {   // what the scoring wave finished during the last tile (the tile before that one)
+      if (span == (S > 1 ? 1 : 0)) store_scores(s_out[buf], fa.scoring, ob, lane);
+    }
     if (keep && tid == 0) ws.hdr[ob.tile_begin + blk].nsteps = n;   // the scoring kernel reads the header from memory
     if (fa.out_vis && span == S - 1 && lane < kTilePts && blk * kTilePts + lane < ob.n_pts) {
       // The visibility mask (Eq. 1) of the tile, as aura_project_visibility writes it; a tile that the producers
@@ -1433,6 +1591,9 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       open_tile<H, PF>(s_steps[buf], nn, a.feat, lane_off, lane, g, wa, rq);
     }
   }
+  if constexpr (SC) {   // the tile before the workgroup's last one (the scoring wave stores the last one itself)
+    if (span == (S > 1 ? 1 : 0)) store_scores(s_out[buf], fa.scoring, ob, lane);
+  }
 }
 
 // Clears the ticket counters of a launch's objects (the prepare kernel does it on the two-kernel path).
@@ -1495,9 +1656,16 @@ static int one_kernel_producers(const FuseArgs& a, int k_stage, int quota, int v
   return 4;
 }
 
+// Whether the one-kernel form of this launch can score its tiles itself: a scoring wave must fit the workgroup (at most
+// three product waves beside the four producers) and one matrix-core tile must hold the materials.
+static bool scoring_wave_fits(const FuseArgs& a, int producers, int product_waves) {
+  return producers == 4 && product_waves + 4 + 1 <= 8 && a.out_factor && a.scoring.G && a.scoring.Kpad == kScoreTileM &&
+         !a.in_mask;
+}
+
 template <int DT, int S, int H, int PF>
 static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
-                              hipStream_t stream) {
+                              hipStream_t stream, bool* scored) {
   const int max_tiles = (max_pts + kTilePts - 1) / kTilePts;
   ProdArgs pa{static_cast<const char*>(a.feat.feat), a.feat.D, ws.hdr, ws.steps, ws.counters + (size_t)ws.obj_base * kXcd,
               ws.quota, a.fused, a.out_factor, a.norm_eps, a.mean_only};
@@ -1510,14 +1678,21 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
     // the machine
     const int groups_max = np == 1 ? kFusedGroupsMax : kFusedGroupsMax / 2;
     const int groups = std::max(kXcd, std::min(max_tiles, (groups_max / n_obj + kXcd - 1) / kXcd * kXcd));
-    const dim3 grid(std::min(groups, max_tiles), n_obj), block(kWave * (S + np));
-    const int keep = a.out_factor != nullptr;   // the scoring kernel follows and reads the k-steps
-    if (np == 1) {
-      if (a.in_mask) hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, true, 1>), grid, block, 0, stream, a, pa, ws, keep, tab);
-      else hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 1>), grid, block, 0, stream, a, pa, ws, keep, tab);
+    const bool scoring = scoring_wave_fits(a, np, S);
+    const dim3 grid(std::min(groups, max_tiles), n_obj), block(kWave * (S + np + (scoring ? 1 : 0)));
+    const int keep = a.out_factor != nullptr && !scoring;   // the scoring kernel follows and reads the k-steps
+    if (scoring) {
+      if constexpr (S <= 3) {
+        pa.factor = nullptr;   // nobody reads the factors back
+        hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 4, true>), grid, block, 0, stream, a, pa, ws, keep, tab);
+        if (scored) *scored = true;
+      }
+    } else if (np == 1) {
+      if (a.in_mask) hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, true, 1, false>), grid, block, 0, stream, a, pa, ws, keep, tab);
+      else hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 1, false>), grid, block, 0, stream, a, pa, ws, keep, tab);
     } else if constexpr (S + 4 <= 8) {
-      if (a.in_mask) hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, true, 4>), grid, block, 0, stream, a, pa, ws, keep, tab);
-      else hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 4>), grid, block, 0, stream, a, pa, ws, keep, tab);
+      if (a.in_mask) hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, true, 4, false>), grid, block, 0, stream, a, pa, ws, keep, tab);
+      else hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 4, false>), grid, block, 0, stream, a, pa, ws, keep, tab);
     }
     return hipGetLastError();
   }
@@ -1534,12 +1709,13 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
 }
 
 hipError_t launch_fuse_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,
-                            hipStream_t stream) {
+                            hipStream_t stream, bool* scored) {
+  if (scored) *scored = false;
   // waves x pieces of 128 channels per wave x k-steps of rows requested ahead, for each supported D
 #define AURA_TILE_CASE(d, s, h, pf)                                                           \
   case d:                                                                                     \
-    return a.feat.dtype == 1 ? launch_tile<1, s, h, pf>(a, ws, tab, n_obj, max_pts, stream)   \
-                             : launch_tile<2, s, h, pf>(a, ws, tab, n_obj, max_pts, stream)
+    return a.feat.dtype == 1 ? launch_tile<1, s, h, pf>(a, ws, tab, n_obj, max_pts, stream, scored)   \
+                             : launch_tile<2, s, h, pf>(a, ws, tab, n_obj, max_pts, stream, scored)
   switch (a.feat.D) {
     AURA_TILE_CASE(256, 1, 2, 2);
     AURA_TILE_CASE(512, 2, 2, 2);

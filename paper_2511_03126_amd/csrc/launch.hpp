@@ -24,13 +24,16 @@ hipError_t launch_project_visibility(const VisArgs& vis, const float* xyz, uint8
 
 struct TileWs;
 // tile_ws == nullptr: per-point gather kernel; otherwise the matrix-core tile path with that workspace.
+struct TileScoring;
 hipError_t launch_fuse_features(const VisArgs& vis, const FeatArgs& feat, const float* xyz, float* fused,
                                 int* out_count, float norm_eps, int mean_only, const TileWs* tile_ws,
                                 const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream,
                                 float* out_factor = nullptr,    // tile path only: see FuseArgs::out_factor
                                 uint8_t* out_vis = nullptr, int vis_pitch = 0,    // tile path only: see FuseArgs::out_vis
                                 const uint8_t* in_mask = nullptr, int in_mask_pitch = 0,     // see FuseArgs::in_mask
-                                int two_kernels = 0);                                       // see FuseArgs::two_kernels
+                                int two_kernels = 0,                                        // see FuseArgs::two_kernels
+                                const TileScoring* scoring = nullptr,    // tile path only: see FuseArgs::scoring
+                                bool* scored = nullptr);                 // whether the launch did what `scoring` asks for
 
 // Sec. 3.2.2, view importance-based filtering (select_views.hip).
 constexpr int kSelectMaxK = 8;

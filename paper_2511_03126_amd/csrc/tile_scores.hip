@@ -142,18 +142,6 @@ struct TileScoreArgs {
   int* label;
 };
 
-// Byte offset of a cell row (a multiple of 512 * units, units = D / 256 in 1..6) -> cell index.
-__device__ __forceinline__ uint32_t cell_index(uint32_t off, uint32_t units) {
-  const uint32_t q = off >> 9;
-  switch (units) {
-    case 1: return q;
-    case 2: return q >> 1;
-    case 3: return (uint32_t)(((unsigned long long)q * 0xAAAAAAABull) >> 33);
-    case 4: return q >> 2;
-    default: return (uint32_t)(((unsigned long long)(q >> 1) * 0xAAAAAAABull) >> 33);   // 6
-  }
-}
-
 template <int DT, int MT>
 __global__ __launch_bounds__(256) void k_tile_scores(TileScoreArgs a, ObjTable tab) {
   __shared__ float ys[kScoreMaxK * kScoreMaxP];
