@@ -74,7 +74,10 @@ enum {
                                   matrix-core kernels apply (16-bit maps, D a multiple of 256).
                                   Meant for point sets that are not spatially sorted            */
   AURA_FUSE_TWO_KERNELS = 8u   /* the matrix-core fusion runs as two kernels (lists, then products) even where
-                                  its one-kernel form applies; same results bit for bit        */
+                                  its one-kernel form applies, and aura_fuse_scores scores with a kernel of its
+                                  own; same results bit for bit wherever every tile's cell list fits the
+                                  one-kernel form's on-chip buffer (a longer list is fused there by the gather
+                                  arithmetic, which can differ in the last bit)                 */
 };
 
 /* Which call a workspace size is asked for. */
