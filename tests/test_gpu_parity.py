@@ -36,6 +36,7 @@ SMALL = [
     ("c4", dict(voxel_res=72)),
     ("c5", dict(n_points=2_500, n_objects=5, ragged_views=True)),
     ("c5", dict(n_points=777, n_objects=70)),          # more objects than one launch table holds
+    ("c2", dict(n_points=1_501, n_objects=3)),         # several objects of 16 views: one launch, workgroups with few or no tiles
 ]
 
 
