@@ -178,6 +178,26 @@ def test_combined_call_scores_from_cell_similarities(H, orc, K, P, dtype):
     assert np.array_equal(sep["fused"].view(np.uint32), gpu["fused"].view(np.uint32))
 
 
+@pytest.mark.parametrize("K,P,D,dtype", [(1, 1, 512, "bf16"), (5, 3, 512, "f16"), (31, 8, 768, "bf16"), (32, 2, 768, "f16")])
+def test_combined_call_with_the_scoring_wave(H, orc, K, P, D, dtype):
+    """aura_fuse_scores where the fusion kernel scores its tiles itself (more than 8 views, at most 32 materials,
+    at most 768 channels): material counts that do and do not fill a vector, ragged last tile, and the same bits
+    as the form with the scoring kernel."""
+    s = _custom_scene(N=12_300 + K, V=12, D=D, K=K, P=P, dtype=dtype)
+    assert s.n_views * s.Hf * s.Wf <= s.N
+    d = H.DeviceScene(s)
+    d.step_combined()
+    gpu = d.results()
+    ref = H.oracle_points(orc, s)
+    print(H.compare_points(gpu, ref, s), flush=True)
+    _mass_check(H, orc, s, gpu, ref["prop"], ref["count_fuse"])
+    d.clear_outputs()
+    d.step_combined_two_kernels()
+    two = d.results()
+    for k in ("vis", "count", "fused", "scores", "prop", "label", "mass"):
+        assert np.array_equal(gpu[k].view(np.uint8), two[k].view(np.uint8)), k
+
+
 def test_scores_kernel_alone_on_random_unit_rows(H, orc):
     # isolates the matrix-core contraction: random unit rows, D not a multiple of the 32-channel step
     import paper_2511_03126_amd as aura
