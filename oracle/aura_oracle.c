@@ -334,9 +334,12 @@ int orc_fuse_features(const float* cam, const float* depth, const void* feat, in
 
 /* ---------------------------------------------------------------- exported: a5 + a6, Eq. 4
  * scores[i][k] = <fused_i, temb_k>; prop[i][p] = sum_k softmax_k(scores/T) y[k][p];
- * label[i] = argmax_k scores (lowest index on ties); margin[i] = top1 - top2.     */
+ * label[i] = argmax_k scores (lowest index on ties); margin[i] = top1 - top2.
+ * unseen_zero: Eq. 2 is 0 / 0 for a point that no view sees and the fused row is taken as all zero; Eq. 4 then gives
+ * the plain mean of y (all similarities equal).  With unseen_zero != 0 such a row (every element exactly zero) gets
+ * zero properties instead: the other reading of "no observation".  Scores and label are the same either way.   */
 int orc_material_scores(const double* fused, int64_t N, int D, const float* temb, int K,
-                        const float* y, int P, float T,
+                        const float* y, int P, float T, int unseen_zero,
                         double* scores, double* prop, int32_t* label, double* margin) {
   if (!fused || !temb || !scores) return -1;
   if (N < 0 || D < 1 || K < 1 || P < 0 || (prop && (!y || P < 1)) || !(T > 0.0f)) return -2;
@@ -366,6 +369,11 @@ int orc_material_scores(const double* fused, int64_t N, int D, const float* temb
         for (int p = 0; p < P; ++p) prop[i * P + p] += e * (double)y[(int64_t)k * P + p];
       }
       for (int p = 0; p < P; ++p) prop[i * P + p] /= den;
+      if (unseen_zero) {
+        int all_zero = 1;
+        for (int c = 0; c < D; ++c) if (f[c] != 0.0) { all_zero = 0; break; }
+        if (all_zero) for (int p = 0; p < P; ++p) prop[i * P + p] = 0.0;
+      }
     }
   }
   return 0;

@@ -155,7 +155,7 @@ def fuse_features(cam, depth, feat, feat_dtype, xyz, tau=0.0, z_near=1e-6, norm_
     return {"fused": fused, "count": count}
 
 
-def material_scores(fused, temb, y=None, T=0.1):
+def material_scores(fused, temb, y=None, T=0.1, unseen_zero=False):
     fused = np.ascontiguousarray(fused, dtype=np.float64)
     temb = _f32(temb)
     N, D = fused.shape
@@ -169,7 +169,8 @@ def material_scores(fused, temb, y=None, T=0.1):
     label = np.zeros(N, np.int32)
     margin = np.zeros(N, np.float64)
     rc = lib().orc_material_scores(_p(fused), C.c_int64(N), C.c_int(D), _p(temb), C.c_int(K), _p(y), C.c_int(P),
-                                   C.c_float(T), _p(scores), _p(prop), _p(label), _p(margin))
+                                   C.c_float(T), C.c_int(1 if unseen_zero else 0), _p(scores), _p(prop), _p(label),
+                                   _p(margin))
     _check(rc, "material_scores")
     return {"scores": scores, "prop": prop, "label": label, "margin": margin}
 
@@ -329,7 +330,7 @@ def patch_batch(cam, images, xyz, sel_view, scales, R, mean=None, inv_std=None, 
 
 
 def estimate_normals(xyz, queries, centre, k, pt_offsets=None, q_offsets=None):
-    """Sec. 3.2.2 ("we begin by estimating normal vectors for the sampled sparse point cloud"): for every query the
+    """Sec. 3.2.2 (the normals of the sampled points, which the view importance score needs): for every query the
     plane through its k nearest points of the object's cloud, i.e. the eigenvector of the smallest eigenvalue of their
     covariance, turned to point away from the object's centre.
 

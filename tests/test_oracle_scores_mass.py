@@ -110,6 +110,23 @@ def test_label_takes_lowest_index_on_exact_ties_and_zero_feature_is_uniform(orc)
     assert z["label"][0] == 0 and z["prop"][0, 0] == pytest.approx(3.0, rel=1e-15)
 
 
+def test_unseen_policy_zeroes_only_all_zero_rows(orc):
+    """Sec. 3.1 Eq. 2 is 0 / 0 for a point no view sees; the two readings of its property: Eq. 4 on an all-zero row (the
+    mean of y: hand value 3 for y = 1, 2, 6) and zero.  A row with any non-zero element, however small, and a non-zero
+    row orthogonal to every embedding (equal scores, but an observation) keep Eq. 4's value."""
+    y = np.array([[1.0, 10.0], [2.0, 20.0], [6.0, 60.0]], np.float32)
+    temb = np.eye(3, 4, dtype=np.float32)
+    rows = np.array([[0, 0, 0, 0], [0, 0, 1e-300, 0], [0, 0, 0, 1.0], [0.5, 0.25, 0.125, 0]], np.float64)
+    prior = orc.material_scores(rows, temb, y, T=0.1)
+    zero = orc.material_scores(rows, temb, y, T=0.1, unseen_zero=True)
+    assert np.allclose(prior["prop"][0], [3.0, 30.0], rtol=1e-15)
+    assert np.array_equal(zero["prop"][0], [0.0, 0.0])
+    assert np.array_equal(zero["prop"][1:], prior["prop"][1:])
+    assert np.allclose(zero["prop"][2], [3.0, 30.0], rtol=1e-15)       # orthogonal but observed: still the mean
+    for k in ("scores", "label", "margin"):
+        assert np.array_equal(zero[k], prior[k])
+
+
 # ------------------------------------------------------------------------------------ mass
 
 def _sphere_voxels(res, r):
