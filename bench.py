@@ -4,10 +4,13 @@
 One step = one pass of the whole path over one synthetic scene already resident in HBM:
 aura_fuse_scores (visibility mask and view counts, fusion, scoring) -> aura_property_integrate
 (--staged: aura_project_visibility, aura_fuse_features, aura_material_scores, aura_property_integrate).
-Prints ONE JSON line: whole-path throughput in fused point-views per second, the roofline figure
-of the dominant call (the fusion, HBM bound on writing the fused rows) measured with events on the
-launch stream in a run of its own right after the timed steps, and the CPU oracle timed on a bounded sample of the
-same workload.
+Prints ONE JSON line.  Headline: whole-path throughput in fused point-views per second on the largest configuration
+(c5: 64 objects, 6.4 M points, 13.3 GB per fusion launch), with the roofline figure of the dominant kernel - the fusion
+kernel inside aura_fuse_scores, HBM bound on writing the fused rows - timed with events that the library records around
+that kernel in a second pass over the same steps.  `configs` holds the same measurement for c1-c4, `single_pass` the
+whole path as one call that never writes the fused rows (aura_fuse_score_integrate), `stress` the frustum-only and
+unsorted-points cases, `beyond_hot_path` the calls around the hot path on c2, and `cpu_baseline` the CPU oracle timed on
+a bounded sample of the headline workload.
 """
 import argparse
 import gc
@@ -18,7 +21,6 @@ import time
 
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
-sys.path.insert(0, os.path.join(ROOT, "tests"))
 
 HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E
 
@@ -30,22 +32,21 @@ def fuse_algorithmic_bytes(s):
             + 4 * s.N * s.D + 4 * s.N)
 
 
-# HBM bytes per aura_fuse_features call on workload c2 from the rocprofv3 counter runs summarised in
-# profiles/whole_path_c2_hbm_traffic.md (FETCH_SIZE and WRITE_SIZE of k_tile_fused, each
-# scaled by the reading of the 256 MiB calibration copy in the same run).  Valid only for the kernel source
-# the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_C2_BYTES = 671120393
-TRAFFIC_SOURCE_SHA256 = "63db4f76e914b9c5077bed0f61aa2c7c53b41fa1caaaf60b6282018b9fe2b1ee"
+# HBM bytes per launch of the dominant kernel from the rocprofv3 counter runs summarised under profiles/ (FETCH_SIZE and
+# WRITE_SIZE, each scaled by the reading of the 256 MiB calibration copy in the same run), per workload.  Valid only for
+# the kernel source the counters were taken with: any change to that file makes the figure null until they are taken again.
+TRAFFIC_BYTES = {}
+TRAFFIC_SOURCE_SHA256 = ""
 
 
-def measured_traffic():
+def measured_traffic(workload):
     import hashlib
     src = os.path.join(ROOT, "paper_2511_03126_amd", "csrc", "fuse_tile.hip")
     try:
         digest = hashlib.sha256(open(src, "rb").read()).hexdigest()
     except OSError:
         return None
-    return TRAFFIC_C2_BYTES if digest == TRAFFIC_SOURCE_SHA256 else None
+    return TRAFFIC_BYTES.get(workload) if digest == TRAFFIC_SOURCE_SHA256 else None
 
 
 def time_densify(torch, d, s, reps, n_sources=150, k=5):
@@ -254,7 +255,7 @@ def cpu_baseline(scene, seconds_target=15.0):
         stages[name] = 0.0           # the sizing run above does not count
     t = run(n)
     reps = 1
-    while t < 0.7 * seconds_target and reps < 64:     # the whole object is quicker than the target: repeat it
+    while t < 0.7 * seconds_target and reps < 1024:   # the whole object is quicker than the target: repeat it
         t += run(n)
         reps += 1
     return {"value": reps * n * v1 / t, "unit": "point-views/s", "cores": orc.max_threads(), "kind": "oracle",
@@ -286,60 +287,126 @@ def calibrate(torch, reps=10):
     return out
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=100,
-                    help="untimed steps before the timed ones; the GPU needs some tens of milliseconds of load to reach its clocks")
-    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--staged", action="store_true", help="fusion and scoring as two library calls")
-    ap.add_argument("--hot-path-only", action="store_true",
-                    help="skip the calls beyond the hot path (densification, thickness integration, view selection)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        sys.exit("bench.py: this library runs on exactly one GPU (the path would shard by points, one GPU each); "
-                 "use --gpus 1")
+MFMA_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 / fp16 matrix cores
+CLOCK_RAMP_MS = 300.0       # load put on the GPU before the counted warm-up, so that the clocks are up whatever --warmup is
+KERNEL_WARMUP = 3           # steps before the per-kernel event pass (its own, not tied to --warmup)
 
-    import torch
-    import gpu_harness as H
-    from workloads.scenes import make_scene
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
 
-    s = make_scene(args.workload)
-    d = H.DeviceScene(s)
-    if args.staged:
-        names = ["project_visibility", "fuse_features", "material_scores", "property_integrate"]
-        calls = [d.project_visibility, d.fuse_features, d.material_scores, d.property_integrate]
-    else:
-        names = ["fuse_scores", "property_integrate"]       # the mask and view counts come out of the fusion
-        calls = [d.fuse_scores_vis, d.property_integrate]
-    # Python's cyclic garbage collector is off during the warm-up and the timed steps: a full collection (it comes
-    # after a few hundred steps' worth of allocations and walks every object torch has created) stops the host for
-    # about 40 ms, the launch queue runs dry and the figure would be the host's, not the GPU's.
-    gc.collect()
-    gc.disable()
-    for _ in range(max(args.warmup, 0)):
-        for call in calls:
-            call()
+def single_pass_algorithmic_bytes(s):
+    """aura_fuse_score_integrate: every input once; scores, properties, labels, view counts and the mask once."""
+    elt = 4 if s.feat_dtype == "f32" else 2
+    return (12 * s.N + 64 * s.n_views + 4 * s.n_views * s.H * s.W + elt * s.n_views * s.Hf * s.Wf * s.D
+            + 4 * s.K * s.D + 4 * s.N * s.K + 4 * s.N * s.P + 4 * s.N + 4 * s.N + s.N * s.vis_pitch)
+
+
+def timed_steps(torch, calls, steps):
+    """Exactly `steps` steps between two synchronisations; returns (ms per step, host enqueue ms per step)."""
     torch.cuda.synchronize()
-
-    # The timed region: exactly args.steps steps between two synchronisations, nothing else on the stream.
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         for call in calls:
             call()
     t_enqueued = time.perf_counter()
     torch.cuda.synchronize()
     t1 = time.perf_counter()
+    return (t1 - t0) * 1e3 / steps, (t_enqueued - t0) * 1e3 / steps
 
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    # host time to enqueue one step; once the launch queue is full it is the GPU's pace, not the host's cost
-    enqueue_ms_per_step = (t_enqueued - t0) * 1e3 / args.steps
 
-    # Time per call, from a short run of its own with an event after every call.
-    n_split = min(args.steps, 20)
+def clock_ramp(torch, calls, ramp_ms):
+    """The same calls as the timed steps for at least ramp_ms of wall time (the GPU reaches its clocks only after some tens
+    of milliseconds of load); the host waits every few steps so that the queue does not run far ahead."""
+    t0 = time.perf_counter()
+    while (time.perf_counter() - t0) * 1e3 < ramp_ms:
+        for _ in range(4):
+            for call in calls:
+                call()
+        torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3
+
+
+def fusion_kernel_ms(torch, calls, steps):
+    """Average duration of the fusion kernel inside the step's calls: the library records a pair of events around that
+    kernel (aura_time_next_fusion) on the launch stream, one pair per step, over `steps` further steps queued back to back."""
+    import paper_2511_03126_amd as aura
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for a, b in pairs:      # a first record creates the handles the library records on
+        a.record()
+        b.record()
+    for _ in range(KERNEL_WARMUP):
+        for call in calls:
+            call()
+    torch.cuda.synchronize()
+    for a, b in pairs:
+        aura.time_next_fusion(a, b)
+        for call in calls:
+            call()
+    aura.time_next_fusion(None, None)
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) for a, b in pairs)
+    return sum(t) / len(t), {"min_ms": t[0], "median_ms": t[len(t) // 2], "max_ms": t[-1]}
+
+
+def marker_overhead_ms(torch, n=20):
+    """What a pair of stream markers adds to the interval they bracket: the same two event records around a 16-byte fill
+    (a kernel of a few microseconds), queued back to back like the pairs of fusion_kernel_ms."""
+    from paper_2511_03126_amd import binding
+    tiny = torch.zeros(16, dtype=torch.uint8, device="cuda")
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    binding.calibration_fill(tiny, 0)
+    for a, b in pairs:
+        a.record()
+        binding.calibration_fill(tiny, 0)
+        b.record()
+    torch.cuda.synchronize()
+    t = sorted(a.elapsed_time(b) for a, b in pairs)
+    return t[len(t) // 2]
+
+
+def back_to_back_ms(torch, call, n):
+    """n launches of one call between one pair of events: no marker between the launches."""
+    for _ in range(KERNEL_WARMUP):
+        call()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(n):
+        call()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / n
+
+
+def tile_steps(torch, d, s):
+    """k-steps (16 feature cells each) per 32-point tile of the matrix-core fusion, read from the tile headers that the
+    two-kernel form leaves in the workspace; None where the gather kernel runs."""
+    if d.ws_fuse is None:
+        return None
+    import numpy as np
+    d.fuse_features(two_kernels=True)
+    torch.cuda.synchronize()
+    ntile = int(np.sum((np.diff(s.pt_offsets) + 31) // 32))
+    n = d.ws_fuse[:ntile * 144].cpu().numpy().view(np.int32).reshape(ntile, 36)[:, 0]
+    return {"tiles": ntile, "mean": float(n[n >= 0].mean()) if (n >= 0).any() else 0.0, "max": int(n.max()),
+            "fused_by_gather": int((n < 0).sum()), "total": int(n[n >= 0].sum())}
+
+
+def measure(torch, s, name, steps, warmup, staged=False, flags=0, want_single_pass=True):
+    """One workload: the timed steps, the time per call, the fusion kernel's roofline figure, and the single-pass call."""
+    from paper_2511_03126_amd.device_scene import DeviceScene
+    d = DeviceScene(s, flags=flags)
+    if staged:
+        names = ["project_visibility", "fuse_features", "material_scores", "property_integrate"]
+        calls = [d.project_visibility, d.fuse_features, d.material_scores, d.property_integrate]
+    else:
+        names = ["fuse_scores", "property_integrate"]       # the mask and view counts come out of the fusion
+        calls = [d.fuse_scores_vis, d.property_integrate]
+    ramp_ms = clock_ramp(torch, calls, CLOCK_RAMP_MS)
+    for _ in range(max(warmup, 0)):
+        for call in calls:
+            call()
+    ms_per_step, enqueue_ms = timed_steps(torch, calls, steps)
+
+    # time per call, from a short run of its own with an event after every call
+    n_split = min(steps, 20)
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls) + 1)] for _ in range(n_split)]
     for k in range(n_split):
         ev[k][0].record()
@@ -347,81 +414,161 @@ def main():
             call()
             ev[k][c + 1].record()
     torch.cuda.synchronize()
-    call_ms = {n: sum(ev[k][c].elapsed_time(ev[k][c + 1]) for k in range(n_split)) / n_split
-               for c, n in enumerate(names)}
+    call_ms = {n: sum(ev[k][c].elapsed_time(ev[k][c + 1]) for k in range(n_split)) / n_split for c, n in enumerate(names)}
+
     pv = s.point_views
     tile = d.ws_fuse is not None
-    gpu = d.results()
-
-    # Roofline of the dominant work: the fusion proper (the matrix-core kernels, or k_fuse_gather), which writes
-    # the fused rows.  Inside aura_fuse_scores it cannot be bracketed by events, so it is timed through
-    # aura_fuse_features (same inputs, same workspace) right after the timed steps, with events on the launch
-    # stream.  Inside aura_fuse_scores the same kernels also serve the scoring (a scoring wave per workgroup, or the
-    # k-steps left in memory for the scoring kernel; see calls_ms for the whole call).
-    fuse_reps = max(args.steps, 10)
-    fuse_warmup = max(3, min(args.warmup, 50))
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for _ in range(fuse_warmup):
-        d.fuse_features()
-    e0.record()
-    for _ in range(fuse_reps):
-        d.fuse_features()
-    e1.record()
-    torch.cuda.synchronize()
-    fuse_ms = e0.elapsed_time(e1) / fuse_reps
-    # the same call one at a time (its own pair of events): spread of the launches, and a second figure with the
-    # caches flushed by a 512 MiB fill before every call (maps, depth and workspace then come from HBM)
-    def one_by_one(flush):
-        big = torch.empty(512 << 20, dtype=torch.uint8, device="cuda") if flush else None
-        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(fuse_reps)]
-        from paper_2511_03126_amd import binding
-        for a, b in pairs:
-            if flush:
-                binding.calibration_fill(big, 1)
-            a.record()
-            d.fuse_features()
-            b.record()
-        torch.cuda.synchronize()
-        t = sorted(a.elapsed_time(b) for a, b in pairs)
-        return {"min_ms": t[0], "median_ms": t[len(t) // 2], "max_ms": t[-1]}
-    warm_each, cold_each = one_by_one(False), one_by_one(True)
-    calibration = calibrate(torch)   # after the measurements above: its 256 MiB sweeps leave the caches full of its data
+    vis_frac = float(d.vis.float().mean())
+    unseen = float((d.count_fuse == 0).float().mean())
+    kernel_ms, spread = fusion_kernel_ms(torch, calls, max(steps, 10))
     fuse_bytes = fuse_algorithmic_bytes(s)
-    achieved = fuse_bytes / (fuse_ms * 1e-3) / 1e9
-    kernel = "aura_fuse_features: " + (f"matrix-core fusion <{s.feat_dtype}, {s.D // 256} product waves> (k_tile_fused where the "
-                                       "one-kernel form applies, else k_tile_prepare + k_tile_product)" if tile
-                                       else "k_fuse_gather")
-    traffic = measured_traffic() if (tile and args.workload == "c2") else None
-    extras = {}
-    if not args.hot_path_only:
-        extras = {"densify": time_densify(torch, d, s, max(args.steps // 2, 5)),
-                  "thickness_integrate": time_thickness(torch, d, s, max(args.steps // 2, 5)),
-                  "view_selection": time_selection(torch, d, s, max(args.steps // 2, 5)),
-                  "voxel_downsample": time_downsample(torch, d, s, max(args.steps // 2, 5)),
-                  "estimate_normals": time_normals(torch, d, s, max(args.steps // 2, 5)),
-                  "patch_batch": time_patches(torch, d, s, max(args.steps // 2, 5)),
-                  "patch_batch_f16": time_patches(torch, d, s, max(args.steps // 2, 5), half=True)}
-    gc.enable()
+    achieved = fuse_bytes / (kernel_ms * 1e-3) / 1e9
+    kernel = (f"matrix-core fusion <{s.feat_dtype}, {s.D // 256} product waves> inside {names[1] if staged else names[0]} "
+              "(k_tile_fused; k_tile_prepare + k_tile_product where the lists do not fit the one-kernel form)"
+              if tile else f"k_fuse_gather inside {names[1] if staged else names[0]}")
     out = {
-        "metric": "fused point-views/sec", "value": pv / (ms_per_step * 1e-3), "unit": "point-views/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": f"{args.workload}: N={s.N} points, B={s.B} objects, {s.n_views} views {s.H}x{s.W}, "
-                               f"feature grid {s.Hf}x{s.Wf}x{s.D} {s.feat_dtype}, K={s.K} materials, P={s.P}, "
-                               f"mass grid G={s.G}", "point_views": pv,
-                   "visible_point_views_per_s": float(gpu["vis"].mean()) * pv / (ms_per_step * 1e-3),
-                   "visible_fraction": float(gpu["vis"].mean()), "unseen_points": float((gpu["count_fuse"] == 0).mean()),
-                   "order": s.meta["order"], "seed": s.meta["seed"]},
-        "calls_ms": call_ms, "host_enqueue_ms_per_step": enqueue_ms_per_step,
-        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved,
-                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
-                     "algorithmic_bytes": fuse_bytes, "avg_launch_ms": fuse_ms, "launches": fuse_reps, "warmup_launches": fuse_warmup,
-                     "single_launches": warm_each, "single_launches_caches_flushed": cold_each,
-                     "frac_caches_flushed": fuse_bytes / (cold_each["median_ms"] * 1e-3) / 1e9 / HBM_PEAK_GBPS,
-                     "frac_of_fill_kernel": achieved / calibration["fill_GBps"]},
-        **extras,
-        "calibration": calibration,
+        "workload": f"{name}: N={s.N} points, B={s.B} objects, {s.n_views} views {s.H}x{s.W}, "
+                    f"feature grid {s.Hf}x{s.Wf}x{s.D} {s.feat_dtype}, K={s.K} materials, P={s.P}, mass grid G={s.G}",
+        "point_views": pv, "ms_per_step": ms_per_step, "point_views_per_s": pv / (ms_per_step * 1e-3),
+        "visible_fraction": vis_frac, "visible_point_views_per_s": vis_frac * pv / (ms_per_step * 1e-3),
+        "unseen_points": unseen, "order": s.meta["order"], "seed": s.meta["seed"], "flags": flags,
+        "clock_ramp_ms": ramp_ms, "calls_ms": call_ms, "host_enqueue_ms_per_step": enqueue_ms,
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": measured_traffic(name) if (tile and not flags) else None,
+                     "algorithmic_bytes": fuse_bytes, "avg_launch_ms": kernel_ms, "launches": max(steps, 10),
+                     "launch_spread": spread,
+                     # context for short kernels: the interval between the two markers holds the kernel plus the markers'
+                     # own cost; the same fusion launched by aura_fuse_features, many calls between one pair of events
+                     "marker_pair_overhead_ms": marker_overhead_ms(torch),
+                     "fuse_features_back_to_back_ms": back_to_back_ms(torch, d.fuse_features, max(steps, 10))},
     }
+    ks = None if (flags & 4) else tile_steps(torch, d, s)     # (AURA_FUSE_GATHER: no tiles)
+    if ks is not None:
+        out["tile_k_steps"] = {k: ks[k] for k in ("tiles", "mean", "max", "fused_by_gather")}
+    if want_single_pass:
+        one = [d.step_single_pass_call]
+        clock_ramp(torch, one, 50.0)
+        sp_ms, _ = timed_steps(torch, one, steps)
+        sp_kernel_ms, sp_spread = fusion_kernel_ms(torch, one, max(steps, 10))
+        sp_bytes = single_pass_algorithmic_bytes(s)
+        sp = {"call": "aura_fuse_score_integrate", "ms_per_step": sp_ms, "point_views_per_s": pv / (sp_ms * 1e-3),
+              "fusion_kernel_ms": sp_kernel_ms, "launch_spread": sp_spread, "algorithmic_bytes": sp_bytes,
+              "algorithmic_GBps": sp_bytes / (sp_ms * 1e-3) / 1e9,
+              "hbm_frac": sp_bytes / (sp_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS}
+        if ks is not None and ks["fused_by_gather"] == 0:
+            # Matrix-core work of the fusion kernel: per k-step the 32 x 16 weights (two 16-bit terms) times 16 x D cells;
+            # where it scores its tiles itself, three partial products of 32 x 16 by 16 x 32 more.  Not what bounds the
+            # kernel (its producer waves are: dependent chains of projection, depth read, cell lists), reported for scale.
+            flops = ks["total"] * (2 * 2 * 32 * 16 * s.D)
+            sp["roofline"] = {"bound": "mfma", "kernel": "fusion kernel of aura_fuse_score_integrate (no row stores)",
+                              "achieved": flops / (sp_kernel_ms * 1e-3) / 1e12, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                              "frac": flops / (sp_kernel_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, "traffic": None,
+                              "algorithmic_flops": flops}
+        out["single_pass"] = sp
+    return out, d
+
+
+def _make(job):
+    """Scene generation in a worker process (numpy only; started before this process touches the GPU)."""
+    from workloads.scenes import make_scene
+    name, order = job
+    return make_scene(name, order=order)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5,
+                    help="untimed steps before the timed ones (after a time-based clock ramp of the same calls)")
+    ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"],
+                    help="the headline workload; the others are reported under `configs`")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--staged", action="store_true", help="fusion and scoring as two library calls")
+    ap.add_argument("--only-headline", action="store_true",
+                    help="skip the other configurations, the stress cases and the calls beyond the hot path")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this library runs on exactly one GPU (the path would shard by points, one GPU each); "
+                 "use --gpus 1")
+
+    # every scene is generated up front, in worker processes forked before anything touches the GPU
+    from concurrent.futures import ProcessPoolExecutor
+    import multiprocessing
+    others = [] if args.only_headline else [w for w in ("c1", "c2", "c3", "c4") if w != args.workload]
+    jobs = [(args.workload, "morton")] + [(w, "morton") for w in others]
+    if not args.only_headline:
+        jobs += [("c2", "random"), ("c5", "random")]
+    with ProcessPoolExecutor(max_workers=min(len(jobs), 8), mp_context=multiprocessing.get_context("fork")) as pool:
+        scenes = dict(zip(jobs, pool.map(_make, jobs)))
+
+    import torch
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    # Python's cyclic garbage collector is off during the measurements: a full collection (it comes after a few hundred
+    # steps' worth of allocations and walks every object torch has created) stops the host for about 40 ms, the launch
+    # queue runs dry and the figure would be the host's, not the GPU's.
+    gc.collect()
+    gc.disable()
+
+    def release(d):
+        del d
+        gc.collect()
+        torch.cuda.empty_cache()
+
+    s = scenes[(args.workload, "morton")]
+    head, d = measure(torch, s, args.workload, args.steps, args.warmup, staged=args.staged)
+    release(d)
+    out = {
+        "metric": "fused point-views/sec", "value": head["point_views_per_s"], "unit": "point-views/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": s.feat_dtype, "data": "synthetic",
+        "clock_ramp_ms": head["clock_ramp_ms"],
+        "config": {"workload": head["workload"], "point_views": head["point_views"],
+                   "visible_point_views_per_s": head["visible_point_views_per_s"],
+                   "visible_fraction": head["visible_fraction"], "unseen_points": head["unseen_points"],
+                   "order": head["order"], "seed": head["seed"]},
+        "calls_ms": head["calls_ms"], "host_enqueue_ms_per_step": head["host_enqueue_ms_per_step"],
+        "roofline": head["roofline"], "single_pass": head.get("single_pass"),
+    }
+    if "tile_k_steps" in head:
+        out["tile_k_steps"] = head["tile_k_steps"]
+    if not args.only_headline:
+        configs = []
+        for w in others:
+            r, d = measure(torch, scenes[(w, "morton")], w, args.steps, args.warmup, staged=args.staged)
+            if w == "c2":
+                reps = max(args.steps // 2, 5)
+                d.step_combined()      # the calls beyond the hot path take the fused rows and scores as input
+                out["beyond_hot_path"] = {"workload": "c2",
+                                          "densify": time_densify(torch, d, d.scene, reps),
+                                          "thickness_integrate": time_thickness(torch, d, d.scene, reps),
+                                          "view_selection": time_selection(torch, d, d.scene, reps),
+                                          "voxel_downsample": time_downsample(torch, d, d.scene, reps),
+                                          "estimate_normals": time_normals(torch, d, d.scene, reps),
+                                          "patch_batch": time_patches(torch, d, d.scene, reps),
+                                          "patch_batch_f16": time_patches(torch, d, d.scene, reps, half=True)}
+            release(d)
+            configs.append(r)
+        out["configs"] = configs
+        # Stress cases.  c4 with the depth test off: 94 % of its voxels are inside the solid and seen by no view, so only
+        # without the test do all its pairs gather.  Points in generation order instead of Morton order: the tiles' cell
+        # lists outgrow their storage and the in-kernel gather takes over; AURA_FUSE_GATHER is the kernel meant for that.
+        from paper_2511_03126_amd import binding
+        stress = {}
+        r, d = measure(torch, scenes[("c4", "morton")] if args.workload != "c4" else s, "c4", args.steps, args.warmup,
+                       flags=binding.VIS_FRUSTUM_ONLY)
+        release(d)
+        stress["c4_frustum_only"] = r
+        for w in ("c2", "c5"):
+            for label, flags in (("matrix_core_path", 0), ("gather_kernel", binding.FUSE_GATHER)):
+                r, d = measure(torch, scenes[(w, "random")], w, max(args.steps // 2, 5), 2, flags=flags,
+                               want_single_pass=False)
+                release(d)
+                stress[f"{w}_unsorted_{label}"] = {k: r[k] for k in ("workload", "order", "ms_per_step", "point_views_per_s",
+                                                                     "calls_ms", "roofline", "tile_k_steps") if k in r}
+        out["stress"] = stress
+    out["calibration"] = calibrate(torch)
+    gc.enable()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(s)
     print(json.dumps(out))

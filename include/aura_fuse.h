@@ -13,9 +13,10 @@
  *   aura_select_views         Sec. 3.2.2: view importance scores and the top-k views per point
  *   aura_fuse_selected        Sec. 3.2.3: Eq. 2 over the kept views only
  *   aura_patch_batch          Sec. 3.2.3: the multi-scale image patches of the kept views as one batch for the encoder
- *   aura_fuse_scores          the two calls above in one (Eq. 2, then Sec. 3.4.1 / Eq. 4)
+ *   aura_fuse_scores          aura_fuse_features and aura_material_scores in one (Eq. 2, then Sec. 3.4.1 / Eq. 4)
+ *   aura_fuse_score_integrate Eq. 1-2, Sec. 3.4.1 / Eq. 4 and Sec. 3.4.2 in one pass that never writes the fused features
  *   aura_knn_densify          Sec. 3.4.1 Eq. 5: feature-space k-NN densification, then Eq. 4
- *   aura_property_integrate   Sec. 3.4.2: voxel integration over volumes (mass)
+ *   aura_property_integrate   Sec. 3.4.2: property times voxel volume, summed per object (mass)
  *   aura_thickness_integrate  Sec. 3.4.2: thickness-based integration (b_adap x b_adap x theta voxels, factor
  *                             lambda) and the centre of mass of Sec. 2.1 / 3.4
  *
@@ -77,13 +78,20 @@ enum {
                                   its one-kernel form applies, and aura_fuse_scores scores with a kernel of its
                                   own; same results bit for bit wherever every tile's cell list fits the
                                   one-kernel form's on-chip buffer (a longer list is fused there by the gather
-                                  arithmetic, which can differ in the last bit)                 */
+                                  arithmetic, which can differ in the last bit)                 */,
+  AURA_UNSEEN_PRIOR = 0u,      /* default.  A point that no view sees (Eq. 2 is 0 / 0 there: all-zero fused row, view
+                                  count 0) has similarity 0 to every material, so Eq. 4 gives it the plain mean of y -
+                                  the value before any observation.  It never enters an integral: aura_property_integrate
+                                  and aura_thickness_integrate skip points whose count is 0                       */
+  AURA_UNSEEN_ZERO = 16u       /* the scoring calls write 0 instead of that mean into the properties of a point whose
+                                  similarities are all exactly zero (what an all-zero fused row gives): property fields
+                                  in which "not observed" must not look like a material.  Scores and labels unchanged  */
 };
 
 /* Which call a workspace size is asked for. */
 enum { AURA_CALL_MATERIAL_SCORES = 1, AURA_CALL_PROPERTY_INTEGRATE = 2, AURA_CALL_FUSE_FEATURES = 3,
        AURA_CALL_FUSE_SCORES = 4, AURA_CALL_KNN_DENSIFY = 5,
-       AURA_CALL_THICKNESS_INTEGRATE = 6 };
+       AURA_CALL_THICKNESS_INTEGRATE = 6, AURA_CALL_FUSE_SCORE_INTEGRATE = 7 };
 
 /* Problem sizes for aura_workspace_bytes; fields a call does not list are ignored. */
 typedef struct aura_sizes_t {
@@ -95,6 +103,7 @@ typedef struct aura_sizes_t {
   int32_t K;            /* candidate materials                                                 */
   int32_t G;            /* voxels per axis of the integration grid, 0 = point-volume mode      */
   int32_t Ns;           /* source points of aura_knn_densify                                   */
+  int32_t P;            /* property columns                                                    */
 } aura_sizes_t;
 
 /* One set of calibrated views (Sec. 3.1: poses, Depth_v and F_v for v in V). */
@@ -143,10 +152,24 @@ int32_t aura_last_hip_error(void);
  *   AURA_CALL_FUSE_SCORES         N, B, n_views, Hf, Wf, D, feat_dtype, K
  *   AURA_CALL_KNN_DENSIFY         D, Ns
  *   AURA_CALL_THICKNESS_INTEGRATE N, B
+ *   AURA_CALL_FUSE_SCORE_INTEGRATE N, B, n_views, Hf, Wf, D, feat_dtype, K, P, G
  * Errors: AURA_ERR_NULL (sizes, bytes), AURA_ERR_SHAPE, AURA_ERR_DTYPE, AURA_ERR_UNSUPPORTED
  * (unknown call, or sizes beyond the limits of the call).
  */
 aura_status_t aura_workspace_bytes(int32_t call, const aura_sizes_t* sizes, size_t* bytes);
+
+/*
+ * Where the status word of a fusion call lies inside its workspace.  The one-kernel form of the matrix-core fusion
+ * (see aura_fuse_features) lets the waves that build a tile's cell lists wait for one another with a bounded number of
+ * looks; should such a wait ever run out (it cannot, short of a defect in the library or the machine), the kernel
+ * still ends, the results of the call are not to be trusted, and bit 0 of this 32-bit word is set.  Every call clears
+ * the word when it starts.  The library never copies to the host: a caller who wants the guarantee reads the word
+ * (workspace + *offset, device memory) after the stream has passed the call; zero means nothing to report.
+ *   call  AURA_CALL_FUSE_FEATURES (also for aura_fuse_selected), AURA_CALL_FUSE_SCORES or AURA_CALL_FUSE_SCORE_INTEGRATE
+ *   sizes as for aura_workspace_bytes     *present = 0: these sizes run kernels that have no such wait (no word)
+ * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_DTYPE, AURA_ERR_UNSUPPORTED (another call).
+ */
+aura_status_t aura_fuse_status_offset(int32_t call, const aura_sizes_t* sizes, size_t* offset, int32_t* present);
 
 /*
  * Sec. 3.1 "Visibility Checking", Eq. 1.  Projects every point into every view of its object
@@ -204,7 +227,8 @@ aura_status_t aura_fuse_features(const aura_views_t* views, const aura_params_t*
  * evaluated with the row maximum subtracted.  label[i] = argmax_k scores[i][k], the lowest k
  * on exact ties.  An all-zero fused row therefore gives the plain mean of y and label 0.
  *
- *   fused  [device] [N][D] fp32          temb  [device] [K][D] fp32 (temb_dtype must be AURA_F32)
+ *   fused  [device] [N][D] fp32          temb  [device] [K][D] of temb_dtype (AURA_F32, AURA_BF16 or AURA_F16;
+ *          16-bit embeddings are widened exactly to fp32 first, into the workspace)
  *   y      [device] [K][P] fp32 or NULL  scores [device] [N][K] fp32
  *   prop   [device] [N][P] fp32 or NULL (needs y)   label [device] [N] int32 or NULL
  *   workspace [device] aura_workspace_bytes(AURA_CALL_MATERIAL_SCORES, ...) bytes, 256-byte aligned
@@ -238,7 +262,7 @@ aura_status_t aura_material_scores(const float* fused, int64_t N, int32_t D,
  *   fused  [device] [N][D] fp32, 16-byte aligned (required)    count [device] [N] int32 or NULL
  *   vis    [device] [N][vis_pitch] uint8 or NULL: the mask of Eq. 1 exactly as aura_project_visibility writes it
  *          (the fusion evaluates it anyway), vis_pitch >= the largest per-object view count
- *   temb   [device] [K][D] fp32 (temb_dtype must be AURA_F32)  y     [device] [K][P] fp32 or NULL
+ *   temb   [device] [K][D] of temb_dtype (AURA_F32, AURA_BF16 or AURA_F16)  y     [device] [K][P] fp32 or NULL
  *   scores [device] [N][K] fp32   prop [device] [N][P] fp32 or NULL (needs y)   label [device] [N] or NULL
  *   workspace [device] aura_workspace_bytes(AURA_CALL_FUSE_SCORES, ...) bytes, 256-byte aligned (required)
  * Limits: 1 <= K <= 128, 1 <= P <= 8.
@@ -251,6 +275,39 @@ aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* p
                                float* fused, int32_t* count, uint8_t* vis, int32_t vis_pitch,
                                float* scores, float* prop, int32_t* label,
                                void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Sec. 3.1 Eq. 1-2, then Sec. 3.4.1 / Eq. 4, then Sec. 3.4.2 (the voxel sum of property times volume), in one pass: what
+ * aura_fuse_scores followed by aura_property_integrate (column p_index of the properties, the view counts of the
+ * fusion as `count`) computes, for callers that want scores, property fields and the integrated property but not the
+ * fused features themselves.  Sec. 3.4.1 and 3.4.2 consume only omega, rho and the mass; the fused feature of Eq. 2 is
+ * an intermediate, and here its [N][D] array is never written to memory:
+ *   - where the fusion runs on the matrix cores (see aura_fuse_features) and the call has at most four times as many
+ *     feature cells as points, the scores come from per-cell similarities as in aura_fuse_scores, the fusion kernels
+ *     keep each tile's rows in registers only as long as the L2 norm needs them;
+ *   - otherwise the rows of 32768 points at a time pass through a buffer in the workspace between the gather kernel and
+ *     the scoring kernel.
+ * Results equal those of the two calls up to fp32 rounding (bit for bit where aura_fuse_scores takes the same kernels).
+ * Arguments as in aura_fuse_scores and aura_property_integrate, except:
+ *   y      [device] [K][P] fp32, required (P >= 1)
+ *   count  [device] [N] int32 or NULL     vis [device] [N][vis_pitch] uint8 or NULL
+ *   scores [device] [N][K] fp32 (required)   prop [device] [N][P] fp32 or NULL   label [device] [N] int32 or NULL
+ *   mass   [device] [B] fp32 (required)   n_used [device] [B] int64 or NULL
+ *   workspace [device] aura_workspace_bytes(AURA_CALL_FUSE_SCORE_INTEGRATE, ...) bytes, 256-byte aligned (required)
+ * A point no view sees has scores 0 and the mean of y as its property (0 with AURA_UNSEEN_ZERO), and does not enter
+ * the mass.
+ * Errors: those of aura_fuse_scores and aura_property_integrate.
+ */
+aura_status_t aura_fuse_score_integrate(const aura_views_t* views, const aura_params_t* params,
+                                        const float* xyz, int64_t N,
+                                        const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                                        const void* temb, int32_t temb_dtype, int32_t K, const float* y, int32_t P,
+                                        int32_t p_index, const float* vol, float vol_uniform,
+                                        const float* grid_lo, const float* grid_h, int32_t G,
+                                        int32_t* count, uint8_t* vis, int32_t vis_pitch,
+                                        float* scores, float* prop, int32_t* label,
+                                        float* mass, int64_t* n_used,
+                                        void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * Sec. 3.4.1 Eq. 5, densification.  Ns sparse source points carry material vectors ws[j] (the K numbers
@@ -282,7 +339,7 @@ aura_status_t aura_knn_densify(const float* fq, int64_t Nq, int32_t D, const flo
                                int32_t* nn_idx, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Sec. 3.4.2 "voxel integration over volumes".  Each point is the centre of a voxel; the
+ * Sec. 3.4.2, integration of a property over voxels.  Each point is the centre of a voxel; the
  * integrated property of object b is the sum of property times voxel volume.  A point is used
  * when count is NULL or count[i] > 0.
  *   G == 0, point-volume mode:  mass[b] = sum_i prop[i][p_index] * vol_i,  vol_i = vol[i] if vol is
@@ -343,10 +400,10 @@ aura_status_t aura_voxel_downsample(const float* xyz, int64_t N, const int64_t* 
                                     int32_t* voxel_of_point, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
- * Sec. 3.2.2: "we begin by estimating normal vectors for the sampled sparse point cloud".  For every query point q of
+ * Sec. 3.2.2, the normals of the sampled points that the view importance score needs.  For every query point q of
  * object b: the k points of the object's cloud nearest to q; the normal is the unit eigenvector of the smallest
  * eigenvalue of their covariance (the plane through them), with the sign that points away from centre[b]
- * ("oriented outward"; when it is at right angles to q - centre the sign is arbitrary).  The paper names no
+ * (the outward orientation the section asks for; when it is at right angles to q - centre the sign is arbitrary).  The paper names no
  * neighbourhood size: k is an argument.
  * Which points are nearest is decided on the fp32 distance d = (dx dx + dy dy) + dz dz, dx = p_x - q_x, every
  * operation rounded to fp32; of equal distances the lower index first.  Sums, covariance and eigenvectors are fp64.
@@ -434,7 +491,7 @@ aura_status_t aura_patch_batch(const float* cam, int32_t n_views, int32_t H, int
  *     com[b]   = sum zeta[s] xyz[s] / total[b], the centre of mass (Sec. 2.1 names it among the integral
  *                estimates; zero when total[b] is 0)
  * L is box_len[b] when box_len is given, else the longest side of the axis-aligned bounding box of all the
- * object's points (the paper says "characteristic length of its bounding box" without choosing one).
+ * object's points (the paper asks for a length that characterises the bounding box without choosing one).
  * T = params->temperature; the paper takes T = 0.1 and lambda = 0.6.  fp32 per point, fp64 sums in a fixed order.
  *
  *   scores [device] [N][K] fp32       y [device] [K][P] fp32       theta [device] [K] fp32
@@ -452,6 +509,19 @@ aura_status_t aura_thickness_integrate(const float* scores, int64_t N, int32_t K
                                        const aura_params_t* params, float lambda, float scale_factor,
                                        float* zeta, float* total, float* com, float* b_adap, int64_t* n_used,
                                        void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Timing aid (not part of the method).  The next call of aura_fuse_features, aura_fuse_selected, aura_fuse_scores or
+ * aura_fuse_score_integrate made by this host thread records start_event on its stream right before, and stop_event
+ * right after, the launch of its fusion kernel (the kernel that evaluates Eq. 1-2 and writes the fused rows; both
+ * kernels where the matrix-core fusion runs as two; of a call with more than 64 objects the first launch).  The time
+ * between the two events is the kernel's duration plus what the two stream markers cost (some microseconds).  One shot:
+ * the request is consumed by that launch.  Both NULL withdraws a pending request.  The benchmark uses it to time the
+ * dominant kernel inside a call that launches several.
+ *   start_event, stop_event  hipEvent_t created by the caller with timing enabled
+ * Errors: AURA_ERR_NULL (exactly one of the two is NULL).
+ */
+aura_status_t aura_time_next_fusion(void* start_event, void* stop_event);
 
 /*
  * Bandwidth calibration (not part of the method).  A plain copy of `bytes` bytes from src to dst,

@@ -15,9 +15,10 @@ import torch
 _LIB_PATH = Path(__file__).resolve().parent / "libaura_fuse.so"
 
 F32, BF16, F16 = 0, 1, 2
-VIS_FRUSTUM_ONLY, FUSE_MEAN_ONLY, FUSE_GATHER = 1, 2, 4
+VIS_FRUSTUM_ONLY, FUSE_MEAN_ONLY, FUSE_GATHER, FUSE_TWO_KERNELS, UNSEEN_ZERO = 1, 2, 4, 8, 16
 CALL_MATERIAL_SCORES, CALL_PROPERTY_INTEGRATE, CALL_FUSE_FEATURES, CALL_FUSE_SCORES, CALL_KNN_DENSIFY = 1, 2, 3, 4, 5
 CALL_THICKNESS_INTEGRATE = 6
+CALL_FUSE_SCORE_INTEGRATE = 7
 
 _TORCH_DTYPE = {torch.float32: F32, torch.bfloat16: BF16, torch.float16: F16}
 
@@ -39,7 +40,8 @@ class _ViewsT(C.Structure):
 
 class _SizesT(C.Structure):
     _fields_ = [("N", C.c_int64), ("B", C.c_int32), ("n_views", C.c_int32), ("Hf", C.c_int32), ("Wf", C.c_int32),
-                ("D", C.c_int32), ("feat_dtype", C.c_int32), ("K", C.c_int32), ("G", C.c_int32), ("Ns", C.c_int32)]
+                ("D", C.c_int32), ("feat_dtype", C.c_int32), ("K", C.c_int32), ("G", C.c_int32), ("Ns", C.c_int32),
+                ("P", C.c_int32)]
 
 
 class _ParamsT(C.Structure):
@@ -64,6 +66,8 @@ def lib():
         L.aura_workspace_bytes.restype = C.c_int32
         L.aura_workspace_bytes.argtypes = [C.c_int32, C.POINTER(_SizesT), C.POINTER(C.c_size_t)]
         vp, i32, i64, f32 = C.c_void_p, C.c_int32, C.c_int64, C.c_float
+        L.aura_fuse_status_offset.restype = C.c_int32
+        L.aura_fuse_status_offset.argtypes = [C.c_int32, C.POINTER(_SizesT), C.POINTER(C.c_size_t), C.POINTER(C.c_int32)]
         L.aura_project_visibility.restype = C.c_int32
         L.aura_project_visibility.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32,
                                               vp, i32, vp, vp, vp]
@@ -76,6 +80,12 @@ def lib():
         L.aura_fuse_scores.restype = C.c_int32
         L.aura_fuse_scores.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32, vp, i32, i32, vp,
                                        i32, vp, vp, vp, i32, vp, vp, vp, vp, C.c_size_t, vp]
+        L.aura_fuse_score_integrate.restype = C.c_int32
+        L.aura_fuse_score_integrate.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32, vp, i32, i32,
+                                                vp, i32, i32, vp, f32, vp, vp, i32, vp, vp, i32, vp, vp, vp, vp, vp, vp,
+                                                C.c_size_t, vp]
+        L.aura_time_next_fusion.restype = C.c_int32
+        L.aura_time_next_fusion.argtypes = [vp, vp]
         L.aura_knn_densify.restype = C.c_int32
         L.aura_knn_densify.argtypes = [vp, i64, i32, vp, i32, vp, i32, i32, vp, i32, C.POINTER(_ParamsT), vp, vp, vp, vp,
                                        vp, C.c_size_t, vp]
@@ -158,6 +168,13 @@ def _ptr(t):
     return None if t is None else t.data_ptr()
 
 
+def _temb(t):
+    """Text embeddings [K][D]: float32, bfloat16 or float16."""
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.is_contiguous() and t.dtype in _TORCH_DTYPE):
+        raise TypeError("temb must be a contiguous device tensor of float32, bfloat16 or float16")
+    return t
+
+
 def _host(a, dtype):
     """Object offsets and grid descriptions live in host memory (numpy)."""
     return None if a is None else np.ascontiguousarray(a, dtype=dtype)
@@ -177,11 +194,23 @@ def _check(status, what):
 
 
 def workspace_bytes(call: int, N: int = 0, B: int = 1, D: int = 1, K: int = 1, G: int = 0, n_views: int = 1,
-                    Hf: int = 1, Wf: int = 1, feat_dtype: int = F32, Ns: int = 1) -> int:
+                    Hf: int = 1, Wf: int = 1, feat_dtype: int = F32, Ns: int = 1, P: int = 1) -> int:
     out = C.c_size_t(0)
-    sz = _SizesT(N, B, n_views, Hf, Wf, D, feat_dtype, K, G, Ns)
+    sz = _SizesT(N, B, n_views, Hf, Wf, D, feat_dtype, K, G, Ns, P)
     _check(lib().aura_workspace_bytes(call, C.byref(sz), C.byref(out)), "aura_workspace_bytes")
     return int(out.value)
+
+
+def fuse_status_word(call: int, views: "Views", N: int, workspace, B: int = 1, K: int = 1, P: int = 1, G: int = 0):
+    """The status word that the fusion kernels of `call` keep in `workspace` (read back, which synchronises): 0 =
+    nothing to report; None where the sizes run kernels without one."""
+    f = views.feat
+    sz = _SizesT(N, B, f.shape[0], f.shape[1], f.shape[2], f.shape[3], _TORCH_DTYPE[f.dtype], K, G, 1, P)
+    off, present = C.c_size_t(0), C.c_int32(0)
+    _check(lib().aura_fuse_status_offset(call, C.byref(sz), C.byref(off), C.byref(present)), "aura_fuse_status_offset")
+    if not present.value or workspace is None:
+        return None
+    return int(workspace[off.value:off.value + 4].view(torch.int32).item())
 
 
 def fuse_workspace_bytes(views: "Views", N: int, B: int = 1) -> int:
@@ -224,12 +253,12 @@ def fuse_features(views: Views, params: Params, xyz, fused, count=None, pt_offse
 def material_scores(fused, temb, y, params: Params, scores, prop=None, label=None, workspace=None):
     """scores [N][K], prop [N][P], label [N] are filled in place; workspace is a uint8 device tensor."""
     fused = _dev(fused, torch.float32, "fused")
-    temb = _dev(temb, torch.float32, "temb")
+    temb = _temb(temb)
     N, D = fused.shape
     K = temb.shape[0]
     P = 0 if y is None else y.shape[1]
     p = params.c()
-    _check(lib().aura_material_scores(fused.data_ptr(), N, D, temb.data_ptr(), F32, K, _ptr(y), P, C.byref(p),
+    _check(lib().aura_material_scores(fused.data_ptr(), N, D, temb.data_ptr(), _TORCH_DTYPE[temb.dtype], K, _ptr(y), P, C.byref(p),
                                       scores.data_ptr(), _ptr(prop), _ptr(label), _ptr(workspace),
                                       0 if workspace is None else workspace.numel(), _stream()),
            "aura_material_scores")
@@ -248,15 +277,52 @@ def fuse_scores(views: Views, params: Params, xyz, temb, y, fused, scores, count
     visibility mask vis [N][vis_pitch] uint8, if given) filled in place."""
     xyz = _dev(xyz, torch.float32, "xyz")
     _dev(fused, torch.float32, "fused")
-    temb = _dev(temb, torch.float32, "temb")
+    temb = _temb(temb)
     po, vo, B = _objects(pt_offsets, view_offsets)
     v, p = views.c(), params.c()
     K = temb.shape[0]
     P = 0 if y is None else y.shape[1]
     _check(lib().aura_fuse_scores(C.byref(v), C.byref(p), xyz.data_ptr(), xyz.shape[0], _hptr(po), _hptr(vo), B,
-                                  temb.data_ptr(), F32, K, _ptr(y), P, fused.data_ptr(), _ptr(count),
+                                  temb.data_ptr(), _TORCH_DTYPE[temb.dtype], K, _ptr(y), P, fused.data_ptr(), _ptr(count),
                                   _ptr(vis), 0 if vis is None else vis.shape[1], scores.data_ptr(), _ptr(prop), _ptr(label), _ptr(workspace),
                                   0 if workspace is None else workspace.numel(), _stream()), "aura_fuse_scores")
+
+
+def fuse_score_integrate_workspace_bytes(views: "Views", N: int, K: int, P: int, B: int = 1, G: int = 0) -> int:
+    """Workspace size of fuse_score_integrate for these views, K materials, P properties and a G^3 mass grid."""
+    f = views.feat
+    return workspace_bytes(CALL_FUSE_SCORE_INTEGRATE, N=N, B=B, D=f.shape[3], K=K, n_views=f.shape[0], Hf=f.shape[1],
+                           Wf=f.shape[2], feat_dtype=_TORCH_DTYPE[f.dtype], P=P, G=G)
+
+
+def fuse_score_integrate(views: Views, params: Params, xyz, temb, y, scores, mass, p_index=0, count=None, vis=None,
+                         prop=None, label=None, n_used=None, vol=None, vol_uniform=1.0, pt_offsets=None,
+                         view_offsets=None, grid_lo=None, grid_h=None, G=0, workspace=None):
+    """The whole path in one call without the fused rows: scores [N][K] and mass [B] (and count, vis, prop, label,
+    n_used when given) are filled in place."""
+    xyz = _dev(xyz, torch.float32, "xyz")
+    temb = _temb(temb)
+    y = _dev(y, torch.float32, "y")
+    _dev(scores, torch.float32, "scores")
+    _dev(mass, torch.float32, "mass")
+    po, vo, B = _objects(pt_offsets, view_offsets)
+    glo, gh = _host(grid_lo, np.float32), _host(grid_h, np.float32)
+    v, p = views.c(), params.c()
+    _check(lib().aura_fuse_score_integrate(C.byref(v), C.byref(p), xyz.data_ptr(), xyz.shape[0], _hptr(po), _hptr(vo), B,
+                                           temb.data_ptr(), _TORCH_DTYPE[temb.dtype], temb.shape[0], y.data_ptr(), y.shape[1],
+                                           p_index,
+                                           _ptr(vol), vol_uniform, _hptr(glo), _hptr(gh), G, _ptr(count), _ptr(vis),
+                                           0 if vis is None else vis.shape[1], scores.data_ptr(), _ptr(prop), _ptr(label),
+                                           mass.data_ptr(), _ptr(n_used), _ptr(workspace),
+                                           0 if workspace is None else workspace.numel(), _stream()),
+           "aura_fuse_score_integrate")
+
+
+def time_next_fusion(start: "torch.cuda.Event | None", stop: "torch.cuda.Event | None"):
+    """The next fusion call of this thread records the two events around its fusion kernel (both None: withdraw).
+    The events must have been recorded once before, so that their handles exist."""
+    h = lambda e: None if e is None else C.c_void_p(e.cuda_event)
+    _check(lib().aura_time_next_fusion(h(start), h(stop)), "aura_time_next_fusion")
 
 
 def knn_densify(fq, fs, ws, k, y, params: Params, wq, prop=None, label=None, nn_idx=None, workspace=None):

@@ -8,21 +8,19 @@
 #include <vector>
 
 #include "../../include/aura_fuse.h"
+#include "abi_util.hpp"
 #include "fuse_args.hpp"
 #include "launch.hpp"
 #include "tile_scores.hpp"
+#include "timing.hpp"
 
 namespace {
 
 thread_local int32_t g_last_hip_error = 0;
+thread_local aura::TimingRequest g_timing;
 
-aura_status_t hip_status(hipError_t e) {
-  if (e == hipSuccess) return AURA_OK;
-  g_last_hip_error = (int32_t)e;
-  return AURA_ERR_HIP;
-}
-
-bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+using aura::aligned;
+using aura::hip_status;
 
 // Checks the object ranges and expands the "one object" shorthand.
 aura_status_t check_objects(int64_t N, int32_t n_views, const int64_t* pt_offsets, const int32_t* view_offsets,
@@ -102,9 +100,21 @@ aura_status_t for_each_table(const std::vector<aura::ObjRange>& objs, F launch) 
 
 }  // namespace
 
+aura_status_t aura::hip_status(hipError_t e) {
+  if (e == hipSuccess) return AURA_OK;
+  g_last_hip_error = (int32_t)e;
+  return AURA_ERR_HIP;
+}
+
+aura::TimingRequest aura::take_timing_request() {
+  const TimingRequest r = g_timing;
+  g_timing = TimingRequest{};
+  return r;
+}
+
 extern "C" {
 
-int32_t aura_version(void) { return 100; }
+int32_t aura_version(void) { return 200; }
 
 const char* aura_strerror(aura_status_t status) {
   switch (status) {
@@ -128,22 +138,33 @@ static bool tile_path(int32_t dtype, int32_t D, int32_t Hf, int32_t Wf, int32_t 
   return aura::fuse_tile_supported(dtype, D, Hf, Wf, feat_bytes);
 }
 
+static bool known_dtype(int32_t t) { return t == AURA_F32 || t == AURA_BF16 || t == AURA_F16; }
+
 // Workspace of aura_fuse_scores: the fusion workspace, then (where the scores come from per-cell
-// similarities) the factor and similarity arrays, then the workspace of aura_material_scores.
+// similarities) the factor and similarity arrays, then the workspace of aura_material_scores.  For
+// aura_fuse_score_integrate (`single_pass`) the view counts and properties (for callers that do not want them), the
+// workspace of the integration and, where the fused rows cannot be avoided, room for one chunk of them follow.
 struct FuseScoresLayout {
   bool tile;        // fusion on the matrix cores
-  bool by_cells;    // scores from per-cell similarities (needs tile and fewer cells than points)
+  bool by_cells;    // scores from per-cell similarities (needs tile and not too many cells)
   size_t fuse_off, cells_off, scores_off, total;
+  size_t count_off, prop_off, mass_off, chunk_off;   // single pass only
+  int64_t chunk_pts;                                  // points per chunk of fused rows
 };
+
+constexpr int64_t kChunkPts = 32768;   // aura_fuse_score_integrate without per-cell scores: fused rows live one chunk at a time
 
 static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 static FuseScoresLayout fuse_scores_layout(int64_t N, int32_t B, int32_t n_views, int32_t Hf, int32_t Wf, int32_t D,
-                                           int32_t dtype, int32_t K) {
+                                           int32_t dtype, int32_t K, bool single_pass = false, int32_t P = 0, int32_t G = 0) {
   FuseScoresLayout l{};
   const int64_t n_cells = (int64_t)n_views * Hf * Wf;
   l.tile = tile_path(dtype, D, Hf, Wf, n_views);
-  l.by_cells = l.tile && n_cells <= N;
+  // Per-cell similarities cost one pass over the maps; they pay when that is less than reading the fused rows back
+  // (fewer cells than points), and without fused rows as long as the maps are not much larger than the rows would be.
+  l.by_cells = l.tile && n_cells <= (single_pass ? 4 * N : N);
+  if (single_pass && !l.by_cells) l.tile = false;   // chunks of rows from the gather kernel
   size_t off = 0;
   l.fuse_off = off;
   if (l.tile) off += round256(aura::fuse_tile_workspace_bytes(N, B, n_views));
@@ -151,6 +172,17 @@ static FuseScoresLayout fuse_scores_layout(int64_t N, int32_t B, int32_t n_views
   if (l.by_cells) off += round256(aura::tile_scores_workspace_bytes(N, n_cells, K));
   l.scores_off = off;
   off += round256(aura::scores_workspace_bytes(D, K));
+  if (single_pass) {
+    l.count_off = off;
+    off += round256((size_t)N * sizeof(int32_t));
+    l.prop_off = off;
+    off += round256((size_t)N * (size_t)P * sizeof(float));
+    l.mass_off = off;
+    off += round256(aura::integrate_workspace_bytes(N, B, G));
+    l.chunk_off = off;
+    l.chunk_pts = std::min<int64_t>(N, kChunkPts);   // also with per-cell scores: AURA_FUSE_GATHER switches them off
+    off += round256((size_t)l.chunk_pts * (size_t)D * sizeof(float));
+  }
   l.total = off;
   return l;
 }
@@ -190,6 +222,17 @@ aura_status_t aura_workspace_bytes(int32_t call, const aura_sizes_t* sz, size_t*
     *bytes = aura::thickness_workspace_bytes(sz->N, sz->B);
     return AURA_OK;
   }
+  if (call == AURA_CALL_FUSE_SCORE_INTEGRATE) {
+    if (sz->N < 0 || sz->B < 1 || sz->n_views < 1 || sz->Hf < 1 || sz->Wf < 1 || sz->D < 1 || sz->K < 1 || sz->P < 1 ||
+        sz->G < 0)
+      return AURA_ERR_SHAPE;
+    if (sz->feat_dtype != AURA_F32 && sz->feat_dtype != AURA_BF16 && sz->feat_dtype != AURA_F16) return AURA_ERR_DTYPE;
+    if (sz->K > 128 || sz->P > 8 || sz->B > 4096 || sz->G > 512 ||
+        (sz->G > 0 && (int64_t)sz->B * sz->G * sz->G * sz->G >= (1ll << 31)))
+      return AURA_ERR_UNSUPPORTED;
+    *bytes = fuse_scores_layout(sz->N, sz->B, sz->n_views, sz->Hf, sz->Wf, sz->D, sz->feat_dtype, sz->K, true, sz->P, sz->G).total;
+    return AURA_OK;
+  }
   if (call == AURA_CALL_FUSE_SCORES) {
     if (sz->N < 0 || sz->B < 1 || sz->n_views < 1 || sz->Hf < 1 || sz->Wf < 1 || sz->D < 1 || sz->K < 1) return AURA_ERR_SHAPE;
     if (sz->feat_dtype != AURA_F32 && sz->feat_dtype != AURA_BF16 && sz->feat_dtype != AURA_F16) return AURA_ERR_DTYPE;
@@ -198,6 +241,25 @@ aura_status_t aura_workspace_bytes(int32_t call, const aura_sizes_t* sz, size_t*
     return AURA_OK;
   }
   return AURA_ERR_UNSUPPORTED;
+}
+
+aura_status_t aura_fuse_status_offset(int32_t call, const aura_sizes_t* sz, size_t* offset, int32_t* present) {
+  if (!sz || !offset || !present) return AURA_ERR_NULL;
+  *offset = 0;
+  *present = 0;
+  if (call != AURA_CALL_FUSE_FEATURES && call != AURA_CALL_FUSE_SCORES && call != AURA_CALL_FUSE_SCORE_INTEGRATE)
+    return AURA_ERR_UNSUPPORTED;
+  if (sz->N < 0 || sz->B < 1 || sz->n_views < 1 || sz->Hf < 1 || sz->Wf < 1 || sz->D < 1) return AURA_ERR_SHAPE;
+  if (!known_dtype(sz->feat_dtype)) return AURA_ERR_DTYPE;
+  bool tile = tile_path(sz->feat_dtype, sz->D, sz->Hf, sz->Wf, sz->n_views);
+  if (call == AURA_CALL_FUSE_SCORE_INTEGRATE) {
+    if (sz->K < 1) return AURA_ERR_SHAPE;
+    tile = fuse_scores_layout(sz->N, sz->B, sz->n_views, sz->Hf, sz->Wf, sz->D, sz->feat_dtype, sz->K, true, sz->P, sz->G).tile;
+  }
+  if (!tile) return AURA_OK;   // the gather kernel has nothing to report
+  *offset = aura::fuse_tile_status_offset(sz->N, sz->B);   // the fusion workspace comes first in every layout
+  *present = 1;
+  return AURA_OK;
 }
 
 aura_status_t aura_project_visibility(const aura_views_t* views, const aura_params_t* params,
@@ -279,6 +341,14 @@ static aura_status_t fuse_features_impl(const aura_views_t* views, const aura_pa
       return AURA_ERR_WORKSPACE;
     tws = aura::fuse_tile_workspace(workspace, N, B, views->n_views);
   }
+  if (!tile && workspace && aligned(workspace, 256) &&
+      tile_path(views->feat_dtype, views->D, views->Hf, views->Wf, views->n_views) &&
+      workspace_bytes >= aura::fuse_tile_workspace_bytes(N, B, views->n_views)) {
+    // AURA_FUSE_GATHER with the workspace of the matrix-core kernels: its status word still says "nothing to report"
+    const aura_status_t sc = hip_status(aura::launch_calibration_fill(
+        static_cast<char*>(workspace) + aura::fuse_tile_status_offset(N, B), 16, 0u, st));
+    if (sc != AURA_OK) return sc;
+  }
   return for_each_table(objs, [&](const aura::ObjTable& tab, int n, int max_pts, int obj_base) {
     tws.obj_base = obj_base;
     return aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only, tile ? &tws : nullptr,
@@ -320,34 +390,55 @@ aura_status_t aura_select_views(const aura_views_t* views, const aura_params_t* 
   });
 }
 
-aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* params,
-                               const float* xyz, int64_t N,
-                               const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
-                               const void* temb, int32_t temb_dtype, int32_t K, const float* y, int32_t P,
-                               float* fused, int32_t* count, uint8_t* vis, int32_t vis_pitch,
-                               float* scores, float* prop, int32_t* label,
-                               void* workspace, size_t workspace_bytes, void* stream) {
+// The text embeddings as fp32: as given, or (bf16 / fp16) widened into the copy area of a scoring workspace.
+static aura_status_t embeddings_f32(const void* temb, int32_t temb_dtype, int32_t K, int32_t D, char* scores_ws,
+                                    hipStream_t st, const float** out) {
+  if (temb_dtype == AURA_F32) {
+    *out = static_cast<const float*>(temb);
+    return AURA_OK;
+  }
+  float* copy = reinterpret_cast<float*>(scores_ws + aura::scores_split_bytes(D, K));
+  *out = copy;
+  return hip_status(aura::launch_widen_embeddings(temb, temb_dtype, (long long)K * D, copy, st));
+}
+
+// What aura_fuse_scores and aura_fuse_score_integrate share: the checks (everything except the workspace and the
+// outputs that only one of them has), then the launches.
+static aura_status_t check_fuse_scores(const aura_views_t* views, const aura_params_t* params, int64_t N,
+                                       const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B, const void* temb,
+                                       int32_t temb_dtype, int32_t K, const float* y, int32_t P, const float* prop,
+                                       const uint8_t* vis, int32_t vis_pitch, std::vector<aura::ObjRange>* objs) {
   aura_status_t s = check_views(views, params, true);
   if (s != AURA_OK) return s;
   if (!temb) return AURA_ERR_NULL;
   if (N < 0 || K < 1 || P < 0) return AURA_ERR_SHAPE;
-  if (temb_dtype != AURA_F32) return temb_dtype == AURA_BF16 || temb_dtype == AURA_F16 ? AURA_ERR_UNSUPPORTED : AURA_ERR_DTYPE;
+  if (!known_dtype(temb_dtype)) return AURA_ERR_DTYPE;
   if (prop && (!y || P < 1)) return AURA_ERR_NULL;
   if (!(params->temperature > 0.0f)) return AURA_ERR_SHAPE;
   if (K > 128 || P > 8) return AURA_ERR_UNSUPPORTED;
-  std::vector<aura::ObjRange> objs;
   int max_views = 0;
-  s = check_objects(N, views->n_views, pt_offsets, view_offsets, B, &objs, &max_views);
+  s = check_objects(N, views->n_views, pt_offsets, view_offsets, B, objs, &max_views);
   if (s != AURA_OK) return s;
   if (vis && (vis_pitch < max_views || vis_pitch < 1)) return AURA_ERR_SHAPE;
-  if (N == 0) return AURA_OK;
-  if (!xyz || !fused || !scores) return AURA_ERR_NULL;
-  if (!aligned(fused, 16)) return AURA_ERR_ALIGN;
-  FuseScoresLayout lay = fuse_scores_layout(N, B, views->n_views, views->Hf, views->Wf, views->D, views->feat_dtype, K);
-  if (!workspace || !aligned(workspace, 256) || workspace_bytes < lay.total) return AURA_ERR_WORKSPACE;
-  char* wbase = static_cast<char*>(workspace);
-  if (params->flags & AURA_FUSE_GATHER) lay.tile = lay.by_cells = false;
+  return AURA_OK;
+}
 
+// fused == nullptr (aura_fuse_score_integrate): no [N][D] array exists.  With per-cell scores the fusion kernels simply
+// do not store their rows; otherwise the rows of lay.chunk_pts points at a time go through the chunk buffer in the
+// workspace (small enough to stay in the last-level cache between the fusion and the scoring kernel).
+static aura_status_t run_fuse_scores(const aura_views_t* views, const aura_params_t* params, const float* xyz, int64_t N,
+                                     int32_t B, const std::vector<aura::ObjRange>& objs, const void* temb,
+                                     int32_t temb_dtype, int32_t K,
+                                     const float* y, int32_t P, float* fused, int32_t* count, uint8_t* vis,
+                                     int32_t vis_pitch, float* scores, float* prop, int32_t* label, FuseScoresLayout lay,
+                                     char* wbase, hipStream_t st) {
+  if ((params->flags & AURA_FUSE_GATHER) && lay.tile) {
+    // the matrix-core kernels stay out: the status word in their part of the workspace still says "nothing to report"
+    const aura_status_t sc = hip_status(aura::launch_calibration_fill(
+        wbase + lay.fuse_off + aura::fuse_tile_status_offset(N, B), 16, 0u, st));
+    if (sc != AURA_OK) return sc;
+    lay.tile = lay.by_cells = false;
+  }
   const aura::VisArgs va = vis_args(views, params);
   aura::FeatArgs fa{};
   fa.feat = views->feat;
@@ -358,9 +449,43 @@ aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* p
   fa.pitch_x = (float)views->W / (float)views->Wf;
   fa.pitch_y = (float)views->H / (float)views->Hf;
   const int mean_only = (params->flags & AURA_FUSE_MEAN_ONLY) ? 1 : 0;
-  const hipStream_t st = static_cast<hipStream_t>(stream);
-  const float* t32 = static_cast<const float*>(temb);
   const int64_t n_cells = (int64_t)views->n_views * views->Hf * views->Wf;
+  const int unseen_zero = (params->flags & AURA_UNSEEN_ZERO) ? 1 : 0;
+  const float* t32 = nullptr;
+  aura_status_t s = embeddings_f32(temb, temb_dtype, K, views->D, wbase + lay.scores_off, st, &t32);
+  if (s != AURA_OK) return s;
+
+  if (!fused && !lay.by_cells) {
+    float* chunk = reinterpret_cast<float*>(wbase + lay.chunk_off);
+    std::vector<aura::ObjRange> part;
+    for (int64_t c0 = 0; c0 < N; c0 += lay.chunk_pts) {
+      const int64_t c1 = std::min(N, c0 + lay.chunk_pts);
+      part.clear();
+      for (const aura::ObjRange& o : objs) {
+        const int64_t p0 = std::max<int64_t>(o.pt_begin, c0), p1 = std::min<int64_t>(o.pt_begin + o.n_pts, c1);
+        if (p1 <= p0) continue;
+        aura::ObjRange r = o;
+        r.pt_begin = p0;
+        r.n_pts = (int)(p1 - p0);
+        r.tile_begin = 0;
+        part.push_back(r);
+      }
+      // the kernels index rows by absolute point number: row c0 is the chunk's first
+      float* rows = reinterpret_cast<float*>(reinterpret_cast<uintptr_t>(chunk) - (uintptr_t)c0 * (uintptr_t)views->D * sizeof(float));
+      s = for_each_table(part, [&](const aura::ObjTable& tab, int n, int max_pts, int) {
+        hipError_t e = hipSuccess;
+        if (vis) e = aura::launch_project_visibility(va, xyz, vis, vis_pitch, nullptr, nullptr, tab, n, max_pts, st);
+        if (e != hipSuccess) return e;
+        return aura::launch_fuse_features(va, fa, xyz, rows, count, params->norm_eps, mean_only, nullptr, tab, n, max_pts, st);
+      });
+      if (s != AURA_OK) return s;
+      s = hip_status(aura::launch_material_scores(chunk, c1 - c0, views->D, t32, K, y, P, params->temperature,
+                                                  scores + c0 * K, prop ? prop + c0 * P : nullptr,
+                                                  label ? label + c0 : nullptr, wbase + lay.scores_off, st, unseen_zero));
+      if (s != AURA_OK) return s;
+    }
+    return AURA_OK;
+  }
 
   aura::TileWs tws{};
   aura::TileScoreWs sws{};
@@ -376,19 +501,101 @@ aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* p
     if (vis && !lay.tile)   // the gather kernel does not write the mask: the visibility kernel does
       e = aura::launch_project_visibility(va, xyz, vis, vis_pitch, nullptr, nullptr, tab, n, max_pts, st);
     if (e != hipSuccess) return e;
-    const aura::TileScoring want{sws.G, sws.Kpad, K, P, t32, y, 1.0f / params->temperature, scores, prop, label};
+    const aura::TileScoring want{sws.G, sws.Kpad, K, P, t32, y, 1.0f / params->temperature, unseen_zero, scores, prop, label};
     bool scored = false;   // the one-kernel form of the fusion scores its tiles itself where it can
     e = aura::launch_fuse_features(va, fa, xyz, fused, count, params->norm_eps, mean_only,
                                    lay.tile ? &tws : nullptr, tab, n, max_pts, st, lay.by_cells ? sws.factor : nullptr,
                                    vis, vis_pitch, nullptr, 0, (params->flags & AURA_FUSE_TWO_KERNELS) ? 1 : 0,
                                    lay.by_cells ? &want : nullptr, &scored);
     if (e != hipSuccess || !lay.by_cells || scored) return e;
-    return aura::launch_tile_scores(fa, tws, sws, fused, t32, K, y, P, params->temperature, scores, prop, label, tab, n,
+    return aura::launch_tile_scores(fa, tws, sws, K, y, P, params->temperature, unseen_zero, scores, prop, label, tab, n,
                                     max_pts, st);
   });
   if (s != AURA_OK || lay.by_cells) return s;
   return hip_status(aura::launch_material_scores(fused, N, views->D, t32, K, y, P, params->temperature, scores, prop,
-                                                 label, wbase + lay.scores_off, st));
+                                                 label, wbase + lay.scores_off, st, unseen_zero));
+}
+
+aura_status_t aura_fuse_scores(const aura_views_t* views, const aura_params_t* params,
+                               const float* xyz, int64_t N,
+                               const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                               const void* temb, int32_t temb_dtype, int32_t K, const float* y, int32_t P,
+                               float* fused, int32_t* count, uint8_t* vis, int32_t vis_pitch,
+                               float* scores, float* prop, int32_t* label,
+                               void* workspace, size_t workspace_bytes, void* stream) {
+  std::vector<aura::ObjRange> objs;
+  aura_status_t s = check_fuse_scores(views, params, N, pt_offsets, view_offsets, B, temb, temb_dtype, K, y, P, prop, vis,
+                                      vis_pitch, &objs);
+  if (s != AURA_OK) return s;
+  if (N == 0) return AURA_OK;
+  if (!xyz || !fused || !scores) return AURA_ERR_NULL;
+  if (!aligned(fused, 16)) return AURA_ERR_ALIGN;
+  const FuseScoresLayout lay = fuse_scores_layout(N, B, views->n_views, views->Hf, views->Wf, views->D, views->feat_dtype, K);
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < lay.total) return AURA_ERR_WORKSPACE;
+  return run_fuse_scores(views, params, xyz, N, B, objs, temb, temb_dtype, K, y, P, fused, count, vis, vis_pitch, scores,
+                         prop, label, lay, static_cast<char*>(workspace), static_cast<hipStream_t>(stream));
+}
+
+// Checks the objects of an integration and fills their launch records.
+static aura_status_t mass_objects(int64_t N, const int64_t* pt_offsets, int32_t B, const float* grid_lo, const float* grid_h,
+                                  int32_t G, std::vector<aura::MassObj>* objs) {
+  objs->assign((size_t)B, aura::MassObj{});
+  for (int b = 0; b < B; ++b) {
+    const int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
+    if (p1 < p0 || p0 < 0 || p1 > N || p1 - p0 > 0x7fffffff) return AURA_ERR_SHAPE;
+    if ((b == 0 && p0 != 0) || (b == B - 1 && p1 != N)) return AURA_ERR_SHAPE;
+    aura::MassObj& o = (*objs)[(size_t)b];
+    o.pt_begin = p0;
+    o.n_pts = (int)(p1 - p0);
+    o.lo[0] = o.lo[1] = o.lo[2] = 0.0f;
+    o.h = 1.0f;
+    if (G > 0) {
+      o.lo[0] = grid_lo[3 * b];
+      o.lo[1] = grid_lo[3 * b + 1];
+      o.lo[2] = grid_lo[3 * b + 2];
+      o.h = grid_h[b];
+      if (!(o.h > 0.0f)) return AURA_ERR_SHAPE;
+    }
+  }
+  return AURA_OK;
+}
+
+aura_status_t aura_fuse_score_integrate(const aura_views_t* views, const aura_params_t* params,
+                                        const float* xyz, int64_t N,
+                                        const int64_t* pt_offsets, const int32_t* view_offsets, int32_t B,
+                                        const void* temb, int32_t temb_dtype, int32_t K, const float* y, int32_t P,
+                                        int32_t p_index, const float* vol, float vol_uniform,
+                                        const float* grid_lo, const float* grid_h, int32_t G,
+                                        int32_t* count, uint8_t* vis, int32_t vis_pitch,
+                                        float* scores, float* prop, int32_t* label,
+                                        float* mass, int64_t* n_used,
+                                        void* workspace, size_t workspace_bytes, void* stream) {
+  std::vector<aura::ObjRange> objs;
+  aura_status_t s = check_fuse_scores(views, params, N, pt_offsets, view_offsets, B, temb, temb_dtype, K, y, P, nullptr, vis,
+                                      vis_pitch, &objs);
+  if (s != AURA_OK) return s;
+  if (!y || !mass) return AURA_ERR_NULL;
+  if (P < 1 || p_index < 0 || p_index >= P || G < 0) return AURA_ERR_SHAPE;
+  if (G > 0 && (!grid_lo || !grid_h)) return AURA_ERR_NULL;
+  if (B > 4096 || G > 512 || (G > 0 && (int64_t)B * G * G * G >= (1ll << 31))) return AURA_ERR_UNSUPPORTED;
+  std::vector<aura::MassObj> mobjs;
+  s = mass_objects(N, pt_offsets, B, grid_lo, grid_h, G, &mobjs);
+  if (s != AURA_OK) return s;
+  if (N > 0 && (!xyz || !scores)) return AURA_ERR_NULL;
+  const FuseScoresLayout lay = fuse_scores_layout(N, B, views->n_views, views->Hf, views->Wf, views->D, views->feat_dtype, K,
+                                                  true, P, G);
+  if (!workspace || !aligned(workspace, 256) || workspace_bytes < lay.total) return AURA_ERR_WORKSPACE;
+  char* wbase = static_cast<char*>(workspace);
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  if (!count) count = reinterpret_cast<int32_t*>(wbase + lay.count_off);
+  if (!prop) prop = reinterpret_cast<float*>(wbase + lay.prop_off);
+  if (N > 0) {
+    s = run_fuse_scores(views, params, xyz, N, B, objs, temb, temb_dtype, K, y, P, nullptr, count, vis, vis_pitch, scores,
+                        prop, label, lay, wbase, st);
+    if (s != AURA_OK) return s;
+  }
+  return hip_status(aura::launch_property_integrate(prop, P, p_index, count, vol, vol_uniform, mobjs.data(), B, xyz, G, mass,
+                                                    reinterpret_cast<long long*>(n_used), wbase + lay.mass_off, st));
 }
 
 aura_status_t aura_material_scores(const float* fused, int64_t N, int32_t D,
@@ -398,7 +605,7 @@ aura_status_t aura_material_scores(const float* fused, int64_t N, int32_t D,
                                    void* workspace, size_t workspace_bytes, void* stream) {
   if (!params || !temb) return AURA_ERR_NULL;
   if (N < 0 || D < 1 || K < 1 || P < 0) return AURA_ERR_SHAPE;
-  if (temb_dtype != AURA_F32) return temb_dtype == AURA_BF16 || temb_dtype == AURA_F16 ? AURA_ERR_UNSUPPORTED : AURA_ERR_DTYPE;
+  if (!known_dtype(temb_dtype)) return AURA_ERR_DTYPE;
   if (prop && (!y || P < 1)) return AURA_ERR_NULL;
   if (!(params->temperature > 0.0f)) return AURA_ERR_SHAPE;
   if (K > 128 || P > 8) return AURA_ERR_UNSUPPORTED;
@@ -406,9 +613,12 @@ aura_status_t aura_material_scores(const float* fused, int64_t N, int32_t D,
   if (!fused || !scores) return AURA_ERR_NULL;
   if (!workspace || !aligned(workspace, 256) || workspace_bytes < aura::scores_workspace_bytes(D, K))
     return AURA_ERR_WORKSPACE;
-  return hip_status(aura::launch_material_scores(fused, N, D, static_cast<const float*>(temb), K, y, P,
-                                                 params->temperature, scores, prop, label, workspace,
-                                                 static_cast<hipStream_t>(stream)));
+  const hipStream_t st = static_cast<hipStream_t>(stream);
+  const float* t32 = nullptr;
+  const aura_status_t s = embeddings_f32(temb, temb_dtype, K, D, static_cast<char*>(workspace), st, &t32);
+  if (s != AURA_OK) return s;
+  return hip_status(aura::launch_material_scores(fused, N, D, t32, K, y, P, params->temperature, scores, prop, label,
+                                                 workspace, st, (params->flags & AURA_UNSEEN_ZERO) ? 1 : 0));
 }
 
 aura_status_t aura_knn_densify(const float* fq, int64_t Nq, int32_t D, const float* fs, int32_t Ns,
@@ -438,24 +648,9 @@ aura_status_t aura_property_integrate(const float* prop, int64_t N, int32_t P, i
   if (!mass) return AURA_ERR_NULL;
   if (G > 0 && (!grid_lo || !grid_h)) return AURA_ERR_NULL;
   if (B > 4096 || G > 512 || (G > 0 && (int64_t)B * G * G * G >= (1ll << 31))) return AURA_ERR_UNSUPPORTED;
-  std::vector<aura::MassObj> objs((size_t)B);
-  for (int b = 0; b < B; ++b) {
-    const int64_t p0 = pt_offsets ? pt_offsets[b] : 0, p1 = pt_offsets ? pt_offsets[b + 1] : N;
-    if (p1 < p0 || p0 < 0 || p1 > N || p1 - p0 > 0x7fffffff) return AURA_ERR_SHAPE;
-    if ((b == 0 && p0 != 0) || (b == B - 1 && p1 != N)) return AURA_ERR_SHAPE;
-    aura::MassObj& o = objs[(size_t)b];
-    o.pt_begin = p0;
-    o.n_pts = (int)(p1 - p0);
-    o.lo[0] = o.lo[1] = o.lo[2] = 0.0f;
-    o.h = 1.0f;
-    if (G > 0) {
-      o.lo[0] = grid_lo[3 * b];
-      o.lo[1] = grid_lo[3 * b + 1];
-      o.lo[2] = grid_lo[3 * b + 2];
-      o.h = grid_h[b];
-      if (!(o.h > 0.0f)) return AURA_ERR_SHAPE;
-    }
-  }
+  std::vector<aura::MassObj> objs;
+  const aura_status_t so = mass_objects(N, pt_offsets, B, grid_lo, grid_h, G, &objs);
+  if (so != AURA_OK) return so;
   if (N > 0 && (!prop || (G > 0 && !xyz))) return AURA_ERR_NULL;
   if (!workspace || !aligned(workspace, 256) || workspace_bytes < aura::integrate_workspace_bytes(N, B, G))
     return AURA_ERR_WORKSPACE;
@@ -637,6 +832,13 @@ aura_status_t aura_voxel_downsample(const float* xyz, int64_t N, const int64_t* 
   return hip_status(aura::launch_voxel_downsample(xyz, objs.data(), B, max_abs, N, out_xyz, out_count, out_capacity,
                                                   out_offsets, voxel_of_point, workspace,
                                                   static_cast<hipStream_t>(stream)));
+}
+
+aura_status_t aura_time_next_fusion(void* start_event, void* stop_event) {
+  if ((start_event == nullptr) != (stop_event == nullptr)) return AURA_ERR_NULL;
+  g_timing.start = static_cast<hipEvent_t>(start_event);
+  g_timing.stop = static_cast<hipEvent_t>(stop_event);
+  return AURA_OK;
 }
 
 aura_status_t aura_calibration_copy(void* dst, const void* src, size_t bytes, void* stream) {

@@ -1,5 +1,5 @@
-// aura_estimate_normals: the normals that the view importance score needs (Sec. 3.2.2, "we begin by estimating normal
-// vectors for the sampled sparse point cloud").
+// aura_estimate_normals: the normals of the sampled points, which the view importance score needs (Sec. 3.2.2, first
+// step of the view filtering).
 //
 // For every sampled point q: the k points of the object's cloud nearest to q, the plane through them (eigenvector of
 // the smallest eigenvalue of their covariance), turned to point away from the object's centre.

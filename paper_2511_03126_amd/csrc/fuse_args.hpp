@@ -16,6 +16,7 @@ struct TileScoring {
   const float* temb;    // [K][D] fp32, for tiles without k-steps
   const float* y;       // [K][P], may be nullptr with prop
   float inv_T;
+  int unseen_zero;      // properties of a point with all-zero similarities: 0 instead of the mean of y
   float* scores;        // [N][K]
   float* prop;          // [N][P] or nullptr
   int* label;           // [N] or nullptr
@@ -68,6 +69,7 @@ struct __attribute__((aligned(64))) TileStep {
 struct TileWs {
   TileHdr* hdr;         // [n_tiles]
   unsigned* counters;   // [B][8]: tiles handed out so far, per object and XCD (zeroed by the prepare kernel)
+  unsigned* status;     // one word per call, zero unless a kernel had something to report (see aura_fuse_status_offset)
   TileStep* steps;      // [n_tiles][quota]: every tile owns a fixed run of k-steps
   int quota;
   int obj_base;         // index of the launch's first object within the call
@@ -87,6 +89,7 @@ __device__ __forceinline__ uint32_t cell_index(uint32_t off, uint32_t units) {
 
 bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes);
 size_t fuse_tile_workspace_bytes(long long N, int B, int n_views);
+size_t fuse_tile_status_offset(long long N, int B);   // byte offset of the status word within that workspace
 // Splits a workspace of fuse_tile_workspace_bytes(N, B, n_views) bytes into its parts.
 TileWs fuse_tile_workspace(void* workspace, long long N, int B, int n_views);
 // ws.obj_base set.  *scored (may be nullptr) tells whether the launch also wrote what a.scoring asks for; if not, the

@@ -14,6 +14,7 @@
 #include "aura_device.hpp"
 #include "fuse_args.hpp"
 #include "launch.hpp"
+#include "timing.hpp"
 
 namespace aura {
 
@@ -226,8 +227,12 @@ __global__ __launch_bounds__(kFuseWaves* kWave) void k_fuse_gather(FuseArgs a, O
 template <int DT, int VEC, int PASSES, bool GENERIC>
 static hipError_t launch_one(const FuseArgs& a, const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream) {
   dim3 grid((max_pts + kFusePtsPerBlock - 1) / kFusePtsPerBlock, n_obj), block(kFuseWaves * kWave);
+  const TimingRequest timed = take_timing_request();
+  if (timed.start) (void)hipEventRecord(timed.start, stream);
   hipLaunchKernelGGL((k_fuse_gather<DT, VEC, PASSES, GENERIC>), grid, block, 0, stream, a, tab);
-  return hipGetLastError();
+  const hipError_t e = hipGetLastError();
+  if (timed.stop) (void)hipEventRecord(timed.stop, stream);
+  return e;
 }
 
 template <int DT>

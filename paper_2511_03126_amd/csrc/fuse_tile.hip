@@ -48,6 +48,7 @@
 #include "fuse_args.hpp"
 #include "launch.hpp"
 #include "scores_epilogue.hpp"
+#include "timing.hpp"
 
 namespace aura {
 
@@ -141,7 +142,12 @@ struct PairRec {
 };
 
 // The slow way out when a tile needs more k-steps than it owns: the workgroup fuses its 32 points by a
-// per-point gather (wave per point, lanes over channels, 512 channels per sweep).
+// per-point gather (wave per point, lanes over channels, 512 channels per sweep, the whole row in registers).
+// The row is stored when the call has a place for it (FuseArgs::fused); when the call wants scores as well
+// (FuseArgs::scoring), they are taken here from the row in registers, so that no later kernel needs the row:
+// omega_k by a wave-wide sum per material, then Eq. 4 and the label with lanes over the materials.
+constexpr int kGatherSweeps = 3;   // 512 channels each: D <= 1536 on this path
+
 template <int DT>
 __device__ __forceinline__ void gather_tile(const FuseArgs& a, const ObjRange& ob, int li0, int wave, int n_waves, int lane) {
   const int D = a.feat.D, Hf = a.feat.Hf, Wf = a.feat.Wf;
@@ -151,43 +157,43 @@ __device__ __forceinline__ void gather_tile(const FuseArgs& a, const ObjRange& o
     if (li >= ob.n_pts) break;
     const long long i = ob.pt_begin + li;
     const float x = a.xyz[3 * i], y = a.xyz[3 * i + 1], z = a.xyz[3 * i + 2];
-    float* __restrict__ out_row = a.fused + i * D;
-    float ss = 0.0f;
-    int cnt = 0;
-    for (int cb = 0; cb < D; cb += 8 * kWave) {
-      const int ch = cb + 8 * lane;
-      float acc[8];
+    float acc[kGatherSweeps][8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) acc[e] = 0.0f;
-      cnt = 0;
-      for (int vb = 0; vb < ob.n_views; vb += kWave) {
-        bool seen = false;
-        int x0 = 0, y0 = 0;
-        float ax = 0.0f, ay = 0.0f;
-        if (vb + lane < ob.n_views) {
-          const int v = ob.view_begin + vb + lane;
-          const Proj p = project(a.vis.cam + (long long)v * 16, x, y, z);
-          const float* dv = a.vis.depth ? a.vis.depth + (long long)v * a.vis.H * a.vis.W : nullptr;
-          seen = visible(a.vis, dv, p) && view_kept(a, i, vb + lane);
-          if (a.out_vis && cb == 0) a.out_vis[i * a.vis_pitch + vb + lane] = seen ? 1 : 0;
-          if (seen) {
-            const Tap tx = tap_axis(p.u, a.feat.pitch_x, Wf), ty = tap_axis(p.v, a.feat.pitch_y, Hf);
-            x0 = tx.i0; ax = tx.a;
-            y0 = ty.i0; ay = ty.a;
-          }
+    for (int s = 0; s < kGatherSweeps; ++s)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[s][e] = 0.0f;
+    int cnt = 0;
+    for (int vb = 0; vb < ob.n_views; vb += kWave) {
+      bool seen = false;
+      int x0 = 0, y0 = 0;
+      float ax = 0.0f, ay = 0.0f;
+      if (vb + lane < ob.n_views) {
+        const int v = ob.view_begin + vb + lane;
+        const Proj p = project(a.vis.cam + (long long)v * 16, x, y, z);
+        const float* dv = a.vis.depth ? a.vis.depth + (long long)v * a.vis.H * a.vis.W : nullptr;
+        seen = visible(a.vis, dv, p) && view_kept(a, i, vb + lane);
+        if (a.out_vis) a.out_vis[i * a.vis_pitch + vb + lane] = seen ? 1 : 0;
+        if (seen) {
+          const Tap tx = tap_axis(p.u, a.feat.pitch_x, Wf), ty = tap_axis(p.v, a.feat.pitch_y, Hf);
+          x0 = tx.i0; ax = tx.a;
+          y0 = ty.i0; ay = ty.a;
         }
-        unsigned long long m = __ballot(seen);
-        cnt += __popcll(m);
-        while (m) {
-          const int src = __builtin_ctzll(m);
-          m &= m - 1;
-          const int sx0 = __builtin_amdgcn_readlane(x0, src), sy0 = __builtin_amdgcn_readlane(y0, src);
-          const float sax = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ax), src));
-          const float say = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ay), src));
-          const int sx1 = sx0 + 1 < Wf ? sx0 + 1 : Wf - 1, sy1 = sy0 + 1 < Hf ? sy0 + 1 : Hf - 1;
-          const float wgt[4] = {(1.0f - sax) * (1.0f - say), sax * (1.0f - say), (1.0f - sax) * say, sax * say};
-          const int cell[4] = {sy0 * Wf + sx0, sy0 * Wf + sx1, sy1 * Wf + sx0, sy1 * Wf + sx1};
-          const char* vbase = static_cast<const char*>(a.feat.feat) + (long long)(ob.view_begin + vb + src) * view_bytes;
+      }
+      unsigned long long m = __ballot(seen);
+      cnt += __popcll(m);
+      while (m) {
+        const int src = __builtin_ctzll(m);
+        m &= m - 1;
+        const int sx0 = __builtin_amdgcn_readlane(x0, src), sy0 = __builtin_amdgcn_readlane(y0, src);
+        const float sax = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ax), src));
+        const float say = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(ay), src));
+        const int sx1 = sx0 + 1 < Wf ? sx0 + 1 : Wf - 1, sy1 = sy0 + 1 < Hf ? sy0 + 1 : Hf - 1;
+        const float wgt[4] = {(1.0f - sax) * (1.0f - say), sax * (1.0f - say), (1.0f - sax) * say, sax * say};
+        const int cell[4] = {sy0 * Wf + sx0, sy0 * Wf + sx1, sy1 * Wf + sx0, sy1 * Wf + sx1};
+        const char* vbase = static_cast<const char*>(a.feat.feat) + (long long)(ob.view_begin + vb + src) * view_bytes;
+#pragma unroll
+        for (int s = 0; s < kGatherSweeps; ++s) {
+          const int ch = s * 8 * kWave + 8 * lane;
           if (ch < D) {
 #pragma unroll
             for (int c = 0; c < 4; ++c) {
@@ -202,35 +208,97 @@ __device__ __forceinline__ void gather_tile(const FuseArgs& a, const ObjRange& o
                   lo = (float)__builtin_bit_cast(_Float16, (uint16_t)(raw[j] & 0xffffu));
                   hi = (float)__builtin_bit_cast(_Float16, (uint16_t)(raw[j] >> 16));
                 }
-                acc[2 * j] = __builtin_fmaf(wgt[c], lo, acc[2 * j]);
-                acc[2 * j + 1] = __builtin_fmaf(wgt[c], hi, acc[2 * j + 1]);
+                acc[s][2 * j] = __builtin_fmaf(wgt[c], lo, acc[s][2 * j]);
+                acc[s][2 * j + 1] = __builtin_fmaf(wgt[c], hi, acc[s][2 * j + 1]);
               }
             }
           }
         }
       }
-      const float inv = cnt > 0 ? 1.0f / (float)cnt : 0.0f;
-      if (ch < D) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          acc[e] *= inv;
-          ss = __builtin_fmaf(acc[e], acc[e], ss);
-          out_row[ch + e] = acc[e];
-        }
-      }
     }
+    // mean over the visible views (Eq. 2), then the L2 normalisation
+    const float inv = cnt > 0 ? 1.0f / (float)cnt : 0.0f;
+    float ss = 0.0f;
+#pragma unroll
+    for (int s = 0; s < kGatherSweeps; ++s)
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        acc[s][e] *= inv;
+        ss = __builtin_fmaf(acc[s][e], acc[s][e], ss);
+      }
     if (!a.mean_only) {
       const float scale = 1.0f / fmaxf(sqrtf(wave_sum(ss)), a.norm_eps);
-      // every lane rescales exactly the channels it stored above
-      for (int cb = 0; cb < D; cb += 8 * kWave) {
-        const int ch = cb + 8 * lane;
-        if (ch < D) {
 #pragma unroll
-          for (int e = 0; e < 8; ++e) out_row[ch + e] *= scale;
+      for (int s = 0; s < kGatherSweeps; ++s)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[s][e] *= scale;
+    }
+    if (a.fused) {
+      float* __restrict__ out_row = a.fused + i * D;
+#pragma unroll
+      for (int s = 0; s < kGatherSweeps; ++s) {
+        const int ch = s * 8 * kWave + 8 * lane;
+        if (ch < D) {
+          *reinterpret_cast<f32x4*>(out_row + ch) = f32x4{acc[s][0], acc[s][1], acc[s][2], acc[s][3]};
+          *reinterpret_cast<f32x4*>(out_row + ch + 4) = f32x4{acc[s][4], acc[s][5], acc[s][6], acc[s][7]};
         }
       }
     }
     if (a.out_count && lane == 0) a.out_count[i] = cnt;
+
+    if (a.scoring.G) {
+      // Sec. 3.4.1 for this point: lane l keeps the similarities of materials l and l + 64
+      const TileScoring& sc = a.scoring;
+      float mine[2] = {-INFINITY, -INFINITY};
+      for (int m = 0; m < sc.K; ++m) {
+        const float* __restrict__ t = sc.temb + (long long)m * D;
+        float dot = 0.0f;
+#pragma unroll
+        for (int s = 0; s < kGatherSweeps; ++s) {
+          const int ch = s * 8 * kWave + 8 * lane;
+          if (ch < D) {
+            const f32x4 t0 = *reinterpret_cast<const f32x4*>(t + ch), t1 = *reinterpret_cast<const f32x4*>(t + ch + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              dot = __builtin_fmaf(acc[s][e], t0[e], dot);
+              dot = __builtin_fmaf(acc[s][4 + e], t1[e], dot);
+            }
+          }
+        }
+        dot = wave_sum(dot);
+        if ((m & 63) == lane) mine[m >> 6] = dot;
+      }
+      float best = fmaxf(mine[0], mine[1]);
+      int bidx = mine[1] > mine[0] ? lane + 64 : lane;   // a lane without a material holds -inf
+#pragma unroll
+      for (int o = kWave / 2; o > 0; o >>= 1) {
+        const float ob_ = __shfl_xor(best, o, kWave);
+        const int oi = __shfl_xor(bidx, o, kWave);
+        if (ob_ > best || (ob_ == best && oi < bidx)) { best = ob_; bidx = oi; }   // lowest index wins ties
+      }
+#pragma unroll
+      for (int h = 0; h < 2; ++h) {
+        const int m = lane + 64 * h;
+        if (m < sc.K) sc.scores[i * sc.K + m] = mine[h];
+      }
+      if (sc.label && lane == 0) sc.label[i] = bidx;
+      if (sc.prop) {
+        float e[2];
+#pragma unroll
+        for (int h = 0; h < 2; ++h) e[h] = lane + 64 * h < sc.K ? expf((mine[h] - best) * sc.inv_T) : 0.0f;
+        const float den = wave_sum(e[0] + e[1]);
+        // all similarities exactly zero (nobody sees the point): zero properties where the caller asks for that
+        const bool zero_row = sc.unseen_zero && __ballot((lane < sc.K && mine[0] != 0.0f) || (lane + 64 < sc.K && mine[1] != 0.0f)) == 0;
+        for (int p = 0; p < sc.P; ++p) {
+          float num = 0.0f;
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+            if (lane + 64 * h < sc.K) num = __builtin_fmaf(e[h], sc.y[(lane + 64 * h) * sc.P + p], num);
+          num = wave_sum(num);
+          if (lane == 0) sc.prop[i * sc.P + p] = zero_row ? 0.0f : num / den;
+        }
+      }
+    }
   }
 }
 
@@ -269,6 +337,7 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
 
   if (tid < kTilePts) s_cnt[tid] = 0;
   if (blockIdx.x == 0 && tid < 8) ws.counters[(ws.obj_base + blockIdx.y) * 8 + tid] = 0u;   // for the product kernel
+  if (blockIdx.x == 0 && blockIdx.y == 0 && ws.obj_base == 0 && tid == 0) *ws.status = 0u;      // this form has nothing to report
   int used = 0;   // k-steps written so far (the view batches follow one another in the tile's run)
   bool exhausted = false;
 
@@ -801,12 +870,12 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
       // a tile that the prepare kernel fused itself: n < 0) are dropped by the bounds check instead of by
       // branches.
       const int li0 = blk * kTilePts;
-      float* obase = a.fused + (ob.pt_begin + li0) * D + span * kSpan;
+      float* obase = a.fused ? a.fused + (ob.pt_begin + li0) * D + span * kSpan : nullptr;
       uint32_t row_bytes = (uint32_t)D * 4u;
       // opaque to the optimiser: otherwise the 32 per-row offsets below, which do not change from tile
       // to tile, are kept in registers across the whole tile loop and push other values into scratch
       asm volatile("" : "+s"(row_bytes));
-      const int rows = n >= 0 ? min(kTilePts, ob.n_pts - li0) : 0;
+      const int rows = (n >= 0 && a.fused) ? min(kTilePts, ob.n_pts - li0) : 0;   // no rows wanted: every store is dropped
       const __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(obase, 0, (int)(rows * row_bytes), 0x00020000);
       const uint32_t lane_out = (uint32_t)(4 * g) * row_bytes + (uint32_t)(4 * m) * 4u;
 #pragma unroll
@@ -893,24 +962,28 @@ __device__ __forceinline__ float3 tile_point(const FuseArgs& a, const ObjRange& 
 // Meeting point of the NP producer waves of a workgroup (the workgroup barrier belongs to the tile hand-over, which
 // the product waves take part in).  Every wave publishes the number of the meeting after its LDS traffic and waits
 // until the others have published it too; both producers pass the same meetings in the same order.  The wait is
-// bounded: a producer that never arrives (a programming error) ends in wrong results, not in a hung machine.  The
-// waiting waves look again as soon as the last look is back (no sleep in between: the meeting is on the tile's
-// critical path, and a look is one LDS read for all four flags).
+// bounded: a producer that never arrives (a programming error) ends in wrong results, not in a hung machine - and in
+// a set bit in the call's status word (TileWs::status), which the host can read back, so that wrong results never
+// go unnoticed.  The waiting waves look again as soon as the last look is back (no sleep in between: the meeting is
+// on the tile's critical path, and a look is one LDS read for all four flags).
+constexpr unsigned kStatusMeetingMissed = 1u;
+
 template <int NP>
-__device__ __forceinline__ void producers_meet(volatile int* flags, int w, int& seq, int lane) {
+__device__ __forceinline__ void producers_meet(volatile int* flags, int w, int& seq, int lane, unsigned* status) {
   wave_sync();
   if constexpr (NP > 1) {
     ++seq;
     if (lane == 0) flags[w] = seq;
     static_assert(NP <= 4, "the four flags are read as one 16-byte vector");
     typedef int flags4 __attribute__((ext_vector_type(4)));
-    for (int spins = 0; spins < (1 << 16); ++spins) {
+    bool all = false;
+    for (int spins = 0; spins < (1 << 16) && !all; ++spins) {
       const flags4 f = *reinterpret_cast<const volatile flags4*>(flags);   // one LDS round trip per look
-      bool all = true;
+      all = true;
 #pragma unroll
       for (int o = 0; o < NP; ++o) all = all && (f[o] - seq >= 0);
-      if (all) break;
     }
+    if (!all && lane == 0) atomicOr(status, kStatusMeetingMissed);
     wave_sync();
   }
 }
@@ -962,7 +1035,7 @@ template <int DT, bool SEL, int NP>
 __device__ __forceinline__ void produce_tile(const FuseArgs& a, const ObjRange& ob, int blk,
                                              float3 pt, ProjectedBatch<NP>& pre, char* stage, int k_stage, int& dirty,
                                              TileSlot* slot, ProducerScratch* sc, lds_floats cam_lds, volatile int* flags,
-                                             int w, int& seq, int lane) {
+                                             unsigned* status, int w, int& seq, int lane) {
   constexpr int kTrips = kPBatch / 2 / NP;   // trips of one wave per batch of views
   const int p = lane & 31, h = lane >> 5;
   const int Hf = a.feat.Hf, Wf = a.feat.Wf;
@@ -981,7 +1054,7 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const ObjRange& 
 
   for (int vb0 = 0; vb0 < ob.n_views; vb0 += kPBatch) {
     const int nvb = min(kPBatch, ob.n_views - vb0);
-    if (vb0 > 0) producers_meet<NP>(flags, w, seq, lane);   // the previous batch is done with the tables
+    if (vb0 > 0) producers_meet<NP>(flags, w, seq, lane, status);   // the previous batch is done with the tables
     // the maps of this wave's views (view 2 it + h of trip it): 32 words each
 #pragma unroll
     for (int j = 0; j < kTrips; ++j) {
@@ -1043,7 +1116,7 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const ObjRange& 
       if (has_y1) atomicOr(&sc->bits[vl][(bit + kWinSide) >> 5], 1u << ((bit + kWinSide) & 31));
       if (has_x1 && has_y1) atomicOr(&sc->bits[vl][(bit + kWinSide + 1) >> 5], 1u << ((bit + kWinSide + 1) & 31));
     }
-    producers_meet<NP>(flags, w, seq, lane);   // the maps, boxes and masks of all views are complete
+    producers_meet<NP>(flags, w, seq, lane, status);   // the maps, boxes and masks of all views are complete
 
     // the mask of Eq. 1 for this batch of views goes out with the tile: a product wave writes it to memory (a store
     // of a producer would hold up its next wait for a read: one counter covers both)
@@ -1328,7 +1401,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       project_batch<SEL, NP>(fa, ob, tile_of(t0), pt0, 0, cam_lds, w, lane, pre);
       if (t0 < len) {
         produce_tile<DT, SEL, NP>(fa, ob, r0 + t0, pt0, pre, s_steps[0], kStage, dirty0, &s_slot[0], &s_sc, cam_lds, s_flags,
-                                  w, seq, lane);
+                                  ws.status, w, seq, lane);
       } else if (w == 0 && lane == 0) {
         s_slot[0].tile = -1;
         s_slot[0].nsteps = 0;
@@ -1346,7 +1419,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       const float3 pt_next = tile_point(fa, ob, tile_of(tn), lane);   // requested now, looked at after this tile is built
       if (t < len) {
         produce_tile<DT, SEL, NP>(fa, ob, r0 + t, pt, pre, s_steps[buf ^ 1], kStage, buf ? dirty0 : dirty1, &s_slot[buf ^ 1], &s_sc, cam_lds,
-                                  s_flags, w, seq, lane);
+                                  s_flags, ws.status, w, seq, lane);
       } else if (w == 0 && lane == 0) {
         s_slot[buf ^ 1].tile = -1;
         s_slot[buf ^ 1].nsteps = 0;
@@ -1393,37 +1466,23 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
           const int li = blk_prev * kTilePts + m;
           const bool valid = li < ob.n_pts;
           const long long ip = ob.pt_begin + (valid ? li : ob.n_pts - 1);
-          if (n_prev >= 0) {
-            const float inv = cnt_prev > 0 ? 1.0f / (float)cnt_prev : 0.0f;
-            float tot = 0.0f;
+          // (a tile that the producers fused themselves, n_prev < 0, has its scores already: gather_tile)
+          const float inv = cnt_prev > 0 ? 1.0f / (float)cnt_prev : 0.0f;
+          float tot = 0.0f;
 #pragma unroll
-            for (int wv = 0; wv < S; ++wv) tot += s_ss[buf ^ 1][wv][m];
-            const float normed = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
-            const float factor = a.mean_only ? inv : normed;
+          for (int wv = 0; wv < S; ++wv) tot += s_ss[buf ^ 1][wv][m];
+          const float normed = inv / fmaxf(sqrtf(tot) * inv, a.norm_eps);
+          const float factor = a.mean_only ? inv : normed;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[0][r] *= factor;
-          } else {
-            // fused by the producers before the barrier that opened that tile: plain dot products of the stored row
-            const float* __restrict__ row = a.fused + ip * D;
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-              const int mat = 8 * (r >> 2) + 4 * g + (r & 3);
-              float dot = 0.0f;
-              if (mat < sc.K) {
-                const float* __restrict__ t = sc.temb + (long long)mat * D;
-#pragma unroll 1
-                for (int d = 0; d < D; ++d) dot = __builtin_fmaf(row[d], t[d], dot);
-              }
-              acc[0][r] = dot;
-            }
-          }
+          for (int r = 0; r < 16; ++r) acc[0][r] *= factor;
           if (blk >= 0) {   // a product wave stores the results during the next tile
             ScoreOut& o = s_out[buf ^ 1];
-            if (valid) finish_scores<1>(acc, (long long)m, g, sc.K, sc.P, sc.inv_T, s_ys, o.scores, sc.prop ? o.prop : nullptr,
-                                        sc.label ? o.label : nullptr);
-            if (lane == 0) o.blk = blk_prev;
-          } else if (valid) {   // the workgroup's last tile: nobody is left to hand it to
-            finish_scores<1>(acc, ip, g, sc.K, sc.P, sc.inv_T, s_ys, sc.scores, sc.prop, sc.label);
+            if (valid && n_prev >= 0)
+              finish_scores<1>(acc, (long long)m, g, sc.K, sc.P, sc.inv_T, s_ys, o.scores, sc.prop ? o.prop : nullptr,
+                               sc.label ? o.label : nullptr, sc.unseen_zero != 0);
+            if (lane == 0) o.blk = n_prev >= 0 ? blk_prev : -1;
+          } else if (valid && n_prev >= 0) {   // the workgroup's last tile: nobody is left to hand it to
+            finish_scores<1>(acc, ip, g, sc.K, sc.P, sc.inv_T, s_ys, sc.scores, sc.prop, sc.label, sc.unseen_zero != 0);
           }
         }
         if (blk < 0) break;
@@ -1566,10 +1625,10 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
     }
     {
       const int li0 = blk * kTilePts;
-      float* obase = a.fused + (ob.pt_begin + li0) * D + span * kSpan;
+      float* obase = a.fused ? a.fused + (ob.pt_begin + li0) * D + span * kSpan : nullptr;
       uint32_t row_bytes = (uint32_t)D * 4u;
       asm volatile("" : "+s"(row_bytes));
-      const int rows = n >= 0 ? min(kTilePts, ob.n_pts - li0) : 0;
+      const int rows = (n >= 0 && a.fused) ? min(kTilePts, ob.n_pts - li0) : 0;
       const __amdgpu_buffer_rsrc_t out = __builtin_amdgcn_make_buffer_rsrc(obase, 0, (int)(rows * row_bytes), 0x00020000);
       const uint32_t lane_out = (uint32_t)(4 * g) * row_bytes + (uint32_t)(4 * m) * 4u;
 #pragma unroll
@@ -1597,9 +1656,10 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
 }
 
 // Clears the ticket counters of a launch's objects (the prepare kernel does it on the two-kernel path).
-__global__ void k_clear_counters(unsigned* counters, int n) {
+__global__ void k_clear_counters(unsigned* counters, int n, unsigned* status) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) counters[i] = 0u;
+  if (i == 0 && status) *status = 0u;
 }
 
 // ------------------------------------------------------------------------------------ host
@@ -1617,7 +1677,7 @@ static size_t round256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 size_t fuse_tile_workspace_bytes(long long N, int B, int n_views) {
   const size_t tiles = (size_t)tile_count_bound(N, B);
-  return round256(tiles * sizeof(TileHdr)) + round256((size_t)B * 8 * sizeof(unsigned)) +
+  return round256(tiles * sizeof(TileHdr)) + round256((size_t)B * 8 * sizeof(unsigned)) + 256 +
          tiles * (size_t)steps_quota(B, n_views) * sizeof(TileStep);
 }
 
@@ -1628,10 +1688,16 @@ TileWs fuse_tile_workspace(void* workspace, long long N, int B, int n_views) {
   base += round256((size_t)tile_count_bound(N, B) * sizeof(TileHdr));
   ws.counters = reinterpret_cast<unsigned*>(base);
   base += round256((size_t)B * 8 * sizeof(unsigned));
+  ws.status = reinterpret_cast<unsigned*>(base);
+  base += 256;
   ws.steps = reinterpret_cast<TileStep*>(base);
   ws.quota = steps_quota(B, n_views);
   ws.obj_base = 0;
   return ws;
+}
+
+size_t fuse_tile_status_offset(long long N, int B) {
+  return round256((size_t)tile_count_bound(N, B) * sizeof(TileHdr)) + round256((size_t)B * 8 * sizeof(unsigned));
 }
 
 bool fuse_tile_supported(int dtype, int D, int Hf, int Wf, long long feat_bytes) {
@@ -1673,7 +1739,9 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
   for (int t = 0; t < n_obj; ++t) max_views = std::max(max_views, tab.o[t].n_views);
   const int np = one_kernel_producers(a, stage_steps_for<S * H / 2>(), ws.quota, max_views, S);
   if (np > 0) {
-    hipLaunchKernelGGL(k_clear_counters, dim3((n_obj * kXcd + 63) / 64), dim3(64), 0, stream, pa.counters, n_obj * kXcd);
+    // (the status word of the call is cleared along with the counters of its first launch)
+    hipLaunchKernelGGL(k_clear_counters, dim3((n_obj * kXcd + 63) / 64), dim3(64), 0, stream, pa.counters, n_obj * kXcd,
+                       ws.obj_base == 0 ? ws.status : nullptr);
     // with one producer wave two workgroups fit a compute unit, with four one; several objects in one launch share
     // the machine
     const int groups_max = np == 1 ? kFusedGroupsMax : kFusedGroupsMax / 2;
@@ -1681,6 +1749,8 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
     const bool scoring = scoring_wave_fits(a, np, S);
     const dim3 grid(std::min(groups, max_tiles), n_obj), block(kWave * (S + np + (scoring ? 1 : 0)));
     const int keep = a.out_factor != nullptr && !scoring;   // the scoring kernel follows and reads the k-steps
+    const TimingRequest timed = take_timing_request();
+    if (timed.start) (void)hipEventRecord(timed.start, stream);
     if (scoring) {
       if constexpr (S <= 3) {
         pa.factor = nullptr;   // nobody reads the factors back
@@ -1694,8 +1764,12 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
       if (a.in_mask) hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, true, 4, false>), grid, block, 0, stream, a, pa, ws, keep, tab);
       else hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 4, false>), grid, block, 0, stream, a, pa, ws, keep, tab);
     }
-    return hipGetLastError();
+    const hipError_t e = hipGetLastError();
+    if (timed.stop) (void)hipEventRecord(timed.stop, stream);
+    return e;
   }
+  const TimingRequest timed = take_timing_request();   // two kernels: the events go around the pair
+  if (timed.start) (void)hipEventRecord(timed.start, stream);
   if (a.in_mask)
     hipLaunchKernelGGL((k_tile_prepare<DT, true>), dim3(max_tiles, n_obj), dim3(kPrepThreads), 0, stream, a, ws, tab);
   else
@@ -1705,7 +1779,9 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
   // several objects in one launch share the machine: fewer workgroups per object
   const int groups = std::max(kXcd, std::min(max_tiles, (kProdGroupsMax / n_obj + kXcd - 1) / kXcd * kXcd));
   hipLaunchKernelGGL((k_tile_product<DT, S, H, PF>), dim3(std::min(groups, max_tiles), n_obj), dim3(kWave * S), 0, stream, pa, tab);
-  return hipGetLastError();
+  e = hipGetLastError();
+  if (timed.stop) (void)hipEventRecord(timed.stop, stream);
+  return e;
 }
 
 hipError_t launch_fuse_tile(const FuseArgs& a, const TileWs& ws, const ObjTable& tab, int n_obj, int max_pts,

@@ -41,10 +41,12 @@ hipError_t launch_select_views(const VisArgs& vis, const float* xyz, const float
                                float* sel_score, uint8_t* sel_mask, int mask_pitch, int* n_sel, const ObjTable& tab,
                                int n_obj, int max_pts, hipStream_t stream);
 
-size_t scores_workspace_bytes(int D, int K);
+size_t scores_split_bytes(int D, int K);       // the split embeddings at the start of the scoring workspace
+size_t scores_workspace_bytes(int D, int K);   // ... followed by room for an fp32 copy of 16-bit embeddings
+hipError_t launch_widen_embeddings(const void* src, int dtype, long long n, float* dst, hipStream_t stream);
 hipError_t launch_material_scores(const float* fused, long long N, int D, const float* temb, int K,
                                   const float* y, int P, float temperature, float* scores, float* prop,
-                                  int* label, void* workspace, hipStream_t stream);
+                                  int* label, void* workspace, hipStream_t stream, int unseen_zero = 0);
 
 // Objects of one integration launch (host side; copied into kernel arguments in chunks).
 struct MassObj {

@@ -35,6 +35,7 @@ struct ScoreArgs {
   int D, K, P;
   const float* y;
   float inv_T;
+  int unseen_zero;
   float* scores;
   float* prop;
   int* label;
@@ -89,7 +90,7 @@ __global__ __launch_bounds__(256) void k_material_scores(ScoreArgs a) {
   score_products<MT, ROWS_ALIGNED, false>(row, a.D, a.steps, a.a_split, lane, acc);
 
   if (!valid) return;   // no cross-lane traffic below except with lane ^ 32, which holds the same point
-  finish_scores<MT>(acc, n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label);
+  finish_scores<MT>(acc, n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label, a.unseen_zero != 0);
 }
 
 size_t split_embeddings_bytes(int D, int MT) {
@@ -107,10 +108,31 @@ hipError_t launch_split_embeddings(const float* emb, int n_rows, int D, int MT, 
 static int tiles_m(int K) { return (K + kTileM - 1) / kTileM; }
 static int steps_k(int D) { return (D + kStepK - 1) / kStepK; }
 
-size_t scores_workspace_bytes(int D, int K) {
+size_t scores_split_bytes(int D, int K) {
   int MT = tiles_m(K);
   if (MT == 3) MT = 4;
   return (size_t)steps_k(D) * MT * 2 * 2 * kWave * 8 * sizeof(__bf16);
+}
+
+// the split embeddings, then room for an fp32 copy of embeddings that arrive as 16-bit values
+size_t scores_workspace_bytes(int D, int K) {
+  return scores_split_bytes(D, K) + (((size_t)K * D * sizeof(float) + 255) & ~(size_t)255);
+}
+
+// Text embeddings given as bf16 (dtype 1) or fp16 (dtype 2) values, widened exactly to fp32.
+__global__ __launch_bounds__(256) void k_widen_embeddings(const uint16_t* __restrict__ src, int dtype, long long n,
+                                                          float* __restrict__ dst) {
+  const long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const uint16_t b = src[i];
+  dst[i] = dtype == 1 ? __uint_as_float((uint32_t)b << 16) : (float)__builtin_bit_cast(_Float16, b);
+}
+
+hipError_t launch_widen_embeddings(const void* src, int dtype, long long n, float* dst, hipStream_t stream) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(k_widen_embeddings, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                     static_cast<const uint16_t*>(src), dtype, n, dst);
+  return hipGetLastError();
 }
 
 template <int MT>
@@ -125,7 +147,7 @@ static hipError_t launch_mt(const ScoreArgs& a, bool aligned, hipStream_t stream
 
 hipError_t launch_material_scores(const float* fused, long long N, int D, const float* temb, int K,
                                   const float* y, int P, float temperature, float* scores, float* prop,
-                                  int* label, void* workspace, hipStream_t stream) {
+                                  int* label, void* workspace, hipStream_t stream, int unseen_zero) {
   if (N == 0) return hipSuccess;
   int MT = tiles_m(K);
   if (MT == 3) MT = 4;
@@ -137,7 +159,7 @@ hipError_t launch_material_scores(const float* fused, long long N, int D, const 
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
   }
-  ScoreArgs a{fused, N, D, K, P, y, 1.0f / temperature, scores, prop, label,
+  ScoreArgs a{fused, N, D, K, P, y, 1.0f / temperature, unseen_zero, scores, prop, label,
               static_cast<const bf16x8*>(workspace), S};
   const bool aligned = (D & 3) == 0 && (reinterpret_cast<uintptr_t>(fused) & 15) == 0;
   switch (MT) {

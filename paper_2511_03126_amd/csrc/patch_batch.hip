@@ -2,8 +2,8 @@
 //
 // For every source point, every kept view (aura_select_views) and every scale l, the l x l square of the view's image
 // centred at the projection of the point is resampled to R x R (bilinear between pixel centres, border repeated) and
-// written channel-first, normalised, into one batch [M][k][L][3][R][R] "for unified processing by the encoder"
-// (Sec. 3.2 "Parallelizing Semantic Feature Fusion").
+// written channel-first, normalised, into one batch [M][k][L][3][R][R] that the image encoder can take in one call
+// (Sec. 3.2, the paragraph on parallelising the semantic feature fusion).
 //
 // One workgroup per band of 32 rows of a patch.  The workgroup first copies the image pixels the band touches to LDS,
 // packed to one word per pixel (a band that touches more than the buffer holds reads the image directly).  A thread

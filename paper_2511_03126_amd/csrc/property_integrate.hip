@@ -1,4 +1,4 @@
-// aura_property_integrate: Sec. 3.4.2 "voxel integration over volumes".
+// aura_property_integrate: Sec. 3.4.2, integration of a property over voxels.
 //
 // Point-volume mode: mass[b] = sum_i used_i * prop_i * vol_i.  Each workgroup sums a fixed slice of
 // an object's points in fp64 (fp32 products), a second kernel adds the slices in a fixed order.

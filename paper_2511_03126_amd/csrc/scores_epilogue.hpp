@@ -16,14 +16,17 @@ constexpr int kScoreMaxK = 128;
 // Lane l = 32 g + (point within the wave's 32): accumulator element r of tile mt is the similarity of the
 // lane's point to material mt*32 + 8*(r/4) + 4*g + r%4, so the two lanes l and l ^ 32 hold all K scores of one
 // point between them.  `ys` is y[K][P] in LDS.  Lanes whose point does not exist must not call this.
+// unseen_zero: a point whose similarities are all exactly zero (the fused row of a point that no view sees is all
+// zero) gets zero properties instead of what Eq. 4 gives for equal similarities, the mean of y.
 template <int MT>
 __device__ __forceinline__ void finish_scores(const scores_f32x16 (&acc)[MT], long long n, int g, int K, int P, float inv_T,
                                               const float* __restrict__ ys, float* __restrict__ scores,
-                                              float* __restrict__ prop, int* __restrict__ label) {
+                                              float* __restrict__ prop, int* __restrict__ label, bool unseen_zero = false) {
   float* __restrict__ srow = scores + n * K;
   const bool vec_store = (K & 3) == 0 && ((reinterpret_cast<uintptr_t>(scores) & 15) == 0);
   float best = -INFINITY;
   int bidx = 0;
+  bool any_nonzero = false;
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -43,6 +46,7 @@ __device__ __forceinline__ void finish_scores(const scores_f32x16 (&acc)[MT], lo
       for (int e = 0; e < 4; ++e) {
         const float sc = acc[mt][4 * q + e];
         if (m0 + e < K && sc > best) { best = sc; bidx = m0 + e; }   // ascending m: lowest index wins ties
+        any_nonzero = any_nonzero || (m0 + e < K && sc != 0.0f);
       }
     }
   {
@@ -52,6 +56,7 @@ __device__ __forceinline__ void finish_scores(const scores_f32x16 (&acc)[MT], lo
   }
   if (label && g == 0) label[n] = bidx;
   if (!prop) return;
+  const bool zero_row = unseen_zero && !(any_nonzero || __shfl_xor((int)any_nonzero, 32, kWave) != 0);
 
   float den = 0.0f, num[kScoreMaxP];
 #pragma unroll
@@ -74,7 +79,7 @@ __device__ __forceinline__ void finish_scores(const scores_f32x16 (&acc)[MT], lo
   for (int p = 0; p < kScoreMaxP; ++p) {
     if (p < P) {
       const float t = num[p] + __shfl_xor(num[p], 32, kWave);
-      if (g == 0) prop[n * P + p] = t / den;
+      if (g == 0) prop[n * P + p] = zero_row ? 0.0f : t / den;
     }
   }
 }

@@ -14,7 +14,7 @@
 //                   partial products per k-step (hi*hi, hi*lo, lo*hi), times the point's factor s_i that the
 //                   product kernel left in the workspace; then the shared epilogue (scores, label, Eq. 4).
 //
-// A tile that the prepare kernel fused by itself (no k-steps) is scored from its fused rows.
+// A tile that the fusion kernel fused by a per-point gather (no k-steps) was scored there as well.
 #include "aura_device.hpp"
 #include "fuse_args.hpp"
 #include "launch.hpp"
@@ -132,11 +132,10 @@ struct TileScoreArgs {
   int Kpad;
   uint32_t row_units;    // D / 256
   const float* factor;   // [N]
-  const float* fused;    // [N][D], for tiles without k-steps
-  const float* temb;     // [K][D]
   int D, K, P;
   const float* y;
   float inv_T;
+  int unseen_zero;
   float* scores;
   float* prop;
   int* label;
@@ -167,56 +166,39 @@ __global__ __launch_bounds__(256) void k_tile_scores(TileScoreArgs a, ObjTable t
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
 
-  if (nsteps >= 0) {
-    const TileStep* __restrict__ st = a.steps + (long long)(ob.tile_begin + tile) * a.quota;
-    for (int s = 0; s < nsteps; ++s) {
-      const ts_u32x4 w_hi = st[s].a_hi[lane], w_lo = st[s].a_lo[lane];
-      const ts_u32x4 c0 = *reinterpret_cast<const ts_u32x4*>(&st[s].cell[8 * g]);
-      const ts_u32x4 c1 = *reinterpret_cast<const ts_u32x4*>(&st[s].cell[8 * g + 4]);
-      uint32_t gv[MT][8];
+  if (nsteps < 0) return;   // fused by a gather inside the fusion kernel, which scored the tile's points as well
+  const TileStep* __restrict__ st = a.steps + (long long)(ob.tile_begin + tile) * a.quota;
+  for (int s = 0; s < nsteps; ++s) {
+    const ts_u32x4 w_hi = st[s].a_hi[lane], w_lo = st[s].a_lo[lane];
+    const ts_u32x4 c0 = *reinterpret_cast<const ts_u32x4*>(&st[s].cell[8 * g]);
+    const ts_u32x4 c1 = *reinterpret_cast<const ts_u32x4*>(&st[s].cell[8 * g + 4]);
+    uint32_t gv[MT][8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const uint32_t ci = cell_index(e < 4 ? c0[e] : c1[e - 4], a.row_units);
+    for (int e = 0; e < 8; ++e) {
+      const uint32_t ci = cell_index(e < 4 ? c0[e] : c1[e - 4], a.row_units);
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) gv[mt][e] = a.G[(long long)ci * a.Kpad + mt * 32 + pt];
-      }
-#pragma unroll
-      for (int mt = 0; mt < MT; ++mt) {
-        ts_u32x4 g_hi, g_lo;
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          g_hi[q] = __builtin_amdgcn_perm(gv[mt][2 * q + 1], gv[mt][2 * q], 0x05040100u);
-          g_lo[q] = __builtin_amdgcn_perm(gv[mt][2 * q + 1], gv[mt][2 * q], 0x07060302u);
-        }
-        acc[mt] = ts_mma<DT>(g_hi, w_hi, acc[mt]);
-        acc[mt] = ts_mma<DT>(g_hi, w_lo, acc[mt]);
-        acc[mt] = ts_mma<DT>(g_lo, w_hi, acc[mt]);
-      }
+      for (int mt = 0; mt < MT; ++mt) gv[mt][e] = a.G[(long long)ci * a.Kpad + mt * 32 + pt];
     }
-    const float f = a.factor[n];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+    for (int mt = 0; mt < MT; ++mt) {
+      ts_u32x4 g_hi, g_lo;
 #pragma unroll
-      for (int r = 0; r < 16; ++r) acc[mt][r] *= f;
-  } else {
-    // no k-steps: plain dot products of the point's fused row with the embeddings of the lane's materials
-    const float* __restrict__ row = a.fused + n * a.D;
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int m = mt * kScoreTileM + 8 * (r >> 2) + 4 * g + (r & 3);
-        float dot = 0.0f;
-        if (m < a.K) {
-          const float* __restrict__ t = a.temb + (long long)m * a.D;
-#pragma unroll 1
-          for (int d = 0; d < a.D; ++d) dot = __builtin_fmaf(row[d], t[d], dot);
-        }
-        acc[mt][r] = dot;
+      for (int q = 0; q < 4; ++q) {
+        g_hi[q] = __builtin_amdgcn_perm(gv[mt][2 * q + 1], gv[mt][2 * q], 0x05040100u);
+        g_lo[q] = __builtin_amdgcn_perm(gv[mt][2 * q + 1], gv[mt][2 * q], 0x07060302u);
       }
+      acc[mt] = ts_mma<DT>(g_hi, w_hi, acc[mt]);
+      acc[mt] = ts_mma<DT>(g_hi, w_lo, acc[mt]);
+      acc[mt] = ts_mma<DT>(g_lo, w_hi, acc[mt]);
+    }
   }
+  const float f = a.factor[n];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mt][r] *= f;
   if (!valid) return;
-  finish_scores<MT>(acc, n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label);
+  finish_scores<MT>(acc, n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label, a.unseen_zero != 0);
 }
 
 // ------------------------------------------------------------------------------------ host
@@ -271,11 +253,11 @@ static hipError_t launch_ts(const TileScoreArgs& a, const ObjTable& tab, int n_o
   return hipGetLastError();
 }
 
-hipError_t launch_tile_scores(const FeatArgs& feat, const TileWs& tws, const TileScoreWs& ws, const float* fused,
-                              const float* temb, int K, const float* y, int P, float temperature, float* scores,
+hipError_t launch_tile_scores(const FeatArgs& feat, const TileWs& tws, const TileScoreWs& ws,
+                              int K, const float* y, int P, float temperature, int unseen_zero, float* scores,
                               float* prop, int* label, const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream) {
-  TileScoreArgs a{tws.hdr, tws.steps, tws.quota, ws.G, ws.Kpad, (uint32_t)(feat.D / 256), ws.factor, fused, temb,
-                  feat.D, K, P, y, 1.0f / temperature, scores, prop, label};
+  TileScoreArgs a{tws.hdr, tws.steps, tws.quota, ws.G, ws.Kpad, (uint32_t)(feat.D / 256), ws.factor,
+                  feat.D, K, P, y, 1.0f / temperature, unseen_zero, scores, prop, label};
   return feat.dtype == 1 ? launch_ts<1>(a, tab, n_obj, max_pts, stream) : launch_ts<2>(a, tab, n_obj, max_pts, stream);
 }
 

@@ -21,8 +21,8 @@ hipError_t launch_cell_scores(const FeatArgs& feat, long long n_cells, const flo
                               hipStream_t stream);
 // Scores, labels and properties of the objects of one launch table from the k-steps in `tws` (after the
 // product kernel of the same table has run with ws.factor as its factor output).
-hipError_t launch_tile_scores(const FeatArgs& feat, const TileWs& tws, const TileScoreWs& ws, const float* fused,
-                              const float* temb, int K, const float* y, int P, float temperature, float* scores,
+hipError_t launch_tile_scores(const FeatArgs& feat, const TileWs& tws, const TileScoreWs& ws,
+                              int K, const float* y, int P, float temperature, int unseen_zero, float* scores,
                               float* prop, int* label, const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream);
 
 }  // namespace aura

@@ -43,9 +43,11 @@ def test_version_and_error_strings(B):
 
 
 def test_workspace_sizes(B):
-    assert B.workspace_bytes(B.CALL_MATERIAL_SCORES, D=768, K=32) == 24 * 1 * 4096
-    assert B.workspace_bytes(B.CALL_MATERIAL_SCORES, D=1024, K=128) == 32 * 4 * 4096
-    assert B.workspace_bytes(B.CALL_MATERIAL_SCORES, D=33, K=65) == 2 * 4 * 4096      # 3 tiles round up to 4
+    # split embeddings (4096 bytes per 32 channels and 32 materials), then room for an fp32 copy of 16-bit embeddings
+    copy = lambda D, K: -(-4 * D * K // 256) * 256
+    assert B.workspace_bytes(B.CALL_MATERIAL_SCORES, D=768, K=32) == 24 * 1 * 4096 + copy(768, 32)
+    assert B.workspace_bytes(B.CALL_MATERIAL_SCORES, D=1024, K=128) == 32 * 4 * 4096 + copy(1024, 128)
+    assert B.workspace_bytes(B.CALL_MATERIAL_SCORES, D=33, K=65) == 2 * 4 * 4096 + copy(33, 65)     # 3 tiles round up to 4
     small = B.workspace_bytes(B.CALL_PROPERTY_INTEGRATE, N=1000, B=1, G=0)
     grid = B.workspace_bytes(B.CALL_PROPERTY_INTEGRATE, N=1000, B=2, G=64)
     assert 0 < small < 4096 and grid >= 2 * 64 ** 3 * 12
@@ -64,8 +66,20 @@ def test_workspace_sizes(B):
     assert fuse(D=100, feat_dtype=B.BF16) == 0
     assert fuse(D=1280, feat_dtype=B.F16) == 0
     tiles = 200_000 // 32 + 1
-    assert fuse(D=768, feat_dtype=B.BF16) == -(-tiles * 144 // 256) * 256 + 256 + tiles * 32 * 2112
-    assert fuse(D=768, feat_dtype=B.BF16, n_views=4) == -(-tiles * 144 // 256) * 256 + 256 + tiles * 8 * 2112
+    # tile headers, ticket counters, the status word, then the tiles' k-steps
+    assert fuse(D=768, feat_dtype=B.BF16) == -(-tiles * 144 // 256) * 256 + 256 + 256 + tiles * 32 * 2112
+    assert fuse(D=768, feat_dtype=B.BF16, n_views=4) == -(-tiles * 144 // 256) * 256 + 256 + 256 + tiles * 8 * 2112
+    # where the status word of these calls lies (right behind the counters), and which sizes have none
+    off, present = C.c_size_t(99), C.c_int32(9)
+    sz = B._SizesT(200_000, 1, 16, 32, 32, 768, B.BF16, 33, 0, 1, 1)
+    for call in (B.CALL_FUSE_FEATURES, B.CALL_FUSE_SCORES, B.CALL_FUSE_SCORE_INTEGRATE):
+        assert B.lib().aura_fuse_status_offset(call, C.byref(sz), C.byref(off), C.byref(present)) == 0
+        assert present.value == 1 and off.value == -(-tiles * 144 // 256) * 256 + 256
+    sz32 = B._SizesT(200_000, 1, 16, 32, 32, 768, B.F32, 33, 0, 1, 1)
+    assert B.lib().aura_fuse_status_offset(B.CALL_FUSE_FEATURES, C.byref(sz32), C.byref(off), C.byref(present)) == 0
+    assert present.value == 0
+    assert B.lib().aura_fuse_status_offset(B.CALL_KNN_DENSIFY, C.byref(sz), C.byref(off), C.byref(present)) == -7
+    assert B.lib().aura_fuse_status_offset(B.CALL_FUSE_FEATURES, None, C.byref(off), C.byref(present)) == -1
     with pytest.raises(B.AuraError) as e:
         fuse(D=768, feat_dtype=9)
     assert e.value.status == -3
@@ -135,7 +149,6 @@ def test_argument_validation_returns_status_codes(B):
     assert ms(D=0) == -2
     assert ms(K=129) == -7
     assert ms(P=9) == -7
-    assert ms(dt=B.BF16) == -7
     assert ms(dt=5) == -3
     assert ms(y=None) == -1                                                # prop wanted but no y
     assert ms(ws=None) == -5
@@ -155,7 +168,6 @@ def test_argument_validation_returns_status_codes(B):
     assert fs(v=_views(B, feat=None)) == -1
     assert fs(v=_views(B, feat_dtype=7)) == -3
     assert fs(dt=5) == -3
-    assert fs(dt=B.F16) == -7
     assert fs(K=0) == -2
     assert fs(K=129) == -7
     assert fs(P=9) == -7
@@ -315,3 +327,58 @@ def test_argument_validation_returns_status_codes(B):
     gh = np.zeros(1, np.float32)
     assert pi(G=8, glo=hp(glo), gh=hp(gh), xyz=fake) == -2                 # voxel size must be positive
     assert pi(po_=hp(np.array([0, 4], np.int64))) == -2                    # offsets do not end at N
+
+
+def test_single_pass_call_validation_and_workspace(B):
+    """aura_fuse_score_integrate: the checks of aura_fuse_scores and aura_property_integrate, no fused argument at all."""
+    L = B.lib()
+    p = B.Params().c()
+    cold = B.Params(temperature=0.0).c()
+    fake = C.c_void_p(0x1000)
+    hp = lambda a: a.ctypes.data_as(C.c_void_p)
+    fsi = lambda v=None, N=10, K=8, P=1, pidx=0, temb=fake, dt=B.F32, y=fake, scores=fake, mass=fake, vis=None, pitch=0, G=0, \
+        glo=None, gh=None, xyz=fake, ws=C.c_void_p(0x1000), wsb=1 << 30, par=p, po_=None, vo_=None, B_=1: \
+        L.aura_fuse_score_integrate(C.byref(v if v is not None else _views(B)), C.byref(par), xyz, N, po_, vo_, B_, temb, dt, K,
+                                    y, P, pidx, None, 1.0, glo, gh, G, None, vis, pitch, scores, None, None, mass, None, ws,
+                                    wsb, None)
+    assert fsi(temb=None) == -1 and fsi(y=None) == -1 and fsi(mass=None) == -1
+    assert fsi(xyz=None) == -1 and fsi(scores=None) == -1
+    assert fsi(v=_views(B, feat=None)) == -1
+    assert fsi(v=_views(B, feat_dtype=7)) == -3
+    assert fsi(dt=5) == -3
+    assert fsi(K=0) == -2 and fsi(K=129) == -7 and fsi(P=9) == -7
+    assert fsi(P=0) == -2                                                  # the integration needs a property column
+    assert fsi(pidx=1) == -2
+    assert fsi(par=cold) == -2
+    assert fsi(vis=fake, pitch=3) == -2
+    assert fsi(G=8) == -1                                                  # grid mode without a grid
+    assert fsi(G=600, glo=fake, gh=fake) == -7
+    assert fsi(G=8, glo=hp(np.zeros((1, 3), np.float32)), gh=hp(np.zeros(1, np.float32))) == -2   # voxel size must be positive
+    assert fsi(B_=2) == -1                                                 # two objects need offsets
+    assert fsi(ws=None) == -5 and fsi(wsb=16) == -5 and fsi(ws=C.c_void_p(0x1010)) == -5
+    # workspace: that of aura_fuse_scores (per-cell scores up to four times as many cells as points), view counts,
+    # properties, the integration's scratch and one chunk of fused rows
+    r256 = lambda x: -(-x // 256) * 256
+    kw = dict(N=200_000, B=1, n_views=16, Hf=32, Wf=32, D=768, feat_dtype=B.BF16, K=33)
+    both = B.workspace_bytes(B.CALL_FUSE_SCORES, **kw)
+    mass = B.workspace_bytes(B.CALL_PROPERTY_INTEGRATE, N=200_000, B=1, G=128)
+    assert B.workspace_bytes(B.CALL_FUSE_SCORE_INTEGRATE, P=2, G=128, **kw) == (
+        both + r256(200_000 * 4) + r256(200_000 * 2 * 4) + r256(mass) + r256(32768 * 768 * 4))
+    few = dict(kw, N=5000)       # 16384 cells, 5000 points: per-cell scores here, not in aura_fuse_scores
+    assert B.workspace_bytes(B.CALL_FUSE_SCORE_INTEGRATE, P=1, **few) > B.workspace_bytes(B.CALL_FUSE_SCORES, **few) + \
+        16 * 32 * 32 * 64 * 4
+    with pytest.raises(B.AuraError) as e:
+        B.workspace_bytes(B.CALL_FUSE_SCORE_INTEGRATE, P=0, **kw)
+    assert e.value.status == -2
+    with pytest.raises(B.AuraError) as e:
+        B.workspace_bytes(B.CALL_FUSE_SCORE_INTEGRATE, P=9, **kw)
+    assert e.value.status == -7
+
+
+def test_timing_request_takes_both_events_or_none(B):
+    L = B.lib()
+    fake = C.c_void_p(0x1000)
+    assert L.aura_time_next_fusion(fake, None) == -1
+    assert L.aura_time_next_fusion(None, fake) == -1
+    assert L.aura_time_next_fusion(fake, fake) == 0
+    assert L.aura_time_next_fusion(None, None) == 0      # withdrawn again: nothing is ever recorded on the fake handles

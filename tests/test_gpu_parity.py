@@ -19,7 +19,7 @@ def H():
 
 
 def _mass_check(H, orc, scene, gpu, ref_prop, ref_count):
-    tol = H.tol_for(scene)
+    tol = H.check_tol(scene)
     po = None if scene.B == 1 else scene.pt_offsets
     ref = orc.property_integrate(ref_prop, 0, ref_count, vol_uniform=scene.vol_uniform, pt_offsets=po,
                                  xyz=scene.xyz, grid_lo=scene.grid_lo, grid_h=scene.grid_h, G=scene.G)
@@ -47,11 +47,16 @@ def test_full_path_matches_oracle_on_reduced_scenes(H, orc, name, kw):
     d = H.DeviceScene(s, want_uvz=True)
     ref = H.oracle_points(orc, s, want_uvz=True)
     # one call per stage; fusion and scoring in one call; both again with the matrix-core fusion as two kernels
-    for step in (d.step, d.step_combined, d.step_two_kernels, d.step_combined_two_kernels):
+    # ... and the whole path in one call that writes no fused rows
+    for step in (d.step, d.step_combined, d.step_two_kernels, d.step_combined_two_kernels, d.step_single_pass,
+                 d.step_single_pass_two_kernels):
+        single = step in (d.step_single_pass, d.step_single_pass_two_kernels)
         d.clear_outputs()
         step()
         gpu = d.results()
-        rep = H.compare_points(gpu, ref, s)
+        rep = H.compare_points(gpu, ref, s, no_fused=single)
+        if single:
+            assert np.isnan(gpu["fused"]).all(), "the single-pass call must not touch a fused array"
         rep["mass_rel"] = _mass_check(H, orc, s, gpu, ref["prop"], ref["count_fuse"])
         rep["visible_frac"] = float(ref["vis"].mean())
         print(step.__name__, rep, flush=True)
@@ -60,6 +65,11 @@ def test_full_path_matches_oracle_on_reduced_scenes(H, orc, name, kw):
         again = d.results()
         for k in ("vis", "count", "fused", "scores", "prop", "label", "mass", "n_used"):
             assert np.array_equal(gpu[k].view(np.uint8), again[k].view(np.uint8)), k
+
+
+def _same_bits(a, b, keys):
+    for k in keys:
+        assert np.array_equal(a[k].view(np.uint8), b[k].view(np.uint8)), k
 
 
 FULL = ["c1", "c2", "c3", "c4", "c5"]
@@ -87,11 +97,19 @@ def test_full_size_configs_on_sampled_points(H, orc, name):
     two = d.results()
     _check_full_size(H, orc, s, two, name)
     if name == "c2":     # every list fits both forms of the matrix-core fusion: the same products in the same order
-        for k in ("vis", "count", "fused", "scores", "prop", "label", "mass", "n_used"):
-            assert np.array_equal(one[k].view(np.uint8), two[k].view(np.uint8)), k
+        _same_bits(one, two, ("vis", "count", "fused", "scores", "prop", "label", "mass", "n_used"))
+    # the whole path in one call without the fused rows
+    d.clear_outputs()
+    d.step_single_pass()
+    single = d.results()
+    assert np.isnan(single["fused"]).all()
+    _check_full_size(H, orc, s, single, name, no_fused=True)
+    if name != "c3":     # the same kernels as aura_fuse_scores + aura_property_integrate, minus the row stores (c3: the
+        # combined call scores from the fused rows there, the single pass from per-cell similarities)
+        _same_bits(one, single, ("vis", "count", "scores", "prop", "label", "mass", "n_used"))
 
 
-def _check_full_size(H, orc, s, gpu, name):
+def _check_full_size(H, orc, s, gpu, name, no_fused=False):
     rng = np.random.default_rng(99)
     reps = []
     for b in range(0, s.B, max(1, s.B // 4)):
@@ -105,13 +123,13 @@ def _check_full_size(H, orc, s, gpu, name):
         sub.pt_offsets, sub.view_offsets = np.array([0, s.N], np.int64), np.array([0, v1 - v0], np.int32)
         ref = H.oracle_points(orc, sub, idx=idx)
         g = {k: (v[:, :v1 - v0] if k == "vis" else v) for k, v in gpu.items()}
-        reps.append(H.compare_points(g, ref, s, idx=idx))
+        reps.append(H.compare_points(g, ref, s, idx=idx, no_fused=no_fused))
     mass_rel = _mass_check(H, orc, s, gpu, gpu["prop"].astype(np.float64), gpu["count_fuse"])
     print(dict(samples=reps, mass_rel=mass_rel, visible_frac=float(gpu["vis"].mean()),
                unseen_frac=float((gpu["count"] == 0).mean())), flush=True)
     if name in ("c1", "c2"):     # small enough for the oracle to run the whole path
         ref = H.oracle_points(orc, s)
-        H.compare_points(gpu, ref, s)
+        H.compare_points(gpu, ref, s, no_fused=no_fused)
         _mass_check(H, orc, s, gpu, ref["prop"], ref["count_fuse"])
 
 
@@ -235,10 +253,10 @@ def test_unsorted_points_on_the_matrix_core_path(H, orc, name, kw):
     d = H.DeviceScene(s)
     assert d.ws_fuse is not None
     ref = H.oracle_points(orc, s)
-    for step in (d.step_combined, d.step):     # tiles without k-steps are scored from their fused rows
+    for step in (d.step_combined, d.step, d.step_single_pass):     # tiles without k-steps are scored by the gather that fuses them
         d.clear_outputs()
         step()
-        print(H.compare_points(d.results(), ref, s), flush=True)
+        print(step.__name__, H.compare_points(d.results(), ref, s, no_fused=step == d.step_single_pass), flush=True)
     d.clear_outputs()
     d.step_two_kernels()
     gpu = d.results()

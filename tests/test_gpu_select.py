@@ -121,7 +121,7 @@ def test_fusion_over_the_oracle_selection(orc, name, kw, k):
         nr = np.linalg.norm(ref["fused"], axis=1)
         err = np.linalg.norm(fg - ref["fused"], axis=1) / np.maximum(nr, 1e-12)
         err[(nr == 0) & (np.linalg.norm(fg, axis=1) == 0)] = 0.0
-        assert err.max() <= H.tol_for(s), f"fused rel err {err.max()}"
+        assert err.max() <= H.check_tol(s), f"fused rel err {err.max()}"
 
 
 def test_full_size_pipeline_c2(orc):
@@ -146,5 +146,5 @@ def test_full_size_pipeline_c2(orc):
     fg = d.fused.cpu().numpy()[idx].astype(np.float64)
     err = np.linalg.norm(fg - ref["fused"], axis=1) / np.maximum(np.linalg.norm(ref["fused"], axis=1), 1e-12)
     err[np.linalg.norm(ref["fused"], axis=1) == 0] = 0.0
-    assert err.max() <= H.tol_for(s)
+    assert err.max() <= H.check_tol(s)
     assert np.array_equal(d.count_fuse.cpu().numpy()[idx], ref["count"])
