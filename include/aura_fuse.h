@@ -245,6 +245,27 @@ aura_status_t aura_material_scores(const float* fused, int64_t N, int32_t D,
                                    void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * aura_material_scores for callers that cannot allocate device memory or hand over a workspace: code that runs under
+ * stream capture, serving loops with a fixed memory plan, harnesses that forbid allocation.  Same arguments (without
+ * the workspace), same kernels, same results bit for bit.  The scratch of the call (the text embeddings split into
+ * two 16-bit terms, ceil(D / 32) * ceil(K / 32) * 4096 bytes, three tiles of materials counted as four, plus 4 K D bytes
+ * for the fp32 copy of 16-bit embeddings) lives in a
+ * fixed array of AURA_STATIC_SCRATCH_BYTES inside the library's device image: every GPU the library is used on holds
+ * that array until the process ends, and shapes that need more are refused.  The call allocates and frees nothing.
+ * It works on the GPU that is current when it is called, and `stream` must belong to that GPU.  All calls on one GPU
+ * share the array: two calls whose work overlaps in time on the same GPU (different streams, or different host
+ * threads) race on it and give undefined scores; calls on one stream are ordered and safe.  Each call rewrites the
+ * part of the array it reads, so nothing of an earlier call is seen.
+ * Errors: those of aura_material_scores except AURA_ERR_WORKSPACE; AURA_ERR_UNSUPPORTED also when D and K need more
+ * scratch than the array holds (e.g. D = 4096 with K = 128: 4 MiB); AURA_ERR_HIP when the array cannot be located.
+ */
+#define AURA_STATIC_SCRATCH_BYTES (2u << 20)
+aura_status_t aura_material_scores_static(const float* fused, int64_t N, int32_t D,
+                                          const void* temb, int32_t temb_dtype, int32_t K,
+                                          const float* y, int32_t P, const aura_params_t* params,
+                                          float* scores, float* prop, int32_t* label, void* stream);
+
+/*
  * Sec. 3.1 Eq. 1 and 2 followed by Sec. 3.4.1 / Eq. 4 in one call: everything aura_fuse_features writes
  * (fused, count), optionally the mask of aura_project_visibility, and everything aura_material_scores writes (scores, prop, label) for the same
  * points, with the arguments and rules of those two calls.

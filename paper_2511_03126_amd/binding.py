@@ -77,6 +77,8 @@ def lib():
         L.aura_material_scores.restype = C.c_int32
         L.aura_material_scores.argtypes = [vp, i64, i32, vp, i32, i32, vp, i32, C.POINTER(_ParamsT), vp, vp, vp,
                                            vp, C.c_size_t, vp]
+        L.aura_material_scores_static.restype = C.c_int32
+        L.aura_material_scores_static.argtypes = [vp, i64, i32, vp, i32, i32, vp, i32, C.POINTER(_ParamsT), vp, vp, vp, vp]
         L.aura_fuse_scores.restype = C.c_int32
         L.aura_fuse_scores.argtypes = [C.POINTER(_ViewsT), C.POINTER(_ParamsT), vp, i64, vp, vp, i32, vp, i32, i32, vp,
                                        i32, vp, vp, vp, i32, vp, vp, vp, vp, C.c_size_t, vp]
@@ -262,6 +264,19 @@ def material_scores(fused, temb, y, params: Params, scores, prop=None, label=Non
                                       scores.data_ptr(), _ptr(prop), _ptr(label), _ptr(workspace),
                                       0 if workspace is None else workspace.numel(), _stream()),
            "aura_material_scores")
+
+
+def material_scores_static(fused, temb, y, params: Params, scores, prop=None, label=None):
+    """material_scores without a workspace: the scratch is a fixed array inside the library (nothing is allocated)."""
+    fused = _dev(fused, torch.float32, "fused")
+    temb = _temb(temb)
+    N, D = fused.shape
+    K = temb.shape[0]
+    P = 0 if y is None else y.shape[1]
+    p = params.c()
+    _check(lib().aura_material_scores_static(fused.data_ptr(), N, D, temb.data_ptr(), _TORCH_DTYPE[temb.dtype], K, _ptr(y), P, C.byref(p),
+                                             scores.data_ptr(), _ptr(prop), _ptr(label), _stream()),
+           "aura_material_scores_static")
 
 
 def fuse_scores_workspace_bytes(views: "Views", N: int, K: int, B: int = 1) -> int:

@@ -10,7 +10,7 @@ PKG = Path(__file__).resolve().parent
 CSRC = PKG / "csrc"
 LIB = PKG / "libaura_fuse.so"
 SOURCES = ["aura_abi.hip", "project_visibility.hip", "fuse_features.hip", "fuse_tile.hip", "material_scores.hip",
-           "tile_scores.hip", "knn_densify.hip", "thickness_integrate.hip", "select_views.hip", "voxel_downsample.hip", "patch_batch.hip", "estimate_normals.hip", "property_integrate.hip", "calibrate.hip"]
+           "tile_scores.hip", "knn_densify.hip", "thickness_integrate.hip", "select_views.hip", "voxel_downsample.hip", "patch_batch.hip", "estimate_normals.hip", "property_integrate.hip", "calibrate.hip", "no_alloc.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-fast-math",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

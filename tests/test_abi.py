@@ -382,3 +382,18 @@ def test_timing_request_takes_both_events_or_none(B):
     assert L.aura_time_next_fusion(None, fake) == -1
     assert L.aura_time_next_fusion(fake, fake) == 0
     assert L.aura_time_next_fusion(None, None) == 0      # withdrawn again: nothing is ever recorded on the fake handles
+
+
+def test_static_scratch_call_refuses_what_does_not_fit(B):
+    binding = B
+    L = binding.lib()
+    p = binding.Params().c()
+    fake = C.c_void_p(0x1000)
+    call = lambda N=10, D=64, K=8, P=1, temb=fake, dt=binding.F32, y=fake, prop=fake, fused=fake, scores=fake: \
+        L.aura_material_scores_static(fused, N, D, temb, dt, K, y, P, C.byref(p), scores, prop, None, None)
+    # 128 channel steps x 4 material tiles x 4096 bytes of split embeddings + 2 MiB for an fp32 copy: beyond the 2 MiB array
+    assert call(D=4096, K=128) == -7
+    assert call(temb=None) == -1 and call(y=None) == -1
+    assert call(K=129) == -7 and call(P=9) == -7 and call(D=0) == -2
+    assert call(dt=5) == -3
+    assert call(N=0, fused=None, scores=None) == 0       # (every call above is refused before anything is launched)
