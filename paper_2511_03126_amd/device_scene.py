@@ -18,7 +18,7 @@ def _feat_tensor(scene, dev):
 class DeviceScene:
     """Device-resident copy of a scene plus preallocated outputs and workspaces."""
 
-    def __init__(self, scene, dev="cuda:0", want_uvz=False, flags=0, want_fused=True):
+    def __init__(self, scene, dev="cuda:0", want_uvz=False, flags=0, want_fused=True, temb_dtype=None):
         s = self.scene = scene
         self.dev = dev
         self.xyz = torch.from_numpy(s.xyz).to(dev)
@@ -28,6 +28,8 @@ class DeviceScene:
         # the same with the matrix-core fusion forced into its two-kernel form (AURA_FUSE_TWO_KERNELS)
         self.params_two = aura.Params(tau=s.tau, z_near=s.z_near, temperature=s.temperature, norm_eps=1e-12, flags=flags | 8)
         self.temb = torch.from_numpy(s.temb).to(dev)
+        if temb_dtype is not None:      # text embeddings handed over as 16-bit values (the scene's must be exact in it)
+            self.temb = self.temb.to(temb_dtype)
         self.y = torch.from_numpy(s.y).to(dev)
         N, V = s.N, s.vis_pitch
         self.single = s.B == 1

@@ -25,7 +25,7 @@ def check_tol(scene):
     return min(tol_for(scene), REGRESSION_TOL)
 
 
-def oracle_points(orc, scene, idx=None, flags=0, want_uvz=False):
+def oracle_points(orc, scene, idx=None, flags=0, want_uvz=False, unseen_zero=False):
     """Oracle outputs for all points (idx None) or for a subset of point indices (single object)."""
     s = scene
     xyz = s.xyz if idx is None else s.xyz[idx]
@@ -36,7 +36,7 @@ def oracle_points(orc, scene, idx=None, flags=0, want_uvz=False):
                                 view_offsets=vo, vis_pitch=s.vis_pitch, want_diag=True, want_uvz=want_uvz)
     fu = orc.fuse_features(s.cam, s.depth, s.feat, s.feat_dtype, xyz, tau=s.tau, z_near=s.z_near, flags=flags & 3,
                            pt_offsets=po, view_offsets=vo)
-    sc = orc.material_scores(fu["fused"], s.temb, s.y, T=s.temperature)
+    sc = orc.material_scores(fu["fused"], s.temb, s.y, T=s.temperature, unseen_zero=unseen_zero)
     return {**pv, "fused": fu["fused"], "count_fuse": fu["count"], **sc}
 
 

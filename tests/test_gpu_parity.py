@@ -109,7 +109,7 @@ def test_full_size_configs_on_sampled_points(H, orc, name):
         _same_bits(one, single, ("vis", "count", "scores", "prop", "label", "mass", "n_used"))
 
 
-def _check_full_size(H, orc, s, gpu, name, no_fused=False):
+def _check_full_size(H, orc, s, gpu, name, no_fused=False, flags=0):
     rng = np.random.default_rng(99)
     reps = []
     for b in range(0, s.B, max(1, s.B // 4)):
@@ -121,16 +121,70 @@ def _check_full_size(H, orc, s, gpu, name, no_fused=False):
         sub = copy.copy(s)       # the object's own views, as a single-object scene
         sub.cam, sub.depth, sub.feat = s.cam[v0:v1], s.depth[v0:v1], s.feat[v0:v1]
         sub.pt_offsets, sub.view_offsets = np.array([0, s.N], np.int64), np.array([0, v1 - v0], np.int32)
-        ref = H.oracle_points(orc, sub, idx=idx)
+        ref = H.oracle_points(orc, sub, idx=idx, flags=flags)
         g = {k: (v[:, :v1 - v0] if k == "vis" else v) for k, v in gpu.items()}
         reps.append(H.compare_points(g, ref, s, idx=idx, no_fused=no_fused))
     mass_rel = _mass_check(H, orc, s, gpu, gpu["prop"].astype(np.float64), gpu["count_fuse"])
     print(dict(samples=reps, mass_rel=mass_rel, visible_frac=float(gpu["vis"].mean()),
                unseen_frac=float((gpu["count"] == 0).mean())), flush=True)
     if name in ("c1", "c2"):     # small enough for the oracle to run the whole path
-        ref = H.oracle_points(orc, s)
+        ref = H.oracle_points(orc, s, flags=flags)
         H.compare_points(gpu, ref, s, no_fused=no_fused)
         _mass_check(H, orc, s, gpu, ref["prop"], ref["count_fuse"])
+
+
+def test_full_size_c4_without_the_depth_test(H, orc):
+    """c4 with AURA_VIS_FRUSTUM_ONLY: with the depth test 94 % of its voxels (the inside of the solid) are seen by nobody;
+    without it every pair that lands in an image gathers, about ten times the cell lists per tile.  Sampled points, the
+    combined call and the single pass."""
+    from paper_2511_03126_amd import binding
+    s = make_scene("c4")
+    d = H.DeviceScene(s, flags=binding.VIS_FRUSTUM_ONLY)
+    d.step_combined()
+    one = d.results()
+    assert one["vis"].mean() > 0.5
+    _check_full_size(H, orc, s, one, "c4", flags=binding.VIS_FRUSTUM_ONLY)
+    d.clear_outputs()
+    d.step_single_pass()
+    single = d.results()
+    assert np.isnan(single["fused"]).all()
+    _check_full_size(H, orc, s, single, "c4", no_fused=True, flags=binding.VIS_FRUSTUM_ONLY)
+    _same_bits(one, single, ("vis", "count", "scores", "prop", "label", "mass", "n_used"))
+
+
+@pytest.mark.parametrize("name,kw,temb_dtype", [
+    ("c5", dict(n_points=2_500, n_objects=3), torch.float16),                 # one producer wave, scoring kernel on the k-steps
+    ("c2", dict(n_points=20_011), torch.bfloat16),                            # scoring wave inside the fusion kernel
+    ("c1", dict(n_points=3001), torch.float16),                               # fp32 maps: gather kernel + scoring kernel
+    ("c3", dict(n_points=15_000, overrides=dict(V=5, HW=112, grid=112)), None),   # more cells than points
+])
+def test_unseen_points_get_zero_properties_on_request_and_16_bit_text_embeddings(H, orc, name, kw, temb_dtype):
+    """AURA_UNSEEN_ZERO through every scoring path (points no view sees: the far side of the objects), with the text
+    embeddings handed over as fp16 / bf16 values where a type is given (rounded first, so that both sides hold the same
+    numbers)."""
+    from paper_2511_03126_amd import binding
+    s = make_scene(name, **kw)
+    if temb_dtype is not None:
+        s.temb = torch.from_numpy(s.temb).to(temb_dtype).to(torch.float32).numpy()
+    if name != "c5":     # a wall in front of every camera but the first, which keeps the lower half of its image
+        s.depth[1:] = 0.25
+        s.depth[0, : s.H // 2, :] = 0.25
+    d = H.DeviceScene(s, flags=binding.UNSEEN_ZERO, temb_dtype=temb_dtype)
+    ref = H.oracle_points(orc, s, unseen_zero=True)
+    unseen = ref["count_fuse"] == 0
+    assert unseen.any() and (~unseen).any()
+    assert not ref["prop"][unseen].any() and ref["prop"][~unseen].all()
+    for step in (d.step, d.step_combined, d.step_combined_two_kernels, d.step_single_pass):
+        d.clear_outputs()
+        step()
+        gpu = d.results()
+        print(step.__name__, H.compare_points(gpu, ref, s, no_fused=step == d.step_single_pass), flush=True)
+        assert not gpu["prop"][unseen].any()          # exact zeros, not small numbers
+        _mass_check(H, orc, s, gpu, ref["prop"], ref["count_fuse"])
+    # without the flag the same points carry the mean of y (Eq. 4 on equal similarities)
+    d0 = H.DeviceScene(s, temb_dtype=temb_dtype)
+    d0.step_combined()
+    assert np.allclose(d0.results()["prop"][unseen], s.y.astype(np.float64).mean(0), rtol=1e-6)
 
 
 def _custom_scene(N=1500, V=3, D=512, K=12, P=1, dtype="f32", seed=5, **over):
