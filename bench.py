@@ -35,8 +35,8 @@ def fuse_algorithmic_bytes(s):
 # HBM bytes per launch of the dominant kernel from the rocprofv3 counter runs summarised under profiles/ (FETCH_SIZE and
 # WRITE_SIZE, each scaled by the reading of the 256 MiB calibration copy in the same run), per workload.  Valid only for
 # the kernel source the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_BYTES = {}
-TRAFFIC_SOURCE_SHA256 = ""
+TRAFFIC_BYTES = {'c5': 13703351607}
+TRAFFIC_SOURCE_SHA256 = "94755482c5d8983ccc557512eba9de5dc7ee1e6d13e8409bf1cb2fe513d5e78d"
 
 
 def measured_traffic(workload):
@@ -389,13 +389,21 @@ def tile_steps(torch, d, s):
             "fused_by_gather": int((n < 0).sum()), "total": int(n[n >= 0].sum())}
 
 
-def measure(torch, s, name, steps, warmup, staged=False, flags=0, want_single_pass=True):
-    """One workload: the timed steps, the time per call, the fusion kernel's roofline figure, and the single-pass call."""
+def measure(torch, s, name, steps, warmup, step="combined", flags=0, want_single_pass=True, extras=True):
+    """One workload: the timed steps, the time per call, the fusion kernel's roofline figure, and the single-pass call.
+    step: which calls make a step (combined: aura_fuse_scores + aura_property_integrate; staged: one call per stage;
+    single_pass: aura_fuse_score_integrate).  extras=False leaves out everything that launches the fusion kernels in
+    another way (for profiler runs, where launches are told apart by kernel name only)."""
     from paper_2511_03126_amd.device_scene import DeviceScene
     d = DeviceScene(s, flags=flags)
+    staged = step == "staged"
     if staged:
         names = ["project_visibility", "fuse_features", "material_scores", "property_integrate"]
         calls = [d.project_visibility, d.fuse_features, d.material_scores, d.property_integrate]
+    elif step == "single_pass":
+        names = ["fuse_score_integrate"]
+        calls = [d.step_single_pass_call]
+        want_single_pass = False
     else:
         names = ["fuse_scores", "property_integrate"]       # the mask and view counts come out of the fusion
         calls = [d.fuse_scores_vis, d.property_integrate]
@@ -421,9 +429,10 @@ def measure(torch, s, name, steps, warmup, staged=False, flags=0, want_single_pa
     vis_frac = float(d.vis.float().mean())
     unseen = float((d.count_fuse == 0).float().mean())
     kernel_ms, spread = fusion_kernel_ms(torch, calls, max(steps, 10))
-    fuse_bytes = fuse_algorithmic_bytes(s)
+    fuse_bytes = single_pass_algorithmic_bytes(s) if step == "single_pass" else fuse_algorithmic_bytes(s)
     achieved = fuse_bytes / (kernel_ms * 1e-3) / 1e9
-    kernel = (f"matrix-core fusion <{s.feat_dtype}, {s.D // 256} product waves> inside {names[1] if staged else names[0]} "
+    fusion_call = names[1] if staged else names[0]
+    kernel = (f"matrix-core fusion <{s.feat_dtype}, {s.D // 256} product waves> inside {fusion_call} "
               "(k_tile_fused; k_tile_prepare + k_tile_product where the lists do not fit the one-kernel form)"
               if tile else f"k_fuse_gather inside {names[1] if staged else names[0]}")
     out = {
@@ -439,9 +448,11 @@ def measure(torch, s, name, steps, warmup, staged=False, flags=0, want_single_pa
                      "launch_spread": spread,
                      # context for short kernels: the interval between the two markers holds the kernel plus the markers'
                      # own cost; the same fusion launched by aura_fuse_features, many calls between one pair of events
-                     "marker_pair_overhead_ms": marker_overhead_ms(torch),
-                     "fuse_features_back_to_back_ms": back_to_back_ms(torch, d.fuse_features, max(steps, 10))},
+                     "marker_pair_overhead_ms": marker_overhead_ms(torch)},
     }
+    if not extras:
+        return out, d
+    out["roofline"]["fuse_features_back_to_back_ms"] = back_to_back_ms(torch, d.fuse_features, max(steps, 10))
     ks = None if (flags & 4) else tile_steps(torch, d, s)     # (AURA_FUSE_GATHER: no tiles)
     if ks is not None:
         out["tile_k_steps"] = {k: ks[k] for k in ("tiles", "mean", "max", "fused_by_gather")}
@@ -484,7 +495,12 @@ def main():
     ap.add_argument("--workload", default="c5", choices=["c1", "c2", "c3", "c4", "c5"],
                     help="the headline workload; the others are reported under `configs`")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--staged", action="store_true", help="fusion and scoring as two library calls")
+    ap.add_argument("--staged", action="store_true", help="one library call per stage (same as --step staged)")
+    ap.add_argument("--step", default="combined", choices=["combined", "staged", "single_pass"],
+                    help="the calls of a step: aura_fuse_scores + aura_property_integrate; one call per stage; or "
+                         "aura_fuse_score_integrate alone")
+    ap.add_argument("--plain", action="store_true",
+                    help="with --only-headline: nothing but the step's own calls (for profiler runs)")
     ap.add_argument("--only-headline", action="store_true",
                     help="skip the other configurations, the stress cases and the calls beyond the hot path")
     args = ap.parse_args()
@@ -516,7 +532,8 @@ def main():
         torch.cuda.empty_cache()
 
     s = scenes[(args.workload, "morton")]
-    head, d = measure(torch, s, args.workload, args.steps, args.warmup, staged=args.staged)
+    step = "staged" if args.staged else args.step
+    head, d = measure(torch, s, args.workload, args.steps, args.warmup, step=step, extras=not args.plain)
     release(d)
     out = {
         "metric": "fused point-views/sec", "value": head["point_views_per_s"], "unit": "point-views/s",
@@ -535,7 +552,7 @@ def main():
     if not args.only_headline:
         configs = []
         for w in others:
-            r, d = measure(torch, scenes[(w, "morton")], w, args.steps, args.warmup, staged=args.staged)
+            r, d = measure(torch, scenes[(w, "morton")], w, args.steps, args.warmup, step=step)
             if w == "c2":
                 reps = max(args.steps // 2, 5)
                 d.step_combined()      # the calls beyond the hot path take the fused rows and scores as input
