@@ -1519,9 +1519,6 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
     int my_cnt = 0;                      // views that see point (lane % 32) of this tile
 #pragma unroll
     for (int o = 0; o < NP; ++o) my_cnt += s_slot[buf].cnt[o][m];
-    if (n >= 0 && span == 0 && tid < kTilePts && fa.out_count && blk * kTilePts + tid < ob.n_pts)
-      fa.out_count[ob.pt_begin + blk * kTilePts + tid] = my_cnt;
-
     f32x16 acc[4 * H];
 #pragma unroll
     for (int t = 0; t < 4 * H; ++t)
@@ -1529,50 +1526,6 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       for (int r = 0; r < 16; ++r) acc[t][r] = 0.0f;
 
     const char* sb = s_steps[buf];
-    if constexpr (SC) {   // what the scoring wave finished during the last tile (the tile before that one)
-      if (span == (S > 1 ? 1 : 0)) store_scores(s_out[buf], fa.scoring, ob, lane);
-    }
-    if (keep && tid == 0) ws.hdr[ob.tile_begin + blk].nsteps = n;   // the scoring kernel reads the header from memory
-    if (fa.out_vis && span == S - 1 && lane < kTilePts && blk * kTilePts + lane < ob.n_pts) {
-      // The visibility mask (Eq. 1) of the tile, as aura_project_visibility writes it; a tile that the producers
-      // fused themselves has its mask already, up to the columns beyond the object's views.
-      uint8_t* __restrict__ vrow = fa.out_vis + (ob.pt_begin + blk * kTilePts + lane) * fa.vis_pitch;
-      const uint32_t* vm = s_slot[buf].vmask;
-      if (n >= 0) {
-        const bool wide = (fa.vis_pitch & 15) == 0 && (reinterpret_cast<uintptr_t>(fa.out_vis) & 15) == 0;
-        const bool words = (fa.vis_pitch & 3) == 0 && (reinterpret_cast<uintptr_t>(fa.out_vis) & 3) == 0;
-        for (int v0 = 0; v0 < ob.n_views; v0 += 16) {   // 16 views = 16 bytes of the point's row
-          uint32_t wd[4];
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            wd[q] = 0;
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-              if (v0 + 4 * q + e < ob.n_views) wd[q] |= ((vm[v0 + 4 * q + e] >> lane) & 1u) << (8 * e);
-          }
-          if (wide && v0 + 16 <= ob.n_views) {
-            *reinterpret_cast<u32x4*>(vrow + v0) = u32x4{wd[0], wd[1], wd[2], wd[3]};
-          } else {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              if (words && v0 + 4 * q + 4 <= ob.n_views) {
-                *reinterpret_cast<uint32_t*>(vrow + v0 + 4 * q) = wd[q];
-              } else {
-                for (int e = 0; e < 4 && v0 + 4 * q + e < ob.n_views; ++e) vrow[v0 + 4 * q + e] = (uint8_t)((wd[q] >> (8 * e)) & 1u);
-              }
-            }
-          }
-        }
-      }
-      for (int j = ob.n_views; j < fa.vis_pitch; ++j) vrow[j] = 0;
-    }
-    if (keep && n > 0) {
-      // The scoring kernel wants the k-steps in memory: the product waves, which have issue slots to spare, copy the
-      // staged tile out (the producers do not: their vector ALU work is what the tile waits for).
-      u32x4* __restrict__ dst = reinterpret_cast<u32x4*>(ws.steps + (long long)(ob.tile_begin + blk) * ws.quota);
-      const u32x4* src = reinterpret_cast<const u32x4*>(sb);
-      for (int q = span * kWave + lane; q < n * (int)(sizeof(TileStep) / 16); q += S * kWave) dst[q] = src[q];
-    }
     {
       const int cnt = max(n, 0), l0 = cnt - 1;
       int s = 0;
@@ -1596,6 +1549,57 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       }
     }
 
+    // What goes to memory besides the fused rows.  After the products, not before: the memory counter is in order
+    // and covers stores as well, so a store issued ahead of the first product (behind a condition, which makes the
+    // compiler count it as possibly absent) would have to be acknowledged before the cell rows requested earlier count
+    // as arrived - one store round trip per tile on the critical path.
+    if (n >= 0 && span == 0 && tid < kTilePts && fa.out_count && blk * kTilePts + tid < ob.n_pts)
+      fa.out_count[ob.pt_begin + blk * kTilePts + tid] = my_cnt;
+    if constexpr (SC) {   // what the scoring wave finished during the last tile (the tile before that one)
+      if (span == (S > 1 ? 1 : 0)) store_scores(s_out[buf], fa.scoring, ob, lane);
+    }
+    if (keep && tid == 0) ws.hdr[ob.tile_begin + blk].nsteps = n;   // the scoring kernel reads the header from memory
+    if (fa.out_vis && lane < kTilePts && blk * kTilePts + lane < ob.n_pts) {
+      // The visibility mask (Eq. 1) of the tile, as aura_project_visibility writes it: lane = point, and the product
+      // waves share the views, eight at a time (eight bytes of the point's row).  A tile that the producers fused
+      // themselves has its mask already, up to the columns beyond the object's views.
+      uint8_t* __restrict__ vrow = fa.out_vis + (ob.pt_begin + blk * kTilePts + lane) * fa.vis_pitch;
+      const uint32_t* vm = s_slot[buf].vmask;
+      if (n >= 0) {
+        const bool pairs = (fa.vis_pitch & 7) == 0 && (reinterpret_cast<uintptr_t>(fa.out_vis) & 7) == 0;
+        const bool words = (fa.vis_pitch & 3) == 0 && (reinterpret_cast<uintptr_t>(fa.out_vis) & 3) == 0;
+        // who takes the first eight views, the next eight, ...: the last wave, the first, then the others, with the
+        // second wave (which stores the scores where the workgroup has a scoring wave) at the end
+        const int turn = span == S - 1 ? 0 : (span == 0 ? 1 : (span == 1 ? S - 1 : span));
+        for (int v0 = 8 * turn; v0 < ob.n_views; v0 += 8 * S) {
+          uint32_t wd[2] = {0u, 0u};
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            if (v0 + e < ob.n_views) wd[e >> 2] |= ((vm[v0 + e] >> lane) & 1u) << (8 * (e & 3));
+          if (pairs && v0 + 8 <= ob.n_views) {
+            *reinterpret_cast<u32x2*>(vrow + v0) = u32x2{wd[0], wd[1]};
+          } else {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+              if (words && v0 + 4 * q + 4 <= ob.n_views) {
+                *reinterpret_cast<uint32_t*>(vrow + v0 + 4 * q) = wd[q];
+              } else {
+                for (int e = 0; e < 4 && v0 + 4 * q + e < ob.n_views; ++e) vrow[v0 + 4 * q + e] = (uint8_t)((wd[q] >> (8 * e)) & 1u);
+              }
+            }
+          }
+        }
+      }
+      if (span == S - 1)
+        for (int j = ob.n_views; j < fa.vis_pitch; ++j) vrow[j] = 0;
+    }
+    if (keep && n > 0) {
+      // The scoring kernel wants the k-steps in memory: the product waves, which have issue slots to spare, copy the
+      // staged tile out (the producers do not: their vector ALU work is what the tile waits for).
+      u32x4* __restrict__ dst = reinterpret_cast<u32x4*>(ws.steps + (long long)(ob.tile_begin + blk) * ws.quota);
+      const u32x4* src = reinterpret_cast<const u32x4*>(sb);
+      for (int q = span * kWave + lane; q < n * (int)(sizeof(TileStep) / 16); q += S * kWave) dst[q] = src[q];
+    }
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const int row = 8 * (r >> 2) + 4 * g + (r & 3);
