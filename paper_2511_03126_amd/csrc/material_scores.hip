@@ -12,6 +12,8 @@
 // flop per byte, far below the machine balance): the matrix cores are the right instruction,
 // not the bound.  The text embeddings are split once per call by a small preparation kernel into
 // the workspace, already in the per-lane operand order, and stay resident in L2.
+#include <algorithm>
+
 #include "aura_device.hpp"
 #include "launch.hpp"
 #include "scores_core.hpp"
@@ -93,6 +95,202 @@ __global__ __launch_bounds__(256) void k_material_scores(ScoreArgs a) {
   finish_scores<MT>(acc, n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label, a.unseen_zero != 0);
 }
 
+// The same contraction for whole macro steps and 16-byte aligned rows, software-pipelined: what step s + 1 needs - the
+// lane's 64 bytes of each of its RT rows and, with PRE_A, the split embeddings of the step (MT * 4 KiB, L2 hits) - is
+// requested before the products of step s and kept in a second set of registers (the loop is unrolled by two, so
+// that nothing that is still on its way has to be copied).  The memory counter returns reads in order: the requests
+// for the next step are always the youngest, so waiting for this step's operands never waits for them.  Without the
+// pipeline a wave asked for a step only when it needed it, and the kernel reached 4.0 of the 5.3 TB/s that the same
+// read pattern reaches without arithmetic.  RT tiles of 32 points per wave share the embeddings of a step.
+template <int MT, int RT, bool PRE_A>
+__global__ __launch_bounds__(256) void k_material_scores_rt(ScoreArgs a) {
+  __shared__ float ys[kMaxK * kMaxP];
+  if (a.prop) {
+    for (int t = threadIdx.x; t < a.K * a.P; t += blockDim.x) ys[t] = a.y[t];
+  }
+  __syncthreads();
+
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const long long n0 = ((long long)blockIdx.x * 4 + wave) * (kTileN * RT);
+  if (n0 >= a.N) return;
+  const int g = lane / 32;
+  const float* __restrict__ row[RT];
+#pragma unroll
+  for (int t = 0; t < RT; ++t) {
+    const long long n = n0 + t * kTileN + (lane & 31);
+    row[t] = a.fused + (n < a.N ? n : a.N - 1) * a.D + g * 16;
+  }
+  f32x16 acc[RT][MT];
+#pragma unroll
+  for (int t = 0; t < RT; ++t)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[t][mt][r] = 0.0f;
+
+  struct Rows { f32x4 v[RT][4]; };
+  struct Emb { bf16x8 hi[MT][2], lo[MT][2]; };
+  auto load_rows = [&](int s, Rows& r) {
+#pragma unroll
+    for (int t = 0; t < RT; ++t)
+#pragma unroll
+      for (int q = 0; q < 4; ++q) r.v[t][q] = *reinterpret_cast<const f32x4*>(row[t] + s * kStepK + 4 * q);
+  };
+  auto load_emb = [&](int s, Emb& e) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const bf16x8* slot = a.a_split + ((long long)(s * MT + mt) * 2 + j) * 2 * kWave + lane;
+        e.hi[mt][j] = slot[0];
+        e.lo[mt][j] = slot[kWave];
+      }
+  };
+  auto products = [&](const Rows& r, const Emb& e) {
+#pragma unroll
+    for (int t = 0; t < RT; ++t) {
+      bf16x8 bh[2], bl[2];
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int c = 0; c < 8; ++c) {
+          const float x = r.v[t][2 * j + (c >> 2)][c & 3];
+          const __bf16 h = (__bf16)x;
+          bh[j][c] = h;
+          bl[j][c] = (__bf16)(x - (float)h);
+        }
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          acc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(e.hi[mt][j], bh[j], acc[t][mt], 0, 0, 0);
+          acc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(e.hi[mt][j], bl[j], acc[t][mt], 0, 0, 0);
+          acc[t][mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(e.lo[mt][j], bh[j], acc[t][mt], 0, 0, 0);
+        }
+    }
+  };
+
+  const int last = a.steps - 1;
+  Rows r0, r1;
+  Emb e0, e1;
+  load_rows(0, r0);
+  if constexpr (PRE_A) load_emb(0, e0);
+  for (int s = 0; s < a.steps; s += 2) {
+    // step s from set 0 while step s + 1 arrives in set 1 (past the end: the last step again, read and not used)
+    if constexpr (PRE_A) load_emb(min(s + 1, last), e1); else load_emb(s, e0);
+    load_rows(min(s + 1, last), r1);
+    __builtin_amdgcn_sched_barrier(0);
+    products(r0, e0);
+    __builtin_amdgcn_sched_barrier(0);
+    if (s + 1 < a.steps) {   // uniform
+      if constexpr (PRE_A) load_emb(min(s + 2, last), e0); else load_emb(s + 1, e1);
+      load_rows(min(s + 2, last), r0);
+      __builtin_amdgcn_sched_barrier(0);
+      products(r1, e1);
+      __builtin_amdgcn_sched_barrier(0);
+    }
+  }
+#pragma unroll
+  for (int t = 0; t < RT; ++t) {
+    const long long n = n0 + t * kTileN + (lane & 31);
+    if (n < a.N)   // lanes l and l ^ 32 hold the same point: the exchanges inside stay within existing points
+      finish_scores<MT>(acc[t], n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label, a.unseen_zero != 0);
+  }
+}
+
+// Where all the split embeddings of a call fit into LDS (steps * MT <= kLdsSlots blocks of 4 KiB: up to 1024 channels
+// for 32 materials, 512 for 64), one workgroup of 16 waves per compute unit copies them there once and then walks over
+// tiles of 32 points: the embeddings no longer come from L2 once per tile - reading them there costs the row stream 15 %
+// of its rate (a read-only probe of the same pattern: 5.3 TB/s alone, 4.5 TB/s with those reads beside it).  The rows are
+// requested one macro step ahead, across tile boundaries, so the stream never pauses.
+constexpr int kLdsSlots = 32;
+
+// kLdsWaves waves per workgroup: 16 for up to 32 materials (128 registers per wave), 8 for up to 64.
+template <int MT, int kLdsWaves>
+__global__ __launch_bounds__(kLdsWaves* kWave) void k_material_scores_lds(ScoreArgs a) {
+  __shared__ float ys[kMaxK * kMaxP];
+  __shared__ __attribute__((aligned(16))) bf16x8 s_a[kLdsSlots * 2 * 2 * kWave];   // 128 KiB
+  if (a.prop) {
+    for (int t = threadIdx.x; t < a.K * a.P; t += blockDim.x) ys[t] = a.y[t];
+  }
+  for (int t = threadIdx.x; t < a.steps * MT * 2 * 2 * kWave; t += blockDim.x) s_a[t] = a.a_split[t];
+  __syncthreads();
+
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int g = lane / 32;
+  const long long n_tiles = (a.N + kTileN - 1) / kTileN;
+  const long long stride = (long long)gridDim.x * kLdsWaves;
+  long long tile = (long long)blockIdx.x * kLdsWaves + wave;
+  if (tile >= n_tiles) return;
+  auto row_of = [&](long long tl) {
+    const long long n = tl * kTileN + (lane & 31);
+    return a.fused + (n < a.N ? n : a.N - 1) * a.D + g * 16;
+  };
+  struct Rows { f32x4 v[4]; };
+  auto load_rows = [&](const float* __restrict__ row, int s, Rows& r) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r.v[q] = *reinterpret_cast<const f32x4*>(row + s * kStepK + 4 * q);
+  };
+  f32x16 acc[MT];
+  auto products = [&](const Rows& r, int s) {
+    bf16x8 bh[2], bl[2];
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int c = 0; c < 8; ++c) {
+        const float x = r.v[2 * j + (c >> 2)][c & 3];
+        const __bf16 h = (__bf16)x;
+        bh[j][c] = h;
+        bl[j][c] = (__bf16)(x - (float)h);
+      }
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const bf16x8* slot = s_a + ((s * MT + mt) * 2 + j) * 2 * kWave + lane;
+        const bf16x8 ah = slot[0], al = slot[kWave];
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bh[j], acc[mt], 0, 0, 0);
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ah, bl[j], acc[mt], 0, 0, 0);
+        acc[mt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, bh[j], acc[mt], 0, 0, 0);
+      }
+  };
+
+  const int last = a.steps - 1;
+  const float* __restrict__ row = row_of(tile);
+  Rows r0, r1;
+  load_rows(row, 0, r0);
+  while (true) {
+    const long long next = tile + stride;
+    const float* __restrict__ row_next = row_of(next < n_tiles ? next : tile);   // no further tile: this one again, unused
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
+    for (int s = 0; s < a.steps; s += 2) {
+      // step s from set 0 while step s + 1 arrives in set 1, and the other way round; after the tile's last step
+      // the next tile's first
+      if (s + 1 <= last) load_rows(row, s + 1, r1); else load_rows(row_next, 0, r1);
+      __builtin_amdgcn_sched_barrier(0);
+      products(r0, s);
+      __builtin_amdgcn_sched_barrier(0);
+      if (s + 1 <= last) {   // uniform
+        if (s + 2 <= last) load_rows(row, s + 2, r0); else load_rows(row_next, 0, r0);
+        __builtin_amdgcn_sched_barrier(0);
+        products(r1, s + 1);
+        __builtin_amdgcn_sched_barrier(0);
+      } else {
+        r0 = r1;   // odd number of steps: the next tile's first step sits in set 1
+      }
+    }
+    const long long n = tile * kTileN + (lane & 31);
+    if (n < a.N)   // lanes l and l ^ 32 hold the same point: the exchanges inside stay within existing points
+      finish_scores<MT>(acc, n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label, a.unseen_zero != 0);
+    if (next >= n_tiles) break;
+    tile = next;
+    row = row_next;
+  }
+}
+
 size_t split_embeddings_bytes(int D, int MT) {
   return (size_t)((D + kStepK - 1) / kStepK) * MT * 2 * 2 * kWave * 8 * sizeof(__bf16);
 }
@@ -135,8 +333,35 @@ hipError_t launch_widen_embeddings(const void* src, int dtype, long long n, floa
   return hipGetLastError();
 }
 
+#ifndef AURA_SCORES_RT
+#define AURA_SCORES_RT 1
+#endif
+
 template <int MT>
 static hipError_t launch_mt(const ScoreArgs& a, bool aligned, hipStream_t stream) {
+  // embeddings of the next step in registers where they are few (up to 64 materials)
+  constexpr int RT = MT == 1 ? AURA_SCORES_RT : 1;
+  constexpr bool PRE_A = MT <= 2;
+  if constexpr (MT <= 2) {
+    if (aligned && a.D % kStepK == 0 && a.steps * MT <= kLdsSlots) {
+      constexpr int kWaves = MT == 1 ? 16 : 8;
+      int dev = 0, cus = 256;
+      if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+      const long long n_tiles = (a.N + kTileN - 1) / kTileN;
+      // worth it from about six tiles per wave: with fewer, the waves that get one tile more than the others set the
+      // time (200 000 points are 1.5 tiles per wave), and every workgroup pays for its copy of the embeddings
+      if (n_tiles >= 6ll * cus * kWaves) {
+        hipLaunchKernelGGL((k_material_scores_lds<MT, kWaves>), dim3((unsigned)cus), dim3(kWaves * kWave), 0, stream, a);
+        return hipGetLastError();
+      }
+    }
+  }
+  if (aligned && a.D % kStepK == 0) {
+    const long long per_group = 4ll * kTileN * RT;
+    hipLaunchKernelGGL((k_material_scores_rt<MT, RT, PRE_A>), dim3((unsigned)((a.N + per_group - 1) / per_group)), dim3(256),
+                       0, stream, a);
+    return hipGetLastError();
+  }
   dim3 grid((unsigned)((a.N + 4 * kTileN - 1) / (4 * kTileN))), block(256);
   if (aligned)
     hipLaunchKernelGGL((k_material_scores<MT, true>), grid, block, 0, stream, a);
