@@ -215,7 +215,22 @@ def time_normals(torch, d, s, reps, n_target=150, k=30):
         run()
     e1.record()
     torch.cuda.synchronize()
-    return {"call": "aura_estimate_normals", "queries": int(q.shape[0]), "cloud": p1, "k": k, "ms": e0.elapsed_time(e1) / reps}
+    out = {"call": "aura_estimate_normals", "queries": int(q.shape[0]), "cloud": p1, "k": k, "ms": e0.elapsed_time(e1) / reps}
+    # the same queries against a cloud of 1.7 M points (the voxel centres of workload c4 are that many): the object's
+    # points tiled and shifted by multiples of its extent
+    reps_cloud = 8
+    big = torch.cat([cloud + float(j) * 10.0 for j in range(reps_cloud)]) if p1 * reps_cloud <= 2_000_000 else cloud
+    big[:p1] = cloud
+    run_big = lambda: aura.estimate_normals(big, q, centre, k, normals)
+    for _ in range(2):
+        run_big()
+    e0.record()
+    for _ in range(reps):
+        run_big()
+    e1.record()
+    torch.cuda.synchronize()
+    out["large_cloud"] = {"cloud": int(big.shape[0]), "ms": e0.elapsed_time(e1) / reps}
+    return out
 
 
 def cpu_baseline(scene, seconds_target=15.0):

@@ -5,14 +5,20 @@
 // the smallest eigenvalue of their covariance), turned to point away from the object's centre.
 //
 // One workgroup per query.  Which points are nearest is decided on the fp32 distance d = (dx dx + dy dy) + dz dz
-// (every operation rounded, no contraction), of equal distances the lower index first:
-//   1. the k-th smallest distance by a radix select over the bit pattern of d (non-negative floats order like their
-//      bits): three sweeps over the cloud, each a histogram of the next 11 / 11 / 10 bits among the candidates left;
-//   2. when more points share that distance than are still needed, the same select over their indices;
-//   3. one sweep that sums r and r r^T (r = p - q, exact in fp64) over the selected points, in fp64 and in a fixed
-//      order, then the covariance and a cyclic Jacobi iteration on the 3 x 3 matrix by one thread.
-// The cloud of an object (a few MB) stays in L2 across the sweeps and the queries of a call run side by side; a call
-// for ~150 source points is a fraction of a millisecond.
+// (every operation rounded, no contraction), of equal distances the lower index first.
+//
+// Usual path (k up to 256), one sweep over the cloud:
+//   1. an upper bound of the k-th smallest distance that is exact by construction: the k-th smallest distance among
+//      every stride-th point (at most 16384 of them; the k-th smallest of a subset can only be larger);
+//   2. one sweep over the whole cloud collects the points within that bound (about k * stride of them) in LDS;
+//   3. among those, the k-th smallest distance by a radix select over the bit pattern of d (non-negative floats order
+//      like their bits: histograms of the next 11 / 11 / 10 bits among the candidates left) and, when more points share
+//      that distance than are still needed, the same select over their indices;
+//   4. the selected points in index order: r and r r^T (r = p - q, exact in fp64) summed in that order by one
+//      thread, then the covariance and a cyclic Jacobi iteration on the 3 x 3 matrix.
+// General path (larger k, or more candidates than the LDS list holds, e.g. thousands of points at one distance): the
+// radix select over the whole cloud (three sweeps), then one sweep for the sums.
+// The queries of a call run side by side; the cloud comes from L2 (a few MB) or the last-level cache.
 #include "aura_device.hpp"
 #include "launch.hpp"
 
@@ -20,6 +26,9 @@ namespace aura {
 
 constexpr int kNrmBlock = 1024;   // a sweep over the cloud is shared by 16 waves
 constexpr int kNrmBins = 2048;
+constexpr int kNrmSub = 16384;    // points of the strided subset that bounds the k-th distance
+constexpr int kNrmCand = 4096;    // candidates the LDS list holds
+constexpr int kNrmSel = 256;      // largest k of the one-sweep path
 
 struct NrmObjDev {
   long long pt_begin;
@@ -176,6 +185,23 @@ __device__ void smallest_eigenvector(const double (&c)[6], double (&w)[3], doubl
   for (int r = 0; r < 3; ++r) n[r] = v[r][order[0]] / len;
 }
 
+// From the sums of r and r r^T over the kk selected points to the stored normal (one thread).
+__device__ void finish_normal(const NrmArgs& a, const NrmObjDev& ob, long long m, float qx, float qy, float qz, int kk,
+                              const double (&s1)[3], const double (&s2)[6]) {
+  const double inv = 1.0 / (double)kk;
+  const double mx = s1[0] * inv, my = s1[1] * inv, mz = s1[2] * inv;
+  const double cov[6] = {s2[0] * inv - mx * mx, s2[1] * inv - mx * my, s2[2] * inv - mx * mz,
+                         s2[3] * inv - my * my, s2[4] * inv - my * mz, s2[5] * inv - mz * mz};
+  double w[3], nv[3];
+  smallest_eigenvector(cov, w, nv);
+  const double ox = (double)qx - (double)ob.centre[0], oy = (double)qy - (double)ob.centre[1], oz = (double)qz - (double)ob.centre[2];
+  const double sgn = nv[0] * ox + nv[1] * oy + nv[2] * oz < 0.0 ? -1.0 : 1.0;
+  for (int c = 0; c < 3; ++c) {
+    a.normals[3 * m + c] = (float)(sgn * nv[c]);
+    if (a.evals) a.evals[3 * m + c] = (float)w[c];
+  }
+}
+
 __global__ __launch_bounds__(kNrmBlock) void k_estimate_normals(NrmArgs a, NrmTable tab) {
   __shared__ uint32_t s_hist[kNrmBins];
   __shared__ int s_pick[3];
@@ -196,6 +222,70 @@ __global__ __launch_bounds__(kNrmBlock) void k_estimate_normals(NrmArgs a, NrmTa
   }
   auto dist = [&](int i) { return dist_bits(pts + 3 * (long long)i, qx, qy, qz); };
   int n_equal, need;
+  if (kk <= kNrmSel) {
+    __shared__ uint32_t s_cd[kNrmCand];   // candidates: distance bits ...
+    __shared__ int s_ci[kNrmCand];        // ... and point index
+    __shared__ int s_cn, s_ns;
+    __shared__ int s_sel[kNrmSel];        // the k selected points, unordered, then in index order
+    __shared__ float s_pt[kNrmSel][3];
+    const int stride = (n + kNrmSub - 1) / kNrmSub;
+    const int m_sub = (n + stride - 1) / stride;   // >= kk: kk <= n, and kk <= 256 < 16384 where stride > 1
+    const uint32_t bound = radix_select(m_sub, kk, [&](int j) { return dist(j * stride); }, [](int) { return true; }, s_hist,
+                                        s_pick, &n_equal, &need);
+    if (threadIdx.x == 0) { s_cn = 0; s_ns = 0; }
+    __syncthreads();
+    for (int i0 = threadIdx.x; i0 < n; i0 += 8 * kNrmBlock) {   // eight points per thread and trip: reads in flight together
+      uint32_t d[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) d[e] = dist(min(i0 + e * kNrmBlock, n - 1));
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int i = i0 + e * kNrmBlock;
+        if (i < n && d[e] <= bound) {
+          const int pos = atomicAdd(&s_cn, 1);
+          if (pos < kNrmCand) { s_cd[pos] = d[e]; s_ci[pos] = i; }
+        }
+      }
+    }
+    __syncthreads();
+    const int cn = s_cn;
+    if (cn <= kNrmCand) {   // uniform; otherwise the general path below
+      const uint32_t tau = radix_select(cn, kk, [&](int j) { return s_cd[j]; }, [](int) { return true; }, s_hist, s_pick,
+                                        &n_equal, &need);
+      int last_idx = 0x7fffffff;   // points at distance tau are taken up to this index
+      if (need < n_equal) {
+        int e2, n2;
+        last_idx = (int)radix_select(cn, need, [&](int j) { return (uint32_t)s_ci[j]; }, [&](int j) { return s_cd[j] == tau; },
+                                     s_hist, s_pick, &e2, &n2);
+      }
+      for (int j = threadIdx.x; j < cn; j += kNrmBlock)
+        if (s_cd[j] < tau || (s_cd[j] == tau && s_ci[j] <= last_idx)) s_sel[atomicAdd(&s_ns, 1)] = s_ci[j];   // exactly kk
+      __syncthreads();
+      // index order: the rank of a selected point is the number of selected points before it
+      int mine = -1, rank = 0;
+      if ((int)threadIdx.x < kk) {
+        mine = s_sel[threadIdx.x];
+        for (int j = 0; j < kk; ++j) rank += s_sel[j] < mine ? 1 : 0;
+      }
+      __syncthreads();
+      if (mine >= 0) {
+        const float* __restrict__ pm = pts + 3 * (long long)mine;
+        s_pt[rank][0] = pm[0]; s_pt[rank][1] = pm[1]; s_pt[rank][2] = pm[2];
+      }
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        double s1[3] = {0, 0, 0}, s2[6] = {0, 0, 0, 0, 0, 0};
+        for (int j = 0; j < kk; ++j) {
+          const double rx = (double)s_pt[j][0] - (double)qx, ry = (double)s_pt[j][1] - (double)qy, rz = (double)s_pt[j][2] - (double)qz;
+          s1[0] += rx; s1[1] += ry; s1[2] += rz;
+          s2[0] += rx * rx; s2[1] += rx * ry; s2[2] += rx * rz;
+          s2[3] += ry * ry; s2[4] += ry * rz; s2[5] += rz * rz;
+        }
+        finish_normal(a, ob, m, qx, qy, qz, kk, s1, s2);
+      }
+      return;
+    }
+  }
   const uint32_t tau = radix_select(n, kk, dist, [](int) { return true; }, s_hist, s_pick, &n_equal, &need);
   int last_idx = 0x7fffffff;   // points at distance tau are taken up to this index
   if (need < n_equal) {
@@ -231,20 +321,7 @@ __global__ __launch_bounds__(kNrmBlock) void k_estimate_normals(NrmArgs a, NrmTa
   for (int c = 0; c < 3; ++c) s1[c] = nrm_block_sum(s1[c], s_red);
 #pragma unroll
   for (int c = 0; c < 6; ++c) s2[c] = nrm_block_sum(s2[c], s_red);
-  if (threadIdx.x == 0) {
-    const double inv = 1.0 / (double)kk;
-    const double mx = s1[0] * inv, my = s1[1] * inv, mz = s1[2] * inv;
-    const double cov[6] = {s2[0] * inv - mx * mx, s2[1] * inv - mx * my, s2[2] * inv - mx * mz,
-                           s2[3] * inv - my * my, s2[4] * inv - my * mz, s2[5] * inv - mz * mz};
-    double w[3], nv[3];
-    smallest_eigenvector(cov, w, nv);
-    const double ox = (double)qx - (double)ob.centre[0], oy = (double)qy - (double)ob.centre[1], oz = (double)qz - (double)ob.centre[2];
-    const double sgn = nv[0] * ox + nv[1] * oy + nv[2] * oz < 0.0 ? -1.0 : 1.0;
-    for (int c = 0; c < 3; ++c) {
-      a.normals[3 * m + c] = (float)(sgn * nv[c]);
-      if (a.evals) a.evals[3 * m + c] = (float)w[c];
-    }
-  }
+  if (threadIdx.x == 0) finish_normal(a, ob, m, qx, qy, qz, kk, s1, s2);
 }
 
 hipError_t launch_estimate_normals(const float* xyz, const float* queries, const NrmObj* objs, int n_obj, int k,

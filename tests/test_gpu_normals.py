@@ -104,3 +104,45 @@ def test_full_size_c2(orc):
     g_n, g_w = _gpu(s.xyz, q, centre, 30)
     ref = orc.estimate_normals(s.xyz, q, centre, 30)
     _compare(g_n, g_w, ref, q, np.repeat(centre.astype(np.float64), len(q), 0), s.xyz, s.pt_offsets, np.array([0, len(q)]))
+
+
+def test_full_size_c4_cloud(orc):
+    """The 1.68 M voxel centres of c4 as the cloud (one sweep per query over 20 MB), ~150 sampled points as queries."""
+    from workloads.scenes import make_scene
+    s = make_scene("c4")
+    q = orc.voxel_downsample(s.xyz, 150)["xyz"].astype(np.float32)
+    centre = s.xyz.mean(0, keepdims=True).astype(np.float32)
+    g_n, g_w = _gpu(s.xyz, q, centre, 30)
+    ref = orc.estimate_normals(s.xyz, q, centre, 30)
+    # a regular voxel grid: many equal distances (ties at the k-th place go by index on both sides) and neighbourhoods
+    # inside the solid that are not planes at all: the eigenvalues and the quadratic form decide, not the direction
+    lam = ref["evals"]
+    assert np.abs(g_w - lam).max() <= 1e-5 * lam[:, 2].max()
+    P = s.xyz.astype(np.float64)
+    for m in range(len(q)):
+        nb = P[ref["nn_idx"][m]]
+        cov = np.cov(nb.T, bias=True)
+        assert g_n[m] @ cov @ g_n[m] <= lam[m, 0] + 1e-6 * lam[m, 2] + 1e-30
+
+
+@pytest.mark.parametrize("k", [1, 255, 256, 257, 600])
+def test_neighbourhood_sizes_around_the_limit_of_the_one_sweep_path(orc, k):
+    """k up to 256 takes one sweep and an on-chip list, larger k the three-sweep radix select over the cloud; a cloud where
+    thousands of points share the k-th distance overflows the list and takes the general path too."""
+    from workloads.scenes import make_scene
+    s = make_scene("c1", n_points=30_000)
+    q = s.xyz[np.linspace(0, s.N - 1, 24).astype(np.int64)]
+    centre = s.xyz.mean(0, keepdims=True).astype(np.float32)
+    g_n, g_w = _gpu(s.xyz, q, centre, k)
+    ref = orc.estimate_normals(s.xyz, q, centre, k)
+    assert np.abs(g_w - ref["evals"]).max() <= 1e-5 * ref["evals"][:, 2].max()
+    if k >= 255:      # many neighbours: a well-defined plane everywhere
+        assert np.abs(np.abs(np.einsum("ij,ij->i", g_n, ref["normals"])) - 1.0).max() < 1e-6
+    if k == 1:        # a shell of 6000 points at one distance from the query: more candidates than the list holds
+        rng = np.random.default_rng(3)
+        d = rng.standard_normal((6000, 3)); d /= np.linalg.norm(d, axis=1, keepdims=True)
+        shell = np.concatenate([np.zeros((1, 3)), 0.5 * d]).astype(np.float32)
+        shell[1:] = (0.5 * np.sign(d) * (np.abs(d) == np.abs(d).max(1, keepdims=True))).astype(np.float32)   # exactly 0.5 away
+        g_n, g_w = _gpu(shell, np.zeros((1, 3), np.float32), [[0, 0, -1]], 200)
+        ref = orc.estimate_normals(shell, np.zeros((1, 3), np.float32), [[0, 0, -1]], 200)
+        assert np.abs(g_w - ref["evals"]).max() <= 1e-5 * ref["evals"][:, 2].max()
