@@ -35,8 +35,8 @@ def fuse_algorithmic_bytes(s):
 # HBM bytes per launch of the dominant kernel from the rocprofv3 counter runs summarised under profiles/ (FETCH_SIZE and
 # WRITE_SIZE, each scaled by the reading of the 256 MiB calibration copy in the same run), per workload.  Valid only for
 # the kernel source the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_BYTES = {'c5': 13703351607}
-TRAFFIC_SOURCE_SHA256 = "94755482c5d8983ccc557512eba9de5dc7ee1e6d13e8409bf1cb2fe513d5e78d"
+TRAFFIC_BYTES = {'c5': 13705897137}
+TRAFFIC_SOURCE_SHA256 = "df9db3a29ed20bf94409fcac666d47e76ebb17cb784f74eb74211bfda973dc33"
 
 
 def measured_traffic(workload):
