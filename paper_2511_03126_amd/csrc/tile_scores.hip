@@ -59,15 +59,89 @@ struct CellArgs {
   int D, K, Kpad;
   const float* temb;    // [K][D] fp32
   uint32_t* G;          // [n_cells][Kpad]: hi | lo << 16
+  ts_u32x4* t_split;    // the text embeddings as matrix-core operands: [D / 16][Kpad / 32][hi, lo][64 lanes] x 16 bytes
 };
+
+// The text embeddings split into two terms of the maps' 16-bit type, once per call, in the order in which the lanes of
+// k_cell_scores take them: lane (material n = l % 32, kg = l / 32) of slot (step s, tile mt) holds channels
+// 16 s + 8 kg .. + 7 of material 32 mt + n (zeros beyond K).
+template <int DT>
+__global__ __launch_bounds__(256) void k_split_for_cells(CellArgs a) {
+  const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;   // one thread per (step, tile, lane)
+  const int MT = a.Kpad / 32;
+  if (t >= (long long)(a.D / 16) * MT * kWave) return;
+  const int lane = (int)(t % kWave), mt = (int)((t / kWave) % MT), s = (int)(t / ((long long)kWave * MT));
+  const int n = mt * 32 + (lane & 31), kg = lane >> 5;
+  uint32_t p[8];
+#pragma unroll
+  for (int e = 0; e < 8; ++e) p[e] = split_pack<DT>(n < a.K ? a.temb[(long long)n * a.D + s * 16 + kg * 8 + e] : 0.0f);
+  ts_u32x4 hi, lo;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    hi[q] = __builtin_amdgcn_perm(p[2 * q + 1], p[2 * q], 0x05040100u);
+    lo[q] = __builtin_amdgcn_perm(p[2 * q + 1], p[2 * q], 0x07060302u);
+  }
+  ts_u32x4* slot = a.t_split + ((long long)(s * MT + mt) * 2) * kWave + lane;
+  slot[0] = hi;
+  slot[kWave] = lo;
+}
 
 // One workgroup of four waves per 32 cells, all materials; wave w takes every fourth group of 16 channels
 // (the sum over channels is a short chain of dependent steps: four waves make it four times shorter) and
 // the four partial results are added through LDS in a fixed order.  A operand: lane (cell i = l % 32,
 // kg = l / 32) holds channels 16 s + 8 kg .. + 7 of cell i (16 contiguous bytes of the stored map);
-// B operand: the same channels of material n = l % 32, split on the fly.
+// B operand: the same channels of material n = l % 32, from the table above (split per wave on the fly, the
+// conversions were most of the kernel's instructions: 1.0 ms for the 1.6 M cells of 512 channels and 64 materials).
 template <int DT, int MT>
 __global__ __launch_bounds__(256) void k_cell_scores(CellArgs a) {
+  __shared__ float s_part[3][MT][16][kWave];
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const long long c0 = (long long)blockIdx.x * 32;
+  const int i = lane & 31, kg = lane >> 5;
+  const long long cell = min(c0 + i, a.n_cells - 1);
+  const char* __restrict__ frow = a.feat + cell * a.D * 2 + kg * 16;
+
+  ts_f32x16 acc[MT];
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
+
+  for (int s = wave; s < a.D / 16; s += 4) {
+    const ts_u32x4 fa = *reinterpret_cast<const ts_u32x4*>(frow + s * 32);
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const ts_u32x4* slot = a.t_split + ((long long)(s * MT + mt) * 2) * kWave + lane;
+      const ts_u32x4 bh = slot[0], bl = slot[kWave];
+      acc[mt] = ts_mma<DT>(fa, bh, acc[mt]);
+      acc[mt] = ts_mma<DT>(fa, bl, acc[mt]);
+    }
+  }
+  if (wave > 0) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) s_part[wave - 1][mt][r][lane] = acc[mt][r];
+  }
+  __syncthreads();
+  if (wave > 0) return;
+  // element r of the lane: cell c0 + 8 (r / 4) + 4 kg + r % 4, material 32 mt + i (0 beyond K)
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const long long c = c0 + 8 * (r >> 2) + 4 * kg + (r & 3);
+      const float sum = ((acc[mt][r] + s_part[0][mt][r][lane]) + s_part[1][mt][r][lane]) + s_part[2][mt][r][lane];
+      const float v = (mt * 32 + i < a.K) ? sum : 0.0f;
+      if (c < a.n_cells) a.G[c * a.Kpad + mt * 32 + i] = split_pack<DT>(v);
+    }
+}
+
+// The same with the embeddings split by every wave on the fly (B operand: the channels of material n = l % 32 read as
+// fp32 and split in registers): no table and no launch to build it, which is what counts for calls with few cells
+// (16 384 cells: 12 us for this kernel alone, while the launch that builds the table costs 5 us by itself).
+template <int DT, int MT>
+__global__ __launch_bounds__(256) void k_cell_scores_small(CellArgs a) {
   __shared__ float s_part[3][MT][16][kWave];
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const long long c0 = (long long)blockIdx.x * 32;
@@ -210,8 +284,12 @@ static int ts_kpad(int K) {
   return mt * 32;
 }
 
+// the split text embeddings for the largest channel count of the matrix-core path (1536)
+static size_t ts_split_bytes(int K) { return (size_t)(1536 / 16) * (ts_kpad(K) / 32) * 2 * kWave * 16; }
+
 size_t tile_scores_workspace_bytes(long long N, long long n_cells, int K) {
-  return ts_round256((size_t)N * sizeof(float)) + ts_round256((size_t)n_cells * ts_kpad(K) * sizeof(uint32_t));
+  return ts_round256((size_t)N * sizeof(float)) + ts_round256((size_t)n_cells * ts_kpad(K) * sizeof(uint32_t)) +
+         ts_split_bytes(K);
 }
 
 TileScoreWs tile_scores_workspace(void* workspace, long long N, long long n_cells, int K) {
@@ -220,12 +298,27 @@ TileScoreWs tile_scores_workspace(void* workspace, long long N, long long n_cell
   ws.factor = reinterpret_cast<float*>(base);
   base += ts_round256((size_t)N * sizeof(float));
   ws.G = reinterpret_cast<uint32_t*>(base);
+  base += ts_round256((size_t)n_cells * ts_kpad(K) * sizeof(uint32_t));
+  ws.t_split = base;
   ws.Kpad = ts_kpad(K);
   return ws;
 }
 
 template <int DT>
 static hipError_t launch_cells(const CellArgs& a, hipStream_t stream) {
+  if (a.n_cells * (a.Kpad / 32) < 32768) {
+    const dim3 grid((unsigned)((a.n_cells + 31) / 32)), block(256);
+    switch (a.Kpad / 32) {
+      case 1: hipLaunchKernelGGL((k_cell_scores_small<DT, 1>), grid, block, 0, stream, a); break;
+      case 2: hipLaunchKernelGGL((k_cell_scores_small<DT, 2>), grid, block, 0, stream, a); break;
+      default: hipLaunchKernelGGL((k_cell_scores_small<DT, 4>), grid, block, 0, stream, a); break;
+    }
+    return hipGetLastError();
+  }
+  const long long slots = (long long)(a.D / 16) * (a.Kpad / 32) * kWave;
+  hipLaunchKernelGGL((k_split_for_cells<DT>), dim3((unsigned)((slots + 255) / 256)), dim3(256), 0, stream, a);
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   const dim3 grid((unsigned)((a.n_cells + 31) / 32)), block(256);
   switch (a.Kpad / 32) {
     case 1: hipLaunchKernelGGL((k_cell_scores<DT, 1>), grid, block, 0, stream, a); break;
@@ -237,7 +330,7 @@ static hipError_t launch_cells(const CellArgs& a, hipStream_t stream) {
 
 hipError_t launch_cell_scores(const FeatArgs& feat, long long n_cells, const float* temb, int K, const TileScoreWs& ws,
                               hipStream_t stream) {
-  CellArgs a{static_cast<const char*>(feat.feat), n_cells, feat.D, K, ws.Kpad, temb, ws.G};
+  CellArgs a{static_cast<const char*>(feat.feat), n_cells, feat.D, K, ws.Kpad, temb, ws.G, static_cast<ts_u32x4*>(ws.t_split)};
   return feat.dtype == 1 ? launch_cells<1>(a, stream) : launch_cells<2>(a, stream);
 }
 

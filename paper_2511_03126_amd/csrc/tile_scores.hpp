@@ -10,6 +10,7 @@ namespace aura {
 struct TileScoreWs {
   float* factor;   // [N]: what the raw tile product of a point is multiplied by (1 / (count * norm), or 1 / count)
   uint32_t* G;     // [n_cells][Kpad]: similarity of every feature cell to every material, two 16-bit terms
+  void* t_split;   // the text embeddings split into two 16-bit terms in operand order (written by launch_cell_scores)
   int Kpad;        // K rounded up to the matrix-core tile (32, 64 or 128)
 };
 

@@ -91,7 +91,8 @@ def test_workspace_sizes(B):
     sc = lambda D, K: B.workspace_bytes(B.CALL_MATERIAL_SCORES, D=D, K=K)
     assert both(D=512, feat_dtype=B.F32) == r256(sc(512, 33))
     assert both(D=768, feat_dtype=B.BF16) == (r256(fuse(D=768, feat_dtype=B.BF16)) + r256(200_000 * 4)
-                                              + r256(16 * 32 * 32 * 64 * 4) + r256(sc(768, 33)))
+                                              + r256(16 * 32 * 32 * 64 * 4) + 96 * 2 * 2048    # + the split embeddings
+                                              + r256(sc(768, 33)))
     assert both(D=768, feat_dtype=B.BF16, N=1000) == r256(fuse(D=768, feat_dtype=B.BF16, N=1000)) + r256(sc(768, 33))
     with pytest.raises(B.AuraError) as e:
         both(D=768, feat_dtype=B.BF16, K=129)
