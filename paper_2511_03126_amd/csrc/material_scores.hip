@@ -105,6 +105,7 @@ __global__ __launch_bounds__(256) void k_material_scores(ScoreArgs a) {
 template <int MT, int RT, bool PRE_A>
 __global__ __launch_bounds__(256) void k_material_scores_rt(ScoreArgs a) {
   __shared__ float ys[kMaxK * kMaxP];
+  __shared__ __attribute__((aligned(16))) float s_stage[4][score_stage_floats<16>()];
   if (a.prop) {
     for (int t = threadIdx.x; t < a.K * a.P; t += blockDim.x) ys[t] = a.y[t];
   }
@@ -192,9 +193,10 @@ __global__ __launch_bounds__(256) void k_material_scores_rt(ScoreArgs a) {
   }
 #pragma unroll
   for (int t = 0; t < RT; ++t) {
-    const long long n = n0 + t * kTileN + (lane & 31);
-    if (n < a.N)   // lanes l and l ^ 32 hold the same point: the exchanges inside stay within existing points
-      finish_scores<MT>(acc[t], n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label, a.unseen_zero != 0);
+    const long long first = n0 + t * kTileN;
+    const int rows = (int)std::min<long long>(kTileN, std::max<long long>(a.N - first, 0));
+    finish_scores_staged<MT, 16>(acc[t], first, rows, lane, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label,
+                                 a.unseen_zero != 0, s_stage[wave]);
   }
 }
 
@@ -208,8 +210,10 @@ constexpr int kLdsSlots = 32;
 // kLdsWaves waves per workgroup: 16 for up to 32 materials (128 registers per wave), 8 for up to 64.
 template <int MT, int kLdsWaves>
 __global__ __launch_bounds__(kLdsWaves* kWave) void k_material_scores_lds(ScoreArgs a) {
-  __shared__ float ys[kMaxK * kMaxP];
+  __shared__ float ys[MT * kTileM * kMaxP];
   __shared__ __attribute__((aligned(16))) bf16x8 s_a[kLdsSlots * 2 * 2 * kWave];   // 128 KiB
+  constexpr int kStageRows = kLdsWaves > 8 ? 8 : 16;
+  __shared__ __attribute__((aligned(16))) float s_stage[kLdsWaves][score_stage_floats<kStageRows>()];
   if (a.prop) {
     for (int t = threadIdx.x; t < a.K * a.P; t += blockDim.x) ys[t] = a.y[t];
   }
@@ -282,9 +286,8 @@ __global__ __launch_bounds__(kLdsWaves* kWave) void k_material_scores_lds(ScoreA
         r0 = r1;   // odd number of steps: the next tile's first step sits in set 1
       }
     }
-    const long long n = tile * kTileN + (lane & 31);
-    if (n < a.N)   // lanes l and l ^ 32 hold the same point: the exchanges inside stay within existing points
-      finish_scores<MT>(acc, n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label, a.unseen_zero != 0);
+    finish_scores_staged<MT, kStageRows>(acc, tile * kTileN, (int)std::min<long long>(kTileN, a.N - tile * kTileN), lane, a.K,
+                                         a.P, a.inv_T, ys, a.scores, a.prop, a.label, a.unseen_zero != 0, s_stage[wave]);
     if (next >= n_tiles) break;
     tile = next;
     row = row_next;

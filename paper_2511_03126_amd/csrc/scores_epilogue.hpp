@@ -84,4 +84,106 @@ __device__ __forceinline__ void finish_scores(const scores_f32x16 (&acc)[MT], lo
   }
 }
 
+// The same for a whole wave whose 32 points are consecutive in memory (n0 .. n0 + rows - 1 exist), with the scores
+// going through a small LDS buffer of the wave's own (kScoreStageFloats floats) so that they reach memory in long runs:
+// in the accumulator layout a store instruction writes 32 bytes of each of 32 rows, and those partial-line writes cost
+// the scoring kernels up to a fifth of their time (6.4 M points x 24 materials: 0.53 of 2.9 ms).  ROWS rows at a time
+// (16, or 8 where LDS is short) are laid out as [row][material] in the buffer and copied out sixteen bytes per lane,
+// eight neighbouring lanes per row.  All 64 lanes call this, also those whose point does not exist.
+constexpr int kScoreStagePitch = 36;   // floats: rows start 4 banks apart
+template <int ROWS>
+constexpr int score_stage_floats() { return ROWS * kScoreStagePitch; }
+
+template <int MT, int ROWS>
+__device__ __forceinline__ void finish_scores_staged(const scores_f32x16 (&acc)[MT], long long n0, int rows, int lane, int K,
+                                                     int P, float inv_T, const float* __restrict__ ys,
+                                                     float* __restrict__ scores, float* __restrict__ prop,
+                                                     int* __restrict__ label, bool unseen_zero, float* stage) {
+  const int pt = lane & 31, g = lane >> 5;
+  const bool valid = pt < rows;
+  const long long n = n0 + (valid ? pt : 0);
+  if ((K & 3) == 0 && ((reinterpret_cast<uintptr_t>(scores) & 15) == 0)) {
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int cols = min(kScoreTileM, K - mt * kScoreTileM);   // a multiple of 4
+      if (cols <= 0) continue;                                    // uniform
+      const int per_row = cols >> 2;
+#pragma unroll
+      for (int part = 0; part < 32 / ROWS; ++part) {
+        if (pt / ROWS == part) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q)
+            *reinterpret_cast<scores_f32x4*>(stage + (pt % ROWS) * kScoreStagePitch + 8 * q + 4 * g) =
+                scores_f32x4{acc[mt][4 * q], acc[mt][4 * q + 1], acc[mt][4 * q + 2], acc[mt][4 * q + 3]};
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        for (int idx = lane; idx < ROWS * per_row; idx += kWave) {
+          const int r = idx / per_row, c4 = idx - r * per_row;
+          const int row = part * ROWS + r;
+          if (row < rows)
+            *reinterpret_cast<scores_f32x4*>(scores + (n0 + row) * K + mt * kScoreTileM + 4 * c4) =
+                *reinterpret_cast<const scores_f32x4*>(stage + r * kScoreStagePitch + 4 * c4);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+      }
+    }
+  } else if (valid) {
+    float* __restrict__ srow = scores + n * K;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int m = mt * kScoreTileM + 8 * (r >> 2) + 4 * g + (r & 3);
+        if (m < K) srow[m] = acc[mt][r];
+      }
+  }
+  // label and Eq. 4 as in finish_scores; the two lanes of a point exchange with each other only
+  float best = -INFINITY;
+  int bidx = 0;
+  bool any_nonzero = false;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {   // ascending material index within the lane: the lowest index wins ties
+      const int m = mt * kScoreTileM + 8 * (r >> 2) + 4 * g + (r & 3);
+      const float sc = acc[mt][r];
+      if (m < K && sc > best) { best = sc; bidx = m; }
+      any_nonzero = any_nonzero || (m < K && sc != 0.0f);
+    }
+  {
+    const float ob = __shfl_xor(best, 32, kWave);
+    const int oi = __shfl_xor(bidx, 32, kWave);
+    if (ob > best || (ob == best && oi < bidx)) { best = ob; bidx = oi; }
+  }
+  if (label && g == 0 && valid) label[n] = bidx;
+  if (!prop) return;
+  const bool zero_row = unseen_zero && !(any_nonzero || __shfl_xor((int)any_nonzero, 32, kWave) != 0);
+  float den = 0.0f, num[kScoreMaxP];
+#pragma unroll
+  for (int p = 0; p < kScoreMaxP; ++p) num[p] = 0.0f;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = mt * kScoreTileM + 8 * (r / 4) + 4 * g + (r & 3);
+      if (m < K) {
+        const float e = expf((acc[mt][r] - best) * inv_T);
+        den += e;
+#pragma unroll
+        for (int p = 0; p < kScoreMaxP; ++p)
+          if (p < P) num[p] = __builtin_fmaf(e, ys[m * P + p], num[p]);
+      }
+    }
+  den += __shfl_xor(den, 32, kWave);
+#pragma unroll
+  for (int p = 0; p < kScoreMaxP; ++p) {
+    if (p < P) {
+      const float t = num[p] + __shfl_xor(num[p], 32, kWave);
+      if (g == 0 && valid) prop[n * P + p] = zero_row ? 0.0f : t / den;
+    }
+  }
+}
+
 }  // namespace aura

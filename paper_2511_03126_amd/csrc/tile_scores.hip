@@ -218,6 +218,7 @@ struct TileScoreArgs {
 template <int DT, int MT>
 __global__ __launch_bounds__(256) void k_tile_scores(TileScoreArgs a, ObjTable tab) {
   __shared__ float ys[kScoreMaxK * kScoreMaxP];
+  __shared__ __attribute__((aligned(16))) float s_stage[4][score_stage_floats<16>()];
   if (a.prop) {
     for (int t = threadIdx.x; t < a.K * a.P; t += blockDim.x) ys[t] = a.y[t];
   }
@@ -271,8 +272,8 @@ __global__ __launch_bounds__(256) void k_tile_scores(TileScoreArgs a, ObjTable t
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] *= f;
-  if (!valid) return;
-  finish_scores<MT>(acc, n, g, a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label, a.unseen_zero != 0);
+  finish_scores_staged<MT, 16>(acc, ob.pt_begin + (long long)tile * kTilePts, min(kTilePts, ob.n_pts - tile * kTilePts), lane,
+                               a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label, a.unseen_zero != 0, s_stage[wave]);
 }
 
 // ------------------------------------------------------------------------------------ host
