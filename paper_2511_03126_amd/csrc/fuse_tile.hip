@@ -966,19 +966,24 @@ __device__ __forceinline__ float3 tile_point(const FuseArgs& a, const ObjRange& 
 // a set bit in the call's status word (TileWs::status), which the host can read back, so that wrong results never
 // go unnoticed.  The waiting waves look again as soon as the last look is back (no sleep in between: the meeting is
 // on the tile's critical path, and a look is one LDS read for all four flags).
+// The flags are reached through a pointer that says LDS.  Through a generic pointer these volatile accesses compile to
+// flat instructions, and a flat read is only complete when every global read of the wave in flight is too (the next
+// tile's points, depth texels): each look then cost a round trip to memory, some thousands of cycles per tile.
 constexpr unsigned kStatusMeetingMissed = 1u;
+typedef volatile int __attribute__((address_space(3))) * lds_flags;
 
 template <int NP>
-__device__ __forceinline__ void producers_meet(volatile int* flags, int w, int& seq, int lane, unsigned* status) {
+__device__ __forceinline__ void producers_meet(lds_flags flags, int w, int& seq, int lane, unsigned* status) {
   wave_sync();
   if constexpr (NP > 1) {
     ++seq;
     if (lane == 0) flags[w] = seq;
     static_assert(NP <= 4, "the four flags are read as one 16-byte vector");
     typedef int flags4 __attribute__((ext_vector_type(4)));
+    typedef const volatile flags4 __attribute__((address_space(3))) * lds_flags4;
     bool all = false;
     for (int spins = 0; spins < (1 << 16) && !all; ++spins) {
-      const flags4 f = *reinterpret_cast<const volatile flags4*>(flags);   // one LDS round trip per look
+      const flags4 f = *(lds_flags4)flags;   // one LDS round trip per look
       all = true;
 #pragma unroll
       for (int o = 0; o < NP; ++o) all = all && (f[o] - seq >= 0);
@@ -1034,7 +1039,7 @@ __device__ __forceinline__ void project_batch(const FuseArgs& a, const ObjRange&
 template <int DT, bool SEL, int NP>
 __device__ __forceinline__ void produce_tile(const FuseArgs& a, const ObjRange& ob, int blk,
                                              float3 pt, ProjectedBatch<NP>& pre, char* stage, int k_stage, int& dirty,
-                                             TileSlot* slot, ProducerScratch* sc, lds_floats cam_lds, volatile int* flags,
+                                             TileSlot* slot, ProducerScratch* sc, lds_floats cam_lds, lds_flags flags,
                                              unsigned* status, int w, int& seq, int lane) {
   constexpr int kTrips = kPBatch / 2 / NP;   // trips of one wave per batch of views
   const int p = lane & 31, h = lane >> 5;
@@ -1400,8 +1405,8 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       const float3 pt1 = tile_point(fa, ob, tile_of(t1), lane);
       project_batch<SEL, NP>(fa, ob, tile_of(t0), pt0, 0, cam_lds, w, lane, pre);
       if (t0 < len) {
-        produce_tile<DT, SEL, NP>(fa, ob, r0 + t0, pt0, pre, s_steps[0], kStage, dirty0, &s_slot[0], &s_sc, cam_lds, s_flags,
-                                  ws.status, w, seq, lane);
+        produce_tile<DT, SEL, NP>(fa, ob, r0 + t0, pt0, pre, s_steps[0], kStage, dirty0, &s_slot[0], &s_sc, cam_lds,
+                                  (lds_flags)&s_flags[0], ws.status, w, seq, lane);
       } else if (w == 0 && lane == 0) {
         s_slot[0].tile = -1;
         s_slot[0].nsteps = 0;
@@ -1419,7 +1424,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       const float3 pt_next = tile_point(fa, ob, tile_of(tn), lane);   // requested now, looked at after this tile is built
       if (t < len) {
         produce_tile<DT, SEL, NP>(fa, ob, r0 + t, pt, pre, s_steps[buf ^ 1], kStage, buf ? dirty0 : dirty1, &s_slot[buf ^ 1], &s_sc, cam_lds,
-                                  s_flags, ws.status, w, seq, lane);
+                                  (lds_flags)&s_flags[0], ws.status, w, seq, lane);
       } else if (w == 0 && lane == 0) {
         s_slot[buf ^ 1].tile = -1;
         s_slot[buf ^ 1].nsteps = 0;
