@@ -63,20 +63,28 @@ __device__ __forceinline__ float score_products_staged(const float* __restrict__
   const float* __restrict__ mine = row + g * 16;     // the lane's 16 channels of step s: mine + 32 s
   float ss = 0.0f;
   sc_bf16x8 stage[MT];
-  sc_f32x4 b[4], bn[4];
+  // The query rows are the stream from far memory, and with two waves per SIMD a compute unit has few of them in
+  // flight: the channels of step s + 2 are requested at the start of step s, into the third of three register sets that
+  // take turns (the loop is unrolled by three so that no set is copied while its reads are still on their way).
+  sc_f32x4 r0[4], r1[4], r2[4];
+  const int last = steps - 1;
+  auto fetch = [&](int s, sc_f32x4 (&r)[4]) {
+    const int sc = min(s, last);   // past the end: the last step again (read, not used)
+#pragma unroll
+    for (int q = 0; q < 4; ++q) r[q] = *reinterpret_cast<const sc_f32x4*>(mine + 32 * sc + 4 * q);
+  };
 #pragma unroll
   for (int u = 0; u < MT; ++u) s_a[threadIdx.x + 256 * u] = a_split[threadIdx.x + 256 * u];
-#pragma unroll
-  for (int q = 0; q < 4; ++q) b[q] = *reinterpret_cast<const sc_f32x4*>(mine + 4 * q);
+  fetch(0, r0);
+  fetch(1, r1);
   __syncthreads();
-  for (int s = 0; s < steps; ++s) {
+  auto step = [&](int s, const sc_f32x4 (&b)[4], sc_f32x4 (&ahead)[4]) {
     const sc_bf16x8* cur = s_a + (s & 1) * kBlock;
     sc_bf16x8* nxt = s_a + ((s + 1) & 1) * kBlock;
-    const int sn = min(s + 1, steps - 1);   // past the end: the last step again (read, not used)
+    const int sn = min(s + 1, last);
 #pragma unroll
     for (int u = 0; u < MT; ++u) stage[u] = a_split[(long long)sn * kBlock + threadIdx.x + 256 * u];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) bn[q] = *reinterpret_cast<const sc_f32x4*>(mine + 32 * sn + 4 * q);
+    fetch(s + 2, ahead);
     __builtin_amdgcn_sched_barrier(0);
     sc_bf16x8 bh[2], bl[2];
 #pragma unroll
@@ -103,9 +111,12 @@ __device__ __forceinline__ float score_products_staged(const float* __restrict__
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int u = 0; u < MT; ++u) nxt[threadIdx.x + 256 * u] = stage[u];
-#pragma unroll
-    for (int q = 0; q < 4; ++q) b[q] = bn[q];
     __syncthreads();   // the next step's operands are in place; everybody is done with this step's
+  };
+  for (int s = 0; s < steps; s += 3) {   // `steps` is uniform over the workgroup: every wave passes the same barriers
+    step(s, r0, r2);
+    if (s + 1 < steps) step(s + 1, r1, r0);
+    if (s + 2 < steps) step(s + 2, r2, r1);
   }
   return ss;
 }
