@@ -1575,7 +1575,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
         const bool words = (fa.vis_pitch & 3) == 0 && (reinterpret_cast<uintptr_t>(fa.out_vis) & 3) == 0;
         // who takes the first eight views, the next eight, ...: the last wave, the first, then the others, with the
         // second wave (which stores the scores where the workgroup has a scoring wave) at the end
-        const int turn = span == S - 1 ? 0 : (span == 0 ? 1 : (span == 1 ? S - 1 : span));
+        const int turn = S <= 2 ? span : (span == S - 1 ? 0 : (span == 0 ? 1 : (span == 1 ? S - 1 : span)));
         for (int v0 = 8 * turn; v0 < ob.n_views; v0 += 8 * S) {
           uint32_t wd[2] = {0u, 0u};
 #pragma unroll
@@ -1734,8 +1734,12 @@ static int one_kernel_producers(const FuseArgs& a, int k_stage, int quota, int v
 // Whether the one-kernel form of this launch can score its tiles itself: a scoring wave must fit the workgroup (at most
 // three product waves beside the four producers) and one matrix-core tile must hold the materials.
 static bool scoring_wave_fits(const FuseArgs& a, int producers, int product_waves) {
-  return producers == 4 && product_waves + 4 + 1 <= 8 && a.out_factor && a.scoring.G && a.scoring.Kpad == kScoreTileM &&
-         !a.in_mask;
+  // With one producer wave (two workgroups of up to four waves per compute unit) the scoring wave pays where no rows are
+  // stored (the single-pass call: C5 2.63 -> 2.45 ms): with rows the call is bound by their stores either way, and the
+  // separate scoring kernel keeps the fusion kernel shorter (C5 combined call 3.12 ms against 3.16 ms).
+  const bool fits = (producers == 4 && product_waves + 4 + 1 <= 8) ||
+                    (producers == 1 && product_waves + 1 + 1 <= 4 && a.fused == nullptr);
+  return fits && a.out_factor && a.scoring.G && a.scoring.Kpad == kScoreTileM && !a.in_mask;
 }
 
 template <int DT, int S, int H, int PF>
@@ -1761,11 +1765,13 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
     const TimingRequest timed = take_timing_request();
     if (timed.start) (void)hipEventRecord(timed.start, stream);
     if (scoring) {
-      if constexpr (S <= 3) {
-        pa.factor = nullptr;   // nobody reads the factors back
-        hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 4, true>), grid, block, 0, stream, a, pa, ws, keep, tab);
-        if (scored) *scored = true;
+      pa.factor = nullptr;   // nobody reads the factors back
+      if (np == 1) {
+        if constexpr (S <= 2) hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 1, true>), grid, block, 0, stream, a, pa, ws, keep, tab);
+      } else {
+        if constexpr (S <= 3) hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 4, true>), grid, block, 0, stream, a, pa, ws, keep, tab);
       }
+      if (scored) *scored = true;
     } else if (np == 1) {
       if (a.in_mask) hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, true, 1, false>), grid, block, 0, stream, a, pa, ws, keep, tab);
       else hipLaunchKernelGGL((k_tile_fused<DT, S, H, PF, false, 1, false>), grid, block, 0, stream, a, pa, ws, keep, tab);
