@@ -497,8 +497,8 @@ def measure(torch, s, name, steps, warmup, step="combined", flags=0, want_single
 def _make(job):
     """Scene generation in a worker process (numpy only; started before this process touches the GPU)."""
     from workloads.scenes import make_scene
-    name, order = job
-    return make_scene(name, order=order)
+    name, order = job[0], job[1]
+    return make_scene(name, order=order, overrides=dict(dtype=job[2]) if len(job) > 2 else None)
 
 
 def main():
@@ -529,7 +529,7 @@ def main():
     others = [] if args.only_headline else [w for w in ("c1", "c2", "c3", "c4") if w != args.workload]
     jobs = [(args.workload, "morton")] + [(w, "morton") for w in others]
     if not args.only_headline:
-        jobs += [("c2", "random"), ("c5", "random")]
+        jobs += [("c2", "random"), ("c5", "random"), ("c2", "morton", "f32")]
     with ProcessPoolExecutor(max_workers=min(len(jobs), 8), mp_context=multiprocessing.get_context("fork")) as pool:
         scenes = dict(zip(jobs, pool.map(_make, jobs)))
 
@@ -598,6 +598,12 @@ def main():
                 release(d)
                 stress[f"{w}_unsorted_{label}"] = {k: r[k] for k in ("workload", "order", "ms_per_step", "point_views_per_s",
                                                                      "calls_ms", "roofline", "tile_k_steps") if k in r}
+        # fp32 feature maps (or a channel count that is not a multiple of 256) take the per-point gather kernel: the
+        # matrix-core path needs 16-bit maps
+        r, d = measure(torch, scenes[("c2", "morton", "f32")], "c2 with fp32 maps", max(args.steps // 2, 5), 2, want_single_pass=False)
+        release(d)
+        stress["c2_fp32_maps_gather_kernel"] = {k: r[k] for k in ("workload", "ms_per_step", "point_views_per_s", "calls_ms",
+                                                                   "roofline") if k in r}
         out["stress"] = stress
     out["calibration"] = calibrate(torch)
     gc.enable()
