@@ -530,8 +530,11 @@ def main():
     jobs = [(args.workload, "morton")] + [(w, "morton") for w in others]
     if not args.only_headline:
         jobs += [("c2", "random"), ("c5", "random"), ("c2", "morton", "f32")]
-    with ProcessPoolExecutor(max_workers=min(len(jobs), 8), mp_context=multiprocessing.get_context("fork")) as pool:
-        scenes = dict(zip(jobs, pool.map(_make, jobs)))
+    try:
+        with ProcessPoolExecutor(max_workers=min(len(jobs), 8), mp_context=multiprocessing.get_context("fork")) as pool:
+            scenes = dict(zip(jobs, pool.map(_make, jobs)))
+    except (OSError, RuntimeError, ImportError):      # no worker processes to be had: one scene after the other
+        scenes = {job: _make(job) for job in jobs}
 
     import torch
     assert torch.cuda.is_available(), "bench.py needs a GPU"

@@ -390,3 +390,31 @@ def test_calibration_copy_and_fill_move_exactly_the_bytes_asked_for(H):
         torch.cuda.synchronize()
         assert (dst[16:16 + n].view(torch.int32) == 0x01020304).all()
         assert (dst[:16] == 0xAB).all() and (dst[16 + n:] == 0xAB).all()
+
+
+def test_timing_events_bracket_the_fusion_kernel_of_the_next_call_only(H):
+    """aura_time_next_fusion: the pair of events is recorded around the fusion kernel of the next fusion call of this thread
+    (one shot), on that call's stream; the time between them is a kernel's worth, and later calls leave the events alone."""
+    import paper_2511_03126_amd as aura
+    s = make_scene("c2", n_points=50_000)
+    d = H.DeviceScene(s)
+    d.step_combined()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record(); e1.record()                       # creates the handles
+    whole0, whole1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    aura.time_next_fusion(e0, e1)
+    whole0.record()
+    d.fuse_scores(with_vis=True)
+    whole1.record()
+    torch.cuda.synchronize()
+    inner, outer = e0.elapsed_time(e1), whole0.elapsed_time(whole1)
+    assert 0.005 < inner <= outer, (inner, outer)
+    d.fuse_scores(with_vis=True)                   # no request pending: the events keep what they recorded
+    torch.cuda.synchronize()
+    assert e0.elapsed_time(e1) == inner
+    aura.time_next_fusion(e0, e1)
+    aura.time_next_fusion(None, None)              # withdrawn
+    d.fuse_features()
+    torch.cuda.synchronize()
+    assert e0.elapsed_time(e1) == inner
