@@ -125,3 +125,32 @@ def test_on_fused_features_of_a_scene_and_full_size_sample(orc):
     print(_compare(gpu, ref, ws, s.y, sel=sel), flush=True)
     # a source is its own nearest neighbour
     assert (gpu["nn_idx"][src, 0] == np.arange(150)).all()
+
+
+def test_nan_and_inf_features_leave_the_other_queries_alone():
+    """A NaN in a query's features makes every comparison of the selection false; the call must still name sources
+    inside the source set for that query (it addresses their material vectors), and the queries beside it must get
+    exactly what they get without it.  Same for a source whose features hold a NaN: it is never selected."""
+    Nq, Ns, D, K, P, k = 700, 70, 96, 12, 2, 6
+    fq, fs, ws, y = _inputs(Nq, Ns, D, K, P, seed=77)
+    clean = _run_gpu(fq, fs, ws, y, k)
+    bad_q = np.array([0, 5, 31, 32, 333, 699])
+    fq2 = fq.copy()
+    fq2[bad_q[:3], 7] = np.nan
+    fq2[bad_q[3:5], :] = np.nan
+    fq2[bad_q[5], 3] = np.inf
+    print("\n[knn] NaN / inf rows among the queries", flush=True)
+    gpu = _run_gpu(fq2, fs, ws, y, k)
+    ok = np.ones(Nq, bool)
+    ok[bad_q] = False
+    for key in ("wq", "prop", "label", "nn_idx"):
+        assert np.array_equal(gpu[key][ok], clean[key][ok]), key
+    assert ((gpu["nn_idx"] >= 0) & (gpu["nn_idx"] < Ns)).all()
+    fs2 = fs.copy()
+    fs2[11, 5] = np.nan
+    print("[knn] a NaN among the sources", flush=True)
+    gpu = _run_gpu(fq, fs2, ws, y, k)
+    assert ((gpu["nn_idx"] >= 0) & (gpu["nn_idx"] < Ns)).all()
+    untouched = ~(clean["nn_idx"] == 11).any(1)
+    assert (gpu["nn_idx"][untouched] == clean["nn_idx"][untouched]).all()
+    assert np.array_equal(gpu["wq"][untouched], clean["wq"][untouched])
