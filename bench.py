@@ -278,6 +278,26 @@ def cpu_baseline(scene, seconds_target=15.0):
             "stage_seconds": {k: round(v, 3) for k, v in stages.items()}}
 
 
+def cpu_single_thread(scene, n=20000):
+    """The oracle on one host thread: the first n points of the smallest workload through the whole path."""
+    from oracle import aura_oracle as orc
+    s = scene
+    threads = orc.max_threads()
+    orc.set_threads(1)
+    try:
+        xyz = s.xyz[:n]
+        t0 = time.perf_counter()
+        fu = orc.fuse_features(s.cam, s.depth, s.feat, s.feat_dtype, xyz, tau=s.tau, z_near=s.z_near)
+        sc = orc.material_scores(fu["fused"], s.temb, s.y, T=s.temperature)
+        orc.property_integrate(sc["prop"], 0, fu["count"], vol_uniform=s.vol_uniform, xyz=xyz,
+                               grid_lo=None if s.G == 0 else s.grid_lo[:1], grid_h=None if s.G == 0 else s.grid_h[:1], G=s.G)
+        t = time.perf_counter() - t0
+    finally:
+        orc.set_threads(threads)
+    return {"value": len(xyz) * s.n_views / t, "unit": "point-views/s", "cores": 1,
+            "sample": f"first {len(xyz)} points of c1 x {s.n_views} views, fusion + scores + integration, {t:.2f} s"}
+
+
 CAL_BYTES = 256 << 20   # size of the calibration copy (read) and of its destination (write)
 
 
@@ -390,6 +410,23 @@ def back_to_back_ms(torch, call, n):
     return e0.elapsed_time(e1) / n
 
 
+def cold_call_ms(torch, call, n=5, flush_bytes=512 << 20):
+    """One call at a time behind a 512 MiB fill that pushes the call's inputs out of the last-level cache; the events
+    bracket the call only.  Median of n."""
+    from paper_2511_03126_amd import binding
+    junk = torch.empty(flush_bytes, dtype=torch.uint8, device="cuda")
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+    for a, b in pairs:
+        binding.calibration_fill(junk, 0)
+        a.record()
+        call()
+        b.record()
+    torch.cuda.synchronize()
+    del junk
+    t = sorted(a.elapsed_time(b) for a, b in pairs)
+    return t[len(t) // 2]
+
+
 def tile_steps(torch, d, s):
     """k-steps (16 feature cells each) per 32-point tile of the matrix-core fusion, read from the tile headers that the
     two-kernel form leaves in the workspace; None where the gather kernel runs."""
@@ -468,6 +505,7 @@ def measure(torch, s, name, steps, warmup, step="combined", flags=0, want_single
     if not extras:
         return out, d
     out["roofline"]["fuse_features_back_to_back_ms"] = back_to_back_ms(torch, d.fuse_features, max(steps, 10))
+    out["roofline"]["fuse_features_cold_ms"] = cold_call_ms(torch, d.fuse_features)   # the markers' cost is in this one
     ks = None if (flags & 4) else tile_steps(torch, d, s)     # (AURA_FUSE_GATHER: no tiles)
     if ks is not None:
         out["tile_k_steps"] = {k: ks[k] for k in ("tiles", "mean", "max", "fused_by_gather")}
@@ -609,9 +647,14 @@ def main():
                                                                    "roofline") if k in r}
         out["stress"] = stress
     out["calibration"] = calibrate(torch)
+    for r in [out] + out.get("configs", []):   # the same figure against what the plainest kernels reach on this machine
+        r["roofline"]["frac_of_copy_kernel"] = r["roofline"]["achieved"] / out["calibration"]["copy_GBps"]
+        r["roofline"]["frac_of_fill_kernel"] = r["roofline"]["achieved"] / out["calibration"]["fill_GBps"]
     gc.enable()
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(s)
+        if ("c1", "morton") in scenes:
+            out["cpu_baseline"]["single_thread_c1"] = cpu_single_thread(scenes[("c1", "morton")])
     print(json.dumps(out))
 
 

@@ -186,4 +186,47 @@ __device__ __forceinline__ void finish_scores_staged(const scores_f32x16 (&acc)[
   }
 }
 
+// What finish_scores_staged writes for 32 consecutive points whose similarities are all exactly +0 (a tile that no view
+// sees), without its exponentials: scores 0, label 0, and the properties Eq. 4 gives for equal similarities - the same
+// sums in the same order (every weight is expf(0 * inv_T) = 1, so a fused multiply-add by it is an addition), hence the
+// same bits - or zeros with unseen_zero.  All 64 lanes call this; the caller has checked that 0 * inv_T is 0.
+template <int MT>
+__device__ __forceinline__ void finish_zero_rows(long long n0, int rows, int lane, int K, int P, const float* __restrict__ ys,
+                                                 float* __restrict__ scores, float* __restrict__ prop, int* __restrict__ label,
+                                                 bool unseen_zero) {
+  const int pt = lane & 31, g = lane >> 5;
+  float* __restrict__ base = scores + n0 * K;
+  const long long total = (long long)rows * K;
+  if ((K & 3) == 0 && ((reinterpret_cast<uintptr_t>(base) & 15) == 0)) {
+    for (long long i = 4 * lane; i < total; i += 4 * kWave) *reinterpret_cast<scores_f32x4*>(base + i) = scores_f32x4{0.0f, 0.0f, 0.0f, 0.0f};
+  } else {
+    for (long long i = lane; i < total; i += kWave) base[i] = 0.0f;
+  }
+  if (label && g == 0 && pt < rows) label[n0 + pt] = 0;
+  if (!prop) return;
+  float den = 0.0f, num[kScoreMaxP];
+#pragma unroll
+  for (int p = 0; p < kScoreMaxP; ++p) num[p] = 0.0f;
+#pragma unroll
+  for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+      const int m = mt * kScoreTileM + 8 * (r / 4) + 4 * g + (r & 3);
+      if (m < K) {
+        den += 1.0f;
+#pragma unroll
+        for (int p = 0; p < kScoreMaxP; ++p)
+          if (p < P) num[p] = __builtin_fmaf(1.0f, ys[m * P + p], num[p]);
+      }
+    }
+  den += __shfl_xor(den, 32, kWave);
+#pragma unroll
+  for (int p = 0; p < kScoreMaxP; ++p) {
+    if (p < P) {
+      const float t = num[p] + __shfl_xor(num[p], 32, kWave);
+      if (g == 0 && pt < rows) prop[(n0 + pt) * P + p] = unseen_zero ? 0.0f : t / den;
+    }
+  }
+}
+
 }  // namespace aura

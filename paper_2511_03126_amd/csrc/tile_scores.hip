@@ -219,21 +219,24 @@ template <int DT, int MT>
 __global__ __launch_bounds__(256) void k_tile_scores(TileScoreArgs a, ObjTable tab) {
   __shared__ float ys[kScoreMaxK * kScoreMaxP];
   __shared__ __attribute__((aligned(16))) float s_stage[4][score_stage_floats<16>()];
-  if (a.prop) {
-    for (int t = threadIdx.x; t < a.K * a.P; t += blockDim.x) ys[t] = a.y[t];
-  }
-  __syncthreads();
-
   const ObjRange ob = tab.o[blockIdx.y];
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
   const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
   const int tile = blockIdx.x * 4 + wave;
-  if (tile >= nblk) return;
+  const int nsteps = tile < nblk ? a.hdr[ob.tile_begin + tile].nsteps : -1;
+  // Nothing to do here for a tile fused by a gather inside the fusion kernel (nsteps < 0: scored there as well) and for
+  // a tile that no view sees (k_tile_zero_rows writes its results); a workgroup of such tiles leaves at once.
+  const bool mine = nsteps > 0 || (nsteps == 0 && !(0.0f * a.inv_T == 0.0f));
+  if (!__syncthreads_or(mine)) return;
+  if (a.prop) {
+    for (int t = threadIdx.x; t < a.K * a.P; t += blockDim.x) ys[t] = a.y[t];
+  }
+  __syncthreads();
+  if (!mine) return;
   const int pt = lane & 31, g = lane >> 5;
   const int li = tile * kTilePts + pt;
   const bool valid = li < ob.n_pts;
   const long long n = ob.pt_begin + (valid ? li : ob.n_pts - 1);
-  const int nsteps = a.hdr[ob.tile_begin + tile].nsteps;
 
   ts_f32x16 acc[MT];
 #pragma unroll
@@ -241,7 +244,6 @@ __global__ __launch_bounds__(256) void k_tile_scores(TileScoreArgs a, ObjTable t
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
 
-  if (nsteps < 0) return;   // fused by a gather inside the fusion kernel, which scored the tile's points as well
   const TileStep* __restrict__ st = a.steps + (long long)(ob.tile_begin + tile) * a.quota;
   for (int s = 0; s < nsteps; ++s) {
     const ts_u32x4 w_hi = st[s].a_hi[lane], w_lo = st[s].a_lo[lane];
@@ -274,6 +276,28 @@ __global__ __launch_bounds__(256) void k_tile_scores(TileScoreArgs a, ObjTable t
     for (int r = 0; r < 16; ++r) acc[mt][r] *= f;
   finish_scores_staged<MT, 16>(acc, ob.pt_begin + (long long)tile * kTilePts, min(kTilePts, ob.n_pts - tile * kTilePts), lane,
                                a.K, a.P, a.inv_T, ys, a.scores, a.prop, a.label, a.unseen_zero != 0, s_stage[wave]);
+}
+
+// The tiles that no view sees (the inside of a solid: 9 of 10 tiles of a voxelised body): every similarity is +0 and the
+// result is known without the products and the exponentials - scores 0, label 0, the properties of Eq. 4 on equal
+// similarities.  A kernel of its own because it is nothing but stores and wants many waves in flight, while the scoring
+// kernel with 128 materials holds three waves per SIMD.  One wave per tile; workgroups without such a tile leave at once.
+template <int MT>
+__global__ __launch_bounds__(256) void k_tile_zero_rows(TileScoreArgs a, ObjTable tab) {
+  __shared__ float ys[kScoreMaxK * kScoreMaxP];
+  const ObjRange ob = tab.o[blockIdx.y];
+  const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int tile = blockIdx.x * 4 + wave;
+  const bool mine = tile < nblk && a.hdr[ob.tile_begin + (tile < nblk ? tile : 0)].nsteps == 0 && 0.0f * a.inv_T == 0.0f;
+  if (!__syncthreads_or(mine)) return;
+  if (a.prop) {
+    for (int t = threadIdx.x; t < a.K * a.P; t += blockDim.x) ys[t] = a.y[t];
+  }
+  __syncthreads();
+  if (!mine) return;
+  finish_zero_rows<MT>(ob.pt_begin + (long long)tile * kTilePts, min(kTilePts, ob.n_pts - tile * kTilePts), lane, a.K, a.P, ys,
+                       a.scores, a.prop, a.label, a.unseen_zero != 0);
 }
 
 // ------------------------------------------------------------------------------------ host
@@ -339,6 +363,13 @@ template <int DT>
 static hipError_t launch_ts(const TileScoreArgs& a, const ObjTable& tab, int n_obj, int max_pts, hipStream_t stream) {
   const int max_tiles = (max_pts + kTilePts - 1) / kTilePts;
   const dim3 grid((unsigned)((max_tiles + 3) / 4), (unsigned)n_obj), block(256);
+  switch (a.Kpad / 32) {
+    case 1: hipLaunchKernelGGL((k_tile_zero_rows<1>), grid, block, 0, stream, a, tab); break;
+    case 2: hipLaunchKernelGGL((k_tile_zero_rows<2>), grid, block, 0, stream, a, tab); break;
+    default: hipLaunchKernelGGL((k_tile_zero_rows<4>), grid, block, 0, stream, a, tab); break;
+  }
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
   switch (a.Kpad / 32) {
     case 1: hipLaunchKernelGGL((k_tile_scores<DT, 1>), grid, block, 0, stream, a, tab); break;
     case 2: hipLaunchKernelGGL((k_tile_scores<DT, 2>), grid, block, 0, stream, a, tab); break;

@@ -46,6 +46,7 @@ def test_full_path_matches_oracle_on_reduced_scenes(H, orc, name, kw):
     print(f"\n[{name} {kw}] N={s.N} V={s.n_views} B={s.B} D={s.D} K={s.K} dtype={s.feat_dtype}", flush=True)
     d = H.DeviceScene(s, want_uvz=True)
     ref = H.oracle_points(orc, s, want_uvz=True)
+    unseen_prop = None
     # one call per stage; fusion and scoring in one call; both again with the matrix-core fusion as two kernels
     # ... and the whole path in one call that writes no fused rows
     for step in (d.step, d.step_combined, d.step_two_kernels, d.step_combined_two_kernels, d.step_single_pass,
@@ -65,6 +66,16 @@ def test_full_path_matches_oracle_on_reduced_scenes(H, orc, name, kw):
         again = d.results()
         for k in ("vis", "count", "fused", "scores", "prop", "label", "mass", "n_used"):
             assert np.array_equal(gpu[k].view(np.uint8), again[k].view(np.uint8)), k
+        # A point that no view sees has similarities of exactly +0 whatever kernel scores it (the scoring kernel on a zero
+        # row, the tile kernels with or without their short cut for tiles that nothing sees): scores 0, label 0, and the
+        # properties of Eq. 4 on equal similarities, the same bits from every form of the step.
+        unseen = ref["count_fuse"] == 0
+        if unseen.any():
+            assert not gpu["scores"][unseen].any() and not gpu["label"][unseen].any()
+            if unseen_prop is None:
+                unseen_prop = gpu["prop"][unseen].copy()
+                assert (unseen_prop == unseen_prop[0]).all()
+            assert np.array_equal(gpu["prop"][unseen].view(np.uint8), unseen_prop.view(np.uint8)), step.__name__
 
 
 def _same_bits(a, b, keys):
