@@ -336,12 +336,19 @@ __global__ __launch_bounds__(kKnnThreads) void k_knn_densify(KnnArgs a) {
   if (a.nn_idx && g == 0 && valid) {
     for (int t = ke; t < a.k; ++t) a.nn_idx[n * a.k + t] = -1;
   }
-  if (fabsf(den) < 1e-12f) {   // no usable weights: the nearest source's vector
-    const float* __restrict__ src = a.ws + (long long)nearest * a.K;
+  if (fabsf(den) < 1e-12f) {   // no usable weights (a query without features, for one): the nearest source's vector
+    if (ws_in_lds) {
 #pragma unroll
-    for (int mt = 0; mt < MTK; ++mt)
+      for (int mt = 0; mt < MTK; ++mt)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) out[mt][r] = src[min(mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3), k_last)];
+        for (int r = 0; r < 16; ++r) out[mt][r] = s_ws[nearest * a.K + min(mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3), k_last)];
+    } else {
+      const float* __restrict__ src = a.ws + (long long)nearest * a.K;
+#pragma unroll
+      for (int mt = 0; mt < MTK; ++mt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[mt][r] = src[min(mt * 32 + 8 * (r >> 2) + 4 * g + (r & 3), k_last)];
+    }
   } else {
     const float inv_den = 1.0f / den;
 #pragma unroll
