@@ -61,7 +61,7 @@ def time_densify(torch, d, s, reps, n_sources=150, k=5):
     label = torch.empty_like(d.label)
     work = torch.empty(aura.workspace_bytes(binding.CALL_KNN_DENSIFY, D=s.D, Ns=ns), dtype=torch.uint8, device=d.dev)
     run = lambda: aura.knn_densify(d.fused, fs, ws, k, d.y, d.params, wq, prop, label, None, work)
-    for _ in range(KERNEL_WARMUP):
+    for _ in range(10):
         run()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
