@@ -26,8 +26,11 @@ namespace aura {
 
 constexpr int kKnnMaxK = 16;       // neighbours per query
 constexpr int kKnnMaxSources = 256;
-constexpr int kKnnWaves = 8;            // waves per workgroup
-constexpr int kKnnThreads = kKnnWaves * kWave;
+// Waves per workgroup.  The waves of a workgroup share the operand blocks and move in step with each other through the
+// barrier of every channel step: they select, and leave the memory system idle, at the same time.  Up to 160 sources
+// (blocks of 20 KB) two workgroups of four waves fit a compute unit and drift apart (200 000 queries, 150 sources: 0.270
+// against 0.287 ms with one workgroup of eight); beyond that one workgroup of eight, which fetches every block once.
+constexpr int knn_waves(int MT) { return MT <= 5 ? 4 : 8; }
 constexpr int kKnnLdsVectors = 6144;    // floats of LDS for the sources' material vectors [Ns][K]; larger sets are read from memory
 
 struct KnnArgs {
@@ -102,6 +105,7 @@ __device__ __forceinline__ float score_products_staged(const float* __restrict__
                                                        const sc_bf16x8* __restrict__ a_split, int lane,
                                                        sc_bf16x8* s_a, sc_f32x16 (&acc)[MT], bool work) {
   constexpr int kBlock = MT * 2 * 2 * kWave;         // 16-byte operand slots per macro step = 256 * MT
+  constexpr int kKnnThreads = knn_waves(MT) * kWave;
   constexpr int kCopies = (kBlock + kKnnThreads - 1) / kKnnThreads;   // 16-byte slots a thread copies per step
   constexpr int kGroups = 2 * MT;                    // (half j, tile mt) groups of a step, j-major: three products each
   constexpr int kPairs = (kGroups + 1) / 2;          // neighbouring groups: different accumulators whenever MT > 1
@@ -206,7 +210,8 @@ __device__ __forceinline__ float score_products_staged(const float* __restrict__
 
 // MT: tiles of 32 sources; MTK: tiles of 32 materials.
 template <int MT, int MTK, bool ROWS_ALIGNED>
-__global__ __launch_bounds__(kKnnThreads) void k_knn_densify(KnnArgs a) {
+__global__ __launch_bounds__(knn_waves(MT) * kWave) __attribute__((amdgpu_waves_per_eu(2))) void k_knn_densify(KnnArgs a) {
+  constexpr int kKnnWaves = knn_waves(MT);
   __shared__ float ys[kScoreMaxK * kScoreMaxP];
   __shared__ float s_ws[kKnnLdsVectors];                // the sources' material vectors, when they fit
   __shared__ float s_out[kKnnWaves * score_stage_floats<16>()];   // per wave: score rows on their way to memory
@@ -384,7 +389,8 @@ static hipError_t launch_knn(const KnnArgs& a, bool aligned, hipStream_t stream)
   KnnArgs b = a;
   b.n_ranges = (int)(a.n_tiles < cus ? a.n_tiles : cus);
   const long long longest = (a.n_tiles + b.n_ranges - 1) / b.n_ranges;   // tiles of the longest range
-  const dim3 grid((unsigned)(((longest + kKnnWaves - 1) / kKnnWaves) * b.n_ranges)), block(kKnnThreads);
+  constexpr int kKnnWaves = knn_waves(MT);
+  const dim3 grid((unsigned)(((longest + kKnnWaves - 1) / kKnnWaves) * b.n_ranges)), block(kKnnWaves * kWave);
   if (aligned)
     hipLaunchKernelGGL((k_knn_densify<MT, MTK, true>), grid, block, 0, stream, b);
   else
