@@ -112,6 +112,13 @@ __device__ __forceinline__ Tap tap_axis(float coord, float pitch, int size_grid)
   return t;
 }
 
+// exp(x) for the weights of Eq. 4 (x <= 0: a similarity minus the row's largest, over T): the hardware's base-2
+// exponential of x * log2(e).  Two instructions where the library routine takes about thirty; the product's rounding
+// costs a weight of exp(-20) a relative 2e-6 and the large weights nothing, far inside what Eq. 4 in fp32 holds anyway
+// (the epilogues of the scoring kernels spend most of their instructions here: 64 exponentials per lane with 128
+// materials).  exp(+0) is exactly 1.
+__device__ __forceinline__ float weight_exp(float x) { return __builtin_amdgcn_exp2f(x * 1.44269504088896340736f); }
+
 __device__ __forceinline__ float wave_sum(float x) {
 #pragma unroll
   for (int o = kWave / 2; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);

@@ -285,7 +285,7 @@ __device__ __forceinline__ void gather_tile(const FuseArgs& a, const ObjRange& o
       if (sc.prop) {
         float e[2];
 #pragma unroll
-        for (int h = 0; h < 2; ++h) e[h] = lane + 64 * h < sc.K ? expf((mine[h] - best) * sc.inv_T) : 0.0f;
+        for (int h = 0; h < 2; ++h) e[h] = lane + 64 * h < sc.K ? weight_exp((mine[h] - best) * sc.inv_T) : 0.0f;
         const float den = wave_sum(e[0] + e[1]);
         // all similarities exactly zero (nobody sees the point): zero properties where the caller asks for that
         const bool zero_row = sc.unseen_zero && __ballot((lane < sc.K && mine[0] != 0.0f) || (lane + 64 < sc.K && mine[1] != 0.0f)) == 0;

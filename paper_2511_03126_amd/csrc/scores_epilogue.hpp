@@ -67,7 +67,7 @@ __device__ __forceinline__ void finish_scores(const scores_f32x16 (&acc)[MT], lo
     for (int r = 0; r < 16; ++r) {
       const int m = mt * kScoreTileM + 8 * (r / 4) + 4 * g + (r & 3);
       if (m < K) {
-        const float e = expf((acc[mt][r] - best) * inv_T);
+        const float e = weight_exp((acc[mt][r] - best) * inv_T);
         den += e;
 #pragma unroll
         for (int p = 0; p < kScoreMaxP; ++p)
@@ -169,7 +169,7 @@ __device__ __forceinline__ void finish_scores_staged(const scores_f32x16 (&acc)[
     for (int r = 0; r < 16; ++r) {
       const int m = mt * kScoreTileM + 8 * (r / 4) + 4 * g + (r & 3);
       if (m < K) {
-        const float e = expf((acc[mt][r] - best) * inv_T);
+        const float e = weight_exp((acc[mt][r] - best) * inv_T);
         den += e;
 #pragma unroll
         for (int p = 0; p < kScoreMaxP; ++p)
@@ -188,7 +188,7 @@ __device__ __forceinline__ void finish_scores_staged(const scores_f32x16 (&acc)[
 
 // What finish_scores_staged writes for 32 consecutive points whose similarities are all exactly +0 (a tile that no view
 // sees), without its exponentials: scores 0, label 0, and the properties Eq. 4 gives for equal similarities - the same
-// sums in the same order (every weight is expf(0 * inv_T) = 1, so a fused multiply-add by it is an addition), hence the
+// sums in the same order (every weight is exp(0 * inv_T) = 1, so a fused multiply-add by it is an addition), hence the
 // same bits - or zeros with unseen_zero.  All 64 lanes call this; the caller has checked that 0 * inv_T is 0.
 template <int MT>
 __device__ __forceinline__ void finish_zero_rows(long long n0, int rows, int lane, int K, int P, const float* __restrict__ ys,
