@@ -349,17 +349,33 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
     // ---- A: project and test; bounding box of the touched cells per view
     PairRec pr[kNIT];
     int my_cnt = 0;
+    // All projections of the batch first, then all depth texels, then the tests: a thread's four pairs are four chains
+    // of camera row -> projection -> texel address -> texel, and in one loop each chain waited for the one before it
+    // (11 K of a tile's 26 K cycles with 32 views).
+    Proj pjs[kNIT];
+    bool frs[kNIT];
+    float deps[kNIT];
+#pragma unroll
+    for (int it = 0; it < kNIT; ++it) {
+      const int v = ob.view_begin + vb0 + min(it * kSlots + slot, nvb - 1);   // (a slot beyond the batch: its last view again)
+      pjs[it] = project(a.vis.cam + (long long)v * 16, px, py, pz);
+      frs[it] = in_frustum(a.vis, pjs[it]);
+    }
+#pragma unroll
+    for (int it = 0; it < kNIT; ++it) {
+      const int v = ob.view_begin + vb0 + min(it * kSlots + slot, nvb - 1);
+      deps[it] = 1.0f;
+      if (a.vis.depth) deps[it] = a.vis.depth[(long long)v * a.vis.H * a.vis.W + (frs[it] ? depth_texel(a.vis, pjs[it]) : 0)];
+    }
 #pragma unroll
     for (int it = 0; it < kNIT; ++it) {
       pr[it].xy = -1;
       pr[it].ax = pr[it].ay = 0.0f;
       if (it * kSlots >= nvb) continue;   // uniform
       const int vl = it * kSlots + slot;
-      const int v = ob.view_begin + vb0 + min(vl, nvb - 1);
-      const Proj pj = project(a.vis.cam + (long long)v * 16, px, py, pz);
-      const bool fr = in_frustum(a.vis, pj);
-      float dep = 1.0f;
-      if (a.vis.depth) dep = a.vis.depth[(long long)v * a.vis.H * a.vis.W + (fr ? depth_texel(a.vis, pj) : 0)];
+      const Proj pj = pjs[it];
+      const bool fr = frs[it];
+      const float dep = deps[it];
       bool seen = vl < nvb && p_valid && fr && (a.vis.frustum_only || passes_depth(a.vis, pj, dep));
       if constexpr (SEL) seen = seen && view_kept(a, ip, vb0 + min(vl, nvb - 1));
       s16x2 lo2 = {0x7fff, 0x7fff}, hi2 = {-1, -1};   // (x, y) of the first / second cell
@@ -467,24 +483,9 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
       }
       // entries that pad the last k-step point at a cell that exists (their weights are zero)
       if (tid >= Lc && tid < ksteps * kStepCells) s_cell[tid] = (uint32_t)((ob.view_begin + vb0) * Hf * Wf) * row_bytes;
-      {   // cells of the views with a map: thread = (view, four rows of the map)
-        const int vl = tid / 8;
-        if (vl < nvb && s_mode[vl] == 1) {
-          const int cell0 = (ob.view_begin + vb0 + vl) * Hf + s_win[vl][1], wx = s_win[vl][0];
-          for (int w = 4 * (tid % 8); w < 4 * (tid % 8) + 4; ++w) {
-            uint32_t bits = s_bits[vl][w];
-            int q = s_base[vl] + s_wbase[vl][w] - c0;
-            while (bits) {
-              const int b = __builtin_ctz(bits);
-              bits &= bits - 1;
-              if (q >= 0 && q < Lc) s_cell[q] = (uint32_t)((cell0 + w) * Wf + wx + b) * row_bytes;
-              ++q;
-            }
-          }
-        }
-      }
       __syncthreads();
-      // weights (and the cells of private entries) of every visible pair
+      // weights and cells of every visible pair (a cell that several points touch gets the same value from each of
+      // them; walking over the set bits of the maps instead kept a few threads busy for 4 K of a tile's 25 K cycles)
 #pragma unroll
       for (int it = 0; it < kNIT; ++it) {
         if (pr[it].xy < 0) continue;
@@ -502,6 +503,8 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
           for (int k = 0; k < 4; ++k) {
             const int b = on[k] ? bs[k] : bit;
             idx[k] = s_base[vl] + s_wbase[vl][b >> 5] + __popc(s_bits[vl][b >> 5] & ((1u << (b & 31)) - 1u)) - c0;
+            if (on[k] && idx[k] >= 0 && idx[k] < Lc)
+              s_cell[idx[k]] = (uint32_t)(((ob.view_begin + vb0 + vl) * Hf + y0 + (k >> 1)) * Wf + x0 + (k & 1)) * row_bytes;
           }
         } else {
           const int first = s_base[vl] + 4 * __popc(s_vmask[vl] & ((1u << p) - 1u)) - c0;
