@@ -35,8 +35,8 @@ def fuse_algorithmic_bytes(s):
 # HBM bytes per launch of the dominant kernel from the rocprofv3 counter runs summarised under profiles/ (FETCH_SIZE and
 # WRITE_SIZE, each scaled by the reading of the 256 MiB calibration copy in the same run), per workload.  Valid only for
 # the kernel source the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_BYTES = {'c5': 13704012030}
-TRAFFIC_SOURCE_SHA256 = "cc4530d5cc16bcb7663dd0f67e25b56351b1515b0f891b21eb5b31348bfeda79"
+TRAFFIC_BYTES = {'c5': 13703606816}
+TRAFFIC_SOURCE_SHA256 = "14950ec70f6dca2998c666df829baf7e36e527d6aaf05df6315ff8a438d325de"
 
 
 def measured_traffic(workload):
