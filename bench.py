@@ -61,8 +61,7 @@ def time_densify(torch, d, s, reps, n_sources=150, k=5):
     label = torch.empty_like(d.label)
     work = torch.empty(aura.workspace_bytes(binding.CALL_KNN_DENSIFY, D=s.D, Ns=ns), dtype=torch.uint8, device=d.dev)
     run = lambda: aura.knn_densify(d.fused, fs, ws, k, d.y, d.params, wq, prop, label, None, work)
-    for _ in range(10):
-        run()
+    clock_ramp(torch, [run], 50.0)   # the GPU has idled while the inputs were put together
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
@@ -176,8 +175,7 @@ def time_patches(torch, d, s, reps, M=150, k=3, R=224, half=False):
     aura.select_views(views, d.params, xyz, nrm, k, sel)
     out = torch.empty((M, k, 3, 3, R, R), dtype=torch.float16 if half else torch.float32, device=d.dev)
     run = lambda: aura.patch_batch(views.cam, images[:v1], xyz, sel, [20.0, 40.0, 60.0], out)
-    for _ in range(2):
-        run()
+    clock_ramp(torch, [run], 50.0)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(reps):
