@@ -350,7 +350,9 @@ aura_status_t aura_fuse_score_integrate(const aura_views_t* views, const aura_pa
  *   workspace [device] aura_workspace_bytes(AURA_CALL_KNN_DENSIFY, ...) bytes, 256-byte aligned
  * The similarities run on the matrix cores with each fp32 operand split into two bf16 terms (error of a
  * similarity near 1e-6), so which of two sources closer than that is "nearer" may differ from an exact
- * evaluation.
+ * evaluation.  A NaN among a query's features makes its similarities unordered: its outputs are then
+ * unspecified (its nn_idx entries still name sources of the set), the other queries are not affected; a source
+ * whose features hold a NaN is never selected.
  * Limits: 1 <= Ns <= 256, 1 <= k <= 16, 1 <= K <= 128, 1 <= P <= 8.
  * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_WORKSPACE, AURA_ERR_UNSUPPORTED, AURA_ERR_HIP.
  */
