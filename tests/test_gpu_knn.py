@@ -103,6 +103,16 @@ def test_special_cases(orc):
     # k = 1 returns the nearest source's vector (phi w / phi in fp32: to rounding)
     g1 = _run_gpu(fq, fs, ws, y, 1)
     assert np.allclose(g1["wq"][rows], ws[g1["nn_idx"][rows, 0]], rtol=1e-6, atol=0)
+    # the zero query again where the sources' vectors are too many for the kernel's on-chip copy (eight-wave workgroups,
+    # four tiles of materials)
+    fq, fs, ws, y = _inputs(300, 256, 64, 128, 2, seed=3)
+    fq[[0, 77, 299]] = 0.0
+    print("[knn] zero queries, 256 sources x 128 materials", flush=True)
+    gpu = _run_gpu(fq, fs, ws, y, 4)
+    ref = orc.knn_densify(fq, fs, ws, 4, y=y)
+    for i in (0, 77, 299):
+        assert list(gpu["nn_idx"][i]) == [0, 1, 2, 3] and np.allclose(gpu["wq"][i], ws[0], rtol=1e-6)
+    assert np.abs(gpu["wq"] - ref["wq"]).max() <= TOL * np.abs(ws).max()
 
 
 def test_on_fused_features_of_a_scene_and_full_size_sample(orc):
