@@ -259,6 +259,23 @@ def test_combined_call_scores_from_cell_similarities(H, orc, K, P, dtype):
     sep = d.results()
     assert np.abs(sep["scores"] - gpu["scores"]).max() <= 2e-5
     assert np.array_equal(sep["fused"].view(np.uint32), gpu["fused"].view(np.uint32))
+    # the same scene behind walls (every camera but the first blocked, the first keeps the lower half of its image):
+    # whole tiles that no view sees get their results from the kernel that only stores, for material counts that do
+    # and do not fill a 16-byte vector; the properties of unseen points carry the bits of the scoring kernel's epilogue
+    s.depth[1:] = 0.25
+    s.depth[0, : s.H // 2, :] = 0.25
+    d = H.DeviceScene(s)
+    ref = H.oracle_points(orc, s)
+    unseen = ref["count_fuse"] == 0
+    assert unseen.mean() > 0.5
+    d.step()
+    staged = d.results()
+    d.clear_outputs()
+    d.step_combined()
+    gpu = d.results()
+    print(H.compare_points(gpu, ref, s), flush=True)
+    assert not gpu["scores"][unseen].any() and not gpu["label"][unseen].any()
+    assert np.array_equal(gpu["prop"][unseen].view(np.uint32), staged["prop"][unseen].view(np.uint32))
 
 
 @pytest.mark.parametrize("K,P,D,dtype", [(1, 1, 512, "bf16"), (5, 3, 512, "f16"), (31, 8, 768, "bf16"), (32, 2, 768, "f16")])
