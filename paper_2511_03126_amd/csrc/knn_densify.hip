@@ -50,37 +50,35 @@ struct KnnArgs {
   int n_ranges;             // contiguous ranges of tiles (see the kernel)
 };
 
-__global__ __launch_bounds__(256) void k_source_norms(const float* __restrict__ fs, int Ns, int D, float* __restrict__ out) {
-  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-  const int j = blockIdx.x * 4 + wave;
-  if (j >= Ns) return;
-  float ss = 0.0f;
-  for (int c = lane; c < D; c += kWave) ss = __builtin_fmaf(fs[(long long)j * D + c], fs[(long long)j * D + c], ss);
-  ss = wave_sum(ss);
-  if (lane == 0) out[j] = ss > 0.0f ? 1.0f / sqrtf(ss) : 0.0f;
-}
-
 // The source features divided by their norms (a zero vector stays zero: similarity 0 to everything), split into
-// two bf16 terms in the operand order of scores_core.hpp.  One thread per (step, tile, half, lane).
-__global__ __launch_bounds__(256) void k_split_sources(const float* __restrict__ fs, const float* __restrict__ inv_norm, int Ns,
-                                                       int D, int MT, int steps, __bf16* __restrict__ out) {
-  const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (t >= (long long)steps * MT * 2 * kWave) return;
-  const int lane = t % kWave;
-  const int j = (t / kWave) % 2;
-  const int mt = (t / (kWave * 2)) % MT;
-  const int s = t / ((long long)kWave * 2 * MT);
-  const int m = mt * 32 + lane % 32, g = lane / 32;
-  const float scale = m < Ns ? inv_norm[m] : 0.0f;
-  __bf16* hi = out + ((((long long)(s * MT + mt) * 2 + j) * 2 + 0) * kWave + lane) * 8;
-  __bf16* lo = hi + kWave * 8;
+// two bf16 terms in the operand order of scores_core.hpp.  One wave per source slot (slots beyond Ns are zero): the
+// wave adds up the squares of its source's channels, then every lane writes the 8-channel pieces (step, half, lane
+// group) that the slot's operand lane holds.
+__global__ __launch_bounds__(256) void k_split_sources(const float* __restrict__ fs, int Ns, int D, int MT, int steps,
+                                                       __bf16* __restrict__ out) {
+  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
+  const int m = blockIdx.x * 4 + wave;
+  if (m >= MT * 32) return;
+  float scale = 0.0f;
+  if (m < Ns) {   // uniform over the wave
+    float ss = 0.0f;
+    for (int c = lane; c < D; c += kWave) ss = __builtin_fmaf(fs[(long long)m * D + c], fs[(long long)m * D + c], ss);
+    ss = wave_sum(ss);
+    scale = ss > 0.0f ? 1.0f / sqrtf(ss) : 0.0f;
+  }
+  const int mt = m / 32;
+  for (int piece = lane; piece < steps * 4; piece += kWave) {
+    const int g = piece & 1, j = (piece >> 1) & 1, s = piece >> 2;
+    __bf16* hi = out + ((((long long)(s * MT + mt) * 2 + j) * 2 + 0) * kWave + g * 32 + (m & 31)) * 8;
+    __bf16* lo = hi + kWave * 8;
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const int c = score_chan_of(s, j, g, e);
-    const float x = (m < Ns && c < D) ? fs[(long long)m * D + c] * scale : 0.0f;
-    const __bf16 h = (__bf16)x;
-    hi[e] = h;
-    lo[e] = (__bf16)(x - (float)h);
+    for (int e = 0; e < 8; ++e) {
+      const int c = score_chan_of(s, j, g, e);
+      const float x = (m < Ns && c < D) ? fs[(long long)m * D + c] * scale : 0.0f;
+      const __bf16 h = (__bf16)x;
+      hi[e] = h;
+      lo[e] = (__bf16)(x - (float)h);
+    }
   }
 }
 
@@ -413,15 +411,10 @@ hipError_t launch_knn_densify(const float* fq, long long Nq, int D, const float*
   const int MT = knn_source_tiles(Ns);
   char* base = static_cast<char*>(workspace);
   void* split = base;
-  float* inv_norm = reinterpret_cast<float*>(base + knn_round256(split_embeddings_bytes(D, MT)));
   const int steps = (D + kScoreStepK - 1) / kScoreStepK;
-  hipLaunchKernelGGL(k_source_norms, dim3((unsigned)((Ns + 3) / 4)), dim3(256), 0, stream, fs, Ns, D, inv_norm);
+  hipLaunchKernelGGL(k_split_sources, dim3((unsigned)(MT * 32 / 4)), dim3(256), 0, stream, fs, Ns, D, MT, steps,
+                     static_cast<__bf16*>(split));
   hipError_t e = hipGetLastError();
-  if (e != hipSuccess) return e;
-  const long long slots = (long long)steps * MT * 2 * kWave;
-  hipLaunchKernelGGL(k_split_sources, dim3((unsigned)((slots + 255) / 256)), dim3(256), 0, stream, fs, inv_norm, Ns, D, MT,
-                     steps, static_cast<__bf16*>(split));
-  e = hipGetLastError();
   if (e != hipSuccess) return e;
   KnnArgs a{fq, Nq, D, Ns, K, P, k, static_cast<const sc_bf16x8*>(split), steps, ws,
             y, 1.0f / temperature, wq, prop, label, nn_idx, (Nq + 31) / 32, 1};
