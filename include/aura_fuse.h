@@ -165,6 +165,11 @@ aura_status_t aura_workspace_bytes(int32_t call, const aura_sizes_t* sizes, size
  * still ends, the results of the call are not to be trusted, and bit 0 of this 32-bit word is set.  Every call clears
  * the word when it starts.  The library never copies to the host: a caller who wants the guarantee reads the word
  * (workspace + *offset, device memory) after the stream has passed the call; zero means nothing to report.
+ * The 32-bit word after it (workspace + *offset + 4) counts the tiles of 32 consecutive points whose list of touched
+ * feature cells outgrew its storage and which were therefore fused point by point inside the kernel: correct, but many
+ * times slower than either path at its best.  Spatially sorted points that are dense against the feature cells give
+ * 0 or a handful; a count near N / 32 says that the 32 points of a tile lie too far apart for this path (points not
+ * sorted, or far sparser than the cells): sort them (Morton order), or pass AURA_FUSE_GATHER.
  *   call  AURA_CALL_FUSE_FEATURES (also for aura_fuse_selected), AURA_CALL_FUSE_SCORES or AURA_CALL_FUSE_SCORE_INTEGRATE
  *   sizes as for aura_workspace_bytes     *present = 0: these sizes run kernels that have no such wait (no word)
  * Errors: AURA_ERR_NULL, AURA_ERR_SHAPE, AURA_ERR_DTYPE, AURA_ERR_UNSUPPORTED (another call).

@@ -203,16 +203,18 @@ def workspace_bytes(call: int, N: int = 0, B: int = 1, D: int = 1, K: int = 1, G
     return int(out.value)
 
 
-def fuse_status_word(call: int, views: "Views", N: int, workspace, B: int = 1, K: int = 1, P: int = 1, G: int = 0):
+def fuse_status_word(call: int, views: "Views", N: int, workspace, B: int = 1, K: int = 1, P: int = 1, G: int = 0,
+                     word: int = 0):
     """The status word that the fusion kernels of `call` keep in `workspace` (read back, which synchronises): 0 =
-    nothing to report; None where the sizes run kernels without one."""
+    nothing to report; None where the sizes run kernels without one.  word = 1: the word after it, the number of
+    tiles that were fused point by point because their cell lists outgrew their storage."""
     f = views.feat
     sz = _SizesT(N, B, f.shape[0], f.shape[1], f.shape[2], f.shape[3], _TORCH_DTYPE[f.dtype], K, G, 1, P)
     off, present = C.c_size_t(0), C.c_int32(0)
     _check(lib().aura_fuse_status_offset(call, C.byref(sz), C.byref(off), C.byref(present)), "aura_fuse_status_offset")
     if not present.value or workspace is None:
         return None
-    return int(workspace[off.value:off.value + 4].view(torch.int32).item())
+    return int(workspace[off.value + 4 * word:off.value + 4 * word + 4].view(torch.int32).item())
 
 
 def fuse_workspace_bytes(views: "Views", N: int, B: int = 1) -> int:

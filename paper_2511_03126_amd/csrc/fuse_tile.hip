@@ -337,7 +337,6 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
 
   if (tid < kTilePts) s_cnt[tid] = 0;
   if (blockIdx.x == 0 && tid < 8) ws.counters[(ws.obj_base + blockIdx.y) * 8 + tid] = 0u;   // for the product kernel
-  if (blockIdx.x == 0 && blockIdx.y == 0 && ws.obj_base == 0 && tid == 0) *ws.status = 0u;      // this form has nothing to report
   int used = 0;   // k-steps written so far (the view batches follow one another in the tile's run)
   bool exhausted = false;
 
@@ -546,7 +545,10 @@ void k_tile_prepare(FuseArgs a, TileWs ws, ObjTable tab) {
   }
   __syncthreads();
   if (exhausted) {
-    if (tid == 0) hdr->nsteps = -1;
+    if (tid == 0) {
+      hdr->nsteps = -1;
+      atomicAdd(ws.status + 1, 1u);   // second status word: tiles fused by the gather
+    }
     gather_tile<DT>(a, ob, li0, tid / kWave, kPrepThreads / kWave, lane);
     return;
   }
@@ -1256,6 +1258,7 @@ __device__ __forceinline__ void produce_tile(const FuseArgs& a, const ObjRange& 
   if (w == 0 && lane == 0) {
     slot->tile = blk;
     slot->nsteps = exhausted ? -1 : used;
+    if (exhausted) atomicAdd(status + 1, 1u);   // second status word: tiles fused by the gather
   }
   if (lane < kTilePts) slot->cnt[w][lane] = mine;
   dirty = used;   // the same in every producer wave
@@ -1671,7 +1674,10 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
 __global__ void k_clear_counters(unsigned* counters, int n, unsigned* status) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) counters[i] = 0u;
-  if (i == 0 && status) *status = 0u;
+  if (i == 0 && status) {
+    status[0] = 0u;
+    status[1] = 0u;
+  }
 }
 
 // ------------------------------------------------------------------------------------ host
@@ -1785,6 +1791,11 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
     const hipError_t e = hipGetLastError();
     if (timed.stop) (void)hipEventRecord(timed.stop, stream);
     return e;
+  }
+  if (ws.obj_base == 0) {   // the status words of the call (the prepare kernel clears its objects' ticket counters itself)
+    hipLaunchKernelGGL(k_clear_counters, dim3(1), dim3(64), 0, stream, pa.counters, 0, ws.status);
+    const hipError_t ec = hipGetLastError();
+    if (ec != hipSuccess) return ec;
   }
   const TimingRequest timed = take_timing_request();   // two kernels: the events go around the pair
   if (timed.start) (void)hipEventRecord(timed.start, stream);

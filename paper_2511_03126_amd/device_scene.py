@@ -153,8 +153,9 @@ class DeviceScene:
             t.fill_(-7)
         self.vis.fill_(9)      # uvz (debug output of aura_project_visibility alone) is left as it is
 
-    def status_words(self):
-        """The status words of the fusion workspaces that exist (all zero unless a kernel had something to report)."""
+    def status_words(self, word=0):
+        """The status words of the fusion workspaces that exist (all zero unless a kernel had something to report);
+        word = 1: the counts of tiles fused point by point."""
         s = self.scene
         out = {}
         for name, call, ws in (("fuse_features", binding.CALL_FUSE_FEATURES, self.ws_fuse),
@@ -162,7 +163,7 @@ class DeviceScene:
                                ("fuse_score_integrate", binding.CALL_FUSE_SCORE_INTEGRATE, self.ws_single)):
             if name not in self._ran:
                 continue
-            w = binding.fuse_status_word(call, self.views, s.N, ws, B=s.B, K=s.K, P=s.P, G=s.G)
+            w = binding.fuse_status_word(call, self.views, s.N, ws, B=s.B, K=s.K, P=s.P, G=s.G, word=word)
             if w is not None:
                 out[name] = w
         return out

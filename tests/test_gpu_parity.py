@@ -348,6 +348,19 @@ def test_unsorted_points_on_the_matrix_core_path(H, orc, name, kw):
     nseg = d.ws_fuse[:ntile * 144].cpu().numpy().view(np.int32).reshape(ntile, 36)[:, 0]
     print(f"tiles {ntile}, fused by the in-kernel gather {int((nseg < 0).sum())}", flush=True)
     assert (nseg < 0).any() and ((nseg > 0).any() or name != "c3")
+    # the count of such tiles that every fusion call leaves beside its status word: the two-kernel call just made ...
+    assert d.status_words(word=1)["fuse_features"] == int((nseg < 0).sum())
+    # ... and the one-kernel form (its on-chip tile buffers hold another number of k-steps than the workspace quota, so
+    # its count differs); a sorted scene of the same size reports none or a handful
+    d.fuse_features()
+    one = d.status_words(word=1)["fuse_features"]
+    assert 0 < one <= ntile or name == "c5"
+    if name != "c3":   # (the reduced c3 scene is sparse against its pixel-sized cells: long lists even when sorted)
+        ds = H.DeviceScene(make_scene(name, **kw))
+        ds.fuse_features()
+        ds.fuse_features(two_kernels=True)
+        torch.cuda.synchronize()
+        assert ds.status_words(word=1)["fuse_features"] <= max(2, ntile // 50)
 
 
 def test_flags_and_degenerate_inputs(H, orc):
