@@ -1767,10 +1767,18 @@ static hipError_t launch_tile(const FuseArgs& a, const TileWs& ws, const ObjTabl
     // with one producer wave two workgroups fit a compute unit, with four one; several objects in one launch share
     // the machine
     const int groups_max = np == 1 ? kFusedGroupsMax : kFusedGroupsMax / 2;
-    const int groups = std::max(kXcd, std::min(max_tiles, (groups_max / n_obj + kXcd - 1) / kXcd * kXcd));
     const bool scoring = scoring_wave_fits(a, np, S);
-    const dim3 grid(std::min(groups, max_tiles), n_obj), block(kWave * (S + np + (scoring ? 1 : 0)));
     const int keep = a.out_factor != nullptr && !scoring;   // the scoring kernel follows and reads the k-steps
+    // Several objects in one launch: many more workgroups per object than are resident at a time.  The workgroups of
+    // an object share its tiles through the per-XCD tickets and are dispatched object after object, so the machine
+    // works on a few objects at a time - their depth and feature maps stay in L2, where with eight workgroups per object
+    // all 64 objects of a launch were in progress at once - and no workgroup is left with a fixed share of one object
+    // while others have run out (64 objects of 100 000 points and 4 views: the workgroups' end times were spread over
+    // the last quarter of the kernel; fusion call 2.79 -> 2.33 ms with 256 workgroups per object, the combined call,
+    // whose workgroups also write the k-steps for the scoring kernel, 3.10 -> 2.94 ms with 64 and slower beyond).
+    const int per_object = n_obj > 1 ? ((keep || scoring) ? 64 : 256) : 0;
+    const int groups = std::max(kXcd, std::min(max_tiles, std::max((groups_max / n_obj + kXcd - 1) / kXcd * kXcd, per_object)));
+    const dim3 grid(std::min(groups, max_tiles), n_obj), block(kWave * (S + np + (scoring ? 1 : 0)));
     const TimingRequest timed = take_timing_request();
     if (timed.start) (void)hipEventRecord(timed.start, stream);
     if (scoring) {
