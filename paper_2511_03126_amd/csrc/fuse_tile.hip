@@ -1361,8 +1361,12 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
   const int groups = min(nblk, (int)gridDim.x);
   if ((int)blockIdx.x >= groups) return;
-  const int xcd = blockIdx.x % kXcd, per = nblk / kXcd, rem = nblk % kXcd;
-  const int r0 = xcd * per + min(xcd, rem), len = per + (xcd < rem ? 1 : 0);
+  // the XCD's tiles: chunks of consecutive tiles taken in turn by the eight XCDs, as in k_tile_product
+  const int xcd = blockIdx.x % kXcd;
+  const int sh = 31 - __builtin_clz(max(1, min(64, nblk / (8 * kXcd))));
+  const int chunk = 1 << sh, round_tiles = chunk * kXcd;
+  const int len = (nblk / round_tiles) * chunk + min(max(nblk % round_tiles - xcd * chunk, 0), chunk);
+  auto tile_at = [&](int t) { return ((((t >> sh) * kXcd + xcd) << sh) | (t & (chunk - 1))); };
   unsigned* __restrict__ ctr = a.counters + blockIdx.y * kXcd + xcd;
 
   const int tid = threadIdx.x, lane = tid % kWave;
@@ -1407,7 +1411,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
     __syncthreads();   // camera rows, the first plans and the meeting flags are in LDS
     const int last_tile = nblk - 1;
     // a plan past the end reads (and projects) a tile that exists; it is never built
-    auto tile_of = [&](int t) { return min(r0 + t, last_tile); };
+    auto tile_of = [&](int t) { return min(tile_at(t), last_tile); };
     ProjectedBatch<NP> pre;
     int dirty0 = kStage, dirty1 = kStage;   // k-steps of each stage buffer that may hold non-zero weights
     float3 pt;   // the lane's point of the tile that the next trip builds
@@ -1417,7 +1421,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       const float3 pt1 = tile_point(fa, ob, tile_of(t1), lane);
       project_batch<SEL, NP>(fa, ob, tile_of(t0), pt0, 0, cam_lds, w, lane, pre);
       if (t0 < len) {
-        produce_tile<DT, SEL, NP>(fa, ob, r0 + t0, pt0, pre, s_steps[0], kStage, dirty0, &s_slot[0], &s_sc, cam_lds,
+        produce_tile<DT, SEL, NP>(fa, ob, tile_at(t0), pt0, pre, s_steps[0], kStage, dirty0, &s_slot[0], &s_sc, cam_lds,
                                   (lds_flags)&s_flags[0], ws.status, w, seq, lane);
       } else if (w == 0 && lane == 0) {
         s_slot[0].tile = -1;
@@ -1435,7 +1439,7 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
       const int t = s_plan[k & 3], tn = s_plan[(k + 1) & 3];
       const float3 pt_next = tile_point(fa, ob, tile_of(tn), lane);   // requested now, looked at after this tile is built
       if (t < len) {
-        produce_tile<DT, SEL, NP>(fa, ob, r0 + t, pt, pre, s_steps[buf ^ 1], kStage, buf ? dirty0 : dirty1, &s_slot[buf ^ 1], &s_sc, cam_lds,
+        produce_tile<DT, SEL, NP>(fa, ob, tile_at(t), pt, pre, s_steps[buf ^ 1], kStage, buf ? dirty0 : dirty1, &s_slot[buf ^ 1], &s_sc, cam_lds,
                                   (lds_flags)&s_flags[0], ws.status, w, seq, lane);
       } else if (w == 0 && lane == 0) {
         s_slot[buf ^ 1].tile = -1;
