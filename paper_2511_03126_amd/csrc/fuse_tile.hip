@@ -729,6 +729,32 @@ __device__ __forceinline__ void open_tile(const char* sb, int n_staged, const ch
   lds_a(sb, 0, lane, wa[0]);
 }
 
+// Which of an object's tiles an XCD works on, in the order of its tickets.  The tiles go to the XCDs in chunks of
+// consecutive tiles taken in turn (ticket t of XCD x is tile ((t / chunk) * 8 + x) * chunk + t % chunk): neighbouring
+// tiles still meet in one L2, and every XCD gets a sample of the whole object instead of one contiguous eighth, whose
+// k-steps per tile can differ (1 M points on six ellipsoids, 32 views: the eighths finished between 665 and 775 us).
+// The tiles behind the last whole round of chunks are split into eight contiguous parts, so that the XCDs' shares
+// differ by one tile at most and the first XCDs hold the larger ones (handed out as whole chunks, 6250 tiles gave two XCDs 832 and 810 tiles and the others 768).
+struct XcdTiles {
+  int sh, xcd_sh, full, rest_at, len;   // chunk = 2^sh; tickets below `full` are chunked, the others contiguous
+  __device__ XcdTiles(int nblk, int xcd) {
+    sh = 31 - __builtin_clz(max(1, min(64, nblk / (8 * kXcd))));   // chunk = 2^sh tiles: 64, fewer for small objects
+    const int rounds = nblk >> (sh + 3);                            // kXcd = 8 chunks per round
+    static_assert(kXcd == 8, "rounds of eight chunks");
+    full = rounds << sh;
+    const int base = rounds << (sh + 3), rest = nblk - base;
+    // XCD x takes rest / 8 of them and one more while x < rest % 8: an object of fewer than eight tiles has workgroups on
+    // its first XCDs only
+    const int q = rest >> 3, extra = rest & 7;
+    rest_at = base + xcd * q + min(xcd, extra) - full;
+    len = full + q + (xcd < extra ? 1 : 0);
+    xcd_sh = xcd << sh;
+  }
+  __device__ int at(int t) const {
+    return t < full ? ((((t >> sh) * kXcd) << sh) + xcd_sh + (t & ((1 << sh) - 1))) : rest_at + t;
+  }
+};
+
 template <int DT, int S, int H, int PF>
 __global__ __launch_bounds__(kWave* S) __attribute__((amdgpu_waves_per_eu(H == 1 ? 3 : 2, H == 1 ? 3 : 2)))
 void k_tile_product(ProdArgs a, ObjTable tab) {
@@ -742,15 +768,11 @@ void k_tile_product(ProdArgs a, ObjTable tab) {
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
   const int groups = min(nblk, (int)gridDim.x);   // workgroups that work on this object
   if ((int)blockIdx.x >= groups) return;
-  // The XCD's tiles and its counter.  The object's tiles go to the XCDs in chunks of consecutive tiles taken in turn
-  // (ticket t of XCD x is tile ((t / chunk) * 8 + x) * chunk + t % chunk): neighbouring tiles still meet in one L2, and
-  // every XCD gets a sample of the whole object instead of one contiguous eighth, whose k-steps per tile can differ
-  // (1 M points on six ellipsoids, 32 views: the eighths finished between 665 and 775 us).
+  // The XCD's tiles and its counter (see XcdTiles: chunks of consecutive tiles taken in turn by the XCDs).
   const int xcd = blockIdx.x % kXcd;
-  const int sh = 31 - __builtin_clz(max(1, min(64, nblk / (8 * kXcd))));   // chunk = 2^sh tiles: 64, fewer for small objects
-  const int chunk = 1 << sh, round_tiles = chunk * kXcd;
-  const int len = (nblk / round_tiles) * chunk + min(max(nblk % round_tiles - xcd * chunk, 0), chunk);
-  auto tile_at = [&](int t) { return ((((t >> sh) * kXcd + xcd) << sh) | (t & (chunk - 1))); };
+  const XcdTiles mine(nblk, xcd);
+  const int len = mine.len;
+  auto tile_at = [&](int t) { return mine.at(t); };
   unsigned* __restrict__ ctr = a.counters + blockIdx.y * kXcd + xcd;
   const TileHdr* __restrict__ hdrs = a.hdr + ob.tile_begin;
 
@@ -1361,12 +1383,10 @@ void k_tile_fused(FuseArgs fa, ProdArgs a, TileWs ws, int keep, ObjTable tab) {
   const int nblk = (ob.n_pts + kTilePts - 1) / kTilePts;
   const int groups = min(nblk, (int)gridDim.x);
   if ((int)blockIdx.x >= groups) return;
-  // the XCD's tiles: chunks of consecutive tiles taken in turn by the eight XCDs, as in k_tile_product
   const int xcd = blockIdx.x % kXcd;
-  const int sh = 31 - __builtin_clz(max(1, min(64, nblk / (8 * kXcd))));
-  const int chunk = 1 << sh, round_tiles = chunk * kXcd;
-  const int len = (nblk / round_tiles) * chunk + min(max(nblk % round_tiles - xcd * chunk, 0), chunk);
-  auto tile_at = [&](int t) { return ((((t >> sh) * kXcd + xcd) << sh) | (t & (chunk - 1))); };
+  const XcdTiles mine(nblk, xcd);
+  const int len = mine.len;
+  auto tile_at = [&](int t) { return mine.at(t); };
   unsigned* __restrict__ ctr = a.counters + blockIdx.y * kXcd + xcd;
 
   const int tid = threadIdx.x, lane = tid % kWave;
