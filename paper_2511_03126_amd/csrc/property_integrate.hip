@@ -12,7 +12,8 @@
 // All traffic is a few bytes per point plus one sweep over the voxel arrays: the call is a small
 // fraction of the fusion pass and is bound by launch latency for small inputs.  Grid mode is four
 // launches: (1) zero the voxel arrays and take the largest |prop| per slice of points, (2) bin,
-// (3) per-voxel means summed per slice of voxels, (4) the slices added in a fixed order.
+// (3) per-voxel means summed per slice of voxels, (4) the slices added in a fixed order; with more than 1024 slices of
+// points a one-workgroup launch between (1) and (2) reduces the per-slice maxima to one word.
 #include "aura_device.hpp"
 #include "launch.hpp"
 
@@ -21,6 +22,7 @@ namespace aura {
 constexpr int kMassBlock = 256;
 constexpr int kMassPtsPerBlock = 512;    // slice of points summed by one workgroup
 constexpr int kVoxPerBlock = 2048;       // slice of voxels summed by one workgroup
+constexpr int kAbsmaxPerGroup = 1024;    // up to this many slices of points every workgroup takes their maximum itself
 
 struct MassObjDev {
   long long pt_begin;
@@ -47,6 +49,7 @@ struct MassArgs {
   long long* part_used;    // [total slices]
   unsigned* absmax_part;   // [slices of points]: largest |prop| bits per slice (grid mode)
   int n_absmax;            // number of valid entries of absmax_part
+  const unsigned* absmax_call;   // their maximum, where k_mass_absmax has taken it (many slices); else null
   long long* vox_sum;      // [B * G^3] fixed point
   int* vox_cnt;            // [B * G^3]
   int obj_base;            // index of the table's first object within the call
@@ -107,6 +110,7 @@ __global__ __launch_bounds__(kMassBlock) void k_mass_points(MassArgs a, MassTabl
 // workgroup (x, object) with x below the object's slice count also writes the largest |prop| over the used
 // points of its slice, as the bit pattern of a non-negative float (monotone), into its slot.
 typedef uint32_t mass_u32x4 __attribute__((ext_vector_type(4)));
+typedef int mass_i32x4 __attribute__((ext_vector_type(4)));
 
 __global__ __launch_bounds__(kMassBlock) void k_mass_prepare(MassArgs a, MassTable tab, uint32_t* zero_from, long long zero_vecs) {
   {
@@ -137,8 +141,11 @@ __global__ __launch_bounds__(kMassBlock) void k_mass_prepare(MassArgs a, MassTab
   }
 }
 
-// Largest |prop| of the call from the per-slice maxima (every workgroup that needs the scale does this).
+// Largest |prop| of the call from the per-slice maxima.  With few slices every workgroup that needs the scale takes it
+// from them; with many, k_mass_absmax has done that once (64 objects of 100 000 points: 12 544 slices, which each of
+// the 12 544 + 8 192 workgroups of the two kernels below read in 49 trips - more than their own work).
 __device__ __forceinline__ unsigned call_absmax(const MassArgs& a, unsigned* sh) {
+  if (a.absmax_call) return *a.absmax_call;   // the same for every thread of the launch
   unsigned m = 0;
   for (int j = threadIdx.x; j < a.n_absmax; j += kMassBlock) m = max(m, a.absmax_part[j]);
 #pragma unroll
@@ -149,6 +156,12 @@ __device__ __forceinline__ unsigned call_absmax(const MassArgs& a, unsigned* sh)
 #pragma unroll
   for (int w = 1; w < kMassBlock / kWave; ++w) m = max(m, sh[w]);
   return m;
+}
+
+__global__ __launch_bounds__(kMassBlock) void k_mass_absmax(MassArgs a, unsigned* out) {
+  __shared__ unsigned shm[kMassBlock / kWave];
+  const unsigned m = call_absmax(a, shm);
+  if (threadIdx.x == 0) *out = m;
 }
 
 // Power-of-two scale s with |x| * 2^s * (number of points) < 2^62 for every used x.
@@ -223,11 +236,24 @@ __global__ __launch_bounds__(kMassBlock) void k_mass_voxels(MassArgs a, MassTabl
   const int shift = fixed_point_shift(call_absmax(a, shm), a.n_points_bits);
   double s = 0.0;
   long long used = 0;
-  for (long long j = begin + threadIdx.x; j < end; j += kMassBlock) {
-    const int c = a.vox_cnt[vox0 + j];
-    if (c > 0) {
-      s += ldexp((double)a.vox_sum[vox0 + j], -shift) / (double)c;
-      used += c;
+  // a thread takes four consecutive voxels per trip: their counts in one 16-byte read, the sums of the occupied ones only
+  // (the points of a surface occupy a few percent of a 64^3 grid)
+  for (long long j = begin + 4 * threadIdx.x; j < end; j += 4 * kMassBlock) {
+    const int* __restrict__ cp = a.vox_cnt + vox0 + j;
+    int c[4];
+    if (j + 4 <= end && (reinterpret_cast<uintptr_t>(cp) & 15) == 0) {
+      const mass_i32x4 v = *reinterpret_cast<const mass_i32x4*>(cp);
+      c[0] = v[0], c[1] = v[1], c[2] = v[2], c[3] = v[3];
+    } else {
+#pragma unroll
+      for (int e = 0; e < 4; ++e) c[e] = j + e < end ? cp[e] : 0;
+    }
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (c[e] > 0) {
+        s += ldexp((double)a.vox_sum[vox0 + j + e], -shift) / (double)c[e];
+        used += c[e];
+      }
     }
   }
   s = block_sum(s, shd);
@@ -276,7 +302,7 @@ size_t integrate_workspace_bytes(long long N, int B, int G) {
   bytes += align256((size_t)max_slices(N, B, G) * sizeof(long long));
   if (G > 0) {
     size_t vox = (size_t)B * G * G * G;
-    bytes += align256((size_t)(slices_points(N) + B) * sizeof(unsigned));                       // per-slice maxima
+    bytes += align256((size_t)(slices_points(N) + B + 1) * sizeof(unsigned));                   // per-slice maxima, their maximum
     bytes += align256(vox * sizeof(long long)) + align256(vox * sizeof(int));
   }
   return bytes;
@@ -298,7 +324,7 @@ hipError_t launch_property_integrate(const float* prop, int P, int p_index, cons
   const size_t vox = G > 0 ? (size_t)B * G * G * G : 0;
   size_t zero_begin = 0, zero_end = 0;   // the voxel sums and the voxel counts must start at zero
   if (G > 0) {
-    a.absmax_part = reinterpret_cast<unsigned*>(ws + off); off += align256((size_t)(slices_points(N) + B) * sizeof(unsigned));
+    a.absmax_part = reinterpret_cast<unsigned*>(ws + off); off += align256((size_t)(slices_points(N) + B + 1) * sizeof(unsigned));
     zero_begin = off;
     a.vox_sum = reinterpret_cast<long long*>(ws + off); off += align256(vox * sizeof(long long));
     a.vox_cnt = reinterpret_cast<int*>(ws + off);       off += align256(vox * sizeof(int));
@@ -314,6 +340,13 @@ hipError_t launch_property_integrate(const float* prop, int P, int p_index, cons
   const int n_passes = G > 0 ? 4 : 2;
   for (int pass = 0; pass < n_passes; ++pass) {
     int pt_cursor = 0, vox_cursor = 0;
+    if (G > 0 && pass == 1 && a.n_absmax > kAbsmaxPerGroup) {   // the slot behind the last per-slice maximum
+      unsigned* out = a.absmax_part + (slices_points(N) + B);
+      hipLaunchKernelGGL(k_mass_absmax, dim3(1), dim3(kMassBlock), 0, stream, a, out);
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      a.absmax_call = out;
+    }
     for (int c = 0; c < n_chunks; ++c) {
       MassTable tab{};
       const int obj_base = c * kMaxObjPerLaunch;

@@ -418,6 +418,36 @@ def test_point_volume_mode_with_per_point_volumes_and_objects(H, orc):
     assert np.allclose(mass.cpu().numpy(), ref["mass"], rtol=1e-5, atol=0)
 
 
+@pytest.mark.parametrize("N", [300_000, 700_000])
+def test_grid_mode_with_few_and_with_many_slices_of_points(H, orc, N):
+    """Grid mode of Sec. 3.4.2 on random points in three objects: the fixed-point scale comes from the largest |prop|
+    of the call, which the library takes per workgroup for up to 1024 slices of 512 points and once per call beyond
+    (700 000 points: 1369 slices).  Counts exact, mass within fp32 rounding of the oracle's fp64 result."""
+    import paper_2511_03126_amd as aura
+    from paper_2511_03126_amd import binding
+    rng = np.random.default_rng(N)
+    P, G, B = 2, 32, 3
+    prop = rng.uniform(200, 8000, (N, P)).astype(np.float32)
+    prop[N // 2, 1] = 65000.0     # the call's maximum sits in one slice
+    xyz = rng.uniform(-0.5, 0.5, (N, 3)).astype(np.float32)
+    count = rng.integers(0, 3, N).astype(np.int32)
+    off = np.array([0, 1000, N // 3, N], np.int64)
+    lo = np.full((B, 3), -0.5, np.float32)
+    h = np.full(B, 1.0 / G, np.float32)
+    dev = "cuda:0"
+    ws = torch.empty(aura.workspace_bytes(binding.CALL_PROPERTY_INTEGRATE, N=N, B=B, G=G), dtype=torch.uint8, device=dev)
+    mass = torch.empty(B, device=dev); used = torch.empty(B, dtype=torch.int64, device=dev)
+    t = lambda a: torch.from_numpy(a).to(dev)
+    print(f"\n[mass grid] N={N} B={B} G={G}", flush=True)
+    for _ in range(2):   # the second call finds the workspace as the first left it
+        aura.property_integrate(t(prop), mass, p_index=1, count=t(count), pt_offsets=off, xyz=t(xyz), grid_lo=lo,
+                                grid_h=h, G=G, n_used=used, workspace=ws)
+        torch.cuda.synchronize()
+        ref = orc.property_integrate(prop.astype(np.float64), 1, count, pt_offsets=off, xyz=xyz, grid_lo=lo, grid_h=h, G=G)
+        assert np.array_equal(used.cpu().numpy(), ref["n_used"])
+        assert np.allclose(mass.cpu().numpy(), ref["mass"], rtol=2e-6, atol=0)
+
+
 def test_calibration_copy_and_fill_move_exactly_the_bytes_asked_for(H):
     from paper_2511_03126_amd import binding
     for n in (16, 4096 + 16, 3 * 1024 * 1024 + 48, 64 * 1024 * 1024):
