@@ -158,10 +158,27 @@ __device__ __forceinline__ unsigned call_absmax(const MassArgs& a, unsigned* sh)
   return m;
 }
 
-__global__ __launch_bounds__(kMassBlock) void k_mass_absmax(MassArgs a, unsigned* out) {
-  __shared__ unsigned shm[kMassBlock / kWave];
-  const unsigned m = call_absmax(a, shm);
-  if (threadIdx.x == 0) *out = m;
+constexpr int kAbsmaxBlock = 1024;
+
+__global__ __launch_bounds__(kAbsmaxBlock) void k_mass_absmax(MassArgs a, unsigned* out) {
+  __shared__ unsigned shm[kAbsmaxBlock / kWave];
+  unsigned m = 0;
+  const int n4 = a.n_absmax / 4;   // the array starts on a 256-byte boundary
+  const mass_u32x4* __restrict__ p4 = reinterpret_cast<const mass_u32x4*>(a.absmax_part);
+  for (int j = threadIdx.x; j < n4; j += kAbsmaxBlock) {
+    const mass_u32x4 v = p4[j];
+    m = max(m, max(max(v[0], v[1]), max(v[2], v[3])));
+  }
+  for (int j = 4 * n4 + threadIdx.x; j < a.n_absmax; j += kAbsmaxBlock) m = max(m, a.absmax_part[j]);
+#pragma unroll
+  for (int o = kWave / 2; o > 0; o >>= 1) m = max(m, (unsigned)__shfl_xor((int)m, o, kWave));
+  if (threadIdx.x % kWave == 0) shm[threadIdx.x / kWave] = m;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kAbsmaxBlock / kWave; ++w) m = max(m, shm[w]);
+    *out = m;
+  }
 }
 
 // Power-of-two scale s with |x| * 2^s * (number of points) < 2^62 for every used x.
@@ -194,15 +211,19 @@ __global__ __launch_bounds__(kMassBlock) void k_mass_bin(MassArgs a, MassTable t
   for (int l0 = begin; l0 < end; l0 += kMassBlock) {   // uniform trip count: the lanes of a wave exchange values below
     const int li = l0 + threadIdx.x;
     const long long i = ob.pt_begin + min(li, end - 1);
-    const bool used = li < end && !(a.count && a.count[i] <= 0);
+    // all of a point's reads are issued together (the index is clamped: in bounds whether the point is used or not)
+    const int cnt = a.count ? a.count[i] : 1;
+    const float px = a.xyz[3 * i], py = a.xyz[3 * i + 1], pz = a.xyz[3 * i + 2];
+    const float pr = a.prop[i * a.P + a.p_index];
+    const bool used = li < end && cnt > 0;
     long long vidx = -1 - lane;   // unused lanes: a voxel id no neighbour shares
     long long q = 0;
     if (used) {
-      const int ix = voxel_axis(a.xyz[3 * i], ob.lo[0], inv_h, a.G);
-      const int iy = voxel_axis(a.xyz[3 * i + 1], ob.lo[1], inv_h, a.G);
-      const int iz = voxel_axis(a.xyz[3 * i + 2], ob.lo[2], inv_h, a.G);
+      const int ix = voxel_axis(px, ob.lo[0], inv_h, a.G);
+      const int iy = voxel_axis(py, ob.lo[1], inv_h, a.G);
+      const int iz = voxel_axis(pz, ob.lo[2], inv_h, a.G);
       vidx = vox0 + ((long long)iz * G + iy) * G + ix;
-      q = __double2ll_rn(ldexp((double)a.prop[i * a.P + a.p_index], shift));
+      q = __double2ll_rn(ldexp((double)pr, shift));
     }
     // Spatially sorted points fall into the same voxel in runs: the lanes of a run add up (integers: the
     // order does not matter) and its last lane issues one pair of atomics for the whole run.
@@ -342,7 +363,7 @@ hipError_t launch_property_integrate(const float* prop, int P, int p_index, cons
     int pt_cursor = 0, vox_cursor = 0;
     if (G > 0 && pass == 1 && a.n_absmax > kAbsmaxPerGroup) {   // the slot behind the last per-slice maximum
       unsigned* out = a.absmax_part + (slices_points(N) + B);
-      hipLaunchKernelGGL(k_mass_absmax, dim3(1), dim3(kMassBlock), 0, stream, a, out);
+      hipLaunchKernelGGL(k_mass_absmax, dim3(1), dim3(kAbsmaxBlock), 0, stream, a, out);
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
       a.absmax_call = out;
