@@ -86,20 +86,26 @@ __global__ __launch_bounds__(256) void k_split_for_cells(CellArgs a) {
   slot[kWave] = lo;
 }
 
-// One workgroup of four waves per 32 cells, all materials; wave w takes every fourth group of 16 channels
-// (the sum over channels is a short chain of dependent steps: four waves make it four times shorter) and
-// the four partial results are added through LDS in a fixed order.  A operand: lane (cell i = l % 32,
-// kg = l / 32) holds channels 16 s + 8 kg .. + 7 of cell i (16 contiguous bytes of the stored map);
-// B operand: the same channels of material n = l % 32, from the table above (split per wave on the fly, the
-// conversions were most of the kernel's instructions: 1.0 ms for the 1.6 M cells of 512 channels and 64 materials).
+// One workgroup of four waves per 128 cells, all materials, all channels: wave w multiplies the rows of cells
+// 32 w .. 32 w + 31.  The table above passes through LDS in chunks of 32 KiB (16 / MT groups of 16 channels), double
+// buffered: the workgroup copies the next chunk in while it multiplies with this one, so the table comes from L2 once per
+// 128 cells (with one workgroup per 32 cells, every wave reading its operands from L2, it was 16 KiB of table per cell
+// against 2 KiB of features for 1024 channels and 128 materials, and a 48 KiB buffer for the partial sums held a compute
+// unit to three workgroups).  A operand: lane (cell i = l % 32, kg = l / 32) holds channels 16 s + 8 kg .. + 7 of cell i
+// (16 contiguous bytes of the stored map), requested one chunk ahead; B operand: the same channels of material
+// n = l % 32.  One chain of partial sums per (cell, material): channel groups in ascending order, hi then lo.
 template <int DT, int MT>
 __global__ __launch_bounds__(256) void k_cell_scores(CellArgs a) {
-  __shared__ float s_part[3][MT][16][kWave];
-  const int wave = threadIdx.x / kWave, lane = threadIdx.x % kWave;
-  const long long c0 = (long long)blockIdx.x * 32;
+  constexpr int CS = 16 / MT;                   // groups of 16 channels per chunk
+  constexpr int kChunkVecs = 16 * 2 * kWave;    // 16-byte units per chunk: CS * MT slots of hi and lo
+  constexpr int kCopies = kChunkVecs / 256;     // per thread
+  __shared__ ts_u32x4 s_tab[2][kChunkVecs];
+  const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
+  const long long c0 = (long long)blockIdx.x * 128 + wave * 32;
   const int i = lane & 31, kg = lane >> 5;
   const long long cell = min(c0 + i, a.n_cells - 1);
   const char* __restrict__ frow = a.feat + cell * a.D * 2 + kg * 16;
+  const int n_chunks = a.D / (16 * CS);
 
   ts_f32x16 acc[MT];
 #pragma unroll
@@ -107,32 +113,48 @@ __global__ __launch_bounds__(256) void k_cell_scores(CellArgs a) {
 #pragma unroll
     for (int r = 0; r < 16; ++r) acc[mt][r] = 0.0f;
 
-  for (int s = wave; s < a.D / 16; s += 4) {
-    const ts_u32x4 fa = *reinterpret_cast<const ts_u32x4*>(frow + s * 32);
+  ts_u32x4 tab_r[kCopies], f_cur[CS], f_nxt[CS];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-      const ts_u32x4* slot = a.t_split + ((long long)(s * MT + mt) * 2) * kWave + lane;
-      const ts_u32x4 bh = slot[0], bl = slot[kWave];
-      acc[mt] = ts_mma<DT>(fa, bh, acc[mt]);
-      acc[mt] = ts_mma<DT>(fa, bl, acc[mt]);
-    }
-  }
-  if (wave > 0) {
+  for (int v = 0; v < kCopies; ++v) tab_r[v] = a.t_split[v * 256 + tid];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+  for (int q = 0; q < CS; ++q) f_cur[q] = *reinterpret_cast<const ts_u32x4*>(frow + q * 32);
 #pragma unroll
-      for (int r = 0; r < 16; ++r) s_part[wave - 1][mt][r][lane] = acc[mt][r];
-  }
+  for (int v = 0; v < kCopies; ++v) s_tab[0][v * 256 + tid] = tab_r[v];
   __syncthreads();
-  if (wave > 0) return;
+
+  for (int c = 0; c < n_chunks; ++c) {
+    const bool more = c + 1 < n_chunks;
+    if (more) {
+#pragma unroll
+      for (int v = 0; v < kCopies; ++v) tab_r[v] = a.t_split[(long long)(c + 1) * kChunkVecs + v * 256 + tid];
+#pragma unroll
+      for (int q = 0; q < CS; ++q) f_nxt[q] = *reinterpret_cast<const ts_u32x4*>(frow + ((c + 1) * CS + q) * 32);
+    }
+    const ts_u32x4* tab = s_tab[c & 1];
+#pragma unroll
+    for (int q = 0; q < CS; ++q) {
+#pragma unroll
+      for (int mt = 0; mt < MT; ++mt) {
+        const ts_u32x4 bh = tab[((q * MT + mt) * 2) * kWave + lane], bl = tab[((q * MT + mt) * 2 + 1) * kWave + lane];
+        acc[mt] = ts_mma<DT>(f_cur[q], bh, acc[mt]);
+        acc[mt] = ts_mma<DT>(f_cur[q], bl, acc[mt]);
+      }
+    }
+    if (more) {   // nobody reads the other buffer between the previous trip's barrier and this trip's
+#pragma unroll
+      for (int v = 0; v < kCopies; ++v) s_tab[(c + 1) & 1][v * 256 + tid] = tab_r[v];
+#pragma unroll
+      for (int q = 0; q < CS; ++q) f_cur[q] = f_nxt[q];
+    }
+    __syncthreads();
+  }
   // element r of the lane: cell c0 + 8 (r / 4) + 4 kg + r % 4, material 32 mt + i (0 beyond K)
 #pragma unroll
   for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
     for (int r = 0; r < 16; ++r) {
       const long long c = c0 + 8 * (r >> 2) + 4 * kg + (r & 3);
-      const float sum = ((acc[mt][r] + s_part[0][mt][r][lane]) + s_part[1][mt][r][lane]) + s_part[2][mt][r][lane];
-      const float v = (mt * 32 + i < a.K) ? sum : 0.0f;
+      const float v = (mt * 32 + i < a.K) ? acc[mt][r] : 0.0f;
       if (c < a.n_cells) a.G[c * a.Kpad + mt * 32 + i] = split_pack<DT>(v);
     }
 }
@@ -344,7 +366,7 @@ static hipError_t launch_cells(const CellArgs& a, hipStream_t stream) {
   hipLaunchKernelGGL((k_split_for_cells<DT>), dim3((unsigned)((slots + 255) / 256)), dim3(256), 0, stream, a);
   const hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  const dim3 grid((unsigned)((a.n_cells + 31) / 32)), block(256);
+  const dim3 grid((unsigned)((a.n_cells + 127) / 128)), block(256);
   switch (a.Kpad / 32) {
     case 1: hipLaunchKernelGGL((k_cell_scores<DT, 1>), grid, block, 0, stream, a); break;
     case 2: hipLaunchKernelGGL((k_cell_scores<DT, 2>), grid, block, 0, stream, a); break;
