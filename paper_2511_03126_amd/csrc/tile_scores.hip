@@ -87,8 +87,8 @@ __global__ __launch_bounds__(256) void k_split_for_cells(CellArgs a) {
 }
 
 // One workgroup of four waves per 128 cells, all materials, all channels: wave w multiplies the rows of cells
-// 32 w .. 32 w + 31.  The table above passes through LDS in chunks of 32 KiB (16 / MT groups of 16 channels), double
-// buffered: the workgroup copies the next chunk in while it multiplies with this one, so the table comes from L2 once per
+// 32 w .. 32 w + 31.  The table above passes through LDS in chunks of 16 KiB (8 / MT groups of 16 channels), double
+// buffered (four workgroups fit a compute unit): the workgroup copies the next chunk in while it multiplies with this one, so the table comes from L2 once per
 // 128 cells (with one workgroup per 32 cells, every wave reading its operands from L2, it was 16 KiB of table per cell
 // against 2 KiB of features for 1024 channels and 128 materials, and a 48 KiB buffer for the partial sums held a compute
 // unit to three workgroups).  A operand: lane (cell i = l % 32, kg = l / 32) holds channels 16 s + 8 kg .. + 7 of cell i
@@ -96,8 +96,8 @@ __global__ __launch_bounds__(256) void k_split_for_cells(CellArgs a) {
 // n = l % 32.  One chain of partial sums per (cell, material): channel groups in ascending order, hi then lo.
 template <int DT, int MT>
 __global__ __launch_bounds__(256) void k_cell_scores(CellArgs a) {
-  constexpr int CS = 16 / MT;                   // groups of 16 channels per chunk
-  constexpr int kChunkVecs = 16 * 2 * kWave;    // 16-byte units per chunk: CS * MT slots of hi and lo
+  constexpr int CS = 8 / MT;                    // groups of 16 channels per chunk
+  constexpr int kChunkVecs = 8 * 2 * kWave;     // 16-byte units per chunk: CS * MT slots of hi and lo
   constexpr int kCopies = kChunkVecs / 256;     // per thread
   __shared__ ts_u32x4 s_tab[2][kChunkVecs];
   const int tid = threadIdx.x, wave = tid / kWave, lane = tid % kWave;
