@@ -35,7 +35,7 @@ def fuse_algorithmic_bytes(s):
 # HBM bytes per launch of the dominant kernel from the rocprofv3 counter runs summarised under profiles/ (FETCH_SIZE and
 # WRITE_SIZE, each scaled by the reading of the 256 MiB calibration copy in the same run), per workload.  Valid only for
 # the kernel source the counters were taken with: any change to that file makes the figure null until they are taken again.
-TRAFFIC_BYTES = {'c5': 13697207338}
+TRAFFIC_BYTES = {'c5': 13697295716}
 TRAFFIC_SOURCE_SHA256 = "2f4d7b709ce57a2d0d6fbca40083399d1a869fcd639011d54007a03e0707784c"
 
 
